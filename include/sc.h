@@ -1,0 +1,163 @@
+/*
+ * sc.h - C ABI of the MI355X symmetric tensor contraction library (libsc_mi355x.so).
+ *
+ * The operation is the "higher-order feature computation" of MACE, Algorithm 2 of
+ * arXiv 2504.10700 (Section 4.1) together with the message equation of Section 2.2:
+ * for every atom i, channel k and output component (L,M)
+ *
+ *   B[i,k,(L,M)] = sum_{nu=1..nu_max} sum_{eta} W[z_i, p(nu,L,eta), k]
+ *                  * sum_{a_1..a_nu} U^{(nu,L,eta)}[M; a_1..a_nu] * prod_{xi=1..nu} A[i,k,a_xi]
+ *
+ * where A are the atomic-basis features in the real spherical-harmonic basis
+ * (component index a = l*l + l + m, l = 0..l_max, parity (-1)^l), z_i the element
+ * index of atom i, W the element-dependent per-channel weights and U the generalized
+ * Clebsch-Gordan coefficients of the coupling path eta.  The backward entry point
+ * returns the gradients of sum(dB * B) with respect to A and W.
+ *
+ * Coupling paths (the paper's eta; it indexes weights by the l-tuple only, which is
+ * ambiguous for nu = 3): a path is an ORDERED l-tuple plus, for nu = 3, the
+ * intermediate L2 of the chain ((l1 x l2) -> L2) x l3 -> L.  Every path the triangle
+ * rule (Section 4.2) and parity allow is present.  Global path index p: nu ascending,
+ * then output irrep in the order given in sc_config, then (l1, l2, L2, l3) ascending.
+ * U chains real-basis coupling tensors C(l1,l2,l3) - the unique rotation-invariant
+ * tensor of the three irreps, unit Frobenius norm, first non-zero entry in row-major
+ * (m1,m2,m3) order positive - with no further factor:
+ *   nu=1: U[M;a] = delta(a, L*L+L+M)      nu=2: U[M;a1,a2] = C(l1,l2,L)[m1,m2,M]
+ *   nu=3: U[M;a1,a2,a3] = sum_M2 C(l1,l2,L2)[m1,m2,M2] * C(L2,l3,L)[M2,m3,M].
+ *
+ * Conventions for every entry point
+ *  - All tensor arguments of sc_forward / sc_backward are DEVICE pointers owned by the
+ *    caller: dense, row-major, no strides, 16-byte aligned.  Arguments of the plan /
+ *    info / table helpers are HOST pointers.
+ *  - sc_forward / sc_backward only enqueue work on the given HIP stream (NULL = the
+ *    default stream) and never synchronise.  The plan is immutable after creation and
+ *    may be used from several streams; a workspace must not be shared by calls that
+ *    can overlap in time.
+ *  - Outputs are overwritten (never accumulated into); inputs are never modified;
+ *    outputs must not alias inputs or each other.
+ *  - Errors are reported by return code only; sc_last_error() gives a thread-local
+ *    message for the last failing call of the calling thread.  Argument errors are
+ *    found on the host before anything is launched.  Element indices outside
+ *    [0, num_elements) are NOT detected: such nodes are skipped by the grouping
+ *    pass (their rows of B / dA are left unwritten); no out-of-bounds access results.
+ */
+#ifndef SC_MI355X_H
+#define SC_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sc_plan sc_plan; /* opaque; created and destroyed only by this library */
+
+typedef enum {
+  SC_OK = 0,
+  SC_ERR_INVALID_ARG = 1, /* null pointer, bad size, misaligned pointer, bad struct_size   */
+  SC_ERR_UNSUPPORTED = 2, /* configuration outside what the library implements             */
+  SC_ERR_WORKSPACE = 3,   /* workspace missing or smaller than sc_workspace_bytes()        */
+  SC_ERR_HIP = 4,         /* a HIP runtime call failed (message has the HIP error string)  */
+  SC_ERR_ALLOC = 5        /* host or device allocation failed                              */
+} sc_status;
+
+typedef enum { SC_F32 = 0, SC_F64 = 1 } sc_dtype;
+
+#define SC_MAX_OUT 4       /* output irreps per plan                                       */
+#define SC_MAX_L 3         /* largest l_max and largest output L                           */
+#define SC_MAX_NU 3        /* largest correlation order                                    */
+#define SC_MAX_ELEMENTS 1024
+
+/* sc_config.flags */
+#define SC_PLAN_HOST_ONLY 1u     /* build tables only; no device is touched, compute calls fail   */
+#define SC_PLAN_FORCE_GENERIC 2u /* use the table-driven kernels even if a specialised one exists */
+
+/* flags of sc_forward / sc_backward */
+#define SC_REUSE_GROUPING 1u /* the workspace still holds the grouping written by the previous
+                                sc_forward/sc_backward call of this plan with the same
+                                n_nodes and the same z contents: skip regrouping           */
+
+typedef struct {
+  int32_t struct_size;            /* = sizeof(sc_config), ABI guard                                  */
+  int32_t num_channels;           /* K >= 1                          (N_channels of Algorithm 2)     */
+  int32_t l_max;                  /* A carries l = 0..l_max, 0..SC_MAX_L     (L_max of Algorithm 2)  */
+  int32_t nu_max;                 /* correlation order 1..SC_MAX_NU          (nu_max of Algorithm 2) */
+  int32_t num_elements;           /* Z: z values lie in [0, Z), 1..SC_MAX_ELEMENTS                   */
+  int32_t num_out;                /* number of output irreps, 1..SC_MAX_OUT                          */
+  int32_t out_l[SC_MAX_OUT];      /* L of each output irrep, 0..SC_MAX_L                             */
+  int32_t out_parity[SC_MAX_OUT]; /* +1 = even ("e"), -1 = odd ("o")                                 */
+  int32_t dtype;                  /* sc_dtype of A, W, B, dB, dA, dW                                 */
+  int32_t device;                 /* HIP device ordinal (ignored with SC_PLAN_HOST_ONLY)             */
+  uint32_t flags;                 /* SC_PLAN_*                                                       */
+} sc_config;
+
+typedef struct {
+  int32_t n_lm;        /* (l_max+1)^2 components of A per (node, channel)          */
+  int32_t n_LM;        /* sum of (2L+1) over the output irreps                     */
+  int32_t num_paths;   /* P: second extent of W and dW                             */
+  int32_t specialised; /* 1 if a generated straight-line kernel serves this plan   */
+} sc_info;
+
+/* Section 4.1, inputs of Algorithm 2: fixes K, l_max, nu_max, the element range and
+ * the output irreps; derives the coupling tables (host, Wigner 3j by the Racah sum,
+ * moved to the real basis) and uploads them to cfg->device.
+ * On success *out_plan owns host and device memory until sc_plan_destroy.
+ * Fails with SC_ERR_UNSUPPORTED for parameters beyond the SC_MAX_* limits or output
+ * irreps no path can reach; never later. */
+sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan);
+
+/* Frees the plan (NULL is a no-op returning SC_OK).  The caller must make sure no
+ * enqueued work still uses it. */
+sc_status sc_plan_destroy(sc_plan* plan);
+
+sc_status sc_plan_info(const sc_plan* plan, sc_info* out);
+
+/* paths: host buffer of num_paths rows {nu, out_index, l1, l2, l3, L2}, unused = -1,
+ * in the global path order defined above (the eta of Section 2.2's message equation). */
+sc_status sc_plan_paths(const sc_plan* plan, int32_t* paths);
+
+/* Sparse form of one path's generalized coupling tensor after merging slot
+ * permutations (A is the same in every slot, Section 4.1 "multiple copies of the
+ * message"): term t says  P_{p,M[t]}(a) += coef[t] * a[i1[t]] * a[i2[t]] * a[i3[t]]
+ * with i1 <= i2 <= i3 and unused slots = -1.  Call with capacity 0 to query the
+ * count (*n_terms); host buffers.  Exists for tests and the kernel generator. */
+sc_status sc_plan_path_terms(const sc_plan* plan, int32_t path, int32_t capacity, int32_t* n_terms,
+                             int32_t* M, int32_t* i1, int32_t* i2, int32_t* i3, double* coef);
+
+/* C(l1,l2,l3) of the header comment (Clebsch-Gordan coefficients of the paper's
+ * notation table in the real basis), row-major [2l1+1][2l2+1][2l3+1] doubles into a
+ * host buffer; all zero when the triangle rule fails.  0 <= l <= 2*SC_MAX_L. */
+sc_status sc_coupling_tensor(int32_t l1, int32_t l2, int32_t l3, double* out);
+
+/* Bytes of device workspace sc_forward / sc_backward need for up to n_nodes nodes. */
+sc_status sc_workspace_bytes(const sc_plan* plan, int64_t n_nodes, size_t* bytes);
+
+/* Forward of Algorithm 2.
+ *   A  dev [n_nodes][K][n_lm]         z  dev int32 [n_nodes]
+ *   W  dev [Z][num_paths][K]          B  dev [n_nodes][K][n_LM]   (overwritten)
+ * workspace: device memory, 256-byte aligned, >= sc_workspace_bytes(plan, n_nodes).
+ * It receives the grouping of nodes by element (reusable by the backward of the
+ * same batch, see SC_REUSE_GROUPING).  n_nodes == 0 is valid and does nothing. */
+sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W,
+                     void* B, void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream);
+
+/* Backward of Algorithm 2 for an upstream gradient dB (training, Section 2.2: energies
+ * and forces are trained by gradient descent through this operation).
+ *   dB dev [n_nodes][K][n_LM]
+ *   dA dev [n_nodes][K][n_lm]  (overwritten)   dA[i,k,a] = sum_LM dB * dB[i,k,LM]/dA[i,k,a]
+ *   dW dev [Z][num_paths][K]   (overwritten)   dW[e,p,k] = sum_{i: z_i = e} sum_M dB[i,k,(L_p,M)] * P_{p,M}(A[i,k,:])
+ * Rows of dW for elements that do not occur are zero.  n_nodes == 0 zeroes dW.
+ * dW is reduced per element in a fixed order (no floating-point atomics): results
+ * are bitwise reproducible for identical inputs. */
+sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W,
+                      const void* dB, void* dA, void* dW, void* workspace, size_t workspace_bytes,
+                      uint32_t flags, void* hip_stream);
+
+/* Thread-local message of the last failing call on this thread; never NULL. */
+const char* sc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SC_MI355X_H */

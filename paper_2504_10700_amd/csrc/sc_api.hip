@@ -1,0 +1,368 @@
+// C ABI entry points (see include/sc.h): argument checks, plan construction, workspace
+// layout and kernel dispatch.  Everything numerical happens in the kernels.
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "sc_internal.h"
+#include "sc_spec.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+sc_status fail(sc_status code, const std::string& msg) {
+  g_last_error = msg;
+  return code;
+}
+
+sc_status fail_hip(hipError_t e, const char* what) {
+  return fail(SC_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Makes `device` current for the lifetime of the guard.
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int device) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == device) || hipSetDevice(device) == hipSuccess;
+    if (prev == device) prev = -1;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+__global__ void fill_zero_kernel(unsigned int* p, size_t n_words) {
+  for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n_words;
+       i += static_cast<size_t>(gridDim.x) * blockDim.x)
+    p[i] = 0u;
+}
+
+size_t elem_size(const sc_plan* plan) { return plan->cfg.dtype == SC_F64 ? 8 : 4; }
+
+bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
+
+}  // namespace
+
+namespace sc {
+
+LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
+  LaunchShape s{};
+  s.chblocks = (plan->cfg.num_channels + kLanes - 1) / kLanes;
+  // Tiles are sized so that one wave of tiles fills every SIMD of the chip about
+  // twice over for small batches and stay bounded for large ones (the per-tile dW
+  // rows cost memory traffic inversely proportional to the tile size).
+  const int waves_per_tile = plan->specialised ? spec_waves_per_tile() : 1;
+  const int64_t slots = static_cast<int64_t>(plan->num_cus) * 4 * 2 / waves_per_tile;
+  int64_t t = (n * s.chblocks + slots - 1) / (slots > 0 ? slots : 1);
+  const int64_t lo = 4 * waves_per_tile, hi = 32 * waves_per_tile;
+  if (t < lo) t = lo;
+  if (t > hi) t = hi;
+  s.tile_nodes = static_cast<int>(t);
+  s.max_tiles = static_cast<int>(n / s.tile_nodes) + plan->cfg.num_elements;
+  int64_t gw = (n + 255) / 256;  // about four 64-node chunks per grouping wave
+  gw = (gw + kGroupWavesPerWG - 1) / kGroupWavesPerWG * kGroupWavesPerWG;
+  if (gw < kGroupWavesPerWG) gw = kGroupWavesPerWG;
+  if (gw > kMaxGroupWaves) gw = kMaxGroupWaves;
+  s.group_waves = static_cast<int>(gw);
+  s.nodes_per_group_wave = static_cast<int>((n + gw - 1) / gw);
+  return s;
+}
+
+Workspace carve_workspace(const sc_plan* plan, int64_t n, const LaunchShape& shape, void* base) {
+  Workspace w{};
+  const int Z = plan->cfg.num_elements;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    void* p = base ? static_cast<char*>(base) + off : nullptr;
+    off = align_up(off + bytes, 256);
+    return p;
+  };
+  w.ntiles = static_cast<int32_t*>(take(sizeof(int32_t)));
+  w.seg_off = static_cast<int32_t*>(take(sizeof(int32_t) * (Z + 1)));
+  w.tile_off = static_cast<int32_t*>(take(sizeof(int32_t) * (Z + 1)));
+  w.counts = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(kMaxGroupWaves) * Z));
+  w.perm = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
+  w.tiles = static_cast<TileDesc*>(take(sizeof(TileDesc) * static_cast<size_t>(shape.max_tiles)));
+  w.partial = take(elem_size(plan) * static_cast<size_t>(shape.max_tiles) * shape.chblocks * plan->S * kLanes);
+  w.max_tiles = shape.max_tiles;
+  w.bytes = off;
+  return w;
+}
+
+}  // namespace sc
+
+extern "C" {
+
+const char* sc_last_error(void) { return g_last_error.c_str(); }
+
+sc_status sc_coupling_tensor(int32_t l1, int32_t l2, int32_t l3, double* out) {
+  if (!out) return fail(SC_ERR_INVALID_ARG, "sc_coupling_tensor: out is NULL");
+  if (l1 < 0 || l2 < 0 || l3 < 0 || l1 > 2 * SC_MAX_L || l2 > 2 * SC_MAX_L || l3 > 2 * SC_MAX_L)
+    return fail(SC_ERR_INVALID_ARG, "sc_coupling_tensor: l outside 0..2*SC_MAX_L");
+  const std::vector<double> c = sc::coupling_tensor(l1, l2, l3);
+  std::memcpy(out, c.data(), c.size() * sizeof(double));
+  return SC_OK;
+}
+
+sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
+  if (!cfg || !out_plan) return fail(SC_ERR_INVALID_ARG, "sc_plan_create: NULL argument");
+  *out_plan = nullptr;
+  if (cfg->struct_size != static_cast<int32_t>(sizeof(sc_config)))
+    return fail(SC_ERR_INVALID_ARG, "sc_plan_create: struct_size does not match this library's sc_config");
+  if (cfg->num_channels < 1) return fail(SC_ERR_INVALID_ARG, "sc_plan_create: num_channels < 1");
+  if (cfg->dtype != SC_F32 && cfg->dtype != SC_F64) return fail(SC_ERR_INVALID_ARG, "sc_plan_create: bad dtype");
+  if (cfg->l_max < 0 || cfg->l_max > SC_MAX_L) return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: l_max outside 0..3");
+  if (cfg->nu_max < 1 || cfg->nu_max > SC_MAX_NU)
+    return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: nu_max outside 1..3");
+  if (cfg->num_elements < 1 || cfg->num_elements > SC_MAX_ELEMENTS)
+    return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: num_elements outside 1..SC_MAX_ELEMENTS");
+  if (cfg->num_out < 1 || cfg->num_out > SC_MAX_OUT)
+    return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: num_out outside 1..SC_MAX_OUT");
+  std::vector<int> out_l, out_p;
+  for (int o = 0; o < cfg->num_out; ++o) {
+    if (cfg->out_l[o] < 0 || cfg->out_l[o] > SC_MAX_L)
+      return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: output L outside 0..3");
+    if (cfg->out_parity[o] != 1 && cfg->out_parity[o] != -1)
+      return fail(SC_ERR_INVALID_ARG, "sc_plan_create: out_parity must be +1 or -1");
+    for (int q = 0; q < o; ++q)
+      if (cfg->out_l[q] == cfg->out_l[o] && cfg->out_parity[q] == cfg->out_parity[o])
+        return fail(SC_ERR_INVALID_ARG, "sc_plan_create: duplicate output irrep");
+    out_l.push_back(cfg->out_l[o]);
+    out_p.push_back(cfg->out_parity[o]);
+  }
+  sc_plan* plan = new (std::nothrow) sc_plan();
+  if (!plan) return fail(SC_ERR_ALLOC, "sc_plan_create: out of host memory");
+  plan->cfg = *cfg;
+  plan->host_only = (cfg->flags & SC_PLAN_HOST_ONLY) != 0;
+  const char* msg = nullptr;
+  if (!sc::build_path_table(cfg->l_max, cfg->nu_max, out_l, out_p, &plan->table, &msg)) {
+    delete plan;
+    return fail(SC_ERR_UNSUPPORTED, std::string("sc_plan_create: ") + (msg ? msg : "cannot build tables"));
+  }
+  const sc::PathTable& T = plan->table;
+  const int P = static_cast<int>(T.paths.size());
+  plan->specialised = (cfg->flags & SC_PLAN_FORCE_GENERIC) ? 0 : sc::spec_lookup(plan);
+  plan->S = plan->specialised ? sc::spec_basis_size(plan->specialised) : P;
+  if (plan->host_only) {
+    *out_plan = plan;
+    return SC_OK;
+  }
+
+  DeviceGuard guard(cfg->device);
+  if (!guard.ok) {
+    delete plan;
+    return fail(SC_ERR_HIP, "sc_plan_create: cannot make cfg->device current");
+  }
+  hipDeviceProp_t prop;
+  hipError_t e = hipGetDeviceProperties(&prop, cfg->device);
+  if (e != hipSuccess) {
+    delete plan;
+    return fail_hip(e, "sc_plan_create: hipGetDeviceProperties");
+  }
+  plan->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+  // one device blob: path_nu | path_col | term_begin | term_idx | term_coef | fold begin | src | coef
+  std::vector<int32_t> path_nu(P), path_col(P), term_begin(P + 1, 0);
+  std::vector<int4> term_idx;
+  std::vector<double> term_coef;
+  for (int p = 0; p < P; ++p) {
+    path_nu[p] = T.paths[p].nu;
+    path_col[p] = T.out_offset[T.paths[p].out];
+    term_begin[p] = static_cast<int32_t>(term_idx.size());
+    for (const sc::Term& t : T.terms[p]) {
+      term_idx.push_back(make_int4(t.M, t.i1, t.i2 < 0 ? 0 : t.i2, t.i3 < 0 ? 0 : t.i3));
+      term_coef.push_back(t.coef);
+    }
+  }
+  term_begin[P] = static_cast<int32_t>(term_idx.size());
+  std::vector<int32_t> fold_begin, fold_src;
+  std::vector<double> fold_coef;
+  if (plan->specialised) sc::spec_fold(plan->specialised, &fold_begin, &fold_src, &fold_coef);
+
+  size_t off = 0;
+  auto reserve = [&](size_t bytes) {
+    const size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  const size_t o_nu = reserve(sizeof(int32_t) * P), o_col = reserve(sizeof(int32_t) * P),
+               o_tb = reserve(sizeof(int32_t) * (P + 1)), o_ti = reserve(sizeof(int4) * term_idx.size()),
+               o_tc = reserve(sizeof(double) * term_coef.size()), o_fb = reserve(sizeof(int32_t) * fold_begin.size()),
+               o_fs = reserve(sizeof(int32_t) * fold_src.size()), o_fc = reserve(sizeof(double) * fold_coef.size());
+  std::vector<unsigned char> host(off ? off : 256, 0);
+  std::memcpy(host.data() + o_nu, path_nu.data(), sizeof(int32_t) * P);
+  std::memcpy(host.data() + o_col, path_col.data(), sizeof(int32_t) * P);
+  std::memcpy(host.data() + o_tb, term_begin.data(), sizeof(int32_t) * (P + 1));
+  std::memcpy(host.data() + o_ti, term_idx.data(), sizeof(int4) * term_idx.size());
+  std::memcpy(host.data() + o_tc, term_coef.data(), sizeof(double) * term_coef.size());
+  if (!fold_begin.empty()) {
+    std::memcpy(host.data() + o_fb, fold_begin.data(), sizeof(int32_t) * fold_begin.size());
+    std::memcpy(host.data() + o_fs, fold_src.data(), sizeof(int32_t) * fold_src.size());
+    std::memcpy(host.data() + o_fc, fold_coef.data(), sizeof(double) * fold_coef.size());
+  }
+  e = hipMalloc(&plan->dev_blob, host.size());
+  if (e != hipSuccess) {
+    delete plan;
+    return fail(SC_ERR_ALLOC, std::string("sc_plan_create: hipMalloc: ") + hipGetErrorString(e));
+  }
+  e = hipMemcpy(plan->dev_blob, host.data(), host.size(), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(plan->dev_blob);
+    delete plan;
+    return fail_hip(e, "sc_plan_create: hipMemcpy");
+  }
+  char* d = static_cast<char*>(plan->dev_blob);
+  plan->gen.num_paths = P;
+  plan->gen.n_lm = T.n_lm;
+  plan->gen.n_LM = T.n_LM;
+  plan->gen.path_nu = reinterpret_cast<const int32_t*>(d + o_nu);
+  plan->gen.path_col = reinterpret_cast<const int32_t*>(d + o_col);
+  plan->gen.term_begin = reinterpret_cast<const int32_t*>(d + o_tb);
+  plan->gen.term_idx = reinterpret_cast<const int4*>(d + o_ti);
+  plan->gen.term_coef = reinterpret_cast<const double*>(d + o_tc);
+  plan->fold.S = plan->S;
+  plan->fold.begin = reinterpret_cast<const int32_t*>(d + o_fb);
+  plan->fold.src = reinterpret_cast<const int32_t*>(d + o_fs);
+  plan->fold.coef = reinterpret_cast<const double*>(d + o_fc);
+  *out_plan = plan;
+  return SC_OK;
+}
+
+sc_status sc_plan_destroy(sc_plan* plan) {
+  if (!plan) return SC_OK;
+  sc_status st = SC_OK;
+  if (plan->dev_blob) {
+    DeviceGuard guard(plan->cfg.device);
+    const hipError_t e = hipFree(plan->dev_blob);
+    if (e != hipSuccess) st = fail_hip(e, "sc_plan_destroy: hipFree");
+  }
+  delete plan;
+  return st;
+}
+
+sc_status sc_plan_info(const sc_plan* plan, sc_info* out) {
+  if (!plan || !out) return fail(SC_ERR_INVALID_ARG, "sc_plan_info: NULL argument");
+  out->n_lm = plan->table.n_lm;
+  out->n_LM = plan->table.n_LM;
+  out->num_paths = static_cast<int32_t>(plan->table.paths.size());
+  out->specialised = plan->specialised ? 1 : 0;
+  return SC_OK;
+}
+
+sc_status sc_plan_paths(const sc_plan* plan, int32_t* paths) {
+  if (!plan || !paths) return fail(SC_ERR_INVALID_ARG, "sc_plan_paths: NULL argument");
+  for (size_t p = 0; p < plan->table.paths.size(); ++p) {
+    const sc::Path& q = plan->table.paths[p];
+    int32_t* row = paths + 6 * p;
+    row[0] = q.nu; row[1] = q.out; row[2] = q.l1; row[3] = q.l2; row[4] = q.l3; row[5] = q.L2;
+  }
+  return SC_OK;
+}
+
+sc_status sc_plan_path_terms(const sc_plan* plan, int32_t path, int32_t capacity, int32_t* n_terms, int32_t* M,
+                             int32_t* i1, int32_t* i2, int32_t* i3, double* coef) {
+  if (!plan || !n_terms) return fail(SC_ERR_INVALID_ARG, "sc_plan_path_terms: NULL argument");
+  if (path < 0 || path >= static_cast<int32_t>(plan->table.paths.size()))
+    return fail(SC_ERR_INVALID_ARG, "sc_plan_path_terms: path index out of range");
+  const std::vector<sc::Term>& t = plan->table.terms[path];
+  *n_terms = static_cast<int32_t>(t.size());
+  if (capacity == 0) return SC_OK;
+  if (capacity < *n_terms || !M || !i1 || !i2 || !i3 || !coef)
+    return fail(SC_ERR_INVALID_ARG, "sc_plan_path_terms: buffers missing or too small");
+  for (size_t i = 0; i < t.size(); ++i) {
+    M[i] = t[i].M; i1[i] = t[i].i1; i2[i] = t[i].i2; i3[i] = t[i].i3; coef[i] = t[i].coef;
+  }
+  return SC_OK;
+}
+
+sc_status sc_workspace_bytes(const sc_plan* plan, int64_t n_nodes, size_t* bytes) {
+  if (!plan || !bytes) return fail(SC_ERR_INVALID_ARG, "sc_workspace_bytes: NULL argument");
+  if (n_nodes < 0 || n_nodes > (int64_t(1) << 30))
+    return fail(SC_ERR_INVALID_ARG, "sc_workspace_bytes: n_nodes outside 0..2^30");
+  const sc::LaunchShape shape = sc::launch_shape(plan, n_nodes);
+  *bytes = sc::carve_workspace(plan, n_nodes, shape, nullptr).bytes;
+  return SC_OK;
+}
+
+static sc_status check_common(const char* fn, const sc_plan* plan, int64_t n, const void* workspace,
+                              size_t workspace_bytes, sc::LaunchShape* shape, sc::Workspace* ws) {
+  if (!plan) return fail(SC_ERR_INVALID_ARG, std::string(fn) + ": plan is NULL");
+  if (plan->host_only) return fail(SC_ERR_UNSUPPORTED, std::string(fn) + ": plan was created with SC_PLAN_HOST_ONLY");
+  if (n < 0 || n > (int64_t(1) << 30)) return fail(SC_ERR_INVALID_ARG, std::string(fn) + ": n_nodes outside 0..2^30");
+  *shape = sc::launch_shape(plan, n);
+  *ws = sc::carve_workspace(plan, n, *shape, const_cast<void*>(workspace));
+  if (n > 0) {
+    if (!workspace || workspace_bytes < ws->bytes)
+      return fail(SC_ERR_WORKSPACE, std::string(fn) + ": workspace missing or smaller than sc_workspace_bytes()");
+    if (misaligned(workspace, 256)) return fail(SC_ERR_WORKSPACE, std::string(fn) + ": workspace not 256-byte aligned");
+  }
+  return SC_OK;
+}
+
+sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W, void* B,
+                     void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream) {
+  sc::LaunchShape shape;
+  sc::Workspace ws;
+  sc_status st = check_common("sc_forward", plan, n_nodes, workspace, workspace_bytes, &shape, &ws);
+  if (st != SC_OK) return st;
+  if (n_nodes == 0) return SC_OK;
+  if (!A || !z || !W || !B) return fail(SC_ERR_INVALID_ARG, "sc_forward: NULL tensor argument");
+  if (misaligned(A, 16) || misaligned(W, 16) || misaligned(B, 16) || misaligned(z, 4))
+    return fail(SC_ERR_INVALID_ARG, "sc_forward: tensor pointer not 16-byte aligned");
+  DeviceGuard guard(plan->cfg.device);
+  if (!guard.ok) return fail(SC_ERR_HIP, "sc_forward: cannot make the plan's device current");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipSuccess;
+  if (!(flags & SC_REUSE_GROUPING)) {
+    e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
+    if (e != hipSuccess) return fail_hip(e, "sc_forward: grouping launch");
+  }
+  e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, W, B, ws, shape, stream)
+                        : sc::launch_generic_forward(plan, n_nodes, A, W, B, ws, shape, stream);
+  if (e != hipSuccess) return fail_hip(e, "sc_forward: kernel launch");
+  return SC_OK;
+}
+
+sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W, const void* dB,
+                      void* dA, void* dW, void* workspace, size_t workspace_bytes, uint32_t flags,
+                      void* hip_stream) {
+  sc::LaunchShape shape;
+  sc::Workspace ws;
+  sc_status st = check_common("sc_backward", plan, n_nodes, workspace, workspace_bytes, &shape, &ws);
+  if (st != SC_OK) return st;
+  if (!dW) return fail(SC_ERR_INVALID_ARG, "sc_backward: dW is NULL");
+  if (misaligned(dW, 16)) return fail(SC_ERR_INVALID_ARG, "sc_backward: dW not 16-byte aligned");
+  DeviceGuard guard(plan->cfg.device);
+  if (!guard.ok) return fail(SC_ERR_HIP, "sc_backward: cannot make the plan's device current");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (n_nodes == 0) {
+    const size_t words = elem_size(plan) / 4 * static_cast<size_t>(plan->cfg.num_elements) *
+                         plan->table.paths.size() * plan->cfg.num_channels;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, stream, static_cast<unsigned int*>(dW), words);
+    const hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return fail_hip(e0, "sc_backward: fill launch");
+    return SC_OK;
+  }
+  if (!A || !z || !W || !dB || !dA) return fail(SC_ERR_INVALID_ARG, "sc_backward: NULL tensor argument");
+  if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(dA, 16) || misaligned(z, 4))
+    return fail(SC_ERR_INVALID_ARG, "sc_backward: tensor pointer not 16-byte aligned");
+  hipError_t e = hipSuccess;
+  if (!(flags & SC_REUSE_GROUPING)) {
+    e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
+    if (e != hipSuccess) return fail_hip(e, "sc_backward: grouping launch");
+  }
+  e = plan->specialised ? sc::launch_spec_backward(plan, n_nodes, A, W, dB, dA, ws, shape, stream)
+                        : sc::launch_generic_backward(plan, n_nodes, A, W, dB, dA, ws, shape, stream);
+  if (e != hipSuccess) return fail_hip(e, "sc_backward: kernel launch");
+  e = sc::launch_finalize(plan, dW, ws, shape, stream);
+  if (e != hipSuccess) return fail_hip(e, "sc_backward: finalize launch");
+  return SC_OK;
+}
+
+}  // extern "C"

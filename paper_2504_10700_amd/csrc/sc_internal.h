@@ -1,0 +1,95 @@
+// Internal declarations shared by the host API and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/sc.h"
+#include "sc_tables.h"
+
+namespace sc {
+
+constexpr int kLanes = 64;          // channels per wave (one lane per channel)
+constexpr int kGroupWavesPerWG = 4; // grouping kernels: waves per workgroup
+constexpr int kMaxGroupWaves = 256; // grouping kernels: total waves (rows of the count matrix)
+
+// One tile = the nodes one workgroup of a main kernel processes: a run of
+// consecutive positions of `perm` that all belong to one element.
+struct TileDesc {
+  int32_t z, start, count, pad;
+};
+
+// Device-side view of the workspace (all pointers into the caller's buffer).
+struct Workspace {
+  int32_t* ntiles;     // [1]
+  int32_t* seg_off;    // [Z+1] first position in perm of each element
+  int32_t* tile_off;   // [Z+1] first tile of each element
+  int32_t* counts;     // [kMaxGroupWaves][Z] scratch of the counting sort
+  int32_t* perm;       // [N] node indices grouped by element (stable)
+  TileDesc* tiles;     // [max_tiles]
+  void* partial;       // [max_tiles][chblocks][S][64] per-tile dW contributions
+  int32_t max_tiles;
+  size_t bytes;
+};
+
+// Table-driven ("generic") kernel tables, device pointers.
+struct GenericTables {
+  int32_t num_paths, n_lm, n_LM;
+  const int32_t* path_nu;     // [P]
+  const int32_t* path_col;    // [P] first LM column of the path's output irrep
+  const int32_t* term_begin;  // [P+1]
+  const int4* term_idx;       // [n_terms] (M, i1, i2, i3)
+  const double* term_coef;    // [n_terms]
+};
+
+// dW' -> dW unfold (specialised kernels work in a reduced path basis): for
+// external path p: dW[z,p,k] = sum_{e in [begin[p],begin[p+1])} coef[e] * dW'[z, src[e], k]
+struct FoldTables {
+  int32_t S;                  // internal basis size (== num_paths and identity when generic)
+  const int32_t* begin;       // [P+1]
+  const int32_t* src;         // [nnz]
+  const double* coef;         // [nnz]
+};
+
+struct LaunchShape {
+  int tile_nodes;   // nodes per tile (per workgroup)
+  int max_tiles;    // upper bound of the tile count = grid size / chblocks
+  int chblocks;     // ceil(K / 64)
+  int group_waves;  // rows used of the count matrix
+  int nodes_per_group_wave;
+};
+
+}  // namespace sc
+
+struct sc_plan {
+  sc_config cfg;
+  sc::PathTable table;
+  bool host_only = false;
+  int specialised = 0;          // 0 = generic, else id of a generated kernel
+  int S = 0;                    // size of the internal path basis
+  int num_cus = 256;
+  // device copies
+  void* dev_blob = nullptr;
+  sc::GenericTables gen{};
+  sc::FoldTables fold{};
+};
+
+namespace sc {
+
+LaunchShape launch_shape(const sc_plan* plan, int64_t n_nodes);
+Workspace carve_workspace(const sc_plan* plan, int64_t n_nodes, const LaunchShape& shape, void* base);
+
+// kernels (defined in the .hip files); all return hipGetLastError() of their launches
+hipError_t launch_grouping(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
+                           const LaunchShape& shape, hipStream_t stream);
+hipError_t launch_generic_forward(const sc_plan* plan, int64_t n, const void* A, const void* W, void* B,
+                                  const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
+hipError_t launch_generic_backward(const sc_plan* plan, int64_t n, const void* A, const void* W,
+                                   const void* dB, void* dA, const Workspace& ws, const LaunchShape& shape,
+                                   hipStream_t stream);
+hipError_t launch_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
+                           hipStream_t stream);
+
+}  // namespace sc

@@ -1,0 +1,21 @@
+// Generated straight-line kernels for selected configurations (see sc_spec.hip).
+#pragma once
+#include "sc_internal.h"
+
+namespace sc {
+
+// Returns the id (> 0) of the generated kernel that serves this plan, 0 if none.
+int spec_lookup(const sc_plan* plan);
+// Size of the internal (reduced) path basis of a generated kernel.
+int spec_basis_size(int id);
+// Waves per workgroup (= per tile) of the generated kernels.
+int spec_waves_per_tile();
+// CSR of the unfold dW[p] = sum coef * dW'[src], rows = external paths.
+void spec_fold(int id, std::vector<int32_t>* begin, std::vector<int32_t>* src, std::vector<double>* coef);
+
+hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const void* W, void* B,
+                               const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
+hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,
+                                void* dA, const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
+
+}  // namespace sc

@@ -1,0 +1,110 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what
+include/sc.h declares, and its own coupling tables (Wigner 3j by the Racah sum)
+agree with the oracle's (null space of the rotation generators)."""
+import itertools
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import coupling as oc
+from oracle import symmetric_contraction as osc
+
+sc = pytest.importorskip("paper_2504_10700_amd.binding")
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+O01 = ((0, 1), (1, -1))
+O012 = ((0, 1), (1, -1), (2, 1))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sc.h")).read()
+    declared = set(re.findall(r"^(?:sc_status|const char\*)\s+(sc_\w+)\s*\(", header, flags=re.M))
+    assert declared == set(sc.EXPORTS)
+    for name in declared:
+        assert getattr(sc.lib, name) is not None
+
+
+def host_plan(K, l_max, nu_max, Z, outs, dtype=sc.SC_F64):
+    return sc.sc_plan_create(K, l_max, nu_max, Z, outs, dtype, 0, sc.SC_PLAN_HOST_ONLY)
+
+
+@pytest.mark.parametrize("l1,l2,l3", [(a, b, c) for a in range(4) for b in range(4) for c in range(7)])
+def test_coupling_tensor_matches_oracle(l1, l2, l3):
+    got = sc.sc_coupling_tensor(l1, l2, l3)
+    assert np.abs(got - oc.coupling_tensor(l1, l2, l3)).max() < 1e-13
+
+
+@pytest.mark.parametrize("l_max,nu_max,Z,outs", [(1, 2, 2, ((0, 1),)), (3, 3, 89, O01), (3, 3, 89, O012),
+                                                 (2, 3, 4, ((1, 1), (2, -1), (3, -1)))])
+def test_paths_and_terms_match_oracle(l_max, nu_max, Z, outs):
+    plan = host_plan(8, l_max, nu_max, Z, outs)
+    cfg = osc.OracleConfig(8, l_max, nu_max, Z, outs)
+    info = sc.sc_plan_info(plan)
+    assert (info.n_lm, info.n_LM) == (cfg.n_lm, cfg.n_LM)
+    paths = sc.sc_plan_paths(plan)
+    ref_paths = osc.enumerate_paths(cfg)
+    assert [tuple(r) for r in paths.tolist()] == ref_paths
+    n = cfg.n_lm
+    for p, path in enumerate(ref_paths):
+        nu = path[0]
+        U = osc.dense_U(cfg, path)
+        # the library merges slot permutations: compare polynomial coefficients
+        want = {}
+        for idx in itertools.product(*([range(U.shape[0])] + [range(n)] * nu)):
+            v = U[idx]
+            if v != 0.0:
+                key = (idx[0],) + tuple(sorted(idx[1:]))
+                want[key] = want.get(key, 0.0) + v
+        want = {k: v for k, v in want.items() if abs(v) > 1e-12}
+        M, i1, i2, i3, coef = sc.sc_plan_path_terms(plan, p)
+        got = {}
+        for t in range(len(M)):
+            key = (int(M[t]),) + tuple(int(x) for x in (i1[t], i2[t], i3[t])[:nu])
+            assert all(x >= 0 for x in key) and list(key[1:]) == sorted(key[1:])
+            assert key not in got
+            got[key] = coef[t]
+        assert set(got) == set(want), path
+        assert max((abs(got[k] - want[k]) for k in want), default=0.0) < 1e-13
+    sc.sc_plan_destroy(plan)
+
+
+def test_argument_errors_are_reported_not_crashed():
+    with pytest.raises(sc.ScError) as e:
+        host_plan(8, 4, 3, 2, O01)
+    assert e.value.status == sc.SC_ERR_UNSUPPORTED and "l_max" in str(e.value)
+    with pytest.raises(sc.ScError) as e:
+        host_plan(8, 3, 4, 2, O01)
+    assert e.value.status == sc.SC_ERR_UNSUPPORTED
+    with pytest.raises(sc.ScError) as e:
+        host_plan(0, 3, 3, 2, O01)
+    assert e.value.status == sc.SC_ERR_INVALID_ARG
+    with pytest.raises(sc.ScError) as e:
+        host_plan(8, 3, 3, 2, ((0, 1), (0, 1)))
+    assert e.value.status == sc.SC_ERR_INVALID_ARG
+    with pytest.raises(sc.ScError) as e:          # 0o cannot be reached with l_max = 0
+        host_plan(8, 0, 3, 2, ((0, -1),))
+    assert e.value.status == sc.SC_ERR_UNSUPPORTED
+    with pytest.raises(sc.ScError) as e:
+        host_plan(8, 3, 3, 5000, O01)
+    assert e.value.status == sc.SC_ERR_UNSUPPORTED
+    plan = host_plan(8, 1, 2, 2, ((0, 1),))
+    with pytest.raises(sc.ScError) as e:          # compute call on a host-only plan
+        sc.sc_forward(plan, 4, 16, 16, 16, 16, 256, 1 << 20, 0, 0)
+    assert e.value.status == sc.SC_ERR_UNSUPPORTED
+    with pytest.raises(sc.ScError):
+        sc.sc_plan_path_terms(plan, 99)
+    with pytest.raises(sc.ScError):
+        sc.sc_workspace_bytes(plan, -1)
+    assert sc.sc_workspace_bytes(plan, 0) >= 0 and sc.sc_workspace_bytes(plan, 1000) > 4000
+    sc.sc_plan_destroy(plan)
+    sc.sc_plan_destroy(None)
+
+
+def test_workspace_grows_with_the_batch():
+    plan = host_plan(128, 3, 3, 89, O01, sc.SC_F32)
+    sizes = [sc.sc_workspace_bytes(plan, n) for n in (1, 100, 3072, 10_000, 200_000)]
+    assert sizes == sorted(sizes)
+    sc.sc_plan_destroy(plan)
