@@ -130,7 +130,9 @@ sc_status sc_plan_path_terms(const sc_plan* plan, int32_t path, int32_t capacity
  * host buffer; all zero when the triangle rule fails.  0 <= l <= 2*SC_MAX_L. */
 sc_status sc_coupling_tensor(int32_t l1, int32_t l2, int32_t l3, double* out);
 
-/* Bytes of device workspace sc_forward / sc_backward need for up to n_nodes nodes. */
+/* Bytes of device workspace sc_forward / sc_backward need for a call with exactly
+ * n_nodes nodes (a caller that sizes one buffer for several batch sizes takes the
+ * maximum over them). */
 sc_status sc_workspace_bytes(const sc_plan* plan, int64_t n_nodes, size_t* bytes);
 
 /* Forward of Algorithm 2.
@@ -153,6 +155,16 @@ sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_
 sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W,
                       const void* dB, void* dA, void* dW, void* workspace, size_t workspace_bytes,
                       uint32_t flags, void* hip_stream);
+
+/* Measurement helper (benchmarks only; not part of the operation).  While enabled,
+ * sc_forward / sc_backward bracket their main kernel - the fused forward kernel, or the
+ * fused dA + per-tile dW kernel; not the grouping pass and not the dW reduction - with
+ * HIP events on the call's stream.  sc_profile_read blocks until the most recent
+ * bracketed call of each kind has finished and returns that kernel's duration in
+ * milliseconds (negative if no such call was made).  While enabled the plan must be used
+ * from one thread and one stream at a time. */
+sc_status sc_profile_enable(sc_plan* plan, int32_t on);
+sc_status sc_profile_read(sc_plan* plan, float* forward_ms, float* backward_ms);
 
 /* Thread-local message of the last failing call on this thread; never NULL. */
 const char* sc_last_error(void);

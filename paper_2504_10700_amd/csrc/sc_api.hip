@@ -234,9 +234,40 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   return SC_OK;
 }
 
+sc_status sc_profile_enable(sc_plan* plan, int32_t on) {
+  if (!plan) return fail(SC_ERR_INVALID_ARG, "sc_profile_enable: plan is NULL");
+  if (plan->host_only) return fail(SC_ERR_UNSUPPORTED, "sc_profile_enable: host-only plan");
+  DeviceGuard guard(plan->cfg.device);
+  if (!guard.ok) return fail(SC_ERR_HIP, "sc_profile_enable: cannot make the plan's device current");
+  if (on && !plan->ev[0]) {
+    for (int i = 0; i < 4; ++i) {
+      const hipError_t e = hipEventCreate(&plan->ev[i]);
+      if (e != hipSuccess) return fail_hip(e, "sc_profile_enable: hipEventCreate");
+    }
+  }
+  plan->profile = on != 0;
+  plan->ev_used[0] = plan->ev_used[1] = false;
+  return SC_OK;
+}
+
+sc_status sc_profile_read(sc_plan* plan, float* forward_ms, float* backward_ms) {
+  if (!plan || !forward_ms || !backward_ms) return fail(SC_ERR_INVALID_ARG, "sc_profile_read: NULL argument");
+  *forward_ms = *backward_ms = -1.0f;
+  float* out[2] = {forward_ms, backward_ms};
+  for (int k = 0; k < 2; ++k) {
+    if (!plan->ev_used[k]) continue;
+    hipError_t e = hipEventSynchronize(plan->ev[2 * k + 1]);
+    if (e == hipSuccess) e = hipEventElapsedTime(out[k], plan->ev[2 * k], plan->ev[2 * k + 1]);
+    if (e != hipSuccess) return fail_hip(e, "sc_profile_read");
+  }
+  return SC_OK;
+}
+
 sc_status sc_plan_destroy(sc_plan* plan) {
   if (!plan) return SC_OK;
   sc_status st = SC_OK;
+  for (int i = 0; i < 4; ++i)
+    if (plan->ev[i]) (void)hipEventDestroy(plan->ev[i]);
   if (plan->dev_blob) {
     DeviceGuard guard(plan->cfg.device);
     const hipError_t e = hipFree(plan->dev_blob);
@@ -323,9 +354,14 @@ sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_
     e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
     if (e != hipSuccess) return fail_hip(e, "sc_forward: grouping launch");
   }
+  if (plan->profile) (void)hipEventRecord(plan->ev[0], stream);
   e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, W, B, ws, shape, stream)
                         : sc::launch_generic_forward(plan, n_nodes, A, W, B, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_forward: kernel launch");
+  if (plan->profile) {
+    (void)hipEventRecord(plan->ev[1], stream);
+    plan->ev_used[0] = true;
+  }
   return SC_OK;
 }
 
@@ -357,9 +393,14 @@ sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32
     e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
     if (e != hipSuccess) return fail_hip(e, "sc_backward: grouping launch");
   }
+  if (plan->profile) (void)hipEventRecord(plan->ev[2], stream);
   e = plan->specialised ? sc::launch_spec_backward(plan, n_nodes, A, W, dB, dA, ws, shape, stream)
                         : sc::launch_generic_backward(plan, n_nodes, A, W, dB, dA, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_backward: kernel launch");
+  if (plan->profile) {
+    (void)hipEventRecord(plan->ev[3], stream);
+    plan->ev_used[1] = true;
+  }
   e = sc::launch_finalize(plan, dW, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_backward: finalize launch");
   return SC_OK;

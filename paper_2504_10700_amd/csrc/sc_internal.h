@@ -70,6 +70,10 @@ struct sc_plan {
   int specialised = 0;          // 0 = generic, else id of a generated kernel
   int S = 0;                    // size of the internal path basis
   int num_cus = 256;
+  // optional kernel timing (sc_profile_enable): [fwd start, fwd stop, bwd start, bwd stop]
+  bool profile = false;
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  bool ev_used[2] = {false, false};
   // device copies
   void* dev_blob = nullptr;
   sc::GenericTables gen{};
