@@ -1,0 +1,280 @@
+"""Generator of the straight-line device code of the specialised kernels.
+
+    python -m paper_2504_10700_amd.codegen.generate            # rewrite csrc/generated/*.inc
+    python -m paper_2504_10700_amd.codegen.generate --check    # fail if a file would change
+
+For every configuration in SPECS it
+  1. asks the library's table builder for the external coupling paths and their
+     polynomials (tables.py),
+  2. chooses a minimal internal basis of coupled paths (one subset of candidates per
+     multiset of l's, found by coordinate descent on the forward + backward operation count),
+  3. solves for the fold matrix F (external polynomial p = sum_s F[s,p] * internal polynomial s)
+     on random samples and checks the residual,
+  4. builds the forward and backward straight-line programs (scheme.py), checks them against
+     the external polynomials (values and, by finite differences, gradients) in fp64,
+  5. writes csrc/generated/sc_gen_<tag>.inc.
+Deterministic: the same library gives the same files.
+"""
+from __future__ import annotations
+
+import argparse
+import itertools
+import os
+import sys
+from typing import Dict, List, Sequence, Tuple
+
+import numpy as np
+
+from .program import Program
+from .scheme import InternalPath, Scheme
+from .tables import HOST_LIB, Tables
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+OUT_DIR = os.path.join(os.path.dirname(_HERE), "csrc", "generated")
+
+# tag -> (l_max, nu_max, output irreps)
+SPECS = {
+    "l3n3_0e1o": (3, 3, ((0, 1), (1, -1))),
+    "l3n3_0e1o2e": (3, 3, ((0, 1), (1, -1), (2, 1))),
+}
+
+
+def candidates(tab: Tables, out: int, ms: Tuple[int, ...]) -> List[InternalPath]:
+    """Coupled paths (pair first, then the third factor) for a sorted multiset of three l's."""
+    L, _ = tab.outs[out]
+    res, seen = [], set()
+    for i in range(3):
+        l3 = ms[i]
+        rest = [ms[j] for j in range(3) if j != i]
+        l1, l2 = min(rest), max(rest)
+        for L2 in range(abs(l1 - l2), l1 + l2 + 1):
+            if l1 == l2 and L2 % 2 == 1:
+                continue  # antisymmetric coupling of two equal factors vanishes
+            if abs(L2 - l3) <= L <= L2 + l3 and (l1, l2, L2, l3) not in seen:
+                seen.add((l1, l2, L2, l3))
+                res.append(InternalPath(3, out, l1, l2, L2, l3))
+    return res
+
+
+def eval_internal(tab: Tables, s: InternalPath, a: np.ndarray) -> np.ndarray:
+    L = tab.outs[s.out][0]
+
+    def al(l):
+        return a[:, l * l:(l + 1) ** 2]
+    if s.nu == 1:
+        return al(s.l1)
+    if s.nu == 2:
+        return np.einsum("abc,na,nb->nc", tab.cg(s.l1, s.l2, L), al(s.l1), al(s.l2))
+    T = np.einsum("abc,na,nb->nc", tab.cg(s.l1, s.l2, s.L2), al(s.l1), al(s.l2))
+    return np.einsum("abc,na,nb->nc", tab.cg(s.L2, s.l3, L), T, al(s.l3))
+
+
+def choose_basis(tab: Tables, samples: np.ndarray):
+    """Returns (basis, fold) with fold[s] = list of (external path, coefficient)."""
+    groups: Dict[Tuple, List[int]] = {}
+    for p, (nu, out, l1, l2, l3, L2) in enumerate(tab.paths):
+        ms = tuple(sorted(l for l in (l1, l2, l3) if l >= 0))
+        groups.setdefault((nu, out, ms), []).append(p)
+    ext = {p: tab.eval_external(p, samples) for p in range(tab.num_paths)}
+    options: Dict[Tuple, List[Tuple[InternalPath, ...]]] = {}
+    for key, plist in groups.items():
+        nu, out, ms = key
+        E = np.stack([ext[p].ravel() for p in plist], 1)
+        r = np.linalg.matrix_rank(E, tol=1e-9)
+        if r == 0:
+            options[key] = [()]
+        elif nu == 1:
+            options[key] = [(InternalPath(1, out, ms[0]),)]
+        elif nu == 2:
+            options[key] = [(InternalPath(2, out, ms[0], ms[1]),)]
+        else:
+            cands = candidates(tab, out, ms)
+            Q = {c: eval_internal(tab, c, samples).ravel() for c in cands}
+            subs = [sub for sub in itertools.combinations(cands, r)
+                    if np.linalg.matrix_rank(np.stack([Q[c] for c in sub], 1), tol=1e-9) == r]
+            assert subs, key
+            options[key] = subs
+    keys = list(options)
+    cur = {k: options[k][0] for k in keys}
+
+    def cost(sel):
+        sch = Scheme(tab.cg, tab.l_max, tab.outs, [c for k in keys for c in sel[k]])
+        return sch.forward().count()["total"] + sch.backward().count()["total"]
+    best = cost(cur)
+    improved = True
+    while improved:
+        improved = False
+        for k in keys:
+            for sub in options[k]:
+                if sub == cur[k]:
+                    continue
+                trial = dict(cur)
+                trial[k] = sub
+                c = cost(trial)
+                if c < best:
+                    best, cur, improved = c, trial, True
+    basis: List[InternalPath] = []
+    fold: List[List[Tuple[int, float]]] = []
+    for k in keys:
+        if not cur[k]:
+            continue
+        plist = groups[k]
+        E = np.stack([ext[p].ravel() for p in plist], 1)
+        Q = np.stack([eval_internal(tab, c, samples).ravel() for c in cur[k]], 1)
+        F, *_ = np.linalg.lstsq(Q, E, rcond=None)
+        assert np.abs(Q @ F - E).max() < 1e-11, (k, np.abs(Q @ F - E).max())
+        for j, c in enumerate(cur[k]):
+            basis.append(c)
+            fold.append([(plist[i], float(F[j, i])) for i in range(len(plist)) if abs(F[j, i]) > 1e-12])
+    return basis, fold
+
+
+def self_check(tab: Tables, basis, fold, fwd: Program, bwd: Program, dtype=np.float64):
+    """Generated programs against the library's external polynomials.  Returns error norms."""
+    rng = np.random.default_rng(12345)
+    n = 2000
+    a = rng.standard_normal((n, tab.n_lm))
+    g = rng.standard_normal((n, tab.n_LM))
+    counts = {}
+    for (nu, out, *_r) in tab.paths:
+        counts[(nu, out)] = counts.get((nu, out), 0) + 1
+    Wext = np.stack([rng.standard_normal(n) / np.sqrt(counts[(p[0], p[1])]) for p in tab.paths], 1)  # [n, P]
+    a, g, Wext = (x.astype(dtype).astype(np.float64) for x in (a, g, Wext))
+    w = np.zeros((n, len(basis)))
+    for s, lst in enumerate(fold):
+        for p, c in lst:
+            w[:, s] += c * Wext[:, p]
+    off = np.cumsum([0] + [2 * L + 1 for L, _ in tab.outs])
+    # reference from the external polynomials (fp64), gradients by differentiating the terms
+    B = np.zeros((n, tab.n_LM))
+    dA = np.zeros((n, tab.n_lm))
+    dWext = np.zeros((n, tab.num_paths))
+    for p, path in enumerate(tab.paths):
+        nu, out = path[0], path[1]
+        M, i1, i2, i3, coef = tab.path_terms(p)
+        for t in range(len(M)):
+            col = off[out] + M[t]
+            f = [a[:, i] for i in (i1[t], i2[t], i3[t])[:nu]]
+            mono = coef[t] * np.prod(f, axis=0)
+            B[:, col] += Wext[:, p] * mono
+            dWext[:, p] += g[:, col] * mono
+            for k, i in enumerate((i1[t], i2[t], i3[t])[:nu]):
+                rest = [f[j] for j in range(nu) if j != k]
+                dA[:, i] += g[:, col] * Wext[:, p] * coef[t] * (np.prod(rest, axis=0) if rest else 1.0)
+    inputs = {f"a[{i}]": a[:, i] for i in range(tab.n_lm)}
+    inputs.update({f"w[{s}]": w[:, s] for s in range(len(basis))})
+    rf = fwd.evaluate(inputs, dtype)
+    Bg = np.stack([rf[f"b[{j}]"] for j in range(tab.n_LM)], 1).astype(np.float64)
+    inputs.update({f"g[{j}]": g[:, j] for j in range(tab.n_LM)})
+    inputs.update({f"dw[{s}]": np.zeros(n) for s in range(len(basis))})
+    rb = bwd.evaluate(inputs, dtype)
+    dAg = np.stack([rb[f"da[{i}]"] for i in range(tab.n_lm)], 1).astype(np.float64)
+    dwg = np.stack([rb[f"dw[{s}]"] for s in range(len(basis))], 1).astype(np.float64)
+    dWg = np.zeros((n, tab.num_paths))
+    for s, lst in enumerate(fold):
+        for p, c in lst:
+            dWg[:, p] += c * dwg[:, s]
+
+    def err(x, y):
+        return float(np.abs(x - y).max() / np.sqrt((y ** 2).mean()))
+    return {"B": err(Bg, B), "dA": err(dAg, dA), "dW(per node)": err(dWg, dWext)}
+
+
+def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program) -> str:
+    S, P = len(basis), tab.num_paths
+    L = []
+    L.append(f"// GENERATED by paper_2504_10700_amd/codegen/generate.py for l_max={tab.l_max}, nu_max={tab.nu_max}, outputs "
+             + "+".join(f"{l}{'e' if p > 0 else 'o'}" for l, p in tab.outs) + ".  Do not edit.")
+    L.append("//")
+    L.append("// Straight-line evaluation of Algorithm 2 of arXiv 2504.10700 (and of its reverse-mode")
+    L.append("// derivative) per (node, channel) in the coupled Horner form described in codegen/scheme.py.")
+    fc, bc = fwd.count(), bwd.count()
+    L.append(f"// Operation counts per (node, channel): forward {fc['total']}, backward {bc['total']}.")
+    L.append("// Internal path basis (index: nu, output irrep, l1, l2, L2, l3):")
+    for i, s in enumerate(basis):
+        L.append(f"//   {i:2d}: nu={s.nu} out={s.out} l1={s.l1} l2={s.l2} L2={s.L2} l3={s.l3}")
+    L.append(f"struct Gen_{tag} {{")
+    L.append(f"  static constexpr int kLmax = {tab.l_max}, kNuMax = {tab.nu_max}, kNumOut = {len(tab.outs)};")
+    L.append(f"  static constexpr int kNlm = {tab.n_lm}, kNLM = {tab.n_LM}, kP = {P}, kS = {S};")
+    L.append("  static constexpr int kOutL[kNumOut] = {" + ", ".join(str(l) for l, _ in tab.outs) + "};")
+    L.append("  static constexpr int kOutParity[kNumOut] = {" + ", ".join(str(p) for _, p in tab.outs) + "};")
+    L.append("")
+    L.append("  // w'[s] = sum_p F[s,p] * W[z,p,k]; Wz points at W[z,0,k], consecutive paths are K apart.")
+    L.append("  template <typename T>")
+    L.append("  static __device__ __forceinline__ void fold(const T* __restrict__ Wz, int K, T (&w)[kS]) {")
+    for s, lst in enumerate(fold):
+        terms = " + ".join(f"T({repr(c)}) * Wz[{p} * K]" for p, c in lst)
+        L.append(f"    w[{s}] = {terms};")
+    L.append("  }")
+    L.append("")
+    L.append("  template <typename T>")
+    L.append("  static __device__ __forceinline__ void forward(const T (&a)[kNlm], const T (&w)[kS], T (&b)[kNLM]) {")
+    L.append(fwd.emit("T", "    "))
+    L.append("  }")
+    L.append("")
+    L.append("  // da is overwritten; dw is accumulated into.")
+    L.append("  template <typename T>")
+    L.append("  static __device__ __forceinline__ void backward(const T (&a)[kNlm], const T (&w)[kS], const T (&g)[kNLM],")
+    L.append("                                                  T (&da)[kNlm], T (&dw)[kS]) {")
+    L.append(bwd.emit("T", "    "))
+    L.append("  }")
+    L.append("};")
+    L.append("")
+    # unfold CSR (rows = external paths) for the host
+    begin, src, coef = [0], [], []
+    by_p: Dict[int, List[Tuple[int, float]]] = {p: [] for p in range(P)}
+    for s, lst in enumerate(fold):
+        for p, c in lst:
+            by_p[p].append((s, c))
+    for p in range(P):
+        for s, c in by_p[p]:
+            src.append(s)
+            coef.append(c)
+        begin.append(len(src))
+    L.append(f"static const int kFoldBegin_{tag}[] = {{" + ", ".join(map(str, begin)) + "};")
+    L.append(f"static const int kFoldSrc_{tag}[] = {{" + ", ".join(map(str, src)) + "};")
+    L.append(f"static const double kFoldCoef_{tag}[] = {{" + ", ".join(repr(c) for c in coef) + "};")
+    return "\n".join(L) + "\n"
+
+
+def generate(tag: str, lib_path: str = HOST_LIB, verbose: bool = True) -> str:
+    l_max, nu_max, outs = SPECS[tag]
+    tab = Tables(lib_path, l_max, nu_max, outs)
+    samples = np.random.default_rng(0).standard_normal((40, tab.n_lm))
+    basis, fold = choose_basis(tab, samples)
+    sch = Scheme(tab.cg, l_max, outs, basis)
+    fwd, bwd = sch.forward(), sch.backward()
+    e64 = self_check(tab, basis, fold, fwd, bwd, np.float64)
+    assert max(e64.values()) < 1e-12, e64
+    if verbose:
+        e32 = self_check(tab, basis, fold, fwd, bwd, np.float32)
+        print(f"[{tag}] S={len(basis)} P={tab.num_paths} ops fwd={fwd.count()['total']} bwd={bwd.count()['total']}")
+        print(f"[{tag}] fp64 self-check max|err|/rms: {e64}")
+        print(f"[{tag}] fp32 emulation  max|err|/rms: {e32}")
+    return emit_inc(tag, tab, basis, fold, fwd, bwd)
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--check", action="store_true")
+    ap.add_argument("--lib", default=HOST_LIB)
+    args = ap.parse_args(argv)
+    os.makedirs(OUT_DIR, exist_ok=True)
+    rc = 0
+    for tag in SPECS:
+        text = generate(tag, args.lib)
+        path = os.path.join(OUT_DIR, f"sc_gen_{tag}.inc")
+        old = open(path).read() if os.path.exists(path) else None
+        if args.check:
+            if old != text:
+                print(f"{path} is out of date", file=sys.stderr)
+                rc = 1
+        elif old != text:
+            with open(path, "w") as f:
+                f.write(text)
+            print("wrote", path)
+    return rc
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,20 +1,251 @@
-// Dispatch to the generated straight-line kernels.
+// Specialised kernels: hand-written memory / scheduling skeleton around generated
+// straight-line arithmetic (csrc/generated/*.inc, written by codegen/generate.py).
+//
+// Mapping (Algorithm 2 of arXiv 2504.10700 is independent per atom and channel):
+//   lane      = channel (64 consecutive channels per wave: the A row of a node is read as
+//               64 B per lane, a wave covers 4 KB of contiguous HBM; B/dB rows are 16 B per lane)
+//   wave      = a run of nodes of ONE element (weights folded once into registers)
+//   workgroup = 4 waves = one tile of the grouping pass x one 64-channel block; its waves
+//               add their dW' rows through LDS, so one partial row set leaves per tile
+//   grid      = tiles x channel blocks, remapped so that each XCD (own L2) gets a contiguous
+//               range of tiles: neighbouring tiles share the element's weights
+// Per node the next node's rows are requested before the current one is evaluated
+// (two register sets, ping-pong), so HBM latency hides behind ~300-800 VALU operations.
 #include "sc_spec.h"
 
 namespace sc {
+namespace {
 
-int spec_lookup(const sc_plan*) { return 0; }
-int spec_basis_size(int) { return 0; }
-int spec_waves_per_tile() { return 4; }
-void spec_fold(int, std::vector<int32_t>*, std::vector<int32_t>*, std::vector<double>*) {}
+__device__ __forceinline__ float sc_fma(float x, float y, float z) { return __builtin_fmaf(x, y, z); }
+__device__ __forceinline__ double sc_fma(double x, double y, double z) { return __builtin_fma(x, y, z); }
 
-hipError_t launch_spec_forward(const sc_plan*, int64_t, const void*, const void*, void*, const Workspace&,
-                               const LaunchShape&, hipStream_t) {
-  return hipErrorNotSupported;
+#include "generated/sc_gen_l3n3_0e1o.inc"
+#include "generated/sc_gen_l3n3_0e1o2e.inc"
+
+constexpr int kSpecWaves = 4;
+constexpr int kSpecThreads = kSpecWaves * kLanes;
+constexpr int kXcds = 8;
+
+// Row of N elements of T at p (p is aligned to the row size if that is a multiple of 16 B,
+// else only to sizeof(T)): 16-byte accesses plus a scalar tail.
+template <typename T, int N>
+struct Row {
+  static constexpr int V = 16 / sizeof(T);
+  static constexpr int kAlign = (N * sizeof(T)) % 16 == 0 ? 16 : sizeof(T);
+  typedef T Vec __attribute__((ext_vector_type(V), aligned(kAlign)));
+
+  static __device__ __forceinline__ void load(const T* __restrict__ p, T (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i + V <= N; i += V) {
+      const Vec x = *reinterpret_cast<const Vec*>(p + i);
+#pragma unroll
+      for (int k = 0; k < V; ++k) v[i + k] = x[k];
+    }
+#pragma unroll
+    for (int i = N / V * V; i < N; ++i) v[i] = p[i];
+  }
+  static __device__ __forceinline__ void store(T* __restrict__ p, const T (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i + V <= N; i += V) {
+      Vec x;
+#pragma unroll
+      for (int k = 0; k < V; ++k) x[k] = v[i + k];
+      *reinterpret_cast<Vec*>(p + i) = x;
+    }
+#pragma unroll
+    for (int i = N / V * V; i < N; ++i) p[i] = v[i];
+  }
+};
+
+// blockIdx -> logical work item such that the blocks an XCD receives (round-robin by
+// blockIdx) form one contiguous range.  gridDim.x is a multiple of kXcds.
+__device__ __forceinline__ int xcd_contiguous_block() {
+  const int per = gridDim.x / kXcds;
+  return (blockIdx.x % kXcds) * per + blockIdx.x / kXcds;
 }
-hipError_t launch_spec_backward(const sc_plan*, int64_t, const void*, const void*, const void*, void*,
-                                const Workspace&, const LaunchShape&, hipStream_t) {
-  return hipErrorNotSupported;
+
+template <typename T, typename G>
+__global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(int K, int chblocks, int n_blocks,
+                                                                    const T* __restrict__ A,
+                                                                    const T* __restrict__ W, T* __restrict__ B,
+                                                                    const int32_t* __restrict__ ntiles,
+                                                                    const TileDesc* __restrict__ tiles,
+                                                                    const int32_t* __restrict__ perm) {
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int logical = xcd_contiguous_block();
+  if (logical >= n_blocks) return;
+  const int tile = logical / chblocks, cb = logical % chblocks;
+  if (tile >= *ntiles) return;
+  const TileDesc td = tiles[tile];
+  const int j0 = td.start + td.count * wave / kSpecWaves;
+  const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
+  if (j0 >= j1) return;
+  const int ch = cb * kLanes + lane;
+  T w[G::kS];
+  G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w);
+
+  T a0[G::kNlm], a1[G::kNlm], b[G::kNLM];
+  size_t node0 = perm[j0], node1 = 0;
+  Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
+  for (int j = j0; j < j1; j += 2) {
+    if (j + 1 < j1) {
+      node1 = perm[j + 1];
+      Row<T, G::kNlm>::load(A + (node1 * K + ch) * G::kNlm, a1);
+    }
+    G::forward(a0, w, b);
+    Row<T, G::kNLM>::store(B + (node0 * K + ch) * G::kNLM, b);
+    if (j + 1 < j1) {
+      if (j + 2 < j1) {
+        node0 = perm[j + 2];
+        Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
+      }
+      G::forward(a1, w, b);
+      Row<T, G::kNLM>::store(B + (node1 * K + ch) * G::kNLM, b);
+    }
+  }
+}
+
+template <typename T, typename G>
+__global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int chblocks, int n_blocks,
+                                                                     const T* __restrict__ A,
+                                                                     const T* __restrict__ W,
+                                                                     const T* __restrict__ dB, T* __restrict__ dA,
+                                                                     T* __restrict__ partial,
+                                                                     const int32_t* __restrict__ ntiles,
+                                                                     const TileDesc* __restrict__ tiles,
+                                                                     const int32_t* __restrict__ perm) {
+  extern __shared__ unsigned char lds_raw[];
+  T* red = reinterpret_cast<T*>(lds_raw);  // [kSpecWaves][kS][64]
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int logical = xcd_contiguous_block();
+  if (logical >= n_blocks) return;  // uniform per workgroup
+  const int tile = logical / chblocks, cb = logical % chblocks;
+  if (tile >= *ntiles) return;      // uniform per workgroup
+  const TileDesc td = tiles[tile];
+  const int j0 = td.start + td.count * wave / kSpecWaves;
+  const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
+  const int ch = cb * kLanes + lane;
+  T dw[G::kS];
+#pragma unroll
+  for (int s = 0; s < G::kS; ++s) dw[s] = T(0);
+  if (j0 < j1) {
+    T w[G::kS];
+    G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w);
+    T a0[G::kNlm], a1[G::kNlm], g0[G::kNLM], g1[G::kNLM], da[G::kNlm];
+    size_t node0 = perm[j0], node1 = 0;
+    Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
+    Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
+    for (int j = j0; j < j1; j += 2) {
+      if (j + 1 < j1) {
+        node1 = perm[j + 1];
+        Row<T, G::kNlm>::load(A + (node1 * K + ch) * G::kNlm, a1);
+        Row<T, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
+      }
+      G::backward(a0, w, g0, da, dw);
+      Row<T, G::kNlm>::store(dA + (node0 * K + ch) * G::kNlm, da);
+      if (j + 1 < j1) {
+        if (j + 2 < j1) {
+          node0 = perm[j + 2];
+          Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
+          Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
+        }
+        G::backward(a1, w, g1, da, dw);
+        Row<T, G::kNlm>::store(dA + (node1 * K + ch) * G::kNlm, da);
+      }
+    }
+  }
+  // sum the waves' dW' rows in wave order and write the tile's partial rows
+#pragma unroll
+  for (int s = 0; s < G::kS; ++s) red[(wave * G::kS + s) * kLanes + lane] = dw[s];
+  __syncthreads();
+  T* out = partial + (static_cast<size_t>(tile) * chblocks + cb) * G::kS * kLanes;
+  for (int i = threadIdx.x; i < G::kS * kLanes; i += kSpecThreads) {
+    T acc = red[i];
+#pragma unroll
+    for (int v = 1; v < kSpecWaves; ++v) acc += red[v * G::kS * kLanes + i];
+    out[i] = acc;
+  }
+}
+
+template <typename G>
+bool matches(const sc_plan* plan) {
+  const sc_config& c = plan->cfg;
+  if (c.l_max != G::kLmax || c.nu_max != G::kNuMax || c.num_out != G::kNumOut) return false;
+  for (int o = 0; o < G::kNumOut; ++o)
+    if (c.out_l[o] != G::kOutL[o] || c.out_parity[o] != G::kOutParity[o]) return false;
+  return c.num_channels % kLanes == 0 && static_cast<int>(plan->table.paths.size()) == G::kP;
+}
+
+template <typename T, typename G>
+hipError_t fwd_launch(const sc_plan* plan, const void* A, const void* W, void* B, const Workspace& ws,
+                      const LaunchShape& shape, hipStream_t stream) {
+  const int n_blocks = shape.max_tiles * shape.chblocks;
+  const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
+  hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), 0, stream,
+                     plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
+                     static_cast<const T*>(W), static_cast<T*>(B), ws.ntiles, ws.tiles, ws.perm);
+  return hipGetLastError();
+}
+
+template <typename T, typename G>
+hipError_t bwd_launch(const sc_plan* plan, const void* A, const void* W, const void* dB, void* dA,
+                      const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
+  const int n_blocks = shape.max_tiles * shape.chblocks;
+  const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
+  const size_t lds = sizeof(T) * kSpecWaves * G::kS * kLanes;
+  hipLaunchKernelGGL((spec_backward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
+                     plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
+                     static_cast<const T*>(W), static_cast<const T*>(dB), static_cast<T*>(dA),
+                     static_cast<T*>(ws.partial), ws.ntiles, ws.tiles, ws.perm);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int spec_lookup(const sc_plan* plan) {
+  if (matches<Gen_l3n3_0e1o>(plan)) return 1;
+  if (matches<Gen_l3n3_0e1o2e>(plan)) return 2;
+  return 0;
+}
+
+int spec_basis_size(int id) { return id == 1 ? Gen_l3n3_0e1o::kS : id == 2 ? Gen_l3n3_0e1o2e::kS : 0; }
+
+int spec_waves_per_tile() { return kSpecWaves; }
+
+void spec_fold(int id, std::vector<int32_t>* begin, std::vector<int32_t>* src, std::vector<double>* coef) {
+  auto fill = [&](const int* b, int nb, const int* s, const double* c) {
+    begin->assign(b, b + nb);
+    src->assign(s, s + b[nb - 1]);
+    coef->assign(c, c + b[nb - 1]);
+  };
+  if (id == 1) fill(kFoldBegin_l3n3_0e1o, Gen_l3n3_0e1o::kP + 1, kFoldSrc_l3n3_0e1o, kFoldCoef_l3n3_0e1o);
+  if (id == 2) fill(kFoldBegin_l3n3_0e1o2e, Gen_l3n3_0e1o2e::kP + 1, kFoldSrc_l3n3_0e1o2e, kFoldCoef_l3n3_0e1o2e);
+}
+
+hipError_t launch_spec_forward(const sc_plan* plan, int64_t, const void* A, const void* W, void* B,
+                               const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
+  const bool f64 = plan->cfg.dtype == SC_F64;
+  if (plan->specialised == 1)
+    return f64 ? fwd_launch<double, Gen_l3n3_0e1o>(plan, A, W, B, ws, shape, stream)
+               : fwd_launch<float, Gen_l3n3_0e1o>(plan, A, W, B, ws, shape, stream);
+  if (plan->specialised == 2)
+    return f64 ? fwd_launch<double, Gen_l3n3_0e1o2e>(plan, A, W, B, ws, shape, stream)
+               : fwd_launch<float, Gen_l3n3_0e1o2e>(plan, A, W, B, ws, shape, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_spec_backward(const sc_plan* plan, int64_t, const void* A, const void* W, const void* dB,
+                                void* dA, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
+  const bool f64 = plan->cfg.dtype == SC_F64;
+  if (plan->specialised == 1)
+    return f64 ? bwd_launch<double, Gen_l3n3_0e1o>(plan, A, W, dB, dA, ws, shape, stream)
+               : bwd_launch<float, Gen_l3n3_0e1o>(plan, A, W, dB, dA, ws, shape, stream);
+  if (plan->specialised == 2)
+    return f64 ? bwd_launch<double, Gen_l3n3_0e1o2e>(plan, A, W, dB, dA, ws, shape, stream)
+               : bwd_launch<float, Gen_l3n3_0e1o2e>(plan, A, W, dB, dA, ws, shape, stream);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace sc

@@ -50,9 +50,12 @@ def full_parity(sc, wl, flags=0, mutate=None):
     dA, dW = run.backward(sc.SC_REUSE_GROUPING)
     dA_ref, dW_ref = osc.backward(T, A, z, W, dB)
     check("dA", dA, dA_ref, wl.dtype)
-    check("dW", dW, dW_ref, wl.dtype)
-    absent = np.setdiff1d(np.arange(wl.num_elements), z)
+    # dW rows of elements that do not occur must be exactly zero; the error scale (rms)
+    # is taken over the rows of the elements that do occur
+    present = np.unique(z)
+    absent = np.setdiff1d(np.arange(wl.num_elements), present)
     assert not dW[absent].any(), "dW rows of absent elements must be exactly zero"
+    check("dW", dW[present], dW_ref[present], wl.dtype)
     # backward alone (regrouping) gives identical bits
     dA2, dW2 = run.backward(0)
     assert np.array_equal(dA, dA2) and np.array_equal(dW, dW2)
