@@ -65,12 +65,19 @@ LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
   if (t > hi) t = hi;
   s.tile_nodes = static_cast<int>(t);
   s.max_tiles = static_cast<int>(n / s.tile_nodes) + plan->cfg.num_elements;
-  int64_t gw = (n + 255) / 256;  // about four 64-node chunks per grouping wave
-  gw = (gw + kGroupWavesPerWG - 1) / kGroupWavesPerWG * kGroupWavesPerWG;
-  if (gw < kGroupWavesPerWG) gw = kGroupWavesPerWG;
-  if (gw > kMaxGroupWaves) gw = kMaxGroupWaves;
-  s.group_waves = static_cast<int>(gw);
-  s.nodes_per_group_wave = static_cast<int>((n + gw - 1) / gw);
+  // Grouping: one single-workgroup launch for small batches (group_waves = 0), else three
+  // launches with about four 64-node chunks per wave, at most kMaxGroupWaves waves.
+  if (n <= 16384 && plan->cfg.num_elements <= 512) {
+    s.group_waves = 0;
+    s.nodes_per_group_wave = 0;
+  } else {
+    int64_t gw = (n + 255) / 256;
+    gw = (gw + kGroupWavesPerWG - 1) / kGroupWavesPerWG * kGroupWavesPerWG;
+    if (gw < kGroupWavesPerWG) gw = kGroupWavesPerWG;
+    if (gw > kMaxGroupWaves) gw = kMaxGroupWaves;
+    s.group_waves = static_cast<int>(gw);
+    s.nodes_per_group_wave = static_cast<int>((n + gw - 1) / gw);
+  }
   return s;
 }
 
@@ -227,6 +234,7 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   plan->gen.term_idx = reinterpret_cast<const int4*>(d + o_ti);
   plan->gen.term_coef = reinterpret_cast<const double*>(d + o_tc);
   plan->fold.S = plan->S;
+  plan->fold_nnz = static_cast<int>(fold_src.size());
   plan->fold.begin = reinterpret_cast<const int32_t*>(d + o_fb);
   plan->fold.src = reinterpret_cast<const int32_t*>(d + o_fs);
   plan->fold.coef = reinterpret_cast<const double*>(d + o_fc);

@@ -30,32 +30,53 @@ __global__ __launch_bounds__(kLanes) void finalize_direct_kernel(int P, int K, i
   if (ch < K) dW[(static_cast<size_t>(e) * P + p) * K + ch] = static_cast<T>(acc);
 }
 
-// Sparse fold (generated kernels).  One workgroup of 4 waves per (element, channel block):
-// the waves first reduce the S internal rows over the element's tiles into LDS, then
-// every external path gathers its few internal rows.
+// Sparse fold (generated kernels).  One workgroup of 8 waves per (element, channel block):
+// the fold table is staged in LDS, the waves reduce the S internal rows over the element's
+// tiles into LDS (independent loads, four in flight per row), then every external path
+// gathers its few internal rows.
+constexpr int kFinalizeWaves = 8;
+
 template <typename T>
-__global__ __launch_bounds__(4 * kLanes) void finalize_fold_kernel(FoldTables fold, int P, int K, int chblocks,
-                                                                   int max_tiles, const T* __restrict__ partial,
-                                                                   const int32_t* __restrict__ tile_off,
-                                                                   T* __restrict__ dW) {
-  extern __shared__ double red[];  // [S][64]
+__global__ __launch_bounds__(kFinalizeWaves * kLanes) void finalize_fold_kernel(
+    FoldTables fold, int nnz, int P, int K, int chblocks, int max_tiles, const T* __restrict__ partial,
+    const int32_t* __restrict__ tile_off, T* __restrict__ dW) {
+  extern __shared__ double lds_d[];
+  const int S = fold.S;
+  double* red = lds_d;                                       // [S][64]
+  double* fcoef = red + S * kLanes;                          // [nnz]
+  int32_t* fsrc = reinterpret_cast<int32_t*>(fcoef + nnz);   // [nnz]
+  int32_t* fbegin = fsrc + nnz;                              // [P+1]
   const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+  for (int i = threadIdx.x; i < nnz; i += blockDim.x) {
+    fcoef[i] = fold.coef[i];
+    fsrc[i] = fold.src[i];
+  }
+  for (int i = threadIdx.x; i <= P; i += blockDim.x) fbegin[i] = fold.begin[i];
   const int cb = blockIdx.x % chblocks;
   const int e = blockIdx.x / chblocks;
   int t0 = tile_off[e], t1 = tile_off[e + 1];
   if (t1 > max_tiles) t1 = max_tiles;
-  const int S = fold.S;
-  for (int s = wave; s < S; s += 4) {
-    double acc = 0.0;
-    for (int t = t0; t < t1; ++t)
-      acc += static_cast<double>(partial[((static_cast<size_t>(t) * chblocks + cb) * S + s) * kLanes + lane]);
-    red[s * kLanes + lane] = acc;
+  const size_t tstride = static_cast<size_t>(chblocks) * S * kLanes;
+  for (int s = wave; s < S; s += kFinalizeWaves) {
+    const T* src = partial + (static_cast<size_t>(cb) * S + s) * kLanes + lane;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    int t = t0;
+    for (; t + 4 <= t1; t += 4) {
+      const T v0 = src[(t + 0) * tstride], v1 = src[(t + 1) * tstride];
+      const T v2 = src[(t + 2) * tstride], v3 = src[(t + 3) * tstride];
+      a0 += static_cast<double>(v0);
+      a1 += static_cast<double>(v1);
+      a2 += static_cast<double>(v2);
+      a3 += static_cast<double>(v3);
+    }
+    for (; t < t1; ++t) a0 += static_cast<double>(src[t * tstride]);
+    red[s * kLanes + lane] = (a0 + a1) + (a2 + a3);
   }
   __syncthreads();
   const int ch = cb * kLanes + lane;
-  for (int p = wave; p < P; p += 4) {
+  for (int p = wave; p < P; p += kFinalizeWaves) {
     double acc = 0.0;
-    for (int i = fold.begin[p]; i < fold.begin[p + 1]; ++i) acc += fold.coef[i] * red[fold.src[i] * kLanes + lane];
+    for (int i = fbegin[p]; i < fbegin[p + 1]; ++i) acc += fcoef[i] * red[fsrc[i] * kLanes + lane];
     if (ch < K) dW[(static_cast<size_t>(e) * P + p) * K + ch] = static_cast<T>(acc);
   }
 }
@@ -70,10 +91,12 @@ hipError_t finalize_t(const sc_plan* plan, void* dW, const Workspace& ws, const 
                        shape.chblocks, shape.max_tiles, static_cast<const T*>(ws.partial), ws.tile_off,
                        static_cast<T*>(dW));
   } else {
-    const size_t lds = static_cast<size_t>(plan->fold.S) * kLanes * sizeof(double);
-    hipLaunchKernelGGL(finalize_fold_kernel<T>, dim3(Z * shape.chblocks), dim3(4 * kLanes), lds, stream, plan->fold,
-                       P, K, shape.chblocks, shape.max_tiles, static_cast<const T*>(ws.partial), ws.tile_off,
-                       static_cast<T*>(dW));
+    const int nnz = plan->fold_nnz;
+    const size_t lds = static_cast<size_t>(plan->fold.S) * kLanes * sizeof(double) + nnz * sizeof(double) +
+                       (nnz + P + 1) * sizeof(int32_t);
+    hipLaunchKernelGGL(finalize_fold_kernel<T>, dim3(Z * shape.chblocks), dim3(kFinalizeWaves * kLanes), lds, stream,
+                       plan->fold, nnz, P, K, shape.chblocks, shape.max_tiles, static_cast<const T*>(ws.partial),
+                       ws.tile_off, static_cast<T*>(dW));
   }
   return hipGetLastError();
 }

@@ -78,6 +78,7 @@ struct sc_plan {
   void* dev_blob = nullptr;
   sc::GenericTables gen{};
   sc::FoldTables fold{};
+  int fold_nnz = 0;
 };
 
 namespace sc {
