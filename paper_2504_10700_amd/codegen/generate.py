@@ -212,6 +212,18 @@ def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program) -> 
     L.append(fwd.emit("T", "    "))
     L.append("  }")
     L.append("")
+    L.append("  // dW[z,p,k] = sum_s F[s,p] * r[s]; out points at dW[z,0,k], consecutive paths are K apart.")
+    L.append("  template <typename T>")
+    L.append("  static __device__ __forceinline__ void unfold(const double (&r)[kS], T* __restrict__ out, int K) {")
+    by_p: Dict[int, List[Tuple[int, float]]] = {p: [] for p in range(P)}
+    for s, lst in enumerate(fold):
+        for p, c in lst:
+            by_p[p].append((s, c))
+    for p in range(P):
+        terms = " + ".join(f"{repr(c)} * r[{s}]" for s, c in by_p[p]) or "0.0"
+        L.append(f"    out[{p} * K] = static_cast<T>({terms});")
+    L.append("  }")
+    L.append("")
     L.append("  // da is overwritten; dw is accumulated into.")
     L.append("  template <typename T>")
     L.append("  static __device__ __forceinline__ void backward(const T (&a)[kNlm], const T (&w)[kS], const T (&g)[kNLM],")
@@ -219,21 +231,6 @@ def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program) -> 
     L.append(bwd.emit("T", "    "))
     L.append("  }")
     L.append("};")
-    L.append("")
-    # unfold CSR (rows = external paths) for the host
-    begin, src, coef = [0], [], []
-    by_p: Dict[int, List[Tuple[int, float]]] = {p: [] for p in range(P)}
-    for s, lst in enumerate(fold):
-        for p, c in lst:
-            by_p[p].append((s, c))
-    for p in range(P):
-        for s, c in by_p[p]:
-            src.append(s)
-            coef.append(c)
-        begin.append(len(src))
-    L.append(f"static const int kFoldBegin_{tag}[] = {{" + ", ".join(map(str, begin)) + "};")
-    L.append(f"static const int kFoldSrc_{tag}[] = {{" + ", ".join(map(str, src)) + "};")
-    L.append(f"static const double kFoldCoef_{tag}[] = {{" + ", ".join(repr(c) for c in coef) + "};")
     return "\n".join(L) + "\n"
 
 

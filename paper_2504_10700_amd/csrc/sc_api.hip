@@ -97,6 +97,7 @@ Workspace carve_workspace(const sc_plan* plan, int64_t n, const LaunchShape& sha
   w.perm = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
   w.tiles = static_cast<TileDesc*>(take(sizeof(TileDesc) * static_cast<size_t>(shape.max_tiles)));
   w.partial = take(elem_size(plan) * static_cast<size_t>(shape.max_tiles) * shape.chblocks * plan->S * kLanes);
+  w.reduced = static_cast<double*>(take(sizeof(double) * static_cast<size_t>(Z) * shape.chblocks * plan->S * kLanes));
   w.max_tiles = shape.max_tiles;
   w.bytes = off;
   return w;
@@ -174,7 +175,7 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   }
   plan->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
-  // one device blob: path_nu | path_col | term_begin | term_idx | term_coef | fold begin | src | coef
+  // one device blob: path_nu | path_col | term_begin | term_idx | term_coef
   std::vector<int32_t> path_nu(P), path_col(P), term_begin(P + 1, 0);
   std::vector<int4> term_idx;
   std::vector<double> term_coef;
@@ -188,9 +189,6 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
     }
   }
   term_begin[P] = static_cast<int32_t>(term_idx.size());
-  std::vector<int32_t> fold_begin, fold_src;
-  std::vector<double> fold_coef;
-  if (plan->specialised) sc::spec_fold(plan->specialised, &fold_begin, &fold_src, &fold_coef);
 
   size_t off = 0;
   auto reserve = [&](size_t bytes) {
@@ -200,19 +198,13 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   };
   const size_t o_nu = reserve(sizeof(int32_t) * P), o_col = reserve(sizeof(int32_t) * P),
                o_tb = reserve(sizeof(int32_t) * (P + 1)), o_ti = reserve(sizeof(int4) * term_idx.size()),
-               o_tc = reserve(sizeof(double) * term_coef.size()), o_fb = reserve(sizeof(int32_t) * fold_begin.size()),
-               o_fs = reserve(sizeof(int32_t) * fold_src.size()), o_fc = reserve(sizeof(double) * fold_coef.size());
+               o_tc = reserve(sizeof(double) * term_coef.size());
   std::vector<unsigned char> host(off ? off : 256, 0);
   std::memcpy(host.data() + o_nu, path_nu.data(), sizeof(int32_t) * P);
   std::memcpy(host.data() + o_col, path_col.data(), sizeof(int32_t) * P);
   std::memcpy(host.data() + o_tb, term_begin.data(), sizeof(int32_t) * (P + 1));
   std::memcpy(host.data() + o_ti, term_idx.data(), sizeof(int4) * term_idx.size());
   std::memcpy(host.data() + o_tc, term_coef.data(), sizeof(double) * term_coef.size());
-  if (!fold_begin.empty()) {
-    std::memcpy(host.data() + o_fb, fold_begin.data(), sizeof(int32_t) * fold_begin.size());
-    std::memcpy(host.data() + o_fs, fold_src.data(), sizeof(int32_t) * fold_src.size());
-    std::memcpy(host.data() + o_fc, fold_coef.data(), sizeof(double) * fold_coef.size());
-  }
   e = hipMalloc(&plan->dev_blob, host.size());
   if (e != hipSuccess) {
     delete plan;
@@ -233,11 +225,6 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   plan->gen.term_begin = reinterpret_cast<const int32_t*>(d + o_tb);
   plan->gen.term_idx = reinterpret_cast<const int4*>(d + o_ti);
   plan->gen.term_coef = reinterpret_cast<const double*>(d + o_tc);
-  plan->fold.S = plan->S;
-  plan->fold_nnz = static_cast<int>(fold_src.size());
-  plan->fold.begin = reinterpret_cast<const int32_t*>(d + o_fb);
-  plan->fold.src = reinterpret_cast<const int32_t*>(d + o_fs);
-  plan->fold.coef = reinterpret_cast<const double*>(d + o_fc);
   *out_plan = plan;
   return SC_OK;
 }
@@ -409,7 +396,8 @@ sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32
     (void)hipEventRecord(plan->ev[3], stream);
     plan->ev_used[1] = true;
   }
-  e = sc::launch_finalize(plan, dW, ws, shape, stream);
+  e = plan->specialised ? sc::launch_spec_finalize(plan, dW, ws, shape, stream)
+                        : sc::launch_finalize(plan, dW, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_backward: finalize launch");
   return SC_OK;
 }

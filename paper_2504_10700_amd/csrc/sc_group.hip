@@ -21,73 +21,84 @@ constexpr int kFusedWaves = 16;
 constexpr int kFusedThreads = kFusedWaves * kLanes;
 
 // Stable scatter of one 64-node chunk: lane holds element e (valid or not); cursor[e *
-// cursor_stride] is this wave's next free position of element e (LDS).
-__device__ __forceinline__ void scatter_chunk(int e, bool valid, int node, int lane, int32_t* cursor,
+// cursor_stride] is this wave's next free position of element e (LDS).  The lanes that
+// hold the same element are found bit by bit (one ballot per bit of the element index),
+// which costs the same whatever the number of distinct elements in the chunk.
+__device__ __forceinline__ void scatter_chunk(int e, bool valid, int node, int lane, int z_bits, int32_t* cursor,
                                               int cursor_stride, int32_t* __restrict__ perm) {
   const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  unsigned long long todo = __ballot(valid);
-  int rank = 0, leader = 0, group = 0;
-  while (todo) {  // one round per distinct element in the chunk
-    const int ld = __ffsll(static_cast<long long>(todo)) - 1;
-    const int el = __shfl(e, ld);
-    const unsigned long long same = __ballot(valid && e == el);
-    if (valid && e == el) {
-      rank = __popcll(same & lt_mask);
-      leader = ld;
-      group = __popcll(same);
-    }
-    todo &= ~same;
+  unsigned long long same = __ballot(valid);
+  for (int b = 0; b < z_bits; ++b) {
+    const bool bit = (e >> b) & 1;
+    const unsigned long long m = __ballot(bit);
+    same &= bit ? m : ~m;
   }
+  // `same` = valid lanes holding this lane's element (meaningless on invalid lanes)
+  const int rank = __popcll(same & lt_mask);
+  const int group = __popcll(same);
+  const int leader = valid ? __ffsll(static_cast<long long>(same)) - 1 : lane;
   int base = 0;
   if (valid && lane == leader) base = atomicAdd(&cursor[e * cursor_stride], group);
   base = __shfl(base, leader);
   if (valid) perm[base + rank] = node;
 }
 
-// Exclusive scan of v[0..n), n <= blockDim.x * 1, one entry per thread, in LDS, in place.
-// Returns the total to every thread.  scratch: blockDim.x ints of LDS.
-__device__ int block_exclusive_scan(int32_t* v, int n, int32_t* scratch) {
-  const int t = threadIdx.x, nt = blockDim.x;
-  const int mine = (t < n) ? v[t] : 0;
-  scratch[t] = mine;
-  __syncthreads();
-  for (int d = 1; d < nt; d <<= 1) {
-    const int add = (t >= d) ? scratch[t - d] : 0;
-    __syncthreads();
-    scratch[t] += add;
-    __syncthreads();
+// Exclusive scan of v[0..n) (LDS, n <= 64 * 16) in place by ONE wave; returns the total to
+// every lane of that wave.
+__device__ int wave_exclusive_scan(int32_t* v, int n, int lane) {
+  constexpr int kMaxPer = SC_MAX_ELEMENTS / kLanes;
+  const int per = (n + kLanes - 1) / kLanes;
+  int c[kMaxPer], local = 0;
+#pragma unroll
+  for (int k = 0; k < kMaxPer; ++k) {
+    const int i = lane * per + k;
+    c[k] = (k < per && i < n) ? v[i] : 0;
+    local += c[k];
   }
-  const int total = scratch[nt - 1];
-  if (t < n) v[t] = scratch[t] - mine;
-  __syncthreads();
-  return total;
+  int incl = local;
+#pragma unroll
+  for (int d = 1; d < kLanes; d <<= 1) {
+    const int up = __shfl_up(incl, d);
+    if (lane >= d) incl += up;
+  }
+  int run = incl - local;
+#pragma unroll
+  for (int k = 0; k < kMaxPer; ++k) {
+    const int i = lane * per + k;
+    if (k < per && i < n) v[i] = run;
+    run += c[k];
+  }
+  return __shfl(incl, kLanes - 1);
 }
 
 // Given total[e] (nodes per element, LDS) writes seg/til (LDS, Z+1 entries), the global
 // copies and the tile table.  All threads of the block call it.
 __device__ void offsets_and_tiles(int Z, int tile_nodes, int max_tiles, const int32_t* total, int32_t* seg,
-                                  int32_t* til, int32_t* scratch, int32_t* __restrict__ seg_off,
-                                  int32_t* __restrict__ tile_off, int32_t* __restrict__ ntiles_out,
-                                  TileDesc* __restrict__ tiles) {
+                                  int32_t* til, int32_t* __restrict__ seg_off, int32_t* __restrict__ tile_off,
+                                  int32_t* __restrict__ ntiles_out, TileDesc* __restrict__ tiles) {
   const int t = threadIdx.x, nt = blockDim.x;
   for (int e = t; e < Z; e += nt) {
     seg[e] = total[e];
     til[e] = (total[e] + tile_nodes - 1) / tile_nodes;
   }
   __syncthreads();
-  const int n_valid = block_exclusive_scan(seg, Z, scratch);
-  const int n_tiles = block_exclusive_scan(til, Z, scratch);
-  if (t == 0) {
-    seg[Z] = n_valid;
-    til[Z] = n_tiles;
-    *ntiles_out = (n_tiles < max_tiles) ? n_tiles : max_tiles;
+  if (t < kLanes) {  // wave 0
+    const int n_valid = wave_exclusive_scan(seg, Z, t);
+    const int n_tiles = wave_exclusive_scan(til, Z, t);
+    if (t == 0) {
+      seg[Z] = n_valid;
+      til[Z] = n_tiles;
+      *ntiles_out = (n_tiles < max_tiles) ? n_tiles : max_tiles;
+    }
   }
   __syncthreads();
+  const int n_tiles = til[Z];
   for (int e = t; e <= Z; e += nt) {
     seg_off[e] = seg[e];
     tile_off[e] = til[e];
   }
   // tile table: element e owns tiles [til[e], til[e+1]); its nodes are split evenly
+  // (the first `rem` tiles take one node more)
   for (int i = t; i < n_tiles && i < max_tiles; i += nt) {
     int lo = 0, hi = Z;  // last e with til[e] <= i (empty elements share an offset with the next one)
     while (hi - lo > 1) {
@@ -97,10 +108,9 @@ __device__ void offsets_and_tiles(int Z, int tile_nodes, int max_tiles, const in
     const int e = lo;
     const int nt_e = til[e + 1] - til[e];
     const int j = i - til[e];
-    const int c = total[e];
-    const int s0 = static_cast<int>(static_cast<long long>(c) * j / nt_e);
-    const int s1 = static_cast<int>(static_cast<long long>(c) * (j + 1) / nt_e);
-    tiles[i] = TileDesc{e, seg[e] + s0, s1 - s0, 0};
+    const int base = total[e] / nt_e, rem = total[e] % nt_e;
+    const int s0 = j * base + (j < rem ? j : rem);
+    tiles[i] = TileDesc{e, seg[e] + s0, base + (j < rem ? 1 : 0), 0};
   }
 }
 
@@ -117,7 +127,6 @@ __global__ __launch_bounds__(kFusedThreads) void group_fused_kernel(const int32_
   int32_t* total = counts + Z * kFusedWaves;    // [Z]
   int32_t* seg = total + Z;                     // [Z+1]
   int32_t* til = seg + Z + 1;                   // [Z+1]
-  int32_t* scratch = til + Z + 1;               // [kFusedThreads]
   const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
   for (int i = threadIdx.x; i < Z * kFusedWaves; i += kFusedThreads) counts[i] = 0;
   __syncthreads();
@@ -139,15 +148,16 @@ __global__ __launch_bounds__(kFusedThreads) void group_fused_kernel(const int32_
     total[e] = run;
   }
   __syncthreads();
-  offsets_and_tiles(Z, tile_nodes, max_tiles, total, seg, til, scratch, seg_off, tile_off, ntiles_out, tiles);
+  offsets_and_tiles(Z, tile_nodes, max_tiles, total, seg, til, seg_off, tile_off, ntiles_out, tiles);
   __syncthreads();
   for (int i = threadIdx.x; i < Z * kFusedWaves; i += kFusedThreads) counts[i] += seg[i / kFusedWaves];
   __syncthreads();
+  const int z_bits = 32 - __builtin_clz(Z);  // bits needed for 0..Z-1 (one spare when Z is a power of two)
   for (int c0 = lo; c0 < hi; c0 += kLanes) {  // wave-uniform trip count
     const int i = c0 + lane;
     int e = -1;
     if (i < hi) e = z[i];
-    scatter_chunk(e, e >= 0 && e < Z, i, lane, counts + wave, kFusedWaves, perm);
+    scatter_chunk(e, e >= 0 && e < Z, i, lane, z_bits, counts + wave, kFusedWaves, perm);
   }
 }
 
@@ -181,7 +191,6 @@ __global__ __launch_bounds__(kFusedThreads) void group_scan_kernel(int Z, int W,
   __shared__ int32_t total[SC_MAX_ELEMENTS];
   __shared__ int32_t seg[SC_MAX_ELEMENTS + 1];
   __shared__ int32_t til[SC_MAX_ELEMENTS + 1];
-  __shared__ int32_t scratch[kFusedThreads];
   const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
   constexpr int kPer = kMaxGroupWaves / kLanes;
   for (int e = wave; e < Z; e += kFusedWaves) {
@@ -209,7 +218,7 @@ __global__ __launch_bounds__(kFusedThreads) void group_scan_kernel(int Z, int W,
     if (lane == kLanes - 1) total[e] = incl;
   }
   __syncthreads();
-  offsets_and_tiles(Z, tile_nodes, max_tiles, total, seg, til, scratch, seg_off, tile_off, ntiles_out, tiles);
+  offsets_and_tiles(Z, tile_nodes, max_tiles, total, seg, til, seg_off, tile_off, ntiles_out, tiles);
 }
 
 __global__ __launch_bounds__(kGroupThreads) void group_scatter_kernel(const int32_t* __restrict__ z, int n, int Z,
@@ -225,11 +234,12 @@ __global__ __launch_bounds__(kGroupThreads) void group_scatter_kernel(const int3
   __syncthreads();
   const long long lo = static_cast<long long>(gw) * nodes_per_wave;
   const long long hi = (lo + nodes_per_wave < n) ? lo + nodes_per_wave : n;
+  const int z_bits = 32 - __builtin_clz(Z);
   for (long long c0 = lo; c0 < hi; c0 += kLanes) {  // wave-uniform trip count
     const long long i = c0 + lane;
     int e = -1;
     if (i < hi) e = z[i];
-    scatter_chunk(e, e >= 0 && e < Z, static_cast<int>(i), lane, cursor, 1, perm);
+    scatter_chunk(e, e >= 0 && e < Z, static_cast<int>(i), lane, z_bits, cursor, 1, perm);
   }
 }
 
@@ -239,7 +249,7 @@ hipError_t launch_grouping(const sc_plan* plan, int64_t n, const int32_t* z, con
                            const LaunchShape& shape, hipStream_t stream) {
   const int Z = plan->cfg.num_elements;
   if (shape.group_waves == 0) {  // single launch
-    const size_t lds = sizeof(int32_t) * (static_cast<size_t>(Z) * kFusedWaves + 3 * Z + 2 + kFusedThreads);
+    const size_t lds = sizeof(int32_t) * (static_cast<size_t>(Z) * kFusedWaves + 3 * Z + 2);
     hipLaunchKernelGGL(group_fused_kernel, dim3(1), dim3(kFusedThreads), lds, stream, z, static_cast<int>(n), Z,
                        shape.tile_nodes, shape.max_tiles, ws.seg_off, ws.tile_off, ws.ntiles, ws.tiles, ws.perm);
     return hipGetLastError();

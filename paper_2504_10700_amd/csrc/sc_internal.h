@@ -30,6 +30,7 @@ struct Workspace {
   int32_t* perm;       // [N] node indices grouped by element (stable)
   TileDesc* tiles;     // [max_tiles]
   void* partial;       // [max_tiles][chblocks][S][64] per-tile dW contributions
+  double* reduced;     // [Z][chblocks][S][64] per-element sums of the internal rows
   int32_t max_tiles;
   size_t bytes;
 };
@@ -42,15 +43,6 @@ struct GenericTables {
   const int32_t* term_begin;  // [P+1]
   const int4* term_idx;       // [n_terms] (M, i1, i2, i3)
   const double* term_coef;    // [n_terms]
-};
-
-// dW' -> dW unfold (specialised kernels work in a reduced path basis): for
-// external path p: dW[z,p,k] = sum_{e in [begin[p],begin[p+1])} coef[e] * dW'[z, src[e], k]
-struct FoldTables {
-  int32_t S;                  // internal basis size (== num_paths and identity when generic)
-  const int32_t* begin;       // [P+1]
-  const int32_t* src;         // [nnz]
-  const double* coef;         // [nnz]
 };
 
 struct LaunchShape {
@@ -77,8 +69,6 @@ struct sc_plan {
   // device copies
   void* dev_blob = nullptr;
   sc::GenericTables gen{};
-  sc::FoldTables fold{};
-  int fold_nnz = 0;
 };
 
 namespace sc {

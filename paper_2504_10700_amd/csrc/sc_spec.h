@@ -10,12 +10,14 @@ int spec_lookup(const sc_plan* plan);
 int spec_basis_size(int id);
 // Waves per workgroup (= per tile) of the generated kernels.
 int spec_waves_per_tile();
-// CSR of the unfold dW[p] = sum coef * dW'[src], rows = external paths.
-void spec_fold(int id, std::vector<int32_t>* begin, std::vector<int32_t>* src, std::vector<double>* coef);
 
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const void* W, void* B,
                                const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
 hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,
                                 void* dA, const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
+
+// dW reduction over the tiles of every element and unfold to the external paths.
+hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
+                                hipStream_t stream);
 
 }  // namespace sc

@@ -169,6 +169,64 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
   }
 }
 
+// Second stage of the dW reduction, two small launches (device-scope fences, which a
+// single-launch "last wave finishes the job" scheme needs, flush the per-XCD L2s and cost
+// far more than a launch on this chip).
+// (1) One wave per (element, channel block, internal row): sums its row over the element's
+//     tiles in tile order (sixteen independent loads in flight) into reduced[e][cb][s][lane]
+//     in fp64.  Elements without nodes own no tiles and get zeros.
+// (2) One wave per (element, channel block): maps the S reduced rows to the P external
+//     paths with the generated unfold.
+// Every sum has a fixed order: results are bitwise reproducible.
+template <typename T, typename G>
+__global__ __launch_bounds__(kLanes) void spec_reduce_kernel(int chblocks, int max_tiles,
+                                                             const T* __restrict__ partial,
+                                                             const int32_t* __restrict__ tile_off,
+                                                             double* __restrict__ reduced) {
+  constexpr int S = G::kS;
+  const int lane = threadIdx.x;
+  const int s = blockIdx.x % S;
+  const int cb = (blockIdx.x / S) % chblocks;
+  const int e = blockIdx.x / (S * chblocks);
+  int t0 = tile_off[e], t1 = tile_off[e + 1];
+  if (t1 > max_tiles) t1 = max_tiles;
+  const size_t tstride = static_cast<size_t>(chblocks) * S * kLanes;
+  const T* src = partial + (static_cast<size_t>(cb) * S + s) * kLanes + lane;
+  constexpr int U = 16;
+  double a[U];
+#pragma unroll
+  for (int k = 0; k < U; ++k) a[k] = 0.0;
+  int t = t0;
+  for (; t + U <= t1; t += U) {
+    T v[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) v[k] = src[(t + k) * tstride];
+#pragma unroll
+    for (int k = 0; k < U; ++k) a[k] += static_cast<double>(v[k]);
+  }
+  for (; t < t1; ++t) a[0] += static_cast<double>(src[t * tstride]);
+#pragma unroll
+  for (int w = U / 2; w >= 1; w /= 2)
+#pragma unroll
+    for (int k = 0; k < w; ++k) a[k] += a[k + w];
+  reduced[((static_cast<size_t>(e) * chblocks + cb) * S + s) * kLanes + lane] = a[0];
+}
+
+template <typename T, typename G>
+__global__ __launch_bounds__(kLanes) void spec_unfold_kernel(int K, int chblocks,
+                                                             const double* __restrict__ reduced,
+                                                             T* __restrict__ dW) {
+  constexpr int S = G::kS;
+  const int lane = threadIdx.x;
+  const int cb = blockIdx.x % chblocks;
+  const int e = blockIdx.x / chblocks;
+  const double* mine = reduced + (static_cast<size_t>(e) * chblocks + cb) * S * kLanes;
+  double r[S];
+#pragma unroll
+  for (int q = 0; q < S; ++q) r[q] = mine[q * kLanes + lane];
+  G::unfold(r, dW + static_cast<size_t>(e) * G::kP * K + cb * kLanes + lane, K);
+}
+
 template <typename G>
 bool matches(const sc_plan* plan) {
   const sc_config& c = plan->cfg;
@@ -202,6 +260,17 @@ hipError_t bwd_launch(const sc_plan* plan, const void* A, const void* W, const v
   return hipGetLastError();
 }
 
+template <typename T, typename G>
+hipError_t finalize_launch(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
+                           hipStream_t stream) {
+  const int Z = plan->cfg.num_elements;
+  hipLaunchKernelGGL((spec_reduce_kernel<T, G>), dim3(Z * shape.chblocks * G::kS), dim3(kLanes), 0, stream,
+                     shape.chblocks, shape.max_tiles, static_cast<const T*>(ws.partial), ws.tile_off, ws.reduced);
+  hipLaunchKernelGGL((spec_unfold_kernel<T, G>), dim3(Z * shape.chblocks), dim3(kLanes), 0, stream,
+                     plan->cfg.num_channels, shape.chblocks, ws.reduced, static_cast<T*>(dW));
+  return hipGetLastError();
+}
+
 }  // namespace
 
 int spec_lookup(const sc_plan* plan) {
@@ -213,16 +282,6 @@ int spec_lookup(const sc_plan* plan) {
 int spec_basis_size(int id) { return id == 1 ? Gen_l3n3_0e1o::kS : id == 2 ? Gen_l3n3_0e1o2e::kS : 0; }
 
 int spec_waves_per_tile() { return kSpecWaves; }
-
-void spec_fold(int id, std::vector<int32_t>* begin, std::vector<int32_t>* src, std::vector<double>* coef) {
-  auto fill = [&](const int* b, int nb, const int* s, const double* c) {
-    begin->assign(b, b + nb);
-    src->assign(s, s + b[nb - 1]);
-    coef->assign(c, c + b[nb - 1]);
-  };
-  if (id == 1) fill(kFoldBegin_l3n3_0e1o, Gen_l3n3_0e1o::kP + 1, kFoldSrc_l3n3_0e1o, kFoldCoef_l3n3_0e1o);
-  if (id == 2) fill(kFoldBegin_l3n3_0e1o2e, Gen_l3n3_0e1o2e::kP + 1, kFoldSrc_l3n3_0e1o2e, kFoldCoef_l3n3_0e1o2e);
-}
 
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t, const void* A, const void* W, void* B,
                                const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
@@ -245,6 +304,18 @@ hipError_t launch_spec_backward(const sc_plan* plan, int64_t, const void* A, con
   if (plan->specialised == 2)
     return f64 ? bwd_launch<double, Gen_l3n3_0e1o2e>(plan, A, W, dB, dA, ws, shape, stream)
                : bwd_launch<float, Gen_l3n3_0e1o2e>(plan, A, W, dB, dA, ws, shape, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
+                                hipStream_t stream) {
+  const bool f64 = plan->cfg.dtype == SC_F64;
+  if (plan->specialised == 1)
+    return f64 ? finalize_launch<double, Gen_l3n3_0e1o>(plan, dW, ws, shape, stream)
+               : finalize_launch<float, Gen_l3n3_0e1o>(plan, dW, ws, shape, stream);
+  if (plan->specialised == 2)
+    return f64 ? finalize_launch<double, Gen_l3n3_0e1o2e>(plan, dW, ws, shape, stream)
+               : finalize_launch<float, Gen_l3n3_0e1o2e>(plan, dW, ws, shape, stream);
   return hipErrorInvalidValue;
 }
 
