@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--workload", default="training_step")
     ap.add_argument("--cpu-sample", type=int, default=1024, help="nodes the oracle is timed on (0 = skip)")
     ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
+    ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -79,7 +80,7 @@ def main():
     elem = 4 if wl.dtype == "f32" else 8
     plan = sc.sc_plan_create(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps,
                              sc.SC_F32 if wl.dtype == "f32" else sc.SC_F64, 0,
-                             sc.SC_PLAN_FORCE_GENERIC if args.generic else 0)
+                             sc.SC_PLAN_FORCE_GENERIC if args.generic else 0, args.tile_nodes)
     info = sc.sc_plan_info(plan)
     paths = sc.sc_plan_paths(plan)
     inp = workloads.make_inputs(wl, paths)
@@ -151,7 +152,7 @@ def main():
                                + "+".join(f"{L}{'e' if p > 0 else 'o'}" for L, p in wl.out_irreps)
                                + (", forward+backward" if wl.backward else ", forward only"),
                    "num_paths": int(info.num_paths), "kernel": "generated" if info.specialised else "table-driven",
-                   "buffer_sets_rotated": n_sets},
+                   "buffer_sets_rotated": n_sets, "tile_nodes": args.tile_nodes},
         "step_hbm_fraction": value * (step_bytes / N) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel_ms": k_ms,

@@ -90,6 +90,8 @@ typedef struct {
   int32_t dtype;                  /* sc_dtype of A, W, B, dB, dA, dW                                 */
   int32_t device;                 /* HIP device ordinal (ignored with SC_PLAN_HOST_ONLY)             */
   uint32_t flags;                 /* SC_PLAN_*                                                       */
+  int32_t tile_nodes;             /* tuning: nodes per tile of the grouping pass; 0 = chosen by the
+                                     library from the batch size and the chip's compute-unit count  */
 } sc_config;
 
 typedef struct {

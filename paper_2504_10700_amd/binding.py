@@ -18,7 +18,7 @@ import numpy as np
 import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsc_mi355x.so")
+LIB_PATH = os.environ.get("SC_LIB_PATH", os.path.join(_HERE, "libsc_mi355x.so"))  # override: development only
 
 SC_OK = 0
 SC_ERR_INVALID_ARG, SC_ERR_UNSUPPORTED, SC_ERR_WORKSPACE, SC_ERR_HIP, SC_ERR_ALLOC = 1, 2, 3, 4, 5
@@ -36,7 +36,7 @@ class sc_config(C.Structure):
     _fields_ = [("struct_size", C.c_int32), ("num_channels", C.c_int32), ("l_max", C.c_int32),
                 ("nu_max", C.c_int32), ("num_elements", C.c_int32), ("num_out", C.c_int32),
                 ("out_l", C.c_int32 * SC_MAX_OUT), ("out_parity", C.c_int32 * SC_MAX_OUT),
-                ("dtype", C.c_int32), ("device", C.c_int32), ("flags", C.c_uint32)]
+                ("dtype", C.c_int32), ("device", C.c_int32), ("flags", C.c_uint32), ("tile_nodes", C.c_int32)]
 
 
 class sc_info(C.Structure):
@@ -119,14 +119,14 @@ def sc_last_error() -> str:
 
 def sc_plan_create(num_channels: int, l_max: int, nu_max: int, num_elements: int,
                    out_irreps: Sequence[Tuple[int, int]], dtype: int = SC_F32, device: int = 0,
-                   flags: int = 0) -> Plan:
+                   flags: int = 0, tile_nodes: int = 0) -> Plan:
     cfg = sc_config()
     cfg.struct_size = C.sizeof(sc_config)
     cfg.num_channels, cfg.l_max, cfg.nu_max, cfg.num_elements = num_channels, l_max, nu_max, num_elements
     cfg.num_out = len(out_irreps)
     for i, (L, p) in enumerate(out_irreps[:SC_MAX_OUT]):
         cfg.out_l[i], cfg.out_parity[i] = L, p
-    cfg.dtype, cfg.device, cfg.flags = dtype, device, flags
+    cfg.dtype, cfg.device, cfg.flags, cfg.tile_nodes = dtype, device, flags, tile_nodes
     h = C.c_void_p()
     _check(lib.sc_plan_create(C.byref(cfg), C.byref(h)))
     return Plan(h.value, cfg)

@@ -24,7 +24,7 @@ class _Config(C.Structure):
     _fields_ = [("struct_size", C.c_int32), ("num_channels", C.c_int32), ("l_max", C.c_int32),
                 ("nu_max", C.c_int32), ("num_elements", C.c_int32), ("num_out", C.c_int32),
                 ("out_l", C.c_int32 * SC_MAX_OUT), ("out_parity", C.c_int32 * SC_MAX_OUT),
-                ("dtype", C.c_int32), ("device", C.c_int32), ("flags", C.c_uint32)]
+                ("dtype", C.c_int32), ("device", C.c_int32), ("flags", C.c_uint32), ("tile_nodes", C.c_int32)]
 
 
 class Tables:

@@ -54,20 +54,22 @@ namespace sc {
 LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
   LaunchShape s{};
   s.chblocks = (plan->cfg.num_channels + kLanes - 1) / kLanes;
-  // Tiles are sized so that one wave of tiles fills every SIMD of the chip about
-  // twice over for small batches and stay bounded for large ones (the per-tile dW
-  // rows cost memory traffic inversely proportional to the tile size).
+  // Tiles are sized for about six (tile x channel block) workgroups per compute unit on
+  // small batches - measured best on MI355X between 3 and 12 - and stay bounded for large
+  // ones (the per-tile dW rows cost memory traffic inversely proportional to the tile size).
   const int waves_per_tile = plan->specialised ? spec_waves_per_tile() : 1;
-  const int64_t slots = static_cast<int64_t>(plan->num_cus) * 4 * 2 / waves_per_tile;
-  int64_t t = (n * s.chblocks + slots - 1) / (slots > 0 ? slots : 1);
+  const int64_t target_wgs = static_cast<int64_t>(plan->num_cus) * (plan->specialised ? 6 : 8);
+  // expected tiles ~ n / t + (half a tile of rounding per element that occurs)
+  int64_t t = (n * s.chblocks + target_wgs - 1) / target_wgs;
   const int64_t lo = 4 * waves_per_tile, hi = 32 * waves_per_tile;
   if (t < lo) t = lo;
   if (t > hi) t = hi;
+  if (plan->cfg.tile_nodes > 0) t = plan->cfg.tile_nodes;
   s.tile_nodes = static_cast<int>(t);
   s.max_tiles = static_cast<int>(n / s.tile_nodes) + plan->cfg.num_elements;
   // Grouping: one single-workgroup launch for small batches (group_waves = 0), else three
   // launches with about four 64-node chunks per wave, at most kMaxGroupWaves waves.
-  if (n <= 16384 && plan->cfg.num_elements <= 512) {
+  if (n <= 16384 && plan->cfg.num_elements <= 512) {  // 16 waves x 16 chunks x 64 nodes
     s.group_waves = 0;
     s.nodes_per_group_wave = 0;
   } else {
@@ -124,6 +126,8 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   if (cfg->struct_size != static_cast<int32_t>(sizeof(sc_config)))
     return fail(SC_ERR_INVALID_ARG, "sc_plan_create: struct_size does not match this library's sc_config");
   if (cfg->num_channels < 1) return fail(SC_ERR_INVALID_ARG, "sc_plan_create: num_channels < 1");
+  if (cfg->tile_nodes < 0 || cfg->tile_nodes > 65536)
+    return fail(SC_ERR_INVALID_ARG, "sc_plan_create: tile_nodes outside 0..65536");
   if (cfg->dtype != SC_F32 && cfg->dtype != SC_F64) return fail(SC_ERR_INVALID_ARG, "sc_plan_create: bad dtype");
   if (cfg->l_max < 0 || cfg->l_max > SC_MAX_L) return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: l_max outside 0..3");
   if (cfg->nu_max < 1 || cfg->nu_max > SC_MAX_NU)

@@ -19,6 +19,8 @@ namespace {
 constexpr int kGroupThreads = kGroupWavesPerWG * kLanes;
 constexpr int kFusedWaves = 16;
 constexpr int kFusedThreads = kFusedWaves * kLanes;
+constexpr int kFusedChunks = 16;   // 64-node chunks per wave of the single-launch kernel
+constexpr int kFusedMaxNodes = kFusedWaves * kFusedChunks * kLanes;
 
 // Stable scatter of one 64-node chunk: lane holds element e (valid or not); cursor[e *
 // cursor_stride] is this wave's next free position of element e (LDS).  The lanes that
@@ -112,6 +114,8 @@ __device__ void offsets_and_tiles(int Z, int tile_nodes, int max_tiles, const in
     const int s0 = j * base + (j < rem ? j : rem);
     tiles[i] = TileDesc{e, seg[e] + s0, base + (j < rem ? 1 : 0), 0};
   }
+  // unused descriptors say "empty": the main kernels need no separate tile count
+  for (int i = n_tiles + t; i < max_tiles; i += nt) tiles[i] = TileDesc{0, 0, 0, 0};
 }
 
 // ---------------------------------------------------------------- one launch (small batches)
@@ -130,13 +134,19 @@ __global__ __launch_bounds__(kFusedThreads) void group_fused_kernel(const int32_
   const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
   for (int i = threadIdx.x; i < Z * kFusedWaves; i += kFusedThreads) counts[i] = 0;
   __syncthreads();
+  // every wave keeps its slice of z in registers (at most kFusedChunks 64-node chunks)
   const int per_wave = ((n + kFusedWaves - 1) / kFusedWaves + kLanes - 1) / kLanes * kLanes;
   const int lo = wave * per_wave;
   const int hi = (lo + per_wave < n) ? lo + per_wave : n;
-  for (int i = lo + lane; i < hi; i += kLanes) {
-    const int e = z[i];
-    if (e >= 0 && e < Z) atomicAdd(&counts[e * kFusedWaves + wave], 1);
+  int zs[kFusedChunks];
+#pragma unroll
+  for (int c = 0; c < kFusedChunks; ++c) {
+    const int i = lo + c * kLanes + lane;
+    zs[c] = (i < hi) ? z[i] : -1;
   }
+#pragma unroll
+  for (int c = 0; c < kFusedChunks; ++c)
+    if (zs[c] >= 0 && zs[c] < Z) atomicAdd(&counts[zs[c] * kFusedWaves + wave], 1);
   __syncthreads();
   for (int e = threadIdx.x; e < Z; e += kFusedThreads) {
     int run = 0;
@@ -153,11 +163,11 @@ __global__ __launch_bounds__(kFusedThreads) void group_fused_kernel(const int32_
   for (int i = threadIdx.x; i < Z * kFusedWaves; i += kFusedThreads) counts[i] += seg[i / kFusedWaves];
   __syncthreads();
   const int z_bits = 32 - __builtin_clz(Z);  // bits needed for 0..Z-1 (one spare when Z is a power of two)
-  for (int c0 = lo; c0 < hi; c0 += kLanes) {  // wave-uniform trip count
-    const int i = c0 + lane;
-    int e = -1;
-    if (i < hi) e = z[i];
-    scatter_chunk(e, e >= 0 && e < Z, i, lane, z_bits, counts + wave, kFusedWaves, perm);
+#pragma unroll
+  for (int c = 0; c < kFusedChunks; ++c) {
+    if (lo + c * kLanes >= hi) break;  // wave-uniform
+    const int e = zs[c];
+    scatter_chunk(e, e >= 0 && e < Z, lo + c * kLanes + lane, lane, z_bits, counts + wave, kFusedWaves, perm);
   }
 }
 

@@ -68,7 +68,6 @@ template <typename T, typename G>
 __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(int K, int chblocks, int n_blocks,
                                                                     const T* __restrict__ A,
                                                                     const T* __restrict__ W, T* __restrict__ B,
-                                                                    const int32_t* __restrict__ ntiles,
                                                                     const TileDesc* __restrict__ tiles,
                                                                     const int32_t* __restrict__ perm) {
   const int lane = threadIdx.x & (kLanes - 1);
@@ -76,11 +75,10 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(int K, int c
   const int logical = xcd_contiguous_block();
   if (logical >= n_blocks) return;
   const int tile = logical / chblocks, cb = logical % chblocks;
-  if (tile >= *ntiles) return;
   const TileDesc td = tiles[tile];
   const int j0 = td.start + td.count * wave / kSpecWaves;
   const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
-  if (j0 >= j1) return;
+  if (j0 >= j1) return;  // also covers the unused descriptors (count 0)
   const int ch = cb * kLanes + lane;
   T w[G::kS];
   G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w);
@@ -112,7 +110,6 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
                                                                      const T* __restrict__ W,
                                                                      const T* __restrict__ dB, T* __restrict__ dA,
                                                                      T* __restrict__ partial,
-                                                                     const int32_t* __restrict__ ntiles,
                                                                      const TileDesc* __restrict__ tiles,
                                                                      const int32_t* __restrict__ perm) {
   extern __shared__ unsigned char lds_raw[];
@@ -122,8 +119,8 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
   const int logical = xcd_contiguous_block();
   if (logical >= n_blocks) return;  // uniform per workgroup
   const int tile = logical / chblocks, cb = logical % chblocks;
-  if (tile >= *ntiles) return;      // uniform per workgroup
   const TileDesc td = tiles[tile];
+  if (td.count == 0) return;        // unused descriptor; uniform per workgroup
   const int j0 = td.start + td.count * wave / kSpecWaves;
   const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
   const int ch = cb * kLanes + lane;
@@ -243,7 +240,7 @@ hipError_t fwd_launch(const sc_plan* plan, const void* A, const void* W, void* B
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
   hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), 0, stream,
                      plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
-                     static_cast<const T*>(W), static_cast<T*>(B), ws.ntiles, ws.tiles, ws.perm);
+                     static_cast<const T*>(W), static_cast<T*>(B), ws.tiles, ws.perm);
   return hipGetLastError();
 }
 
@@ -256,7 +253,7 @@ hipError_t bwd_launch(const sc_plan* plan, const void* A, const void* W, const v
   hipLaunchKernelGGL((spec_backward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
                      plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
                      static_cast<const T*>(W), static_cast<const T*>(dB), static_cast<T*>(dA),
-                     static_cast<T*>(ws.partial), ws.ntiles, ws.tiles, ws.perm);
+                     static_cast<T*>(ws.partial), ws.tiles, ws.perm);
   return hipGetLastError();
 }
 
