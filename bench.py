@@ -142,6 +142,14 @@ def main():
     achieved = k_bytes / (k_ms * 1e-3) / 1e9
     step_bytes = fwd_bytes + (bwd_bytes if wl.backward else 0)
 
+    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath) and wl.backward and info.specialised and args.tile_nodes == 0:
+        ent = json.load(open(tpath)).get(wl.name)
+        if ent:
+            traffic = 1024.0 * (ent["fetch_kib"] * ent["fetch_scale"] + ent["write_kib"] * ent["write_scale"])
+
     out = {
         "metric": "atoms/sec symmetric-contraction fwd+bwd (128ch, l<=3, nu=3); % HBM peak",
         "value": value, "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -155,7 +163,7 @@ def main():
                    "buffer_sets_rotated": n_sets, "tile_nodes": args.tile_nodes},
         "step_hbm_fraction": value * (step_bytes / N) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel_ms": k_ms,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel_ms": k_ms,
                      "forward_kernel_ms": fwd_mean, "algorithmic_bytes_per_launch": k_bytes},
     }
     if args.cpu_sample > 0:
