@@ -56,7 +56,37 @@ def candidates(tab: Tables, out: int, ms: Tuple[int, ...]) -> List[InternalPath]
     return res
 
 
-def eval_internal(tab: Tables, s: InternalPath, a: np.ndarray) -> np.ndarray:
+class ScaledCG:
+    """The library's coupling tensors, each divided by its most frequent |coefficient|.
+
+    The internal basis polynomials may carry any scale (the fold matrix absorbs it), so every
+    coupling tensor is rescaled to make as many of its entries as possible exactly +-1: sums
+    of such terms need no multiplication by a constant.
+    """
+
+    def __init__(self, tab: Tables):
+        self.tab = tab
+        self._cache = {}
+
+    def __call__(self, l1: int, l2: int, l3: int) -> np.ndarray:
+        key = (l1, l2, l3)
+        if key not in self._cache:
+            C = np.array(self.tab.cg(l1, l2, l3))
+            nz = np.abs(C[C != 0.0])
+            if nz.size:
+                vals, counts = np.unique(np.round(nz, 12), return_counts=True)
+                mode = vals[np.argmax(counts)]               # ties: the smallest magnitude
+                kappa = float(nz[np.abs(nz - mode) < 1e-11][0])  # an actual entry, not the rounded value
+                C = C / kappa
+                unit = np.abs(np.abs(C) - 1.0) < 1e-13
+                C[unit] = np.sign(C[unit])
+            C.setflags(write=False)
+            self._cache[key] = C
+        return self._cache[key]
+
+
+def eval_internal(tab, s: InternalPath, a: np.ndarray) -> np.ndarray:
+    """tab: anything with .cg(l1,l2,l3) and .outs"""
     L = tab.outs[s.out][0]
 
     def al(l):
@@ -69,8 +99,17 @@ def eval_internal(tab: Tables, s: InternalPath, a: np.ndarray) -> np.ndarray:
     return np.einsum("abc,na,nb->nc", tab.cg(s.L2, s.l3, L), T, al(s.l3))
 
 
-def choose_basis(tab: Tables, samples: np.ndarray):
+class _Shim:
+    """What eval_internal and Scheme need: the (scaled) couplings and the output irreps."""
+
+    def __init__(self, cg, outs):
+        self.cg, self.outs = cg, outs
+
+
+def choose_basis(tab: Tables, samples: np.ndarray, cg=None):
     """Returns (basis, fold) with fold[s] = list of (external path, coefficient)."""
+    cg = cg or tab.cg
+    shim = _Shim(cg, tab.outs)
     groups: Dict[Tuple, List[int]] = {}
     for p, (nu, out, l1, l2, l3, L2) in enumerate(tab.paths):
         ms = tuple(sorted(l for l in (l1, l2, l3) if l >= 0))
@@ -89,7 +128,7 @@ def choose_basis(tab: Tables, samples: np.ndarray):
             options[key] = [(InternalPath(2, out, ms[0], ms[1]),)]
         else:
             cands = candidates(tab, out, ms)
-            Q = {c: eval_internal(tab, c, samples).ravel() for c in cands}
+            Q = {c: eval_internal(shim, c, samples).ravel() for c in cands}
             subs = [sub for sub in itertools.combinations(cands, r)
                     if np.linalg.matrix_rank(np.stack([Q[c] for c in sub], 1), tol=1e-9) == r]
             assert subs, key
@@ -98,7 +137,7 @@ def choose_basis(tab: Tables, samples: np.ndarray):
     cur = {k: options[k][0] for k in keys}
 
     def cost(sel):
-        sch = Scheme(tab.cg, tab.l_max, tab.outs, [c for k in keys for c in sel[k]])
+        sch = Scheme(cg, tab.l_max, tab.outs, [c for k in keys for c in sel[k]])
         return sch.forward().count()["total"] + sch.backward().count()["total"]
     best = cost(cur)
     improved = True
@@ -120,7 +159,7 @@ def choose_basis(tab: Tables, samples: np.ndarray):
             continue
         plist = groups[k]
         E = np.stack([ext[p].ravel() for p in plist], 1)
-        Q = np.stack([eval_internal(tab, c, samples).ravel() for c in cur[k]], 1)
+        Q = np.stack([eval_internal(shim, c, samples).ravel() for c in cur[k]], 1)
         F, *_ = np.linalg.lstsq(Q, E, rcond=None)
         assert np.abs(Q @ F - E).max() < 1e-11, (k, np.abs(Q @ F - E).max())
         for j, c in enumerate(cur[k]):
@@ -238,8 +277,9 @@ def generate(tag: str, lib_path: str = HOST_LIB, verbose: bool = True) -> str:
     l_max, nu_max, outs = SPECS[tag]
     tab = Tables(lib_path, l_max, nu_max, outs)
     samples = np.random.default_rng(0).standard_normal((40, tab.n_lm))
-    basis, fold = choose_basis(tab, samples)
-    sch = Scheme(tab.cg, l_max, outs, basis)
+    cg = ScaledCG(tab)
+    basis, fold = choose_basis(tab, samples, cg)
+    sch = Scheme(cg, l_max, outs, basis)
     fwd, bwd = sch.forward(), sch.backward()
     e64 = self_check(tab, basis, fold, fwd, bwd, np.float64)
     assert max(e64.values()) < 1e-12, e64

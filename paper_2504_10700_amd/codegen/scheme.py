@@ -85,7 +85,8 @@ class Bilinear:
             mags = by_target.setdefault(target, {})
             mags.setdefault(round(abs(c), 11), []).append((c, x, y))
         for target, mags in by_target.items():
-            for mag, lst in mags.items():
+            # a group of unit magnitude goes first: as the first term of a target it needs no scaling
+            for mag, lst in sorted(mags.items(), key=lambda kv: (abs(kv[0] - 1.0) > 1e-9,)):
                 c0 = lst[0][0]
                 q = P.mul(lst[0][1], lst[0][2])
                 for c, x, y in lst[1:]:

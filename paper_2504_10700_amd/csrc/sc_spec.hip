@@ -26,6 +26,8 @@ constexpr int kSpecWaves = 4;
 constexpr int kSpecThreads = kSpecWaves * kLanes;
 constexpr int kXcds = 8;
 
+__device__ __forceinline__ int wave_of_thread() { return __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes); }
+
 // Row of N elements of T at p (p is aligned to the row size if that is a multiple of 16 B,
 // else only to sizeof(T)): 16-byte accesses plus a scalar tail.
 template <typename T, int N>
@@ -56,6 +58,36 @@ struct Row {
     for (int i = N / V * V; i < N; ++i) p[i] = v[i];
   }
 };
+
+// Store of a wave's rows (N elements per lane, lane rows N elements apart = one contiguous
+// block of 64*N elements) as fully coalesced instructions: each lane's row goes through an
+// LDS block of the same layout and comes back transposed, so that store instruction k
+// writes the k-th contiguous 1 KB of the block instead of 64 scattered 16-byte pieces
+// (four times fewer, four times larger write requests to L2; measured -10% on the whole
+// backward kernel; the same trick on the loads of A gained nothing).  stage: 64*N elements
+// of LDS owned by this wave; block: where lane 0's row goes.
+template <typename T, int N>
+__device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* stage, int lane, const T (&v)[N]) {
+  constexpr int V = 16 / sizeof(T);
+  static_assert(N % V == 0, "row must be a whole number of 16-byte pieces");
+  typedef T Vec __attribute__((ext_vector_type(V)));
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // earlier reads of the stage are done
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int j = 0; j < N / V; ++j) {
+    Vec x;
+#pragma unroll
+    for (int k = 0; k < V; ++k) x[k] = v[j * V + k];
+    *reinterpret_cast<Vec*>(stage + lane * N + j * V) = x;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // other lanes' pieces are visible
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int k = 0; k < N / V; ++k) {
+    const Vec x = *reinterpret_cast<const Vec*>(stage + k * kLanes * V + lane * V);
+    *reinterpret_cast<Vec*>(block + k * kLanes * V + lane * V) = x;
+  }
+}
 
 // blockIdx -> logical work item such that the blocks an XCD receives (round-robin by
 // blockIdx) form one contiguous range.  gridDim.x is a multiple of kXcds.
@@ -114,6 +146,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
                                                                      const int32_t* __restrict__ perm) {
   extern __shared__ unsigned char lds_raw[];
   T* red = reinterpret_cast<T*>(lds_raw);  // [kSpecWaves][kS][64]
+  T* stage = red + kSpecWaves * G::kS * kLanes + wave_of_thread() * kLanes * G::kNlm;  // [64][kNlm] per wave
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
   const int logical = xcd_contiguous_block();
@@ -141,7 +174,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
         Row<T, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
       }
       G::backward(a0, w, g0, da, dw);
-      Row<T, G::kNlm>::store(dA + (node0 * K + ch) * G::kNlm, da);
+      store_rows_coalesced<T, G::kNlm>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da);
       if (j + 1 < j1) {
         if (j + 2 < j1) {
           node0 = perm[j + 2];
@@ -149,7 +182,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
           Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
         }
         G::backward(a1, w, g1, da, dw);
-        Row<T, G::kNlm>::store(dA + (node1 * K + ch) * G::kNlm, da);
+        store_rows_coalesced<T, G::kNlm>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da);
       }
     }
   }
@@ -249,7 +282,12 @@ hipError_t bwd_launch(const sc_plan* plan, const void* A, const void* W, const v
                       const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
-  const size_t lds = sizeof(T) * kSpecWaves * G::kS * kLanes;
+  const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
+  if (lds > 64 * 1024) {  // above the default dynamic LDS limit: raise it for this kernel
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&spec_backward_kernel<T, G>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL((spec_backward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
                      plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
                      static_cast<const T*>(W), static_cast<const T*>(dB), static_cast<T*>(dA),
