@@ -65,27 +65,35 @@ struct Row {
 // writes the k-th contiguous 1 KB of the block instead of 64 scattered 16-byte pieces
 // (four times fewer, four times larger write requests to L2; measured -10% on the whole
 // backward kernel; the same trick on the loads of A gained nothing).  stage: 64*N elements
-// of LDS owned by this wave; block: where lane 0's row goes.
+// of LDS owned by this wave; block: where lane 0's row goes (16-byte aligned).
 template <typename T, int N>
 __device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* stage, int lane, const T (&v)[N]) {
   constexpr int V = 16 / sizeof(T);
-  static_assert(N % V == 0, "row must be a whole number of 16-byte pieces");
   typedef T Vec __attribute__((ext_vector_type(V)));
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // earlier reads of the stage are done
   __builtin_amdgcn_wave_barrier();
+  if constexpr (N % V == 0) {
 #pragma unroll
-  for (int j = 0; j < N / V; ++j) {
-    Vec x;
+    for (int j = 0; j < N / V; ++j) {
+      Vec x;
 #pragma unroll
-    for (int k = 0; k < V; ++k) x[k] = v[j * V + k];
-    *reinterpret_cast<Vec*>(stage + lane * N + j * V) = x;
+      for (int k = 0; k < V; ++k) x[k] = v[j * V + k];
+      *reinterpret_cast<Vec*>(stage + lane * N + j * V) = x;
+    }
+  } else {  // rows that are not a whole number of 16-byte pieces (e.g. 9 components)
+#pragma unroll
+    for (int j = 0; j < N; ++j) stage[lane * N + j] = v[j];
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // other lanes' pieces are visible
   __builtin_amdgcn_wave_barrier();
+  constexpr int kPieces = kLanes * N / V;  // 16-byte pieces of the block (64*N is a multiple of V)
 #pragma unroll
-  for (int k = 0; k < N / V; ++k) {
-    const Vec x = *reinterpret_cast<const Vec*>(stage + k * kLanes * V + lane * V);
-    *reinterpret_cast<Vec*>(block + k * kLanes * V + lane * V) = x;
+  for (int q0 = 0; q0 < kPieces; q0 += kLanes) {
+    const int q = q0 + lane;
+    if (q0 + kLanes <= kPieces || q < kPieces) {
+      const Vec x = *reinterpret_cast<const Vec*>(stage + q * V);
+      *reinterpret_cast<Vec*>(block + q * V) = x;
+    }
   }
 }
 
@@ -102,8 +110,11 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(int K, int c
                                                                     const T* __restrict__ W, T* __restrict__ B,
                                                                     const TileDesc* __restrict__ tiles,
                                                                     const int32_t* __restrict__ perm) {
+  extern __shared__ unsigned char lds_raw[];
   const int lane = threadIdx.x & (kLanes - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int wave = wave_of_thread();
+  T* stage = reinterpret_cast<T*>(lds_raw) + wave * kLanes * G::kNLM;  // [64][kNLM] per wave (if used)
+  constexpr bool kStageB = G::kNLM * sizeof(T) != 16;  // 16-byte rows are coalesced as they are
   const int logical = xcd_contiguous_block();
   if (logical >= n_blocks) return;
   const int tile = logical / chblocks, cb = logical % chblocks;
@@ -124,14 +135,16 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(int K, int c
       Row<T, G::kNlm>::load(A + (node1 * K + ch) * G::kNlm, a1);
     }
     G::forward(a0, w, b);
-    Row<T, G::kNLM>::store(B + (node0 * K + ch) * G::kNLM, b);
+    if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (node0 * K + cb * kLanes) * G::kNLM, stage, lane, b);
+    else Row<T, G::kNLM>::store(B + (node0 * K + ch) * G::kNLM, b);
     if (j + 1 < j1) {
       if (j + 2 < j1) {
         node0 = perm[j + 2];
         Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
       }
       G::forward(a1, w, b);
-      Row<T, G::kNLM>::store(B + (node1 * K + ch) * G::kNLM, b);
+      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (node1 * K + cb * kLanes) * G::kNLM, stage, lane, b);
+      else Row<T, G::kNLM>::store(B + (node1 * K + ch) * G::kNLM, b);
     }
   }
 }
@@ -271,7 +284,8 @@ hipError_t fwd_launch(const sc_plan* plan, const void* A, const void* W, void* B
                       const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
-  hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), 0, stream,
+  const size_t lds = (G::kNLM * sizeof(T) != 16) ? sizeof(T) * kSpecWaves * G::kNLM * kLanes : 0;
+  hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
                      plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
                      static_cast<const T*>(W), static_cast<T*>(B), ws.tiles, ws.perm);
   return hipGetLastError();
