@@ -5,13 +5,26 @@ One "step" = sc_forward + sc_backward (grouping of the nodes by element done onc
 in the forward, and reused by the backward) over one batch of synthetic atoms that
 is already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload training_step|large_batch|wide_high_l|medium_fwd]
+  python bench.py [--gpus 1] [--steps K] [--warmup W]
+                  [--workload training_step|large_batch|wide_high_l|wide_high_l_f64|medium_fwd|tiny]
+
+Default workload: `training_step` (10 000 nodes, 89 elements, 128 channels, l<=3, nu<=3,
+outputs 0e+1o, fp32, forward+backward) - the configuration the metric "atoms/sec
+symmetric-contraction fwd+bwd (128ch, l<=3, nu=3)" is quoted on.  With the default
+workload the same line also carries, under "also", a shorter measurement of
+`large_batch` (200 000 nodes, same shapes): at 10 000 nodes a step is ~0.1 ms and
+launch / fixed costs weigh as much as the data movement, at 200 000 nodes they do not.
 
 value          nodes (atoms) per second, forward + backward, whole step (all launches)
 roofline       the dominant kernel (fused backward: dA + per-tile dW) against the HBM
                peak: algorithmic bytes per launch / its mean duration, the duration
-               taken with HIP events on the launch stream
+               taken with HIP events recorded by the library on the launch stream
 cpu_baseline   the fp64 oracle timed on this machine's host cores on a bounded sample
+
+Cache hygiene: buffer sets (A, dB, B, dA) are rotated so that >= 1 GB of other traffic
+passes before a buffer is touched again, and the backward of a step reads a different
+copy of A than its forward did (in training the two are far apart in time): the
+256 MB last-level cache cannot serve any of the reads.
 """
 from __future__ import annotations
 
@@ -26,6 +39,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+METRIC = "atoms/sec symmetric-contraction fwd+bwd (128ch, l<=3, nu=3); % HBM peak"
 
 
 def algorithmic_bytes(wl, n_nodes, elem):
@@ -38,7 +52,6 @@ def algorithmic_bytes(wl, n_nodes, elem):
 
 
 def cpu_baseline(wl, n_sample):
-    import numpy as np
     from oracle import symmetric_contraction as osc
     from paper_2504_10700_amd import workloads
     cfg = osc.OracleConfig(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps)
@@ -54,46 +67,36 @@ def cpu_baseline(wl, n_sample):
                       f"{'forward+backward' if wl.backward else 'forward'}, {dt:.1f} s"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="training_step")
-    ap.add_argument("--cpu-sample", type=int, default=1024, help="nodes the oracle is timed on (0 = skip)")
-    ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
-    ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+def describe(wl):
+    return (f"{wl.name}: {wl.num_nodes} nodes, {wl.num_elements} elements ({wl.z_mode} z, unsorted), "
+            f"{wl.num_channels} channels, l_max={wl.l_max}, nu_max={wl.nu_max}, outputs "
+            + "+".join(f"{L}{'e' if p > 0 else 'o'}" for L, p in wl.out_irreps)
+            + (", forward+backward" if wl.backward else ", forward only"))
 
+
+def measure(wl, steps, warmup, generic=False, tile_nodes=0):
     import numpy as np
     import torch
     from paper_2504_10700_amd import binding as sc
     from paper_2504_10700_amd import workloads
 
-    wl = workloads.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     tdt = torch.float32 if wl.dtype == "f32" else torch.float64
     elem = 4 if wl.dtype == "f32" else 8
     plan = sc.sc_plan_create(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps,
                              sc.SC_F32 if wl.dtype == "f32" else sc.SC_F64, 0,
-                             sc.SC_PLAN_FORCE_GENERIC if args.generic else 0, args.tile_nodes)
+                             sc.SC_PLAN_FORCE_GENERIC if generic else 0, tile_nodes)
     info = sc.sc_plan_info(plan)
-    paths = sc.sc_plan_paths(plan)
-    inp = workloads.make_inputs(wl, paths)
+    inp = workloads.make_inputs(wl, sc.sc_plan_paths(plan))
     N, K = wl.num_nodes, wl.num_channels
 
-    # Rotating buffer sets so that consecutive steps cannot be served from the 256 MB
-    # last-level cache: at least ~1 GB of distinct A/dB/dA/B per rotation.
     per_set = N * K * (2 * wl.n_lm + 2 * wl.n_LM) * elem
     n_sets = max(2, min(8, int(np.ceil(1.0e9 / per_set))))
     A0 = torch.tensor(inp.A, dtype=tdt, device=dev)
     dB0 = torch.tensor(inp.dB, dtype=tdt, device=dev)
     W = torch.tensor(inp.W, dtype=tdt, device=dev)
     z = torch.tensor(inp.z, dtype=torch.int32, device=dev)
+    del inp
     sets = []
     for s in range(n_sets):
         sets.append({
@@ -107,32 +110,32 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     def step(i):
-        b = sets[i % n_sets]
-        sc.sc_forward(plan, N, b["A"], z, W, b["B"], ws, ws_bytes, 0)
+        f = sets[i % n_sets]
+        sc.sc_forward(plan, N, f["A"], z, W, f["B"], ws, ws_bytes, 0)
         if wl.backward:
+            b = sets[(i + n_sets // 2) % n_sets]   # another copy of A: no cache reuse across fwd -> bwd
             sc.sc_backward(plan, N, b["A"], z, W, b["dB"], b["dA"], dW, ws, ws_bytes, sc.SC_REUSE_GROUPING)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    value = N / (dt / args.steps)
+    value = N / (dt / steps)
 
     # Second pass with the library's event brackets around the main kernels.
     sc.sc_profile_enable(plan, True)
     fwd_ms, bwd_ms = [], []
-    n_prof = min(args.steps, 50)
-    for i in range(n_prof):
+    for i in range(min(steps, 50)):
         step(i)
         f, b = sc.sc_profile_read(plan)
         fwd_ms.append(f)
         bwd_ms.append(b)
     sc.sc_profile_enable(plan, False)
+    sc.sc_plan_destroy(plan)
     fwd_bytes, bwd_bytes = algorithmic_bytes(wl, N, elem)
     fwd_mean = float(np.mean(fwd_ms))
     if wl.backward:
@@ -145,30 +148,56 @@ def main():
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath) and wl.backward and info.specialised and args.tile_nodes == 0:
+    if os.path.exists(tpath) and wl.backward and info.specialised and tile_nodes == 0:
         ent = json.load(open(tpath)).get(wl.name)
         if ent:
             traffic = 1024.0 * (ent["fetch_kib"] * ent["fetch_scale"] + ent["write_kib"] * ent["write_scale"])
-
-    out = {
-        "metric": "atoms/sec symmetric-contraction fwd+bwd (128ch, l<=3, nu=3); % HBM peak",
-        "value": value, "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: {N} nodes, {wl.num_elements} elements ({wl.z_mode} z, unsorted), "
-                               f"{K} channels, l_max={wl.l_max}, nu_max={wl.nu_max}, outputs "
-                               + "+".join(f"{L}{'e' if p > 0 else 'o'}" for L, p in wl.out_irreps)
-                               + (", forward+backward" if wl.backward else ", forward only"),
-                   "num_paths": int(info.num_paths), "kernel": "generated" if info.specialised else "table-driven",
-                   "buffer_sets_rotated": n_sets, "tile_nodes": args.tile_nodes},
+    del sets, A0, dB0, ws
+    torch.cuda.empty_cache()
+    return {
+        "value": value, "unit": "nodes/s", "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3,
+        "dtype": wl.dtype,
+        "config": {"workload": describe(wl), "num_paths": int(info.num_paths),
+                   "kernel": "generated" if info.specialised else "table-driven",
+                   "buffer_sets_rotated": n_sets, "tile_nodes": tile_nodes},
         "step_hbm_fraction": value * (step_bytes / N) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel_ms": k_ms,
                      "forward_kernel_ms": fwd_mean, "algorithmic_bytes_per_launch": k_bytes},
     }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="training_step")
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="nodes the oracle is timed on (0 = skip)")
+    ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
+    ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
+    ap.add_argument("--no-also", action="store_true", help="skip the extra large_batch measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2504_10700_amd import workloads
+
+    wl = workloads.WORKLOADS[args.workload]
+    m = measure(wl, args.steps, args.warmup, args.generic, args.tile_nodes)
+    out = {"metric": METRIC, "value": m["value"], "unit": m["unit"], "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": m["dtype"], "data": "synthetic", "config": m["config"],
+           "step_hbm_fraction": m["step_hbm_fraction"], "roofline": m["roofline"]}
     if args.cpu_sample > 0:
-        out["cpu_baseline"] = cpu_baseline(wl, min(args.cpu_sample, N))
-    sc.sc_plan_destroy(plan)
+        out["cpu_baseline"] = cpu_baseline(wl, min(args.cpu_sample, wl.num_nodes))
+    if args.workload == "training_step" and not args.no_also and not args.generic and args.tile_nodes == 0:
+        big = measure(workloads.WORKLOADS["large_batch"], 30, 5)
+        out["also"] = {"large_batch": {k: big[k] for k in
+                                       ("value", "unit", "steps", "warmup", "ms_per_step", "config",
+                                        "step_hbm_fraction", "roofline")}}
     print(json.dumps(out))
 
 

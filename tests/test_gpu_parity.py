@@ -196,3 +196,87 @@ def test_large_batch_full_size(sc):
 def test_wide_high_l_full_size(sc):
     sampled_parity(sc, workloads.WORKLOADS["wide_high_l"], 96, [3])
     sampled_parity(sc, workloads.WORKLOADS["wide_high_l_f64"], 96, [3, 5])
+
+
+def test_three_launch_grouping_and_many_elements(sc):
+    # more than 16384 nodes: the grouping runs as three launches
+    sampled_parity(sc, wl_of("n20000", 20_000, 89, 128, 3, 3, O01, "f32", 2601), 96, [3, 0])
+    # more than 512 elements: three launches even for a small batch; most elements absent or rare
+    full_parity(sc, wl_of("z600", 300, 600, 64, 3, 3, O01, "f32", 2602, z_mode="uniform"))
+    full_parity(sc, wl_of("z1024", 200, 1024, 64, 2, 2, ((0, 1), (1, -1)), "f64", 2603, z_mode="uniform"))
+
+
+def test_tile_size_knob_does_not_change_results_beyond_rounding(sc):
+    wl = wl_of("tiles", 700, 7, 128, 3, 3, O01, "f32", 2701)
+    T = oracle_tables(wl)
+    inp = workloads.make_inputs(wl, T.paths)
+    ref = None
+    for tile_nodes in (0, 16, 64, 512):     # 512: more than 64 nodes per wave
+        import torch
+        plan = sc.sc_plan_create(wl.num_channels, 3, 3, wl.num_elements, O01, sc.SC_F32, 0, 0, tile_nodes)
+        run = GpuRun.__new__(GpuRun)
+        run.sc, run.wl, run.torch = sc, wl, torch
+        run.dev, run.tdt, run.plan, run.N = torch.device("cuda:0"), torch.float32, plan, wl.num_nodes
+        run.A = torch.tensor(inp.A, dtype=run.tdt, device=run.dev)
+        run.W = torch.tensor(inp.W, dtype=run.tdt, device=run.dev)
+        run.dB = torch.tensor(inp.dB, dtype=run.tdt, device=run.dev)
+        run.z = torch.tensor(inp.z, dtype=torch.int32, device=run.dev)
+        run.B = torch.empty((run.N, wl.num_channels, wl.n_LM), dtype=run.tdt, device=run.dev)
+        run.dA, run.dW = torch.empty_like(run.A), torch.empty_like(run.W)
+        run.ws_bytes = sc.sc_workspace_bytes(plan, run.N)
+        run.ws = torch.empty(run.ws_bytes, dtype=torch.uint8, device=run.dev)
+        B = run.forward()
+        dA, dW = run.backward(sc.SC_REUSE_GROUPING)
+        if ref is None:
+            A, z, W, dB = run.inputs_as_computed()
+            check("B", B, osc.forward(T, A, z, W), "f32")
+            dA_ref, dW_ref = osc.backward(T, A, z, W, dB)
+            check("dA", dA, dA_ref, "f32")
+            ref = (B, dA, dW_ref)
+        else:
+            # per-node results do not depend on the tiling at all; dW only through summation order
+            assert np.array_equal(B, ref[0]) and np.array_equal(dA, ref[1])
+        check("dW", dW, ref[2], "f32")
+        run.close()
+
+
+def test_out_of_range_elements_are_skipped_not_fatal(sc):
+    import torch
+    wl = wl_of("badz", 50, 4, 128, 3, 3, O01, "f32", 2801, z_mode="uniform")
+    T = oracle_tables(wl)
+    inp = workloads.make_inputs(wl, T.paths)
+    bad = np.array([3, 17, 31])
+    inp.z[bad] = [-1, 4, 1000]
+    run = GpuRun(sc, wl, inp)
+    run.B.fill_(7.0)
+    run.dA.fill_(7.0)
+    A, z, W, dB = run.inputs_as_computed()
+    good = np.setdiff1d(np.arange(wl.num_nodes), bad)
+    B = run.forward()
+    dA, dW = run.backward(sc.SC_REUSE_GROUPING)
+    check("B", B[good], osc.forward(T, A[good], z[good], W), "f32")
+    dA_ref, dW_ref = osc.backward(T, A[good], z[good], W, dB[good])
+    check("dA", dA[good], dA_ref, "f32")
+    check("dW", dW, dW_ref, "f32")
+    assert (B[bad] == 7.0).all() and (dA[bad] == 7.0).all()   # rows of skipped nodes are left untouched
+    run.close()
+
+
+def test_calls_on_a_side_stream(sc):
+    import torch
+    wl = wl_of("stream", 90, 5, 128, 3, 3, O01, "f32", 2901)
+    T = oracle_tables(wl)
+    run = GpuRun(sc, wl, workloads.make_inputs(wl, T.paths))
+    A, z, W, dB = run.inputs_as_computed()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sc.sc_forward(run.plan, run.N, run.A, run.z, run.W, run.B, run.ws, run.ws_bytes, 0)   # current stream = side
+        sc.sc_backward(run.plan, run.N, run.A, run.z, run.W, run.dB, run.dA, run.dW, run.ws, run.ws_bytes,
+                       sc.SC_REUSE_GROUPING, stream=side)
+    side.synchronize()
+    check("B", run.B.cpu().numpy(), osc.forward(T, A, z, W), "f32")
+    dA_ref, dW_ref = osc.backward(T, A, z, W, dB)
+    check("dA", run.dA.cpu().numpy(), dA_ref, "f32")
+    check("dW", run.dW.cpu().numpy(), dW_ref, "f32")
+    run.close()
