@@ -19,6 +19,7 @@ namespace {
 constexpr int kGroupThreads = kGroupWavesPerWG * kLanes;
 constexpr int kFusedWaves = 16;
 constexpr int kFusedThreads = kFusedWaves * kLanes;
+constexpr int kBatch = 8;          // 64-node chunks whose z loads are issued together (multi-launch kernels)
 constexpr int kFusedChunks = 16;   // 64-node chunks per wave of the single-launch kernel
 constexpr int kFusedMaxNodes = kFusedWaves * kFusedChunks * kLanes;
 
@@ -183,9 +184,16 @@ __global__ __launch_bounds__(kGroupThreads) void group_count_kernel(const int32_
   __syncthreads();
   const long long lo = static_cast<long long>(gw) * nodes_per_wave;
   const long long hi = (lo + nodes_per_wave < n) ? lo + nodes_per_wave : n;
-  for (long long i = lo + lane; i < hi; i += kLanes) {
-    const int e = z[i];
-    if (e >= 0 && e < Z) atomicAdd(&mine[e], 1);
+  for (long long c0 = lo; c0 < hi; c0 += kBatch * kLanes) {  // kBatch independent loads in flight
+    int zs[kBatch];
+#pragma unroll
+    for (int c = 0; c < kBatch; ++c) {
+      const long long i = c0 + c * kLanes + lane;
+      zs[c] = (i < hi) ? z[i] : -1;
+    }
+#pragma unroll
+    for (int c = 0; c < kBatch; ++c)
+      if (zs[c] >= 0 && zs[c] < Z) atomicAdd(&mine[zs[c]], 1);
   }
   __syncthreads();
   for (int e = lane; e < Z; e += kLanes) counts[static_cast<size_t>(e) * W + gw] = mine[e];
@@ -203,29 +211,40 @@ __global__ __launch_bounds__(kFusedThreads) void group_scan_kernel(int Z, int W,
   __shared__ int32_t til[SC_MAX_ELEMENTS + 1];
   const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
   constexpr int kPer = kMaxGroupWaves / kLanes;
-  for (int e = wave; e < Z; e += kFusedWaves) {
-    int32_t* row = counts + static_cast<size_t>(e) * W;
-    int c[kPer], local = 0;
+  constexpr int kRows = 4;  // rows whose loads are issued together
+  for (int e0 = wave; e0 < Z; e0 += kFusedWaves * kRows) {
+    int c[kRows][kPer];
 #pragma unroll
-    for (int k = 0; k < kPer; ++k) {
-      const int w = lane * kPer + k;
-      c[k] = (w < W) ? row[w] : 0;
-      local += c[k];
-    }
-    int incl = local;  // inclusive scan over the lanes
+    for (int r = 0; r < kRows; ++r) {
+      const int e = e0 + r * kFusedWaves;
 #pragma unroll
-    for (int d = 1; d < kLanes; d <<= 1) {
-      const int up = __shfl_up(incl, d);
-      if (lane >= d) incl += up;
+      for (int k = 0; k < kPer; ++k) {
+        const int w = lane * kPer + k;
+        c[r][k] = (e < Z && w < W) ? counts[static_cast<size_t>(e) * W + w] : 0;
+      }
     }
-    int run = incl - local;
 #pragma unroll
-    for (int k = 0; k < kPer; ++k) {
-      const int w = lane * kPer + k;
-      if (w < W) row[w] = run;
-      run += c[k];
+    for (int r = 0; r < kRows; ++r) {
+      const int e = e0 + r * kFusedWaves;
+      if (e >= Z) break;  // wave-uniform
+      int local = 0;
+#pragma unroll
+      for (int k = 0; k < kPer; ++k) local += c[r][k];
+      int incl = local;  // inclusive scan over the lanes
+#pragma unroll
+      for (int d = 1; d < kLanes; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+      }
+      int run = incl - local;
+#pragma unroll
+      for (int k = 0; k < kPer; ++k) {
+        const int w = lane * kPer + k;
+        if (w < W) counts[static_cast<size_t>(e) * W + w] = run;
+        run += c[r][k];
+      }
+      if (lane == kLanes - 1) total[e] = incl;
     }
-    if (lane == kLanes - 1) total[e] = incl;
   }
   __syncthreads();
   offsets_and_tiles(Z, tile_nodes, max_tiles, total, seg, til, seg_off, tile_off, ntiles_out, tiles);
@@ -245,11 +264,19 @@ __global__ __launch_bounds__(kGroupThreads) void group_scatter_kernel(const int3
   const long long lo = static_cast<long long>(gw) * nodes_per_wave;
   const long long hi = (lo + nodes_per_wave < n) ? lo + nodes_per_wave : n;
   const int z_bits = 32 - __builtin_clz(Z);
-  for (long long c0 = lo; c0 < hi; c0 += kLanes) {  // wave-uniform trip count
-    const long long i = c0 + lane;
-    int e = -1;
-    if (i < hi) e = z[i];
-    scatter_chunk(e, e >= 0 && e < Z, static_cast<int>(i), lane, z_bits, cursor, 1, perm);
+  for (long long c0 = lo; c0 < hi; c0 += kBatch * kLanes) {  // wave-uniform trip count
+    int zs[kBatch];
+#pragma unroll
+    for (int c = 0; c < kBatch; ++c) {
+      const long long i = c0 + c * kLanes + lane;
+      zs[c] = (i < hi) ? z[i] : -1;
+    }
+#pragma unroll
+    for (int c = 0; c < kBatch; ++c) {
+      if (c0 + c * kLanes >= hi) break;  // wave-uniform
+      const int e = zs[c];
+      scatter_chunk(e, e >= 0 && e < Z, static_cast<int>(c0 + c * kLanes + lane), lane, z_bits, cursor, 1, perm);
+    }
   }
 }
 

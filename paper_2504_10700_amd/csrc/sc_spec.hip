@@ -215,44 +215,58 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
 // Second stage of the dW reduction, two small launches (device-scope fences, which a
 // single-launch "last wave finishes the job" scheme needs, flush the per-XCD L2s and cost
 // far more than a launch on this chip).
-// (1) One wave per (element, channel block, internal row): sums its row over the element's
-//     tiles in tile order (sixteen independent loads in flight) into reduced[e][cb][s][lane]
-//     in fp64.  Elements without nodes own no tiles and get zeros.
+// (1) One workgroup of four waves per (element, channel block, internal row): each wave sums
+//     the row over a contiguous quarter of the element's tiles in tile order (sixteen
+//     independent loads in flight), the four sums are added in wave order into
+//     reduced[e][cb][s][lane] in fp64.  Elements without nodes own no tiles and get zeros.
 // (2) One wave per (element, channel block): maps the S reduced rows to the P external
 //     paths with the generated unfold.
 // Every sum has a fixed order: results are bitwise reproducible.
+constexpr int kReduceWaves = 4;
+
 template <typename T, typename G>
-__global__ __launch_bounds__(kLanes) void spec_reduce_kernel(int chblocks, int max_tiles,
-                                                             const T* __restrict__ partial,
-                                                             const int32_t* __restrict__ tile_off,
-                                                             double* __restrict__ reduced) {
+__global__ __launch_bounds__(kReduceWaves * kLanes) void spec_reduce_kernel(int chblocks, int max_tiles,
+                                                                            const T* __restrict__ partial,
+                                                                            const int32_t* __restrict__ tile_off,
+                                                                            double* __restrict__ reduced) {
   constexpr int S = G::kS;
-  const int lane = threadIdx.x;
+  __shared__ double part[kReduceWaves][kLanes];
+  const int lane = threadIdx.x % kLanes, wave = threadIdx.x / kLanes;
   const int s = blockIdx.x % S;
   const int cb = (blockIdx.x / S) % chblocks;
   const int e = blockIdx.x / (S * chblocks);
   int t0 = tile_off[e], t1 = tile_off[e + 1];
   if (t1 > max_tiles) t1 = max_tiles;
+  // the element's tiles are cut into kReduceWaves contiguous ranges, one per wave
+  const int nt = t1 - t0;
+  const int w0 = t0 + nt * wave / kReduceWaves, w1 = t0 + nt * (wave + 1) / kReduceWaves;
   const size_t tstride = static_cast<size_t>(chblocks) * S * kLanes;
   const T* src = partial + (static_cast<size_t>(cb) * S + s) * kLanes + lane;
   constexpr int U = 16;
   double a[U];
 #pragma unroll
   for (int k = 0; k < U; ++k) a[k] = 0.0;
-  int t = t0;
-  for (; t + U <= t1; t += U) {
+  int t = w0;
+  for (; t + U <= w1; t += U) {
     T v[U];
 #pragma unroll
     for (int k = 0; k < U; ++k) v[k] = src[(t + k) * tstride];
 #pragma unroll
     for (int k = 0; k < U; ++k) a[k] += static_cast<double>(v[k]);
   }
-  for (; t < t1; ++t) a[0] += static_cast<double>(src[t * tstride]);
+  for (; t < w1; ++t) a[0] += static_cast<double>(src[t * tstride]);
 #pragma unroll
   for (int w = U / 2; w >= 1; w /= 2)
 #pragma unroll
     for (int k = 0; k < w; ++k) a[k] += a[k + w];
-  reduced[((static_cast<size_t>(e) * chblocks + cb) * S + s) * kLanes + lane] = a[0];
+  part[wave][lane] = a[0];
+  __syncthreads();
+  if (wave == 0) {
+    double sum = part[0][lane];
+#pragma unroll
+    for (int w = 1; w < kReduceWaves; ++w) sum += part[w][lane];
+    reduced[((static_cast<size_t>(e) * chblocks + cb) * S + s) * kLanes + lane] = sum;
+  }
 }
 
 template <typename T, typename G>
@@ -313,7 +327,7 @@ template <typename T, typename G>
 hipError_t finalize_launch(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
                            hipStream_t stream) {
   const int Z = plan->cfg.num_elements;
-  hipLaunchKernelGGL((spec_reduce_kernel<T, G>), dim3(Z * shape.chblocks * G::kS), dim3(kLanes), 0, stream,
+  hipLaunchKernelGGL((spec_reduce_kernel<T, G>), dim3(Z * shape.chblocks * G::kS), dim3(kReduceWaves * kLanes), 0, stream,
                      shape.chblocks, shape.max_tiles, static_cast<const T*>(ws.partial), ws.tile_off, ws.reduced);
   hipLaunchKernelGGL((spec_unfold_kernel<T, G>), dim3(Z * shape.chblocks), dim3(kLanes), 0, stream,
                      plan->cfg.num_channels, shape.chblocks, ws.reduced, static_cast<T*>(dW));
