@@ -205,3 +205,59 @@ def backward(T: OracleTables, A: np.ndarray, z: np.ndarray, W: np.ndarray, dB: n
                 dA[s:s + chunk] += np.einsum("ikabc,ika,ikc->ikb", dX, a, a)
                 dA[s:s + chunk] += np.einsum("ikabc,ika,ikb->ikc", dX, a, a)
     return dA, dW
+
+
+def double_backward(T: OracleTables, A: np.ndarray, z: np.ndarray, W: np.ndarray, dB: np.ndarray,
+                    H: np.ndarray, chunk: int = 64):
+    """Second-order pass needed when a loss depends on dA (forces are derivatives of the
+    energy, Section 2.2, so force training differentiates the backward once more).
+
+    With phi = sum(dB * B(A, W)) and psi = sum(H * dphi/dA) (H has the shape of A) returns
+        ddB = dpsi/d(dB)   [n, K, n_LM]   = directional derivative of B along H
+        dA2 = dpsi/dA      [n, K, n_lm]   = Hessian of phi applied to H
+        dW2 = dpsi/dW      [Z, P, K]
+    written out from the definition of B as a polynomial: the derivative along H replaces
+    one factor A by H in every slot in turn.
+    """
+    cfg = T.cfg
+    A = np.asarray(A, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    dB = np.asarray(dB, dtype=np.float64)
+    H = np.asarray(H, dtype=np.float64)
+    N, K, n = A.shape
+    ddB = np.zeros_like(dB)
+    dA2 = np.zeros_like(A)
+    dW2 = np.zeros_like(W)
+    for s in range(0, N, chunk):
+        a, h, g, zz = A[s:s + chunk], H[s:s + chunk], dB[s:s + chunk], z[s:s + chunk]
+        w = W[zz]
+        c = a.shape[0]
+        for nu, cols in T.cols.items():
+            U = T.Umat[nu].T.reshape((-1,) + (n,) * nu)      # [col, a_1..a_nu]
+            # directional derivative of every path polynomial along h: Pdot[i,k,col]
+            if nu == 1:
+                Pdot = np.einsum("ca,ika->ikc", U, h)
+            elif nu == 2:
+                Pdot = np.einsum("cab,ika,ikb->ikc", U, h, a) + np.einsum("cab,ika,ikb->ikc", U, a, h)
+            else:
+                Pdot = (np.einsum("cabd,ika,ikb,ikd->ikc", U, h, a, a)
+                        + np.einsum("cabd,ika,ikb,ikd->ikc", U, a, h, a)
+                        + np.einsum("cabd,ika,ikb,ikd->ikc", U, a, a, h))
+            gw = np.zeros((c, K, U.shape[0]))                 # dB * W per column
+            for p, c0, c1 in cols:
+                sl = cfg.out_slice(T.paths[p][1])
+                ddB[s:s + chunk, :, sl] += w[:, p, :, None] * Pdot[:, :, c0:c1]
+                np.add.at(dW2[:, p, :], zz, (g[:, :, sl] * Pdot[:, :, c0:c1]).sum(axis=2))
+                gw[:, :, c0:c1] = g[:, :, sl] * w[:, p, :, None]
+            # dA2[b] = sum_col gw[col] * d(Pdot[col])/dA_b : one factor is h, one is removed
+            if nu == 2:
+                dA2[s:s + chunk] += np.einsum("ikc,cab,ika->ikb", gw, U, h)
+                dA2[s:s + chunk] += np.einsum("ikc,cab,ikb->ika", gw, U, h)
+            elif nu == 3:
+                for hs, rs, ks in ((0, 1, 2), (0, 2, 1), (1, 0, 2), (1, 2, 0), (2, 0, 1), (2, 1, 0)):
+                    # slot hs holds h, slot rs is differentiated (free index), slot ks keeps a
+                    idx = ["", "", ""]
+                    idx[hs], idx[rs], idx[ks] = "x", "y", "v"
+                    sub = "ikc,c" + "".join(idx) + ",ikx,ikv->iky"
+                    dA2[s:s + chunk] += np.einsum(sub, gw, U, h, a)
+    return ddB, dA2, dW2
