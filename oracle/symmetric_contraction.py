@@ -233,31 +233,35 @@ def double_backward(T: OracleTables, A: np.ndarray, z: np.ndarray, W: np.ndarray
         w = W[zz]
         c = a.shape[0]
         for nu, cols in T.cols.items():
-            U = T.Umat[nu].T.reshape((-1,) + (n,) * nu)      # [col, a_1..a_nu]
-            # directional derivative of every path polynomial along h: Pdot[i,k,col]
+            Umat = T.Umat[nu]                                  # [n^nu, col]
+            # derivative along h of the monomials a_{a1}..a_{a_nu}: h takes every slot in turn
             if nu == 1:
-                Pdot = np.einsum("ca,ika->ikc", U, h)
+                Xdot = h
             elif nu == 2:
-                Pdot = np.einsum("cab,ika,ikb->ikc", U, h, a) + np.einsum("cab,ika,ikb->ikc", U, a, h)
+                Xdot = np.einsum("ika,ikb->ikab", h, a) + np.einsum("ika,ikb->ikab", a, h)
             else:
-                Pdot = (np.einsum("cabd,ika,ikb,ikd->ikc", U, h, a, a)
-                        + np.einsum("cabd,ika,ikb,ikd->ikc", U, a, h, a)
-                        + np.einsum("cabd,ika,ikb,ikd->ikc", U, a, a, h))
-            gw = np.zeros((c, K, U.shape[0]))                 # dB * W per column
+                aa = np.einsum("ika,ikb->ikab", a, a)
+                ha = np.einsum("ika,ikb->ikab", h, a)
+                ah = np.einsum("ika,ikb->ikab", a, h)
+                Xdot = (np.einsum("ikab,ikd->ikabd", ha, a) + np.einsum("ikab,ikd->ikabd", ah, a)
+                        + np.einsum("ikab,ikd->ikabd", aa, h))
+            Pdot = Xdot.reshape(c, K, -1) @ Umat               # directional derivative of every path polynomial
+            gw = np.zeros((c, K, Umat.shape[1]))               # dB * W per column
             for p, c0, c1 in cols:
                 sl = cfg.out_slice(T.paths[p][1])
                 ddB[s:s + chunk, :, sl] += w[:, p, :, None] * Pdot[:, :, c0:c1]
                 np.add.at(dW2[:, p, :], zz, (g[:, :, sl] * Pdot[:, :, c0:c1]).sum(axis=2))
                 gw[:, :, c0:c1] = g[:, :, sl] * w[:, p, :, None]
-            # dA2[b] = sum_col gw[col] * d(Pdot[col])/dA_b : one factor is h, one is removed
+            # dX[a1..a_nu] = sum_col gw[col] * U[col; a1..a_nu]; in dA2 one slot is the free
+            # index, one holds h and (nu = 3) the last keeps a
+            dX = (gw @ Umat.T).reshape((c, K) + (n,) * nu)
             if nu == 2:
-                dA2[s:s + chunk] += np.einsum("ikc,cab,ika->ikb", gw, U, h)
-                dA2[s:s + chunk] += np.einsum("ikc,cab,ikb->ika", gw, U, h)
+                dA2[s:s + chunk] += np.einsum("ikab,ika->ikb", dX, h)
+                dA2[s:s + chunk] += np.einsum("ikab,ikb->ika", dX, h)
             elif nu == 3:
                 for hs, rs, ks in ((0, 1, 2), (0, 2, 1), (1, 0, 2), (1, 2, 0), (2, 0, 1), (2, 1, 0)):
                     # slot hs holds h, slot rs is differentiated (free index), slot ks keeps a
                     idx = ["", "", ""]
                     idx[hs], idx[rs], idx[ks] = "x", "y", "v"
-                    sub = "ikc,c" + "".join(idx) + ",ikx,ikv->iky"
-                    dA2[s:s + chunk] += np.einsum(sub, gw, U, h, a)
+                    dA2[s:s + chunk] += np.einsum("ik" + "".join(idx) + ",ikx,ikv->iky", dX, h, a)
     return ddB, dA2, dW2
