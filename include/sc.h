@@ -73,10 +73,10 @@ typedef enum { SC_F32 = 0, SC_F64 = 1 } sc_dtype;
 #define SC_PLAN_HOST_ONLY 1u     /* build tables only; no device is touched, compute calls fail   */
 #define SC_PLAN_FORCE_GENERIC 2u /* use the table-driven kernels even if a specialised one exists */
 
-/* flags of sc_forward / sc_backward */
+/* flags of sc_forward / sc_backward / sc_double_backward */
 #define SC_REUSE_GROUPING 1u /* the workspace still holds the grouping written by the previous
-                                sc_forward/sc_backward call of this plan with the same
-                                n_nodes and the same z contents: skip regrouping           */
+                                compute call of this plan with the same n_nodes and the
+                                same z contents: skip regrouping                           */
 
 typedef struct {
   int32_t struct_size;            /* = sizeof(sc_config), ABI guard                                  */
@@ -158,15 +158,31 @@ sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32
                       const void* dB, void* dA, void* dW, void* workspace, size_t workspace_bytes,
                       uint32_t flags, void* hip_stream);
 
+/* Second-order pass of Algorithm 2 (Section 2.2: forces are derivatives of the total energy,
+ * so a loss on forces differentiates the backward pass once more).  With
+ *   psi = sum_{i,k,a} H[i,k,a] * dA[i,k,a](A, W, dB)        (dA as returned by sc_backward)
+ * it returns the gradients of psi with respect to the three arguments of the backward pass:
+ *   H   dev [n_nodes][K][n_lm]   cotangent of dA (input)
+ *   ddB dev [n_nodes][K][n_LM]   (overwritten)  d psi / d dB = directional derivative of B along H
+ *   dA2 dev [n_nodes][K][n_lm]   (overwritten)  d psi / d A  = (Hessian of sum(dB*B) in A) . H
+ *   dW2 dev [Z][num_paths][K]    (overwritten)  d psi / d W
+ * A, z, W, dB, workspace, flags, stream, the zero rows of absent elements, n_nodes == 0 and
+ * reproducibility are as for sc_backward (dW2 is reduced exactly like dW). */
+sc_status sc_double_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W,
+                             const void* dB, const void* H, void* ddB, void* dA2, void* dW2, void* workspace,
+                             size_t workspace_bytes, uint32_t flags, void* hip_stream);
+
 /* Measurement helper (benchmarks only; not part of the operation).  While enabled,
- * sc_forward / sc_backward bracket their main kernel - the fused forward kernel, or the
- * fused dA + per-tile dW kernel; not the grouping pass and not the dW reduction - with
+ * sc_forward / sc_backward / sc_double_backward bracket their main kernel - the fused forward
+ * kernel, or the fused dA + per-tile dW kernel; not the grouping pass and not the dW reduction - with
  * HIP events on the call's stream.  sc_profile_read blocks until the most recent
  * bracketed call of each kind has finished and returns that kernel's duration in
  * milliseconds (negative if no such call was made).  While enabled the plan must be used
  * from one thread and one stream at a time. */
 sc_status sc_profile_enable(sc_plan* plan, int32_t on);
 sc_status sc_profile_read(sc_plan* plan, float* forward_ms, float* backward_ms);
+/* Same for the main kernel of the most recent sc_double_backward call. */
+sc_status sc_profile_read_double_backward(sc_plan* plan, float* ms);
 
 /* Thread-local message of the last failing call on this thread; never NULL. */
 const char* sc_last_error(void);

@@ -28,8 +28,8 @@ SC_PLAN_HOST_ONLY, SC_PLAN_FORCE_GENERIC = 1, 2
 SC_REUSE_GROUPING = 1
 
 EXPORTS = ("sc_plan_create", "sc_plan_destroy", "sc_plan_info", "sc_plan_paths", "sc_plan_path_terms",
-           "sc_coupling_tensor", "sc_workspace_bytes", "sc_forward", "sc_backward", "sc_profile_enable",
-           "sc_profile_read", "sc_last_error")
+           "sc_coupling_tensor", "sc_workspace_bytes", "sc_forward", "sc_backward", "sc_double_backward",
+           "sc_profile_enable", "sc_profile_read", "sc_profile_read_double_backward", "sc_last_error")
 
 
 class sc_config(C.Structure):
@@ -66,7 +66,9 @@ def _load() -> C.CDLL:
     lib.sc_workspace_bytes.argtypes = [vp, i64, C.POINTER(C.c_size_t)]
     lib.sc_forward.argtypes = [vp, i64, vp, vp, vp, vp, vp, C.c_size_t, u32, vp]
     lib.sc_backward.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, u32, vp]
+    lib.sc_double_backward.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, u32, vp]
     lib.sc_profile_enable.argtypes = [vp, i32]
+    lib.sc_profile_read_double_backward.argtypes = [vp, C.POINTER(C.c_float)]
     lib.sc_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.sc_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -190,6 +192,12 @@ def sc_backward(plan: Plan, n_nodes: int, A, z, W, dB, dA, dW, workspace, worksp
                            _ptr(workspace), workspace_bytes, flags, _stream(stream)))
 
 
+def sc_double_backward(plan: Plan, n_nodes: int, A, z, W, dB, H, ddB, dA2, dW2, workspace, workspace_bytes: int,
+                       flags: int = 0, stream=None) -> None:
+    _check(lib.sc_double_backward(plan.handle, n_nodes, _ptr(A), _ptr(z), _ptr(W), _ptr(dB), _ptr(H), _ptr(ddB),
+                                  _ptr(dA2), _ptr(dW2), _ptr(workspace), workspace_bytes, flags, _stream(stream)))
+
+
 def sc_profile_enable(plan: Plan, on: bool) -> None:
     _check(lib.sc_profile_enable(plan.handle, 1 if on else 0))
 
@@ -199,3 +207,10 @@ def sc_profile_read(plan: Plan) -> Tuple[float, float]:
     f, b = C.c_float(), C.c_float()
     _check(lib.sc_profile_read(plan.handle, C.byref(f), C.byref(b)))
     return f.value, b.value
+
+
+def sc_profile_read_double_backward(plan: Plan) -> float:
+    """Duration in ms of the main kernel of the latest bracketed sc_double_backward call."""
+    t = C.c_float()
+    _check(lib.sc_profile_read_double_backward(plan.handle, C.byref(t)))
+    return t.value

@@ -12,7 +12,9 @@ For every configuration in SPECS it
      on random samples and checks the residual,
   4. builds the forward and backward straight-line programs (scheme.py), checks them against
      the external polynomials (values and, by finite differences, gradients) in fp64,
-  5. writes csrc/generated/sc_gen_<tag>.inc.
+  5. derives the second-order program from the forward one (autodiff.py: tangent along H, then
+     the reverse-mode derivative of sum(g * tangent)) and checks it the same way,
+  6. writes csrc/generated/sc_gen_<tag>.inc.
 Deterministic: the same library gives the same files.
 """
 from __future__ import annotations
@@ -25,6 +27,7 @@ from typing import Dict, List, Sequence, Tuple
 
 import numpy as np
 
+from .autodiff import replay_with_tangent, reverse
 from .program import Program
 from .scheme import InternalPath, Scheme
 from .tables import HOST_LIB, Tables
@@ -168,6 +171,99 @@ def choose_basis(tab: Tables, samples: np.ndarray, cg=None):
     return basis, fold
 
 
+def build_double_backward(fwd: Program, n_lm: int, n_LM: int, S: int) -> Program:
+    """Second-order program: with psi = sum_j g[j] * (d b[j] / d a . h),
+    ddb = d psi / d g (the tangent of the forward program along h), da = d psi / d a,
+    dw += d psi / d w."""
+    P = Program()
+    a = [P.inp(f"a[{i}]") for i in range(n_lm)]
+    h = [P.inp(f"h[{i}]") for i in range(n_lm)]
+    w = [P.inp(f"w[{s}]") for s in range(S)]
+    g = [P.inp(f"g[{j}]") for j in range(n_LM)]
+    dw = [P.inp(f"dw[{s}]") for s in range(S)]
+    inputs = {f"a[{i}]": (a[i], h[i]) for i in range(n_lm)}
+    inputs.update({f"w[{s}]": (w[s], None) for s in range(S)})
+    outs = replay_with_tangent(fwd, P, inputs)
+    seeds: Dict[int, int] = {}
+    for j in range(n_LM):
+        t = outs[f"b[{j}]"][1]
+        if t is not None:
+            seeds[t] = P.add(seeds.get(t), g[j])
+    adj = reverse(P, seeds)
+    for j in range(n_LM):
+        P.out(f"ddb[{j}]", outs[f"b[{j}]"][1])
+    for i in range(n_lm):
+        P.out(f"da[{i}]", adj.get(a[i]))
+    for s in range(S):
+        P.out(f"dw[{s}]", P.add(dw[s], adj.get(w[s])))
+    return P
+
+
+def self_check_double(tab: Tables, basis, fold, dbl: Program, dtype=np.float64):
+    """Second-order program against the second derivatives of the external polynomials."""
+    rng = np.random.default_rng(54321)
+    n = 1000
+    a = rng.standard_normal((n, tab.n_lm))
+    h = rng.standard_normal((n, tab.n_lm))
+    g = rng.standard_normal((n, tab.n_LM))
+    counts = {}
+    for (nu, out, *_r) in tab.paths:
+        counts[(nu, out)] = counts.get((nu, out), 0) + 1
+    Wext = np.stack([rng.standard_normal(n) / np.sqrt(counts[(p[0], p[1])]) for p in tab.paths], 1)
+    a, h, g, Wext = (x.astype(dtype).astype(np.float64) for x in (a, h, g, Wext))
+    S = len(basis)
+    w = np.zeros((n, S))
+    for s, lst in enumerate(fold):
+        for p, c in lst:
+            w[:, s] += c * Wext[:, p]
+    off = np.cumsum([0] + [2 * L + 1 for L, _ in tab.outs])
+    ddB = np.zeros((n, tab.n_LM))
+    dA2 = np.zeros((n, tab.n_lm))
+    dW2 = np.zeros((n, tab.num_paths))
+    for p, path in enumerate(tab.paths):
+        nu, out = path[0], path[1]
+        M, i1, i2, i3, coef = tab.path_terms(p)
+        for t in range(len(M)):
+            col = off[out] + M[t]
+            idx = (i1[t], i2[t], i3[t])[:nu]
+            # tangent of the monomial: one factor replaced by h
+            tang = np.zeros(n)
+            for k in range(nu):
+                f = [h[:, idx[j]] if j == k else a[:, idx[j]] for j in range(nu)]
+                tang += np.prod(f, axis=0)
+            ddB[:, col] += Wext[:, p] * coef[t] * tang
+            dW2[:, p] += g[:, col] * coef[t] * tang
+            # derivative of the tangent with respect to the factor in slot m
+            for m in range(nu):
+                d = np.zeros(n)
+                for k in range(nu):
+                    if k == m:
+                        continue
+                    f = [h[:, idx[j]] if j == k else a[:, idx[j]] for j in range(nu) if j != m]
+                    d += np.prod(f, axis=0)
+                dA2[:, idx[m]] += g[:, col] * Wext[:, p] * coef[t] * d
+    inputs = {f"a[{i}]": a[:, i] for i in range(tab.n_lm)}
+    inputs.update({f"h[{i}]": h[:, i] for i in range(tab.n_lm)})
+    inputs.update({f"w[{s}]": w[:, s] for s in range(S)})
+    inputs.update({f"g[{j}]": g[:, j] for j in range(tab.n_LM)})
+    inputs.update({f"dw[{s}]": np.zeros(n) for s in range(S)})
+    r = dbl.evaluate(inputs, dtype)
+
+    def col(v):
+        return np.zeros(n) if v is None else v.astype(np.float64)
+    ddBg = np.stack([col(r[f"ddb[{j}]"]) for j in range(tab.n_LM)], 1)
+    dAg = np.stack([col(r[f"da[{i}]"]) for i in range(tab.n_lm)], 1)
+    dwg = np.stack([col(r[f"dw[{s}]"]) for s in range(S)], 1)
+    dWg = np.zeros((n, tab.num_paths))
+    for s, lst in enumerate(fold):
+        for p, c in lst:
+            dWg[:, p] += c * dwg[:, s]
+
+    def err(x, y):
+        return float(np.abs(x - y).max() / np.sqrt((y ** 2).mean()))
+    return {"ddB": err(ddBg, ddB), "dA2": err(dAg, dA2), "dW2(per node)": err(dWg, dW2)}
+
+
 def self_check(tab: Tables, basis, fold, fwd: Program, bwd: Program, dtype=np.float64):
     """Generated programs against the library's external polynomials.  Returns error norms."""
     rng = np.random.default_rng(12345)
@@ -219,7 +315,7 @@ def self_check(tab: Tables, basis, fold, fwd: Program, bwd: Program, dtype=np.fl
     return {"B": err(Bg, B), "dA": err(dAg, dA), "dW(per node)": err(dWg, dWext)}
 
 
-def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program) -> str:
+def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program, dbl: Program) -> str:
     S, P = len(basis), tab.num_paths
     L = []
     L.append(f"// GENERATED by paper_2504_10700_amd/codegen/generate.py for l_max={tab.l_max}, nu_max={tab.nu_max}, outputs "
@@ -227,8 +323,9 @@ def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program) -> 
     L.append("//")
     L.append("// Straight-line evaluation of Algorithm 2 of arXiv 2504.10700 (and of its reverse-mode")
     L.append("// derivative) per (node, channel) in the coupled Horner form described in codegen/scheme.py.")
-    fc, bc = fwd.count(), bwd.count()
-    L.append(f"// Operation counts per (node, channel): forward {fc['total']}, backward {bc['total']}.")
+    fc, bc, dc = fwd.count(), bwd.count(), dbl.count()
+    L.append(f"// Operation counts per (node, channel): forward {fc['total']}, backward {bc['total']}, "
+             f"second-order pass {dc['total']}.")
     L.append("// Internal path basis (index: nu, output irrep, l1, l2, L2, l3):")
     for i, s in enumerate(basis):
         L.append(f"//   {i:2d}: nu={s.nu} out={s.out} l1={s.l1} l2={s.l2} L2={s.L2} l3={s.l3}")
@@ -269,6 +366,15 @@ def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program) -> 
     L.append("                                                  T (&da)[kNlm], T (&dw)[kS]) {")
     L.append(bwd.emit("T", "    "))
     L.append("  }")
+    L.append("")
+    L.append("  // Second-order pass: with psi = sum_j g[j] * (d b[j] / d a . h): ddb = d psi / d g,")
+    L.append("  // da = d psi / d a (both overwritten); d psi / d w is accumulated into dw.")
+    L.append("  template <typename T>")
+    L.append("  static __device__ __forceinline__ void double_backward(const T (&a)[kNlm], const T (&w)[kS], const T (&g)[kNLM],")
+    L.append("                                                         const T (&h)[kNlm], T (&ddb)[kNLM], T (&da)[kNlm],")
+    L.append("                                                         T (&dw)[kS]) {")
+    L.append(dbl.emit("T", "    "))
+    L.append("  }")
     L.append("};")
     return "\n".join(L) + "\n"
 
@@ -281,14 +387,19 @@ def generate(tag: str, lib_path: str = HOST_LIB, verbose: bool = True) -> str:
     basis, fold = choose_basis(tab, samples, cg)
     sch = Scheme(cg, l_max, outs, basis)
     fwd, bwd = sch.forward(), sch.backward()
+    dbl = build_double_backward(fwd, tab.n_lm, tab.n_LM, len(basis))
     e64 = self_check(tab, basis, fold, fwd, bwd, np.float64)
     assert max(e64.values()) < 1e-12, e64
+    d64 = self_check_double(tab, basis, fold, dbl, np.float64)
+    assert max(d64.values()) < 1e-12, d64
     if verbose:
         e32 = self_check(tab, basis, fold, fwd, bwd, np.float32)
-        print(f"[{tag}] S={len(basis)} P={tab.num_paths} ops fwd={fwd.count()['total']} bwd={bwd.count()['total']}")
-        print(f"[{tag}] fp64 self-check max|err|/rms: {e64}")
-        print(f"[{tag}] fp32 emulation  max|err|/rms: {e32}")
-    return emit_inc(tag, tab, basis, fold, fwd, bwd)
+        d32 = self_check_double(tab, basis, fold, dbl, np.float32)
+        print(f"[{tag}] S={len(basis)} P={tab.num_paths} ops fwd={fwd.count()['total']} bwd={bwd.count()['total']} "
+              f"second-order={dbl.count()['total']}")
+        print(f"[{tag}] fp64 self-check max|err|/rms: {e64} {d64}")
+        print(f"[{tag}] fp32 emulation  max|err|/rms: {e32} {d32}")
+    return emit_inc(tag, tab, basis, fold, fwd, bwd, dbl)
 
 
 def main(argv=None) -> int:

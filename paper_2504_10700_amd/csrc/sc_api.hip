@@ -239,13 +239,13 @@ sc_status sc_profile_enable(sc_plan* plan, int32_t on) {
   DeviceGuard guard(plan->cfg.device);
   if (!guard.ok) return fail(SC_ERR_HIP, "sc_profile_enable: cannot make the plan's device current");
   if (on && !plan->ev[0]) {
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 6; ++i) {
       const hipError_t e = hipEventCreate(&plan->ev[i]);
       if (e != hipSuccess) return fail_hip(e, "sc_profile_enable: hipEventCreate");
     }
   }
   plan->profile = on != 0;
-  plan->ev_used[0] = plan->ev_used[1] = false;
+  plan->ev_used[0] = plan->ev_used[1] = plan->ev_used[2] = false;
   return SC_OK;
 }
 
@@ -262,10 +262,20 @@ sc_status sc_profile_read(sc_plan* plan, float* forward_ms, float* backward_ms) 
   return SC_OK;
 }
 
+sc_status sc_profile_read_double_backward(sc_plan* plan, float* ms) {
+  if (!plan || !ms) return fail(SC_ERR_INVALID_ARG, "sc_profile_read_double_backward: NULL argument");
+  *ms = -1.0f;
+  if (!plan->ev_used[2]) return SC_OK;
+  hipError_t e = hipEventSynchronize(plan->ev[5]);
+  if (e == hipSuccess) e = hipEventElapsedTime(ms, plan->ev[4], plan->ev[5]);
+  if (e != hipSuccess) return fail_hip(e, "sc_profile_read_double_backward");
+  return SC_OK;
+}
+
 sc_status sc_plan_destroy(sc_plan* plan) {
   if (!plan) return SC_OK;
   sc_status st = SC_OK;
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 6; ++i)
     if (plan->ev[i]) (void)hipEventDestroy(plan->ev[i]);
   if (plan->dev_blob) {
     DeviceGuard guard(plan->cfg.device);
@@ -403,6 +413,51 @@ sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32
   e = plan->specialised ? sc::launch_spec_finalize(plan, dW, ws, shape, stream)
                         : sc::launch_finalize(plan, dW, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_backward: finalize launch");
+  return SC_OK;
+}
+
+sc_status sc_double_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W,
+                             const void* dB, const void* H, void* ddB, void* dA2, void* dW2, void* workspace,
+                             size_t workspace_bytes, uint32_t flags, void* hip_stream) {
+  sc::LaunchShape shape;
+  sc::Workspace ws;
+  sc_status st = check_common("sc_double_backward", plan, n_nodes, workspace, workspace_bytes, &shape, &ws);
+  if (st != SC_OK) return st;
+  if (!dW2) return fail(SC_ERR_INVALID_ARG, "sc_double_backward: dW2 is NULL");
+  if (misaligned(dW2, 16)) return fail(SC_ERR_INVALID_ARG, "sc_double_backward: dW2 not 16-byte aligned");
+  DeviceGuard guard(plan->cfg.device);
+  if (!guard.ok) return fail(SC_ERR_HIP, "sc_double_backward: cannot make the plan's device current");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (n_nodes == 0) {
+    const size_t words = elem_size(plan) / 4 * static_cast<size_t>(plan->cfg.num_elements) *
+                         plan->table.paths.size() * plan->cfg.num_channels;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, stream, static_cast<unsigned int*>(dW2), words);
+    const hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return fail_hip(e0, "sc_double_backward: fill launch");
+    return SC_OK;
+  }
+  if (!A || !z || !W || !dB || !H || !ddB || !dA2)
+    return fail(SC_ERR_INVALID_ARG, "sc_double_backward: NULL tensor argument");
+  if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(H, 16) || misaligned(ddB, 16) ||
+      misaligned(dA2, 16) || misaligned(z, 4))
+    return fail(SC_ERR_INVALID_ARG, "sc_double_backward: tensor pointer not 16-byte aligned");
+  hipError_t e = hipSuccess;
+  if (!(flags & SC_REUSE_GROUPING)) {
+    e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
+    if (e != hipSuccess) return fail_hip(e, "sc_double_backward: grouping launch");
+  }
+  if (plan->profile) (void)hipEventRecord(plan->ev[4], stream);
+  e = plan->specialised
+          ? sc::launch_spec_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape, stream)
+          : sc::launch_generic_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape, stream);
+  if (e != hipSuccess) return fail_hip(e, "sc_double_backward: kernel launch");
+  if (plan->profile) {
+    (void)hipEventRecord(plan->ev[5], stream);
+    plan->ev_used[2] = true;
+  }
+  e = plan->specialised ? sc::launch_spec_finalize(plan, dW2, ws, shape, stream)
+                        : sc::launch_finalize(plan, dW2, ws, shape, stream);
+  if (e != hipSuccess) return fail_hip(e, "sc_double_backward: finalize launch");
   return SC_OK;
 }
 

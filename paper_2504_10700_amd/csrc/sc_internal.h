@@ -62,10 +62,11 @@ struct sc_plan {
   int specialised = 0;          // 0 = generic, else id of a generated kernel
   int S = 0;                    // size of the internal path basis
   int num_cus = 256;
-  // optional kernel timing (sc_profile_enable): [fwd start, fwd stop, bwd start, bwd stop]
+  // optional kernel timing (sc_profile_enable): start/stop pairs of the forward, backward and
+  // second-order main kernels
   bool profile = false;
-  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
-  bool ev_used[2] = {false, false};
+  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  bool ev_used[3] = {false, false, false};
   // device copies
   void* dev_blob = nullptr;
   sc::GenericTables gen{};
@@ -84,6 +85,9 @@ hipError_t launch_generic_forward(const sc_plan* plan, int64_t n, const void* A,
 hipError_t launch_generic_backward(const sc_plan* plan, int64_t n, const void* A, const void* W,
                                    const void* dB, void* dA, const Workspace& ws, const LaunchShape& shape,
                                    hipStream_t stream);
+hipError_t launch_generic_double_backward(const sc_plan* plan, int64_t n, const void* A, const void* W,
+                                          const void* dB, const void* H, void* ddB, void* dA2,
+                                          const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
 hipError_t launch_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
                            hipStream_t stream);
 

@@ -15,6 +15,9 @@ hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, co
                                const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
 hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,
                                 void* dA, const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
+hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t n, const void* A, const void* W,
+                                       const void* dB, const void* H, void* ddB, void* dA2, const Workspace& ws,
+                                       const LaunchShape& shape, hipStream_t stream);
 
 // dW reduction over the tiles of every element and unfold to the external paths.
 hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,

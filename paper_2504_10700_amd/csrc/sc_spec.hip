@@ -212,6 +212,66 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
   }
 }
 
+// Second-order pass: the backward skeleton with one more input row (H) and one more output
+// row (ddB) per node; its dW2' rows leave through the same per-tile partial rows.
+template <typename T, typename G>
+__global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
+    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
+    const T* __restrict__ H, T* __restrict__ ddB, T* __restrict__ dA2, T* __restrict__ partial,
+    const TileDesc* __restrict__ tiles, const int32_t* __restrict__ perm) {
+  extern __shared__ unsigned char lds_raw[];
+  T* red = reinterpret_cast<T*>(lds_raw);  // [kSpecWaves][kS][64]
+  T* stage = red + kSpecWaves * G::kS * kLanes + wave_of_thread() * kLanes * G::kNlm;  // [64][kNlm] per wave
+  constexpr bool kStageB = G::kNLM * sizeof(T) != 16;
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int logical = xcd_contiguous_block();
+  if (logical >= n_blocks) return;  // uniform per workgroup
+  const int tile = logical / chblocks, cb = logical % chblocks;
+  const TileDesc td = tiles[tile];
+  if (td.count == 0) return;        // unused descriptor; uniform per workgroup
+  const int j0 = td.start + td.count * wave / kSpecWaves;
+  const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
+  const int ch = cb * kLanes + lane;
+  T dw[G::kS];
+#pragma unroll
+  for (int s = 0; s < G::kS; ++s) dw[s] = T(0);
+  if (j0 < j1) {
+    T w[G::kS];
+    G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w);
+    // one register set of inputs: the next node's rows are requested right after the
+    // arithmetic of the current one has consumed them, ahead of its stores
+    T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
+    size_t node = perm[j0];
+    Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+    Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+    Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+    for (int j = j0; j < j1; ++j) {
+      G::double_backward(a, w, g, h, ddb, da, dw);
+      const size_t cur = node;
+      if (j + 1 < j1) {
+        node = perm[j + 1];
+        Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+        Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+        Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+      }
+      store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da);
+      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb);
+      else Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < G::kS; ++s) red[(wave * G::kS + s) * kLanes + lane] = dw[s];
+  __syncthreads();
+  T* out = partial + (static_cast<size_t>(tile) * chblocks + cb) * G::kS * kLanes;
+  for (int i = threadIdx.x; i < G::kS * kLanes; i += kSpecThreads) {
+    T acc = red[i];
+#pragma unroll
+    for (int v = 1; v < kSpecWaves; ++v) acc += red[v * G::kS * kLanes + i];
+    out[i] = acc;
+  }
+}
+
 // Second stage of the dW reduction, two small launches (device-scope fences, which a
 // single-launch "last wave finishes the job" scheme needs, flush the per-XCD L2s and cost
 // far more than a launch on this chip).
@@ -324,6 +384,24 @@ hipError_t bwd_launch(const sc_plan* plan, const void* A, const void* W, const v
 }
 
 template <typename T, typename G>
+hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const void* dB, const void* H, void* ddB,
+                      void* dA2, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
+  const int n_blocks = shape.max_tiles * shape.chblocks;
+  const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
+  const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
+  if (lds > 64 * 1024) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&spec_double_backward_kernel<T, G>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((spec_double_backward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
+                     plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
+                     static_cast<const T*>(W), static_cast<const T*>(dB), static_cast<const T*>(H),
+                     static_cast<T*>(ddB), static_cast<T*>(dA2), static_cast<T*>(ws.partial), ws.tiles, ws.perm);
+  return hipGetLastError();
+}
+
+template <typename T, typename G>
 hipError_t finalize_launch(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
                            hipStream_t stream) {
   const int Z = plan->cfg.num_elements;
@@ -367,6 +445,19 @@ hipError_t launch_spec_backward(const sc_plan* plan, int64_t, const void* A, con
   if (plan->specialised == 2)
     return f64 ? bwd_launch<double, Gen_l3n3_0e1o2e>(plan, A, W, dB, dA, ws, shape, stream)
                : bwd_launch<float, Gen_l3n3_0e1o2e>(plan, A, W, dB, dA, ws, shape, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t, const void* A, const void* W, const void* dB,
+                                       const void* H, void* ddB, void* dA2, const Workspace& ws,
+                                       const LaunchShape& shape, hipStream_t stream) {
+  const bool f64 = plan->cfg.dtype == SC_F64;
+  if (plan->specialised == 1)
+    return f64 ? dbl_launch<double, Gen_l3n3_0e1o>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream)
+               : dbl_launch<float, Gen_l3n3_0e1o>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream);
+  if (plan->specialised == 2)
+    return f64 ? dbl_launch<double, Gen_l3n3_0e1o2e>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream)
+               : dbl_launch<float, Gen_l3n3_0e1o2e>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream);
   return hipErrorInvalidValue;
 }
 

@@ -117,3 +117,10 @@ def make_inputs(wl: Workload, paths: Sequence[Sequence[int]], num_nodes: Optiona
     W = rng.standard_normal((wl.num_elements, P, wl.num_channels)) * scale[None, :, None]
     dB = rng.standard_normal((N, wl.num_channels, wl.n_LM))
     return Inputs(A=A, z=z, W=W, dB=dB, structure_sizes=sizes)
+
+
+def make_cotangent(wl: Workload, num_nodes: Optional[int] = None) -> np.ndarray:
+    """H, the cotangent of dA for the second-order pass: N(0,1) of the shape of A, fp64,
+    from its own stream default_rng(seed + 7919) so that make_inputs stays unchanged."""
+    N = wl.num_nodes if num_nodes is None else num_nodes
+    return np.random.default_rng(wl.seed + 7919).standard_normal((N, wl.num_channels, wl.n_lm))

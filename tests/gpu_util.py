@@ -64,6 +64,18 @@ class GpuRun:
         self.torch.cuda.synchronize()
         return self.dA.cpu().numpy(), self.dW.cpu().numpy()
 
+    def double_backward(self, H, flags=0):
+        """H: numpy array of the shape of A.  Returns (ddB, dA2, dW2, H as computed in fp64)."""
+        torch = self.torch
+        Hd = torch.tensor(H, dtype=self.tdt, device=self.dev)
+        ddB = torch.full_like(self.B, float("nan"))
+        dA2 = torch.full_like(self.A, float("nan"))
+        dW2 = torch.full_like(self.W, float("nan"))
+        self.sc.sc_double_backward(self.plan, self.N, self.A, self.z, self.W, self.dB, Hd, ddB, dA2, dW2, self.ws,
+                                   self.ws_bytes, flags)
+        torch.cuda.synchronize()
+        return ddB.cpu().numpy(), dA2.cpu().numpy(), dW2.cpu().numpy(), Hd.double().cpu().numpy()
+
     def inputs_as_computed(self):
         """The inputs rounded to the run dtype, as fp64 numpy (what the oracle must see)."""
         return (self.A.double().cpu().numpy(), self.z.cpu().numpy(), self.W.double().cpu().numpy(),
