@@ -13,7 +13,8 @@ outputs 0e+1o, fp32, forward+backward) - the configuration the metric "atoms/sec
 symmetric-contraction fwd+bwd (128ch, l<=3, nu=3)" is quoted on.  With the default
 workload the same line also carries, under "also", a shorter measurement of
 `large_batch` (200 000 nodes, same shapes): at 10 000 nodes a step is ~0.1 ms and
-launch / fixed costs weigh as much as the data movement, at 200 000 nodes they do not.
+launch / fixed costs weigh as much as the data movement, at 200 000 nodes they do not;
+and the second-order pass (sc_double_backward alone) on both workloads.
 
 value          nodes (atoms) per second, forward + backward, whole step (all launches)
 roofline       the dominant kernel (fused backward: dA + per-tile dW) against the HBM
@@ -39,6 +40,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+FP32_PEAK_TFLOPS = 157.3   # MI355X vector fp32, published (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 (FMA) x 2 (packed))
+VALU_ISSUE_PEAK = 256 * 4 * 16 * 2.4e9   # per-lane vector instructions per second at the published clock
 METRIC = "atoms/sec symmetric-contraction fwd+bwd (128ch, l<=3, nu=3); % HBM peak"
 
 
@@ -144,6 +147,8 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0):
         k_ms, k_bytes, k_name = fwd_mean, fwd_bytes, "forward"
     achieved = k_bytes / (k_ms * 1e-3) / 1e9
     step_bytes = fwd_bytes + (bwd_bytes if wl.backward else 0)
+    k_ops = info.ops[1 if wl.backward else 0]     # 0 for the table-driven kernels
+    valu_issue_frac = N * K * k_ops / (k_ms * 1e-3) / VALU_ISSUE_PEAK if k_ops else None
 
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
     traffic = None
@@ -163,7 +168,96 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0):
         "step_hbm_fraction": value * (step_bytes / N) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel_ms": k_ms,
-                     "forward_kernel_ms": fwd_mean, "algorithmic_bytes_per_launch": k_bytes},
+                     "forward_kernel_ms": fwd_mean, "algorithmic_bytes_per_launch": k_bytes,
+                     "valu_issue_frac": valu_issue_frac},
+    }
+
+
+def measure_double_backward(wl, steps, warmup, tile_nodes=0):
+    """The second-order pass alone: one step = sc_double_backward (grouping included)."""
+    import numpy as np
+    import torch
+    from paper_2504_10700_amd import binding as sc
+    from paper_2504_10700_amd import workloads
+
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if wl.dtype == "f32" else torch.float64
+    elem = 4 if wl.dtype == "f32" else 8
+    plan = sc.sc_plan_create(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps,
+                             sc.SC_F32 if wl.dtype == "f32" else sc.SC_F64, 0, 0, tile_nodes)
+    info = sc.sc_plan_info(plan)
+    inp = workloads.make_inputs(wl, sc.sc_plan_paths(plan))
+    N, K = wl.num_nodes, wl.num_channels
+    per_set = N * K * (3 * wl.n_lm + 2 * wl.n_LM) * elem
+    n_sets = max(2, min(8, int(np.ceil(1.0e9 / per_set))))
+    A0 = torch.tensor(inp.A, dtype=tdt, device=dev)
+    dB0 = torch.tensor(inp.dB, dtype=tdt, device=dev)
+    H0 = torch.tensor(workloads.make_cotangent(wl), dtype=tdt, device=dev)
+    W = torch.tensor(inp.W, dtype=tdt, device=dev)
+    z = torch.tensor(inp.z, dtype=torch.int32, device=dev)
+    del inp
+    sets = []
+    for s in range(n_sets):
+        sets.append({
+            "A": A0 if s == 0 else A0.roll(s, 0).contiguous(),
+            "dB": dB0 if s == 0 else dB0.roll(s, 0).contiguous(),
+            "H": H0 if s == 0 else H0.roll(s, 0).contiguous(),
+            "ddB": torch.empty((N, K, wl.n_LM), dtype=tdt, device=dev),
+            "dA2": torch.empty((N, K, wl.n_lm), dtype=tdt, device=dev),
+        })
+    dW2 = torch.empty_like(W)
+    ws_bytes = sc.sc_workspace_bytes(plan, N)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step(i):
+        b = sets[i % n_sets]
+        sc.sc_double_backward(plan, N, b["A"], z, W, b["dB"], b["H"], b["ddB"], b["dA2"], dW2, ws, ws_bytes, 0)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    sc.sc_profile_enable(plan, True)
+    k_ms = []
+    for i in range(min(steps, 50)):
+        step(i)
+        k_ms.append(sc.sc_profile_read_double_backward(plan))
+    sc.sc_profile_enable(plan, False)
+    sc.sc_plan_destroy(plan)
+    k_ms = float(np.mean(k_ms))
+    k_bytes = N * K * (3 * wl.n_lm + 2 * wl.n_LM) * elem   # A, H, dB in; dA2, ddB out
+    achieved = k_bytes / (k_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath) and info.specialised and tile_nodes == 0:
+        ent = json.load(open(tpath)).get("double_backward:" + wl.name)
+        if ent:
+            traffic = 1024.0 * (ent["fetch_kib"] * ent["fetch_scale"] + ent["write_kib"] * ent["write_scale"])
+    # The second-order kernel needs more time on the vector ALUs than on HBM (see "alu"):
+    # both figures are reported, the larger fraction names the bound.
+    hbm = {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+           "traffic": traffic, "algorithmic_bytes_per_launch": k_bytes}
+    if info.specialised and wl.dtype == "f32":
+        tflops = N * K * info.flops[2] / (k_ms * 1e-3) / 1e12
+        roof = {"bound": "alu", "kernel": "double backward (ddB + dA2 + per-tile dW2)", "achieved": tflops,
+                "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / FP32_PEAK_TFLOPS, "traffic": traffic,
+                "kernel_ms": k_ms, "flops_per_node_channel": int(info.flops[2]),
+                "valu_issue_frac": N * K * info.ops[2] / (k_ms * 1e-3) / VALU_ISSUE_PEAK, "hbm": hbm}
+    else:
+        roof = dict(hbm, bound="hbm", kernel="double backward (ddB + dA2 + per-tile dW2)", kernel_ms=k_ms)
+    del sets, A0, dB0, H0, ws
+    torch.cuda.empty_cache()
+    return {
+        "value": N / (dt / steps), "unit": "nodes/s", "steps": steps, "warmup": warmup,
+        "ms_per_step": dt / steps * 1e3, "dtype": wl.dtype,
+        "config": {"workload": describe(wl).replace("forward+backward", "second-order pass only"),
+                   "kernel": "generated" if info.specialised else "table-driven", "buffer_sets_rotated": n_sets,
+                   "tile_nodes": tile_nodes},
+        "roofline": roof,
     }
 
 
@@ -176,7 +270,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=1024, help="nodes the oracle is timed on (0 = skip)")
     ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
     ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
-    ap.add_argument("--no-also", action="store_true", help="skip the extra large_batch measurement")
+    ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
+    ap.add_argument("--double-backward", action="store_true",
+                    help="measure only the second-order pass of --workload and print its object")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -186,6 +282,9 @@ def main():
     from paper_2504_10700_amd import workloads
 
     wl = workloads.WORKLOADS[args.workload]
+    if args.double_backward:
+        print(json.dumps(measure_double_backward(wl, args.steps, args.warmup, args.tile_nodes)))
+        return
     m = measure(wl, args.steps, args.warmup, args.generic, args.tile_nodes)
     out = {"metric": METRIC, "value": m["value"], "unit": m["unit"], "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
@@ -198,6 +297,8 @@ def main():
         out["also"] = {"large_batch": {k: big[k] for k in
                                        ("value", "unit", "steps", "warmup", "ms_per_step", "config",
                                         "step_hbm_fraction", "roofline")}}
+        out["also"]["double_backward_training_step"] = measure_double_backward(wl, 100, 10)
+        out["also"]["double_backward_large_batch"] = measure_double_backward(workloads.WORKLOADS["large_batch"], 20, 3)
     print(json.dumps(out))
 
 

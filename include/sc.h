@@ -99,6 +99,11 @@ typedef struct {
   int32_t n_LM;        /* sum of (2L+1) over the output irreps                     */
   int32_t num_paths;   /* P: second extent of W and dW                             */
   int32_t specialised; /* 1 if a generated straight-line kernel serves this plan   */
+  /* generated kernels only (else 0): vector instructions and floating-point operations
+   * (a fused multiply-add counts as two) per (node, channel) of the forward, backward and
+   * second-order main kernels, for roofline accounting */
+  int32_t ops[3];
+  int32_t flops[3];
 } sc_info;
 
 /* Section 4.1, inputs of Algorithm 2: fixes K, l_max, nu_max, the element range and

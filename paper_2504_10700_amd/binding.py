@@ -40,7 +40,8 @@ class sc_config(C.Structure):
 
 
 class sc_info(C.Structure):
-    _fields_ = [("n_lm", C.c_int32), ("n_LM", C.c_int32), ("num_paths", C.c_int32), ("specialised", C.c_int32)]
+    _fields_ = [("n_lm", C.c_int32), ("n_LM", C.c_int32), ("num_paths", C.c_int32), ("specialised", C.c_int32),
+                ("ops", C.c_int32 * 3), ("flops", C.c_int32 * 3)]
 
 
 class ScError(RuntimeError):

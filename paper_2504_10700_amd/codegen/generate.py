@@ -334,6 +334,13 @@ def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program, dbl
     L.append(f"  static constexpr int kNlm = {tab.n_lm}, kNLM = {tab.n_LM}, kP = {P}, kS = {S};")
     L.append("  static constexpr int kOutL[kNumOut] = {" + ", ".join(str(l) for l, _ in tab.outs) + "};")
     L.append("  static constexpr int kOutParity[kNumOut] = {" + ", ".join(str(p) for _, p in tab.outs) + "};")
+
+    def flops(c):
+        return 2 * (c.get("fma", 0) + c.get("fnma", 0) + c.get("cfma", 0)) + sum(c.get(k, 0) for k in ("mul", "add", "sub", "cmul"))
+    L.append("  // VALU instructions and floating-point operations (a fused multiply-add counts twice) per")
+    L.append("  // (node, channel) of forward, backward and the second-order pass.")
+    L.append(f"  static constexpr int kOps[3] = {{{fc['total']}, {bc['total']}, {dc['total']}}};")
+    L.append(f"  static constexpr int kFlops[3] = {{{flops(fc)}, {flops(bc)}, {flops(dc)}}};")
     L.append("")
     L.append("  // w'[s] = sum_p F[s,p] * W[z,p,k]; Wz points at W[z,0,k], consecutive paths are K apart.")
     L.append("  template <typename T>")

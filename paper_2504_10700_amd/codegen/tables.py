@@ -41,7 +41,7 @@ class Tables:
         cfg.dtype, cfg.device, cfg.flags = 1, 0, 1 | 2      # f64, host only, generic
         self.plan = C.c_void_p()
         self._check(self.lib.sc_plan_create(C.byref(cfg), C.byref(self.plan)))
-        info = (C.c_int32 * 4)()
+        info = (C.c_int32 * 10)()   # sc_info: four counts, then ops[3] and flops[3]
         self._check(self.lib.sc_plan_info(self.plan, info))
         self.n_lm, self.n_LM, self.num_paths = info[0], info[1], info[2]
         paths = np.zeros((self.num_paths, 6), dtype=np.int32)

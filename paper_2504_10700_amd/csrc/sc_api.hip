@@ -292,6 +292,7 @@ sc_status sc_plan_info(const sc_plan* plan, sc_info* out) {
   out->n_LM = plan->table.n_LM;
   out->num_paths = static_cast<int32_t>(plan->table.paths.size());
   out->specialised = plan->specialised ? 1 : 0;
+  sc::spec_op_counts(plan->specialised, out->ops, out->flops);
   return SC_OK;
 }
 

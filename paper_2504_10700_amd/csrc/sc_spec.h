@@ -8,6 +8,8 @@ namespace sc {
 int spec_lookup(const sc_plan* plan);
 // Size of the internal (reduced) path basis of a generated kernel.
 int spec_basis_size(int id);
+// VALU instructions (ops) and flops per (node, channel) of forward, backward, second-order pass.
+void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]);
 // Waves per workgroup (= per tile) of the generated kernels.
 int spec_waves_per_tile();
 

@@ -422,6 +422,20 @@ int spec_lookup(const sc_plan* plan) {
 
 int spec_basis_size(int id) { return id == 1 ? Gen_l3n3_0e1o::kS : id == 2 ? Gen_l3n3_0e1o2e::kS : 0; }
 
+template <typename G>
+void op_counts(int32_t ops[3], int32_t flops[3]) {
+  for (int i = 0; i < 3; ++i) {
+    ops[i] = G::kOps[i];
+    flops[i] = G::kFlops[i];
+  }
+}
+
+void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
+  for (int i = 0; i < 3; ++i) ops[i] = flops[i] = 0;
+  if (id == 1) op_counts<Gen_l3n3_0e1o>(ops, flops);
+  if (id == 2) op_counts<Gen_l3n3_0e1o2e>(ops, flops);
+}
+
 int spec_waves_per_tile() { return kSpecWaves; }
 
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t, const void* A, const void* W, void* B,
