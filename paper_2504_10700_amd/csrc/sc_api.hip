@@ -51,6 +51,8 @@ bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p)
 
 namespace sc {
 
+sc_status set_error(sc_status code, const std::string& msg) { return fail(code, msg); }
+
 LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
   LaunchShape s{};
   s.chblocks = (plan->cfg.num_channels + kLanes - 1) / kLanes;

@@ -4,6 +4,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <string>
 #include <vector>
 
 #include "../../include/sc.h"
@@ -73,6 +74,9 @@ struct sc_plan {
 };
 
 namespace sc {
+
+// Records the calling thread's error message (what sc_last_error returns) and returns code.
+sc_status set_error(sc_status code, const std::string& msg);
 
 LaunchShape launch_shape(const sc_plan* plan, int64_t n_nodes);
 Workspace carve_workspace(const sc_plan* plan, int64_t n_nodes, const LaunchShape& shape, void* base);

@@ -1,0 +1,76 @@
+// Internal declarations of the channelwise tensor product (Algorithm 1 of arXiv 2504.10700).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <array>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/tp.h"
+#include "sc_internal.h"
+
+namespace tp {
+
+struct Term {  // msg[c] += coef * R[p] * Y[a] * h[b]
+  int p, a, b, c;
+  double coef;
+};
+
+// Device view of the sparse coupling terms, sorted by (path, c, a, b).
+struct TermTable {
+  int32_t n_terms, num_paths, n_Y, n_h, n_out;
+  const int4* idx;      // (p, a, b, c)
+  const double* coef;
+};
+
+struct Shape {
+  int chblocks;  // ceil(K / 64)
+};
+
+}  // namespace tp
+
+struct tp_plan {
+  tp_config cfg;
+  std::vector<std::array<int, 3>> paths;
+  std::vector<tp::Term> terms;
+  bool host_only = false;
+  int specialised = 0;
+  int n_Y = 0, n_h = 0, n_out = 0;
+  bool profile = false;
+  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  bool ev_used[3] = {false, false, false};
+  void* dev_blob = nullptr;
+  tp::TermTable tab{};
+};
+
+namespace tp {
+
+struct FwdArgs {
+  int64_t n_in, n_out_nodes, n_edges;
+  const void *Y, *h, *R;
+  const int32_t *sender, *row_ptr;
+  void* A;
+};
+
+struct BwdArgs {
+  int64_t n_in, n_out_nodes, n_edges;
+  const void *Y, *h, *R;
+  const int32_t *sender, *receiver, *row_ptr, *send_ptr, *send_edge;
+  const void* dA;
+  void *dY, *dh, *dR;
+  void* dY_partial;  // [chblocks][n_edges][n_Y] of the plan's dtype
+};
+
+hipError_t launch_generic_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream);
+hipError_t launch_generic_backward_recv(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_generic_backward_send(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_dY_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
+
+// generated kernels (tp_spec.hip)
+int spec_lookup(const tp_plan* plan);
+void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]);
+hipError_t launch_spec_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream);
+hipError_t launch_spec_backward_recv(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_spec_backward_send(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
+
+}  // namespace tp

@@ -124,3 +124,93 @@ def make_cotangent(wl: Workload, num_nodes: Optional[int] = None) -> np.ndarray:
     from its own stream default_rng(seed + 7919) so that make_inputs stays unchanged."""
     N = wl.num_nodes if num_nodes is None else num_nodes
     return np.random.default_rng(wl.seed + 7919).standard_normal((N, wl.num_channels, wl.n_lm))
+
+
+# ---------------------------------------------------------------------------------------
+# Channelwise tensor product (Algorithm 1): a graph, per-edge Y and R, per-node h.
+#
+# The paper's graphs come from a 4 Angstrom cutoff on molecules, liquids and crystals
+# (Evaluation, dataset description): a few to a few tens of neighbours per atom.  The
+# stand-in draws the in-degree of every atom from Poisson(mean_degree) (clipped to
+# 4 * mean_degree, and about 1% of the atoms receive nothing), senders uniformly among the
+# other atoms, edges grouped by receiver as neighbour lists are.  Y, h, dA ~ N(0,1) (the
+# components of spherical harmonics in the usual "component" normalisation have unit rms);
+# R ~ N(0,1) / sqrt(mean_degree * #paths into the same l3) so that A is O(1).
+
+@dataclass(frozen=True)
+class TPWorkload:
+    name: str
+    num_nodes: int
+    mean_degree: int
+    num_channels: int
+    l_Y: int
+    l_h: int
+    L_max: int
+    dtype: str
+    seed: int
+
+    @property
+    def n_Y(self) -> int:
+        return (self.l_Y + 1) ** 2
+
+    @property
+    def n_h(self) -> int:
+        return (self.l_h + 1) ** 2
+
+    @property
+    def n_out(self) -> int:
+        return (self.L_max + 1) ** 2
+
+
+TP_WORKLOADS = {
+    "tp_tiny": TPWorkload("tp_tiny", 40, 5, 8, 1, 1, 1, "f64", 4001),
+    "tp_first_layer": TPWorkload("tp_first_layer", 10_000, 20, 128, 3, 0, 3, "f32", 4002),
+    "tp_training_step": TPWorkload("tp_training_step", 10_000, 20, 128, 3, 1, 3, "f32", 4003),
+}
+
+
+@dataclass
+class TPInputs:
+    Y: np.ndarray          # (E, n_Y)
+    h: np.ndarray          # (N, K, n_h)
+    R: np.ndarray          # (E, P, K)
+    dA: np.ndarray         # (N, K, n_out)
+    sender: np.ndarray     # (E,) int32
+    receiver: np.ndarray   # (E,) int32, ascending
+    row_ptr: np.ndarray    # (N+1,) int32: edges received by node i are row_ptr[i]..row_ptr[i+1]
+    send_ptr: np.ndarray   # (N+1,) int32
+    send_edge: np.ndarray  # (E,) int32: edge ids grouped by sender, ascending within a sender
+
+
+def graph_indices(sender: np.ndarray, receiver: np.ndarray, num_nodes: int):
+    """row_ptr, send_ptr, send_edge for edges already grouped by receiver."""
+    row_ptr = np.zeros(num_nodes + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum(np.bincount(receiver, minlength=num_nodes))
+    send_ptr = np.zeros(num_nodes + 1, dtype=np.int32)
+    send_ptr[1:] = np.cumsum(np.bincount(sender, minlength=num_nodes))
+    send_edge = np.argsort(sender, kind="stable").astype(np.int32)
+    return row_ptr, send_ptr, send_edge
+
+
+def make_tp_inputs(wl: TPWorkload, paths: Sequence[Sequence[int]]) -> TPInputs:
+    """Draws the graph, then Y, h, R, dA (in that order) in fp64 from default_rng(seed).
+    `paths`: the caller's path table, rows (l1, l2, l3), used only to count the paths per l3."""
+    rng = np.random.default_rng(wl.seed)
+    N = wl.num_nodes
+    deg = np.minimum(rng.poisson(wl.mean_degree, size=N), 4 * wl.mean_degree)
+    deg[rng.random(N) < 0.01] = 0
+    if N == 1:
+        deg[:] = 0
+    receiver = np.repeat(np.arange(N, dtype=np.int32), deg)
+    E = int(receiver.size)
+    sender = rng.integers(0, max(N - 1, 1), size=E).astype(np.int32)
+    sender += (sender >= receiver).astype(np.int32)      # never the receiver itself
+    paths = np.asarray(paths, dtype=np.int64).reshape(-1, 3)
+    per_l3 = np.bincount(paths[:, 2], minlength=wl.L_max + 1)
+    scale = 1.0 / np.sqrt(max(wl.mean_degree, 1) * per_l3[paths[:, 2]])
+    Y = rng.standard_normal((E, wl.n_Y))
+    h = rng.standard_normal((N, wl.num_channels, wl.n_h))
+    R = rng.standard_normal((E, paths.shape[0], wl.num_channels)) * scale[None, :, None]
+    dA = rng.standard_normal((N, wl.num_channels, wl.n_out))
+    row_ptr, send_ptr, send_edge = graph_indices(sender, receiver, N)
+    return TPInputs(Y, h, R, dA, sender, receiver, row_ptr, send_ptr, send_edge)

@@ -1,0 +1,185 @@
+"""Parity of the channelwise tensor product (tp_forward / tp_backward through the C ABI) with
+the fp64 CPU oracle of Algorithm 1.  Tolerances as for the contraction: fp32
+max|err|/rms(ref) <= 1e-5 per output tensor, fp64 max(|err| / max(|ref|, rms(ref))) <= 1e-12.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import channelwise_tp as otp
+from paper_2504_10700_amd import workloads
+from gpu_util import check
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tp():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2504_10700_amd import tp_binding
+    return tp_binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+class TPRun:
+    def __init__(self, tp, wl, inp, flags=0):
+        import torch
+        self.tp, self.wl, self.torch = tp, wl, torch
+        dev = torch.device("cuda:0")
+        self.tdt = torch.float32 if wl.dtype == "f32" else torch.float64
+        self.plan = tp.tp_plan_create(wl.num_channels, wl.l_Y, wl.l_h, wl.L_max,
+                                      tp.SC_F32 if wl.dtype == "f32" else tp.SC_F64, 0, flags)
+        self.N, self.E = inp.h.shape[0], inp.Y.shape[0]
+        f = lambda x: torch.tensor(x, dtype=self.tdt, device=dev)
+        i = lambda x: torch.tensor(x, dtype=torch.int32, device=dev)
+        self.Y, self.h, self.R, self.dA = f(inp.Y), f(inp.h), f(inp.R), f(inp.dA)
+        self.sender, self.receiver, self.row_ptr = i(inp.sender), i(inp.receiver), i(inp.row_ptr)
+        self.send_ptr, self.send_edge = i(inp.send_ptr), i(inp.send_edge)
+        self.A = torch.full((self.N, wl.num_channels, wl.n_out), float("nan"), dtype=self.tdt, device=dev)
+        self.dY, self.dh, self.dR = (torch.full_like(x, float("nan")) for x in (self.Y, self.h, self.R))
+        self.ws_bytes = tp.tp_workspace_bytes(self.plan, self.E)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+
+    def forward(self):
+        self.tp.tp_forward(self.plan, self.N, self.N, self.E, self.Y, self.h, self.R, self.sender, self.row_ptr, self.A)
+        self.torch.cuda.synchronize()
+        return self.A.cpu().numpy()
+
+    def backward(self):
+        self.tp.tp_backward(self.plan, self.N, self.N, self.E, self.Y, self.h, self.R, self.sender, self.receiver,
+                            self.row_ptr, self.send_ptr, self.send_edge, self.dA, self.dY, self.dh, self.dR, self.ws,
+                            self.ws_bytes)
+        self.torch.cuda.synchronize()
+        return self.dY.cpu().numpy(), self.dh.cpu().numpy(), self.dR.cpu().numpy()
+
+    def inputs_as_computed(self):
+        return tuple(x.double().cpu().numpy() for x in (self.Y, self.h, self.R, self.dA))
+
+    def close(self):
+        self.tp.tp_plan_destroy(self.plan)
+
+
+def oracle_cfg(wl):
+    return otp.TPConfig(wl.num_channels, wl.l_Y, wl.l_h, wl.L_max)
+
+
+def full_parity(tp, wl, flags=0, mutate=None):
+    say(f"case {wl.name}: N={wl.num_nodes} deg~{wl.mean_degree} K={wl.num_channels} "
+        f"l=({wl.l_Y},{wl.l_h},{wl.L_max}) {wl.dtype} flags={flags}")
+    cfg = oracle_cfg(wl)
+    paths = otp.enumerate_paths(cfg)
+    inp = workloads.make_tp_inputs(wl, paths)
+    if mutate:
+        mutate(inp)
+    run = TPRun(tp, wl, inp, flags)
+    assert [tuple(r) for r in tp.tp_plan_paths(run.plan).tolist()] == paths
+    Y, h, R, dA = run.inputs_as_computed()
+    A = run.forward()
+    check("A", A, otp.forward(cfg, Y, h, R, inp.sender, inp.receiver, run.N), wl.dtype)
+    no_edges = np.nonzero(np.diff(inp.row_ptr) == 0)[0]
+    assert not A[no_edges].any(), "atoms without incoming edges must get exact zeros"
+    dY, dh, dR = run.backward()
+    dY_ref, dh_ref, dR_ref = otp.backward(cfg, Y, h, R, inp.sender, inp.receiver, dA)
+    check("dY", dY, dY_ref, wl.dtype)
+    check("dh", dh, dh_ref, wl.dtype)
+    check("dR", dR, dR_ref, wl.dtype)
+    silent = np.nonzero(np.diff(inp.send_ptr) == 0)[0]
+    assert not dh[silent].any(), "atoms that send nothing must get exact zeros in dh"
+    # bitwise reproducible
+    A2 = run.forward()
+    again = run.backward()
+    assert np.array_equal(A, A2) and all(np.array_equal(x, y) for x, y in zip((dY, dh, dR), again))
+    info = tp.tp_plan_info(run.plan)
+    run.close()
+    return info
+
+
+def wl_of(name, N, deg, K, l_Y, l_h, L_max, dtype, seed):
+    return workloads.TPWorkload(name, N, deg, K, l_Y, l_h, L_max, dtype, seed)
+
+
+@pytest.mark.parametrize("flags", [0, 2])
+def test_tiny_config_fp64(tp, flags):
+    full_parity(tp, workloads.TP_WORKLOADS["tp_tiny"], flags)
+
+
+@pytest.mark.parametrize("flags", [0, 2])
+@pytest.mark.parametrize("dtype", ["f32", "f64"])
+@pytest.mark.parametrize("l_h", [0, 1])
+def test_mace_shapes_small_graph(tp, flags, dtype, l_h):
+    full_parity(tp, wl_of("mace_small", 300, 12, 128, 3, l_h, 3, dtype, 5000 + l_h), flags)
+
+
+@pytest.mark.parametrize("K", [8, 96, 192])
+def test_channel_counts_that_do_not_fill_a_wave(tp, K):
+    full_parity(tp, wl_of(f"k{K}", 60, 6, K, 3, 1, 3, "f32", 5100 + K))
+
+
+@pytest.mark.parametrize("l_Y,l_h,L_max", [(0, 0, 0), (2, 3, 1), (3, 3, 3), (1, 2, 3)])
+def test_other_configurations(tp, l_Y, l_h, L_max):
+    full_parity(tp, wl_of("other", 50, 5, 64, l_Y, l_h, L_max, "f64", 5200))
+
+
+def test_degenerate_graphs(tp):
+    # one node without edges; a star (every edge into node 0); a high-degree tail
+    full_parity(tp, wl_of("one_node", 1, 3, 128, 3, 1, 3, "f32", 5301))
+
+    def star(inp):
+        E = inp.sender.size
+        inp.receiver[:] = 0
+        inp.sender[:] = 1 + np.arange(E) % 29
+        inp.row_ptr[:], inp.send_ptr[:], inp.send_edge[:] = workloads.graph_indices(inp.sender, inp.receiver, 30)
+    full_parity(tp, wl_of("star", 30, 8, 128, 3, 1, 3, "f32", 5302), mutate=star)
+
+
+def test_per_edge_messages_without_pooling(tp):
+    # the literal output of Algorithm 1: every edge is its own output row
+    import torch
+    wl = wl_of("per_edge", 40, 6, 128, 3, 1, 3, "f32", 5401)
+    cfg = oracle_cfg(wl)
+    inp = workloads.make_tp_inputs(wl, otp.enumerate_paths(cfg))
+    run = TPRun(tp, wl, inp)
+    E = run.E
+    ident = torch.arange(E + 1, dtype=torch.int32, device="cuda:0")
+    msg = torch.empty((E, wl.num_channels, wl.n_out), dtype=torch.float32, device="cuda:0")
+    tp.tp_forward(run.plan, run.N, E, E, run.Y, run.h, run.R, run.sender, ident, msg)
+    torch.cuda.synchronize()
+    Y, h, R, _ = run.inputs_as_computed()
+    check("msg", msg.cpu().numpy(), otp.edge_messages(cfg, Y, h, R, inp.sender), "f32")
+    run.close()
+
+
+def test_empty_graph_and_argument_errors(tp):
+    import torch
+    wl = wl_of("err", 20, 4, 128, 3, 1, 3, "f32", 5501)
+    cfg = oracle_cfg(wl)
+    inp = workloads.make_tp_inputs(wl, otp.enumerate_paths(cfg))
+    run = TPRun(tp, wl, inp)
+    # no edges: A and dh are zeroed
+    zeros = torch.zeros(run.N + 1, dtype=torch.int32, device="cuda:0")
+    tp.tp_forward(run.plan, run.N, run.N, 0, None, run.h, None, None, zeros, run.A)
+    tp.tp_backward(run.plan, run.N, run.N, 0, None, run.h, None, None, None, zeros, zeros, None, run.dA, None, run.dh,
+                   None, None, 0)
+    torch.cuda.synchronize()
+    assert not run.A.cpu().numpy().any() and not run.dh.cpu().numpy().any()
+    tp.tp_forward(run.plan, 0, 0, 0, None, None, None, None, None, None)
+    with pytest.raises(tp.ScError) as e:
+        tp.tp_forward(run.plan, run.N, run.N, run.E, run.Y, run.h, None, run.sender, run.row_ptr, run.A)
+    assert e.value.status == 1
+    with pytest.raises(tp.ScError) as e:
+        tp.tp_forward(run.plan, run.N, run.N, run.E, run.Y.data_ptr() + 4, run.h, run.R, run.sender, run.row_ptr, run.A)
+    assert e.value.status == 1
+    with pytest.raises(tp.ScError) as e:
+        tp.tp_backward(run.plan, run.N, run.N, run.E, run.Y, run.h, run.R, run.sender, run.receiver, run.row_ptr,
+                       run.send_ptr, run.send_edge, run.dA, run.dY, run.dh, run.dR, run.ws, 16)
+    assert e.value.status == 3
+    # the plan still works
+    Y, h, R, _ = run.inputs_as_computed()
+    check("A", run.forward(), otp.forward(cfg, Y, h, R, inp.sender, inp.receiver, run.N), "f32")
+    run.close()
