@@ -261,6 +261,83 @@ def measure_double_backward(wl, steps, warmup, tile_nodes=0):
     }
 
 
+def measure_tp(wl, steps, warmup):
+    """Channelwise tensor product (Algorithm 1 with pooling): one step = tp_forward + tp_backward."""
+    import numpy as np
+    import torch
+    from paper_2504_10700_amd import tp_binding as tp
+    from paper_2504_10700_amd import workloads
+
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if wl.dtype == "f32" else torch.float64
+    elem = 4 if wl.dtype == "f32" else 8
+    plan = tp.tp_plan_create(wl.num_channels, wl.l_Y, wl.l_h, wl.L_max, tp.SC_F32 if wl.dtype == "f32" else tp.SC_F64, 0)
+    info = tp.tp_plan_info(plan)
+    inp = workloads.make_tp_inputs(wl, tp.tp_plan_paths(plan))
+    N, K, E, P = wl.num_nodes, wl.num_channels, int(inp.Y.shape[0]), int(info.num_paths)
+    f = lambda x: torch.tensor(x, dtype=tdt, device=dev)
+    i32 = lambda x: torch.tensor(x, dtype=torch.int32, device=dev)
+    Y, h, dA = f(inp.Y), f(inp.h), f(inp.dA)
+    sender, receiver, row_ptr = i32(inp.sender), i32(inp.receiver), i32(inp.row_ptr)
+    send_ptr, send_edge = i32(inp.send_ptr), i32(inp.send_edge)
+    # R and dR are the large tensors (E*P*K): two copies of each are rotated so that a step never
+    # finds the previous step's rows in the 256 MB last-level cache
+    R0 = f(inp.R)
+    del inp
+    Rs = [R0, R0.clone()]
+    dRs = [torch.empty_like(R0), torch.empty_like(R0)]
+    A = torch.empty((N, K, wl.n_out), dtype=tdt, device=dev)
+    dY, dh = torch.empty_like(Y), torch.empty_like(h)
+    ws_bytes = tp.tp_workspace_bytes(plan, E)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step(i):
+        tp.tp_forward(plan, N, N, E, Y, h, Rs[i % 2], sender, row_ptr, A)
+        tp.tp_backward(plan, N, N, E, Y, h, Rs[(i + 1) % 2], sender, receiver, row_ptr, send_ptr, send_edge, dA, dY, dh,
+                       dRs[i % 2], ws, ws_bytes)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tp.tp_profile_enable(plan, True)
+    ms = []
+    for i in range(min(steps, 30)):
+        step(i)
+        ms.append(tp.tp_profile_read(plan))
+    tp.tp_profile_enable(plan, False)
+    tp.tp_plan_destroy(plan)
+    fwd_ms, recv_ms, send_ms = (float(x) for x in np.mean(np.array(ms), axis=0))
+    # algorithmic bytes per launch: the per-edge tensors once each (R, Y, indices; dR, dY out) plus
+    # the per-node tensors once (h / dA in, A / dh out); gathered rows are counted once per node
+    node_in, node_A = N * K * wl.n_h * elem, N * K * wl.n_out * elem
+    fwd_bytes = E * (P * K * elem + wl.n_Y * elem + 4) + node_in + node_A
+    recv_bytes = E * (2 * P * K * elem + 2 * wl.n_Y * elem + 4) + node_in + node_A
+    send_bytes = E * (P * K * elem + wl.n_Y * elem + 8) + node_A + node_in
+    recv_rate = recv_bytes / (recv_ms * 1e-3) / 1e9
+    del Rs, dRs, R0, ws
+    torch.cuda.empty_cache()
+    return {
+        "metric": "edges/sec channelwise tensor product fwd+bwd", "value": E / (dt / steps), "unit": "edges/s",
+        "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3, "dtype": wl.dtype,
+        "config": {"workload": f"{wl.name}: {N} nodes, {E} edges (in-degree ~Poisson({wl.mean_degree})), {K} channels, "
+                               f"l_Y={wl.l_Y}, l_h={wl.l_h}, L_max={wl.L_max}, {P} paths, forward+backward",
+                   "kernel": "generated" if info.specialised else "table-driven"},
+        "step_hbm_fraction": (fwd_bytes + recv_bytes + send_bytes) / (dt / steps) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "backward, receiver side (dR + dY partials)", "achieved": recv_rate,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": recv_rate / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_ms": recv_ms, "algorithmic_bytes_per_launch": recv_bytes,
+                     "forward": {"kernel_ms": fwd_ms, "algorithmic_bytes_per_launch": fwd_bytes,
+                                 "achieved": fwd_bytes / (fwd_ms * 1e-3) / 1e9},
+                     "backward_sender_side": {"kernel_ms": send_ms, "algorithmic_bytes_per_launch": send_bytes,
+                                              "achieved": send_bytes / (send_ms * 1e-3) / 1e9}},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -271,6 +348,8 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
     ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
     ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
+    ap.add_argument("--tp", action="store_true",
+                    help="measure only the channelwise tensor product (--workload tp_training_step|tp_first_layer|tp_tiny)")
     ap.add_argument("--double-backward", action="store_true",
                     help="measure only the second-order pass of --workload and print its object")
     args = ap.parse_args()
@@ -281,6 +360,10 @@ def main():
 
     from paper_2504_10700_amd import workloads
 
+    if args.tp:
+        name = args.workload if args.workload in workloads.TP_WORKLOADS else "tp_training_step"
+        print(json.dumps(measure_tp(workloads.TP_WORKLOADS[name], args.steps, args.warmup)))
+        return
     wl = workloads.WORKLOADS[args.workload]
     if args.double_backward:
         print(json.dumps(measure_double_backward(wl, args.steps, args.warmup, args.tile_nodes)))
@@ -299,6 +382,7 @@ def main():
                                         "step_hbm_fraction", "roofline")}}
         out["also"]["double_backward_training_step"] = measure_double_backward(wl, 100, 10)
         out["also"]["double_backward_large_batch"] = measure_double_backward(workloads.WORKLOADS["large_batch"], 20, 3)
+        out["also"]["channelwise_tp_training_step"] = measure_tp(workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
     print(json.dumps(out))
 
 

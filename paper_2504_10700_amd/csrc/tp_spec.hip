@@ -1,14 +1,339 @@
-// Generated straight-line kernels of the channelwise tensor product (placeholder: none yet).
+// Specialised kernels of the channelwise tensor product: hand-written memory / scheduling
+// skeleton around generated straight-line arithmetic (csrc/generated/tp_gen_*.inc, written by
+// codegen/generate_tp.py).
+//
+// Mapping (Algorithm 1 of arXiv 2504.10700 is independent per edge and channel; the pooling
+// sums the edges of a receiver):
+//   lane      = channel (64 consecutive channels per wave): a path's weights R[e][p][:] are one
+//               contiguous 256 B row per wave, the sender's features h[j][k][:] 16 B per lane
+//   wave      = one (atom, 64-channel block): it walks the atom's edges - the edges it receives
+//               (forward, dR/dY) or the edges it sends (dh) - and keeps the atom's sum in
+//               registers: no atomics, a fixed summation order, one store per atom
+//   Y[e][:]   is the same for all lanes: it is read with scalar loads and enters the
+//               arithmetic as scalar operands
+// The next edge's rows are requested before the current edge is evaluated (two register sets
+// in turn); the index chain (sender / receiver of the edge after next) is read one step
+// further ahead so that no row load waits for an index.
 #include "tp_internal.h"
 
 namespace tp {
+namespace {
 
-int spec_lookup(const tp_plan*) { return 0; }
-void spec_op_counts(int, int32_t ops[3], int32_t flops[3]) {
-  for (int i = 0; i < 3; ++i) ops[i] = flops[i] = 0;
+using sc::kLanes;
+
+__device__ __forceinline__ float sc_fma(float x, float y, float z) { return __builtin_fmaf(x, y, z); }
+__device__ __forceinline__ double sc_fma(double x, double y, double z) { return __builtin_fma(x, y, z); }
+
+#include "generated/tp_gen_y3h0o3.inc"
+#include "generated/tp_gen_y3h1o3.inc"
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * kLanes;
+constexpr int kStageStride = kLanes + 1;  // LDS row stride of the dY transpose (odd: two-way conflicts at most)
+
+// N consecutive elements at p (aligned to 16 B if the row size is a multiple of 16 B).
+template <typename T, int N>
+__device__ __forceinline__ void load_row(const T* __restrict__ p, T (&v)[N]) {
+  constexpr int V = 16 / sizeof(T);
+  if constexpr ((N * sizeof(T)) % 16 == 0) {
+    typedef T Vec __attribute__((ext_vector_type(V)));
+#pragma unroll
+    for (int i = 0; i < N; i += V) {
+      const Vec x = *reinterpret_cast<const Vec*>(p + i);
+#pragma unroll
+      for (int k = 0; k < V; ++k) v[i + k] = x[k];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = p[i];
+  }
 }
-hipError_t launch_spec_forward(const tp_plan*, const FwdArgs&, hipStream_t) { return hipErrorInvalidValue; }
-hipError_t launch_spec_backward_recv(const tp_plan*, const BwdArgs&, hipStream_t) { return hipErrorInvalidValue; }
-hipError_t launch_spec_backward_send(const tp_plan*, const BwdArgs&, hipStream_t) { return hipErrorInvalidValue; }
+
+template <typename T, int N>
+__device__ __forceinline__ void store_row(T* __restrict__ p, const T (&v)[N]) {
+  constexpr int V = 16 / sizeof(T);
+  if constexpr ((N * sizeof(T)) % 16 == 0) {
+    typedef T Vec __attribute__((ext_vector_type(V)));
+#pragma unroll
+    for (int i = 0; i < N; i += V) {
+      Vec x;
+#pragma unroll
+      for (int k = 0; k < V; ++k) x[k] = v[i + k];
+      *reinterpret_cast<Vec*>(p + i) = x;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) p[i] = v[i];
+  }
+}
+
+// R[e][p][ch] for all paths of edge e.
+template <typename T, int P>
+__device__ __forceinline__ void load_weights(const T* __restrict__ R, int e, int K, int ch, T (&r)[P]) {
+  const T* base = R + static_cast<size_t>(e) * P * K + ch;
+#pragma unroll
+  for (int p = 0; p < P; ++p) r[p] = base[static_cast<size_t>(p) * K];
+}
+
+// Y[e][:], identical for all lanes (e is wave-uniform): scalar loads.
+template <typename T, int N>
+__device__ __forceinline__ void load_uniform(const T* __restrict__ Y, int e, T (&y)[N]) {
+  const T* base = Y + static_cast<size_t>(e) * N;
+#pragma unroll
+  for (int a = 0; a < N; ++a) y[a] = base[a];
+}
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+template <typename T, typename G>
+__global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, int64_t n_units,
+                                                           const T* __restrict__ Y, const T* __restrict__ h,
+                                                           const T* __restrict__ R,
+                                                           const int32_t* __restrict__ sender,
+                                                           const int32_t* __restrict__ row_ptr, T* __restrict__ A) {
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = uniform(threadIdx.x / kLanes);
+  const int64_t unit = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+  if (unit >= n_units) return;
+  const size_t node = unit / chblocks;
+  const int cb = static_cast<int>(unit % chblocks);
+  const int ch = cb * kLanes + lane;
+  const int e0 = uniform(row_ptr[node]), e1 = uniform(row_ptr[node + 1]);
+  T acc[G::kNout];
+#pragma unroll
+  for (int c = 0; c < G::kNout; ++c) acc[c] = T(0);
+  if (e0 < e1) {
+    T r0[G::kP], r1[G::kP], h0[G::kNh], h1[G::kNh], y[G::kNY];
+    load_weights<T, G::kP>(R, e0, K, ch, r0);
+    load_row<T, G::kNh>(h + (static_cast<size_t>(sender[e0]) * K + ch) * G::kNh, h0);
+    int jn = (e0 + 1 < e1) ? sender[e0 + 1] : 0;  // sender of the next edge, read one step ahead
+    for (int e = e0; e < e1; e += 2) {
+      int jn2 = 0;
+      if (e + 1 < e1) {
+        load_weights<T, G::kP>(R, e + 1, K, ch, r1);
+        load_row<T, G::kNh>(h + (static_cast<size_t>(jn) * K + ch) * G::kNh, h1);
+        if (e + 2 < e1) jn2 = sender[e + 2];
+      }
+      load_uniform<T, G::kNY>(Y, e, y);
+      G::forward(y, h0, r0, acc);
+      if (e + 1 < e1) {
+        if (e + 2 < e1) {
+          load_weights<T, G::kP>(R, e + 2, K, ch, r0);
+          load_row<T, G::kNh>(h + (static_cast<size_t>(jn2) * K + ch) * G::kNh, h0);
+          if (e + 3 < e1) jn = sender[e + 3];
+        }
+        load_uniform<T, G::kNY>(Y, e + 1, y);
+        G::forward(y, h1, r1, acc);
+      }
+    }
+  }
+  store_row<T, G::kNout>(A + (node * K + ch) * G::kNout, acc);
+}
+
+// dR of every edge and this channel block's partial of dY; walks the edges grouped by receiver.
+template <typename T, typename G>
+__global__ __launch_bounds__(kThreads) void backward_recv_kernel(
+    int K, int chblocks, int64_t n_units, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
+    const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
+    const T* __restrict__ dA, T* __restrict__ dR, T* __restrict__ dY_partial) {
+  __shared__ T stage_all[kWaves][G::kNY * kStageStride];
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = uniform(threadIdx.x / kLanes);
+  T* stage = stage_all[wave];
+  const int64_t unit = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+  if (unit >= n_units) return;
+  const size_t node = unit / chblocks;
+  const int cb = static_cast<int>(unit % chblocks);
+  const int ch = cb * kLanes + lane;
+  const int e0 = uniform(row_ptr[node]), e1 = uniform(row_ptr[node + 1]);
+  if (e0 >= e1) return;
+  T g[G::kNout];
+  load_row<T, G::kNout>(dA + (node * K + ch) * G::kNout, g);
+  T r0[G::kP], r1[G::kP], h0[G::kNh], h1[G::kNh];
+  load_weights<T, G::kP>(R, e0, K, ch, r0);
+  load_row<T, G::kNh>(h + (static_cast<size_t>(sender[e0]) * K + ch) * G::kNh, h0);
+  int jn = (e0 + 1 < e1) ? sender[e0 + 1] : 0;
+
+  // One edge: arithmetic, dR row stores, dY summed over the 64 lanes in a fixed order (lane
+  // 4a+q adds the sixteen lanes 16q..16q+15 of component a from an LDS transpose, then the
+  // four quarters are combined with two exchanges).
+  auto finish_edge = [&](int e, const T (&r)[G::kP], const T (&hh)[G::kNh]) {
+    T y[G::kNY], dr[G::kP], dy[G::kNY];
+    load_uniform<T, G::kNY>(Y, e, y);
+    G::backward_recv(y, hh, r, g, dr, dy);
+    T* out = dR + static_cast<size_t>(e) * G::kP * K + ch;
+#pragma unroll
+    for (int p = 0; p < G::kP; ++p) out[static_cast<size_t>(p) * K] = dr[p];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the previous edge's reads of the stage are done
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int a = 0; a < G::kNY; ++a) stage[a * kStageStride + lane] = dy[a];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int a = lane >> 2, q = lane & 3;
+    T s = T(0);
+    if (a < G::kNY) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s += stage[a * kStageStride + q * 16 + i];
+    }
+    s += __shfl_xor(s, 1);
+    s += __shfl_xor(s, 2);
+    if (q == 0 && a < G::kNY) dY_partial[(static_cast<size_t>(cb) * n_edges + e) * G::kNY + a] = s;
+  };
+
+  for (int e = e0; e < e1; e += 2) {
+    int jn2 = 0;
+    if (e + 1 < e1) {
+      load_weights<T, G::kP>(R, e + 1, K, ch, r1);
+      load_row<T, G::kNh>(h + (static_cast<size_t>(jn) * K + ch) * G::kNh, h1);
+      if (e + 2 < e1) jn2 = sender[e + 2];
+    }
+    finish_edge(e, r0, h0);
+    if (e + 1 < e1) {
+      if (e + 2 < e1) {
+        load_weights<T, G::kP>(R, e + 2, K, ch, r0);
+        load_row<T, G::kNh>(h + (static_cast<size_t>(jn2) * K + ch) * G::kNh, h0);
+        if (e + 3 < e1) jn = sender[e + 3];
+      }
+      finish_edge(e + 1, r1, h1);
+    }
+  }
+}
+
+// dh of every atom: walks the edges grouped by sender.
+template <typename T, typename G>
+__global__ __launch_bounds__(kThreads) void backward_send_kernel(
+    int K, int chblocks, int64_t n_units, const T* __restrict__ Y, const T* __restrict__ R,
+    const int32_t* __restrict__ receiver, const int32_t* __restrict__ send_ptr,
+    const int32_t* __restrict__ send_edge, const T* __restrict__ dA, T* __restrict__ dh) {
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = uniform(threadIdx.x / kLanes);
+  const int64_t unit = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+  if (unit >= n_units) return;
+  const size_t node = unit / chblocks;
+  const int cb = static_cast<int>(unit % chblocks);
+  const int ch = cb * kLanes + lane;
+  const int q0 = uniform(send_ptr[node]), q1 = uniform(send_ptr[node + 1]);
+  T acc[G::kNh];
+#pragma unroll
+  for (int b = 0; b < G::kNh; ++b) acc[b] = T(0);
+  if (q0 < q1) {
+    T r0[G::kP], r1[G::kP], g0[G::kNout], g1[G::kNout], y[G::kNY];
+    int ea = send_edge[q0];                     // edge of buffer set 0
+    load_weights<T, G::kP>(R, ea, K, ch, r0);
+    load_row<T, G::kNout>(dA + (static_cast<size_t>(receiver[ea]) * K + ch) * G::kNout, g0);
+    int eb = 0, ib = 0;                         // edge of buffer set 1 and its receiver, read one step ahead
+    if (q0 + 1 < q1) {
+      eb = send_edge[q0 + 1];
+      ib = receiver[eb];
+    }
+    for (int q = q0; q < q1; q += 2) {
+      int en = 0, in = 0;                       // edge q+2 and its receiver
+      if (q + 1 < q1) {
+        load_weights<T, G::kP>(R, eb, K, ch, r1);
+        load_row<T, G::kNout>(dA + (static_cast<size_t>(ib) * K + ch) * G::kNout, g1);
+        if (q + 2 < q1) {
+          en = send_edge[q + 2];
+          in = receiver[en];
+        }
+      }
+      load_uniform<T, G::kNY>(Y, ea, y);
+      G::backward_send(y, r0, g0, acc);
+      if (q + 1 < q1) {
+        const int ecur = eb;
+        if (q + 2 < q1) {
+          load_weights<T, G::kP>(R, en, K, ch, r0);
+          load_row<T, G::kNout>(dA + (static_cast<size_t>(in) * K + ch) * G::kNout, g0);
+          ea = en;
+          if (q + 3 < q1) {
+            eb = send_edge[q + 3];
+            ib = receiver[eb];
+          }
+        }
+        load_uniform<T, G::kNY>(Y, ecur, y);
+        G::backward_send(y, r1, g1, acc);
+      }
+    }
+  }
+  store_row<T, G::kNh>(dh + (node * K + ch) * G::kNh, acc);
+}
+
+template <typename G>
+bool matches(const tp_plan* plan) {
+  const tp_config& c = plan->cfg;
+  return c.l_Y == G::kLY && c.l_h == G::kLh && c.L_max == G::kLout && c.num_channels % kLanes == 0 &&
+         static_cast<int>(plan->paths.size()) == G::kP;
+}
+
+unsigned grid_for(int64_t n_units) { return static_cast<unsigned>((n_units + kWaves - 1) / kWaves); }
+
+template <typename T, typename G>
+hipError_t fwd_launch(const tp_plan* plan, const FwdArgs& a, hipStream_t stream) {
+  const int K = plan->cfg.num_channels, chblocks = K / kLanes;
+  const int64_t n_units = a.n_out_nodes * chblocks;
+  hipLaunchKernelGGL((forward_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks, n_units,
+                     static_cast<const T*>(a.Y), static_cast<const T*>(a.h), static_cast<const T*>(a.R), a.sender,
+                     a.row_ptr, static_cast<T*>(a.A));
+  return hipGetLastError();
+}
+
+template <typename T, typename G>
+hipError_t recv_launch(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  const int K = plan->cfg.num_channels, chblocks = K / kLanes;
+  const int64_t n_units = a.n_out_nodes * chblocks;
+  hipLaunchKernelGGL((backward_recv_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
+                     n_units, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
+                     static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<const T*>(a.dA),
+                     static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial));
+  return hipGetLastError();
+}
+
+template <typename T, typename G>
+hipError_t send_launch(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  const int K = plan->cfg.num_channels, chblocks = K / kLanes;
+  const int64_t n_units = a.n_in * chblocks;
+  hipLaunchKernelGGL((backward_send_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
+                     n_units, static_cast<const T*>(a.Y), static_cast<const T*>(a.R), a.receiver, a.send_ptr,
+                     a.send_edge, static_cast<const T*>(a.dA), static_cast<T*>(a.dh));
+  return hipGetLastError();
+}
+
+template <typename G>
+void op_counts(int32_t ops[3], int32_t flops[3]) {
+  for (int i = 0; i < 3; ++i) {
+    ops[i] = G::kOps[i];
+    flops[i] = G::kFlops[i];
+  }
+}
+
+}  // namespace
+
+int spec_lookup(const tp_plan* plan) {
+  if (matches<GenTP_y3h0o3>(plan)) return 1;
+  if (matches<GenTP_y3h1o3>(plan)) return 2;
+  return 0;
+}
+
+void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
+  for (int i = 0; i < 3; ++i) ops[i] = flops[i] = 0;
+  if (id == 1) op_counts<GenTP_y3h0o3>(ops, flops);
+  if (id == 2) op_counts<GenTP_y3h1o3>(ops, flops);
+}
+
+#define TP_DISPATCH(fn, args)                                                                        \
+  const bool f64 = plan->cfg.dtype == SC_F64;                                                        \
+  if (plan->specialised == 1) return f64 ? fn<double, GenTP_y3h0o3> args : fn<float, GenTP_y3h0o3> args; \
+  if (plan->specialised == 2) return f64 ? fn<double, GenTP_y3h1o3> args : fn<float, GenTP_y3h1o3> args; \
+  return hipErrorInvalidValue;
+
+hipError_t launch_spec_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream) {
+  TP_DISPATCH(fwd_launch, (plan, a, stream))
+}
+hipError_t launch_spec_backward_recv(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  TP_DISPATCH(recv_launch, (plan, a, stream))
+}
+hipError_t launch_spec_backward_send(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  TP_DISPATCH(send_launch, (plan, a, stream))
+}
 
 }  // namespace tp
