@@ -278,7 +278,7 @@ def measure_tp(wl, steps, warmup):
     f = lambda x: torch.tensor(x, dtype=tdt, device=dev)
     i32 = lambda x: torch.tensor(x, dtype=torch.int32, device=dev)
     Y, h, dA = f(inp.Y), f(inp.h), f(inp.dA)
-    sender, receiver, row_ptr = i32(inp.sender), i32(inp.receiver), i32(inp.row_ptr)
+    sender, row_ptr = i32(inp.sender), i32(inp.row_ptr)
     send_ptr, send_edge = i32(inp.send_ptr), i32(inp.send_edge)
     # R and dR are the large tensors (E*P*K): two copies of each are rotated so that a step never
     # finds the previous step's rows in the 256 MB last-level cache
@@ -293,7 +293,7 @@ def measure_tp(wl, steps, warmup):
 
     def step(i):
         tp.tp_forward(plan, N, N, E, Y, h, Rs[i % 2], sender, row_ptr, A)
-        tp.tp_backward(plan, N, N, E, Y, h, Rs[(i + 1) % 2], sender, receiver, row_ptr, send_ptr, send_edge, dA, dY, dh,
+        tp.tp_backward(plan, N, N, E, Y, h, Rs[(i + 1) % 2], sender, row_ptr, send_ptr, send_edge, dA, dY, dh,
                        dRs[i % 2], ws, ws_bytes)
 
     for i in range(warmup):
@@ -311,14 +311,20 @@ def measure_tp(wl, steps, warmup):
         ms.append(tp.tp_profile_read(plan))
     tp.tp_profile_enable(plan, False)
     tp.tp_plan_destroy(plan)
-    fwd_ms, recv_ms, send_ms = (float(x) for x in np.mean(np.array(ms), axis=0))
-    # algorithmic bytes per launch: the per-edge tensors once each (R, Y, indices; dR, dY out) plus
-    # the per-node tensors once (h / dA in, A / dh out); gathered rows are counted once per node
-    node_in, node_A = N * K * wl.n_h * elem, N * K * wl.n_out * elem
-    fwd_bytes = E * (P * K * elem + wl.n_Y * elem + 4) + node_in + node_A
-    recv_bytes = E * (2 * P * K * elem + 2 * wl.n_Y * elem + 4) + node_in + node_A
-    send_bytes = E * (P * K * elem + wl.n_Y * elem + 8) + node_A + node_in
-    recv_rate = recv_bytes / (recv_ms * 1e-3) / 1e9
+    fwd_ms, bwd_ms, dhs_ms = (float(x) for x in np.mean(np.array(ms), axis=0))
+    # algorithmic bytes per launch: the per-edge tensors once each (R, Y, sender index; dR out) plus
+    # the per-node tensors once (h, dA in; A out); gathered rows are counted once per node.  The
+    # edge-walking backward kernel also writes the per-edge shares of dh and the dY partials
+    # (workspace), which the two small sum kernels read back: counted as its bytes here, not as
+    # algorithmic bytes of the operation.
+    node_h, node_A = N * K * wl.n_h * elem, N * K * wl.n_out * elem
+    chblocks = (K + 63) // 64
+    fwd_bytes = E * (P * K * elem + wl.n_Y * elem + 4) + node_h + node_A
+    bwd_bytes = E * (2 * P * K * elem + wl.n_Y * elem + 4) + node_h + node_A
+    bwd_ws_bytes = E * (K * wl.n_h + chblocks * wl.n_Y) * elem
+    bwd_rate = (bwd_bytes + bwd_ws_bytes) / (bwd_ms * 1e-3) / 1e9
+    step_bytes = fwd_bytes + bwd_bytes + E * wl.n_Y * elem + node_h   # + dY and dh out
+    k_ops = info.ops[1]
     del Rs, dRs, R0, ws
     torch.cuda.empty_cache()
     return {
@@ -327,14 +333,15 @@ def measure_tp(wl, steps, warmup):
         "config": {"workload": f"{wl.name}: {N} nodes, {E} edges (in-degree ~Poisson({wl.mean_degree})), {K} channels, "
                                f"l_Y={wl.l_Y}, l_h={wl.l_h}, L_max={wl.L_max}, {P} paths, forward+backward",
                    "kernel": "generated" if info.specialised else "table-driven"},
-        "step_hbm_fraction": (fwd_bytes + recv_bytes + send_bytes) / (dt / steps) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": "backward, receiver side (dR + dY partials)", "achieved": recv_rate,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": recv_rate / HBM_PEAK_GBS, "traffic": None,
-                     "kernel_ms": recv_ms, "algorithmic_bytes_per_launch": recv_bytes,
+        "step_hbm_fraction": step_bytes / (dt / steps) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "backward over the edges (dR, dY partials, per-edge dh shares)",
+                     "achieved": bwd_rate, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_rate / HBM_PEAK_GBS,
+                     "traffic": None, "kernel_ms": bwd_ms, "algorithmic_bytes_per_launch": bwd_bytes + bwd_ws_bytes,
+                     "valu_issue_frac": E * K * k_ops / (bwd_ms * 1e-3) / VALU_ISSUE_PEAK if k_ops else None,
                      "forward": {"kernel_ms": fwd_ms, "algorithmic_bytes_per_launch": fwd_bytes,
                                  "achieved": fwd_bytes / (fwd_ms * 1e-3) / 1e9},
-                     "backward_sender_side": {"kernel_ms": send_ms, "algorithmic_bytes_per_launch": send_bytes,
-                                              "achieved": send_bytes / (send_ms * 1e-3) / 1e9}},
+                     "dh_sum": {"kernel_ms": dhs_ms, "bytes_per_launch": E * K * wl.n_h * elem + node_h,
+                                "achieved": (E * K * wl.n_h * elem + node_h) / (dhs_ms * 1e-3) / 1e9}},
     }
 
 

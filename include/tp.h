@@ -30,8 +30,8 @@
  * Conventions: as in sc.h (device pointers for tensors and index arrays, dense row-major,
  * 16-byte aligned tensors, 4-byte aligned index arrays; calls enqueue on the given HIP
  * stream and never synchronise; outputs are overwritten; errors by return code with
- * sc_last_error()).  Index arrays are NOT validated on the device: sender / receiver values
- * outside [0, n_nodes), a row_ptr that is not ascending from 0 to n_edges, or a send_edge
+ * sc_last_error()).  Index arrays are NOT validated on the device: sender values
+ * outside [0, n_nodes_in), a row_ptr that is not ascending from 0 to n_edges, or a send_edge
  * that is not a permutation of the edge ids give undefined results.
  * No entry point allocates; no workspace is needed except for tp_backward (see there).
  */
@@ -66,10 +66,9 @@ typedef struct {
   int32_t num_paths;   /* P: second extent of R */
   int32_t specialised; /* 1 if generated straight-line kernels serve this plan */
   /* generated kernels only (else 0): vector instructions / floating-point operations (a fused
-   * multiply-add counts as two) per (edge, channel) of the forward kernel, the receiver-side
-   * backward kernel and the sender-side backward kernel */
-  int32_t ops[3];
-  int32_t flops[3];
+   * multiply-add counts as two) per (edge, channel) of the forward and the backward kernel */
+  int32_t ops[2];
+  int32_t flops[2];
 } tp_info;
 
 /* Section 4.1, inputs of Algorithm 1: fixes K and the three l ranges, derives the sparse
@@ -98,29 +97,30 @@ sc_status tp_forward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, int
                      const void* h, const void* R, const int32_t* sender, const int32_t* row_ptr, void* A,
                      void* hip_stream);
 
-/* Bytes of device workspace tp_backward needs (partial sums of dY per 64-channel block). */
+/* Bytes of device workspace tp_backward needs (partial sums of dY per 64-channel block and
+ * the per-edge shares of dh: about n_edges * (K * n_h + ceil(K/64) * n_Y) elements). */
 sc_status tp_workspace_bytes(const tp_plan* plan, int64_t n_edges, size_t* bytes);
 
 /* Backward of tp_forward for an upstream gradient dA [n_nodes_out][K][n_out] (training by
  * gradient descent, Section 2.2; dY feeds the forces):
  *   dY dev [n_edges][n_Y]   dh dev [n_nodes_in][K][n_h]   dR dev [n_edges][num_paths][K]   (overwritten)
- * receiver dev int32 [n_edges] is the receiver of every edge (consistent with row_ptr);
  * send_ptr dev int32 [n_nodes_in + 1] and send_edge dev int32 [n_edges] group the edges by
  * sender (see the header comment).  workspace: device memory, 256-byte aligned, at least
  * tp_workspace_bytes(plan, n_edges).  All sums have a fixed order: results are bitwise
- * reproducible for identical inputs.  Two launches walk the edges (once grouped by
- * receiver for dR and dY, once grouped by sender for dh) and one sums the dY partials. */
+ * reproducible for identical inputs.  One launch walks the edges grouped by receiver (dR,
+ * partial dY and every edge's share of dh into the workspace), one sums the dY partials and
+ * one sums, per sender, the shares of the edges it sends. */
 sc_status tp_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, int64_t n_edges, const void* Y,
-                      const void* h, const void* R, const int32_t* sender, const int32_t* receiver,
-                      const int32_t* row_ptr, const int32_t* send_ptr, const int32_t* send_edge, const void* dA,
-                      void* dY, void* dh, void* dR, void* workspace, size_t workspace_bytes, void* hip_stream);
+                      const void* h, const void* R, const int32_t* sender, const int32_t* row_ptr,
+                      const int32_t* send_ptr, const int32_t* send_edge, const void* dA, void* dY, void* dh,
+                      void* dR, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Measurement helper as in sc.h: while enabled, tp_forward / tp_backward bracket their
- * edge-walking kernels with HIP events; tp_profile_read returns the durations in
- * milliseconds of the forward kernel, the receiver-side and the sender-side backward
- * kernels of the most recent calls (negative if none). */
+ * main kernels with HIP events; tp_profile_read returns the durations in milliseconds of
+ * the forward kernel, the edge-walking backward kernel and the per-sender sum of dh of the
+ * most recent calls (negative if none). */
 sc_status tp_profile_enable(tp_plan* plan, int32_t on);
-sc_status tp_profile_read(tp_plan* plan, float* forward_ms, float* backward_recv_ms, float* backward_send_ms);
+sc_status tp_profile_read(tp_plan* plan, float* forward_ms, float* backward_ms, float* dh_sum_ms);
 
 #ifdef __cplusplus
 }

@@ -4,12 +4,12 @@
     python -m paper_2504_10700_amd.codegen.generate_tp --check    # fail if a file would change
 
 Per (edge, channel) Algorithm 1 of arXiv 2504.10700 is a sum over paths (l1,l2,l3) of
-R[p] * C(l1,l2,l3) Y_l1 h_l2.  Three programs are emitted per configuration, each a set of
+R[p] * C(l1,l2,l3) Y_l1 h_l2.  Two programs are emitted per configuration, each a set of
 bilinear couplings through the same sparse tensors with a different free index:
 
-  forward        acc[l3]  += C . Y_l1 . (R[p] h_l2)
-  backward_recv  q[l1]     = C . h_l2 . g_l3 ;  dR[p] = Y_l1 . q ;  dY_l1 += R[p] q
-  backward_send  s[l2]     = C . Y_l1 . g_l3 ;  dh_l2 += R[p] s
+  forward   acc[l3] += C . Y_l1 . (R[p] h_l2)
+  backward  q[l1]    = C . h_l2 . g_l3 ;  dR[p] = Y_l1 . q ;  dY_l1 += R[p] q
+            s[l2]    = C . Y_l1 . g_l3 ;  dh_l2 += R[p] s      (the edge's share of its sender's dh)
 
 The sparse terms come from the library's host tables (tp_plan_terms on a host-only plan);
 every coupling tensor is divided by its most frequent |coefficient| (the factor is folded
@@ -61,7 +61,7 @@ class TPTables:
             if st != 0:
                 raise RuntimeError(lib.sc_last_error().decode())
         check(lib.tp_plan_create(C.byref(cfg), C.byref(plan)))
-        info = (C.c_int32 * 11)()
+        info = (C.c_int32 * 9)()
         check(lib.tp_plan_info(plan, info))
         self.n_Y, self.n_h, self.n_out, self.P = info[0], info[1], info[2], info[3]
         paths = np.zeros((self.P, 3), dtype=np.int32)
@@ -101,7 +101,7 @@ def sl(l: int) -> slice:
     return slice(l * l, (l + 1) * (l + 1))
 
 
-def build_programs(tab: TPTables) -> Tuple[Program, Program, Program]:
+def build_programs(tab: TPTables) -> Tuple[Program, Program]:
     scaled = [split_scale(Cp) for Cp in tab.C]
     # forward: acc[c] += sum C[a,b,c] y[a] (kappa r[p] h[b])
     F = Program()
@@ -119,7 +119,7 @@ def build_programs(tab: TPTables) -> Tuple[Program, Program, Program]:
     for c in range(tab.n_out):
         F.out(f"acc[{c}]", acc[c])
 
-    # receiver side of the backward
+    # backward of one edge
     Bq = Program()
     y = [Bq.inp(f"y[{a}]") for a in range(tab.n_Y)]
     h = [Bq.inp(f"h[{b}]") for b in range(tab.n_h)]
@@ -141,27 +141,22 @@ def build_programs(tab: TPTables) -> Tuple[Program, Program, Program]:
                 dy[l1 * l1 + i] = Bq.fma(rk, qa, dy[l1 * l1 + i])
     for a in range(tab.n_Y):
         Bq.out(f"dy[{a}]", dy[a])
-
-    # sender side of the backward: dh[b] += r[p] sum C[a,b,c] y[a] g[c]
-    Bs = Program()
-    y = [Bs.inp(f"y[{a}]") for a in range(tab.n_Y)]
-    r = [Bs.inp(f"r[{p}]") for p in range(tab.P)]
-    g = [Bs.inp(f"g[{c}]") for c in range(tab.n_out)]
-    dh: List[Optional[int]] = [Bs.inp(f"dh[{b}]") for b in range(tab.n_h)]
+    # the edge's share of its sender's gradient: dh[b] = sum_p r[p] sum C[a,b,c] y[a] g[c]
+    dh: List[Optional[int]] = [None] * tab.n_h
     for p, (l1, l2, l3) in enumerate(tab.paths):
         Cs, kappa = scaled[p]
         s: List[Optional[int]] = [None] * (2 * l2 + 1)
-        couple_into(Bs, np.transpose(Cs, (0, 2, 1)), y[sl(l1)], g[sl(l3)], s)   # s[b] = sum C[a,b,c] y[a] g[c]
-        rk = Bs.cmul(r[p], kappa)
+        couple_into(Bq, np.transpose(Cs, (0, 2, 1)), y[sl(l1)], g[sl(l3)], s)   # s[b] = sum C[a,b,c] y[a] g[c]
+        rk = Bq.cmul(r[p], kappa)
         for i, sb in enumerate(s):
             if sb is not None:
-                dh[l2 * l2 + i] = Bs.fma(rk, sb, dh[l2 * l2 + i])
+                dh[l2 * l2 + i] = Bq.fma(rk, sb, dh[l2 * l2 + i])
     for b in range(tab.n_h):
-        Bs.out(f"dh[{b}]", dh[b])
-    return F, Bq, Bs
+        Bq.out(f"dh[{b}]", dh[b])
+    return F, Bq
 
 
-def self_check(tab: TPTables, F: Program, Bq: Program, Bs: Program, dtype=np.float64) -> Dict[str, float]:
+def self_check(tab: TPTables, F: Program, Bq: Program, dtype=np.float64) -> Dict[str, float]:
     rng = np.random.default_rng(2468)
     n = 1500
     y = rng.standard_normal((n, tab.n_Y))
@@ -184,19 +179,18 @@ def self_check(tab: TPTables, F: Program, Bq: Program, Bs: Program, dtype=np.flo
     inputs.update({f"r[{i}]": r[:, i] for i in range(tab.P)})
     inputs.update({f"g[{i}]": g[:, i] for i in range(tab.n_out)})
     inputs.update({f"acc[{i}]": np.zeros(n) for i in range(tab.n_out)})
-    inputs.update({f"dh[{i}]": np.zeros(n) for i in range(tab.n_h)})
 
     def col(v):
         return np.zeros(n) if v is None else v.astype(np.float64)
 
     def err(x, ref):
         return float(np.abs(x - ref).max() / np.sqrt((ref ** 2).mean()))
-    rf, rq, rs = F.evaluate(inputs, dtype), Bq.evaluate(inputs, dtype), Bs.evaluate(inputs, dtype)
+    rf, rq = F.evaluate(inputs, dtype), Bq.evaluate(inputs, dtype)
     return {
         "msg": err(np.stack([col(rf[f"acc[{i}]"]) for i in range(tab.n_out)], 1), msg),
         "dR": err(np.stack([col(rq[f"dr[{i}]"]) for i in range(tab.P)], 1), dr),
         "dY": err(np.stack([col(rq[f"dy[{i}]"]) for i in range(tab.n_Y)], 1), dy),
-        "dh": err(np.stack([col(rs[f"dh[{i}]"]) for i in range(tab.n_h)], 1), dh),
+        "dh": err(np.stack([col(rq[f"dh[{i}]"]) for i in range(tab.n_h)], 1), dh),
     }
 
 
@@ -204,9 +198,9 @@ def flops(c: Dict[str, int]) -> int:
     return 2 * (c.get("fma", 0) + c.get("fnma", 0) + c.get("cfma", 0)) + sum(c.get(k, 0) for k in ("mul", "add", "sub", "cmul"))
 
 
-def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program, Bs: Program) -> str:
+def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program) -> str:
     l_Y, l_h, L_max = spec
-    cs = [F.count(), Bq.count(), Bs.count()]
+    cs = [F.count(), Bq.count()]
     L = []
     L.append(f"// GENERATED by paper_2504_10700_amd/codegen/generate_tp.py for l_Y={l_Y}, l_h={l_h}, L_max={L_max}.  Do not edit.")
     L.append("//")
@@ -216,9 +210,9 @@ def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program, Bs: Program
     L.append(f"  static constexpr int kLY = {l_Y}, kLh = {l_h}, kLout = {L_max};")
     L.append(f"  static constexpr int kNY = {tab.n_Y}, kNh = {tab.n_h}, kNout = {tab.n_out}, kP = {tab.P};")
     L.append("  // vector instructions / flops (a fused multiply-add counts twice) per (edge, channel):")
-    L.append("  // forward, receiver side of the backward, sender side of the backward")
-    L.append("  static constexpr int kOps[3] = {" + ", ".join(str(c["total"]) for c in cs) + "};")
-    L.append("  static constexpr int kFlops[3] = {" + ", ".join(str(flops(c)) for c in cs) + "};")
+    L.append("  // forward, backward")
+    L.append("  static constexpr int kOps[2] = {" + ", ".join(str(c["total"]) for c in cs) + "};")
+    L.append("  static constexpr int kFlops[2] = {" + ", ".join(str(flops(c)) for c in cs) + "};")
     L.append("")
     L.append("  // acc += message of one edge")
     L.append("  template <typename T>")
@@ -227,18 +221,12 @@ def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program, Bs: Program
     L.append(F.emit("T", "    "))
     L.append("  }")
     L.append("")
-    L.append("  // g = dA of the receiver; dr and dy (this channel's share of dY) are overwritten")
+    L.append("  // g = dA of the receiver; overwritten: dr, dy (this channel's share of the edge's dY) and dh")
+    L.append("  // (the edge's share of the gradient of its sender's features)")
     L.append("  template <typename T>")
-    L.append("  static __device__ __forceinline__ void backward_recv(const T (&y)[kNY], const T (&h)[kNh], const T (&r)[kP],")
-    L.append("                                                       const T (&g)[kNout], T (&dr)[kP], T (&dy)[kNY]) {")
+    L.append("  static __device__ __forceinline__ void backward(const T (&y)[kNY], const T (&h)[kNh], const T (&r)[kP],")
+    L.append("                                                  const T (&g)[kNout], T (&dr)[kP], T (&dy)[kNY], T (&dh)[kNh]) {")
     L.append(Bq.emit("T", "    "))
-    L.append("  }")
-    L.append("")
-    L.append("  // dh += contribution of one edge to the gradient of its sender's features")
-    L.append("  template <typename T>")
-    L.append("  static __device__ __forceinline__ void backward_send(const T (&y)[kNY], const T (&r)[kP], const T (&g)[kNout],")
-    L.append("                                                       T (&dh)[kNh]) {")
-    L.append(Bs.emit("T", "    "))
     L.append("  }")
     L.append("};")
     return "\n".join(L) + "\n"
@@ -247,16 +235,15 @@ def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program, Bs: Program
 def generate(tag: str, lib_path: str = HOST_LIB, verbose: bool = True) -> str:
     spec = SPECS[tag]
     tab = TPTables(lib_path, *spec)
-    F, Bq, Bs = build_programs(tab)
-    e64 = self_check(tab, F, Bq, Bs, np.float64)
+    F, Bq = build_programs(tab)
+    e64 = self_check(tab, F, Bq, np.float64)
     assert max(e64.values()) < 1e-12, e64
     if verbose:
-        e32 = self_check(tab, F, Bq, Bs, np.float32)
-        print(f"[tp {tag}] P={tab.P} terms={len(tab.terms[4])} ops fwd={F.count()['total']} "
-              f"bwd_recv={Bq.count()['total']} bwd_send={Bs.count()['total']}")
+        e32 = self_check(tab, F, Bq, np.float32)
+        print(f"[tp {tag}] P={tab.P} terms={len(tab.terms[4])} ops fwd={F.count()['total']} bwd={Bq.count()['total']}")
         print(f"[tp {tag}] fp64 self-check max|err|/rms: {e64}")
         print(f"[tp {tag}] fp32 emulation  max|err|/rms: {e32}")
-    return emit_inc(tag, spec, tab, F, Bq, Bs)
+    return emit_inc(tag, spec, tab, F, Bq)
 
 
 def main(argv=None) -> int:

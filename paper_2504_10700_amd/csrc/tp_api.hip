@@ -39,6 +39,8 @@ sc_status check_sizes(const char* fn, const tp_plan* plan, int64_t n_in, int64_t
   const int64_t lim = int64_t(1) << 30;
   if (n_in < 0 || n_in > lim || n_out < 0 || n_out > lim || n_edges < 0 || n_edges > lim)
     return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": a size is outside 0..2^30");
+  if (n_edges > 0 && (n_in == 0 || n_out == 0))
+    return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": edges without nodes");
   if (n_out * chblocks_of(plan) > lim || n_in * chblocks_of(plan) > lim)
     return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": nodes x channel blocks exceeds 2^30");
   return SC_OK;
@@ -187,10 +189,10 @@ sc_status tp_profile_enable(tp_plan* plan, int32_t on) {
   return SC_OK;
 }
 
-sc_status tp_profile_read(tp_plan* plan, float* forward_ms, float* backward_recv_ms, float* backward_send_ms) {
-  if (!plan || !forward_ms || !backward_recv_ms || !backward_send_ms)
+sc_status tp_profile_read(tp_plan* plan, float* forward_ms, float* backward_ms, float* dh_sum_ms) {
+  if (!plan || !forward_ms || !backward_ms || !dh_sum_ms)
     return set_error(SC_ERR_INVALID_ARG, "tp_profile_read: NULL argument");
-  float* out[3] = {forward_ms, backward_recv_ms, backward_send_ms};
+  float* out[3] = {forward_ms, backward_ms, dh_sum_ms};
   for (int k = 0; k < 3; ++k) {
     *out[k] = -1.0f;
     if (!plan->ev_used[k]) continue;
@@ -231,20 +233,21 @@ sc_status tp_workspace_bytes(const tp_plan* plan, int64_t n_edges, size_t* bytes
   if (!plan || !bytes) return set_error(SC_ERR_INVALID_ARG, "tp_workspace_bytes: NULL argument");
   if (n_edges < 0 || n_edges > (int64_t(1) << 30))
     return set_error(SC_ERR_INVALID_ARG, "tp_workspace_bytes: n_edges outside 0..2^30");
-  *bytes = align_up(static_cast<size_t>(chblocks_of(plan)) * n_edges * plan->n_Y * elem_size(plan), 256) + 256;
+  *bytes = align_up(static_cast<size_t>(chblocks_of(plan)) * n_edges * plan->n_Y * elem_size(plan), 256) +
+           align_up(static_cast<size_t>(n_edges) * plan->cfg.num_channels * plan->n_h * elem_size(plan), 256) + 256;
   return SC_OK;
 }
 
 sc_status tp_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, int64_t n_edges, const void* Y,
-                      const void* h, const void* R, const int32_t* sender, const int32_t* receiver,
-                      const int32_t* row_ptr, const int32_t* send_ptr, const int32_t* send_edge, const void* dA,
-                      void* dY, void* dh, void* dR, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                      const void* h, const void* R, const int32_t* sender, const int32_t* row_ptr,
+                      const int32_t* send_ptr, const int32_t* send_edge, const void* dA, void* dY, void* dh,
+                      void* dR, void* workspace, size_t workspace_bytes, void* hip_stream) {
   sc_status st = check_sizes("tp_backward", plan, n_nodes_in, n_nodes_out, n_edges);
   if (st != SC_OK) return st;
   if (n_nodes_in > 0 && (!dh || !send_ptr)) return set_error(SC_ERR_INVALID_ARG, "tp_backward: dh or send_ptr is NULL");
   if (n_nodes_out > 0 && !row_ptr) return set_error(SC_ERR_INVALID_ARG, "tp_backward: row_ptr is NULL");
   if (n_edges > 0) {
-    if (!Y || !h || !R || !sender || !receiver || !send_edge || !dA || !dY || !dR)
+    if (!Y || !h || !R || !sender || !send_edge || !dA || !dY || !dR)
       return set_error(SC_ERR_INVALID_ARG, "tp_backward: NULL tensor argument");
     size_t need = 0;
     (void)tp_workspace_bytes(plan, n_edges, &need);
@@ -253,20 +256,22 @@ sc_status tp_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, in
     if (misaligned(workspace, 256)) return set_error(SC_ERR_WORKSPACE, "tp_backward: workspace not 256-byte aligned");
   }
   if (misaligned(Y, 16) || misaligned(h, 16) || misaligned(R, 16) || misaligned(dA, 16) || misaligned(dY, 16) ||
-      misaligned(dh, 16) || misaligned(dR, 16) || misaligned(sender, 4) || misaligned(receiver, 4) ||
+      misaligned(dh, 16) || misaligned(dR, 16) || misaligned(sender, 4) ||
       misaligned(row_ptr, 4) || misaligned(send_ptr, 4) || misaligned(send_edge, 4))
     return set_error(SC_ERR_INVALID_ARG, "tp_backward: tensor pointer not 16-byte aligned");
   DeviceGuard guard(plan->cfg.device);
   if (!guard.ok) return set_error(SC_ERR_HIP, "tp_backward: cannot make the plan's device current");
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const tp::BwdArgs a{n_nodes_in, n_nodes_out, n_edges, Y, h, R, sender, receiver, row_ptr, send_ptr, send_edge,
-                      dA, dY, dh, dR, workspace};
+  char* dh_edge = workspace ? static_cast<char*>(workspace) +
+                                  align_up(static_cast<size_t>(chblocks_of(plan)) * n_edges * plan->n_Y * elem_size(plan), 256)
+                            : nullptr;
+  const tp::BwdArgs a{n_nodes_in, n_nodes_out, n_edges, Y,  h,  R,         sender,
+                      row_ptr,    send_ptr,    send_edge, dA, dY, dh, dR, workspace, dh_edge};
   hipError_t e = hipSuccess;
   if (n_nodes_out > 0 && n_edges > 0) {
     if (plan->profile) (void)hipEventRecord(plan->ev[2], stream);
-    e = plan->specialised ? tp::launch_spec_backward_recv(plan, a, stream)
-                          : tp::launch_generic_backward_recv(plan, a, stream);
-    if (e != hipSuccess) return fail_hip(e, "tp_backward: receiver-side launch");
+    e = plan->specialised ? tp::launch_spec_backward(plan, a, stream) : tp::launch_generic_backward(plan, a, stream);
+    if (e != hipSuccess) return fail_hip(e, "tp_backward: edge kernel launch");
     if (plan->profile) {
       (void)hipEventRecord(plan->ev[3], stream);
       plan->ev_used[1] = true;
@@ -276,9 +281,8 @@ sc_status tp_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, in
   }
   if (n_nodes_in > 0) {
     if (plan->profile) (void)hipEventRecord(plan->ev[4], stream);
-    e = plan->specialised ? tp::launch_spec_backward_send(plan, a, stream)
-                          : tp::launch_generic_backward_send(plan, a, stream);
-    if (e != hipSuccess) return fail_hip(e, "tp_backward: sender-side launch");
+    e = tp::launch_dh_sum(plan, a, stream);
+    if (e != hipSuccess) return fail_hip(e, "tp_backward: dh sum launch");
     if (plan->profile) {
       (void)hipEventRecord(plan->ev[5], stream);
       plan->ev_used[2] = true;

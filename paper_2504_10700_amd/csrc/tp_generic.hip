@@ -54,18 +54,20 @@ __global__ __launch_bounds__(kLanes) void generic_forward_kernel(TermTable tab, 
     for (int c = 0; c < tab.n_out; ++c) A[(node * K + ch) * tab.n_out + c] = static_cast<T>(sA[c * kLanes + lane]);
 }
 
-// Receiver side of the backward: dR of every edge and the per-channel-block partial of dY.
+// Backward over the edges grouped by receiver: dR of every edge, the per-channel-block partial
+// of dY and the edge's share of its sender's dh.
 template <typename T>
-__global__ __launch_bounds__(kLanes) void generic_backward_recv_kernel(
+__global__ __launch_bounds__(kLanes) void generic_backward_kernel(
     TermTable tab, int K, int chblocks, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
     const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
-    const T* __restrict__ dA, T* __restrict__ dR, T* __restrict__ dY_partial) {
+    const T* __restrict__ dA, T* __restrict__ dR, T* __restrict__ dY_partial, T* __restrict__ dh_edge) {
   extern __shared__ unsigned char lds_raw[];
   double* sH = reinterpret_cast<double*>(lds_raw);  // [n_h][64]
   double* sR = sH + tab.n_h * kLanes;               // [P][64]
   double* sG = sR + tab.num_paths * kLanes;         // [n_out][64]  dA of the receiver
   double* sDR = sG + tab.n_out * kLanes;            // [P][64]
   double* sDY = sDR + tab.num_paths * kLanes;       // [n_Y][64]    this lane's share of dY
+  double* sDH = sDY + tab.n_Y * kLanes;             // [n_h][64]
   const int lane = threadIdx.x;
   const size_t node = blockIdx.x / chblocks;
   const int cb = blockIdx.x % chblocks;
@@ -76,7 +78,10 @@ __global__ __launch_bounds__(kLanes) void generic_backward_recv_kernel(
   const int e0 = row_ptr[node], e1 = row_ptr[node + 1];
   for (int e = e0; e < e1; ++e) {
     const size_t j = sender[e];
-    for (int b = 0; b < tab.n_h; ++b) sH[b * kLanes + lane] = active ? static_cast<double>(h[(j * K + ch) * tab.n_h + b]) : 0.0;
+    for (int b = 0; b < tab.n_h; ++b) {
+      sH[b * kLanes + lane] = active ? static_cast<double>(h[(j * K + ch) * tab.n_h + b]) : 0.0;
+      sDH[b * kLanes + lane] = 0.0;
+    }
     for (int p = 0; p < tab.num_paths; ++p) {
       sR[p * kLanes + lane] = active ? static_cast<double>(R[(static_cast<size_t>(e) * tab.num_paths + p) * K + ch]) : 0.0;
       sDR[p * kLanes + lane] = 0.0;
@@ -85,13 +90,19 @@ __global__ __launch_bounds__(kLanes) void generic_backward_recv_kernel(
     const T* y = Y + static_cast<size_t>(e) * tab.n_Y;
     for (int t = 0; t < tab.n_terms; ++t) {
       const int4 ix = tab.idx[t];
-      const double gh = tab.coef[t] * sG[ix.w * kLanes + lane] * sH[ix.z * kLanes + lane];
-      sDR[ix.x * kLanes + lane] += gh * static_cast<double>(y[ix.y]);
-      sDY[ix.y * kLanes + lane] += gh * sR[ix.x * kLanes + lane];
+      const double cg = tab.coef[t] * sG[ix.w * kLanes + lane];
+      const double gh = cg * sH[ix.z * kLanes + lane];
+      const double ya = static_cast<double>(y[ix.y]), rp = sR[ix.x * kLanes + lane];
+      sDR[ix.x * kLanes + lane] += gh * ya;
+      sDY[ix.y * kLanes + lane] += gh * rp;
+      sDH[ix.z * kLanes + lane] += cg * rp * ya;
     }
-    if (active)
+    if (active) {
       for (int p = 0; p < tab.num_paths; ++p)
         dR[(static_cast<size_t>(e) * tab.num_paths + p) * K + ch] = static_cast<T>(sDR[p * kLanes + lane]);
+      for (int b = 0; b < tab.n_h; ++b)
+        dh_edge[(static_cast<size_t>(e) * K + ch) * tab.n_h + b] = static_cast<T>(sDH[b * kLanes + lane]);
+    }
     for (int a = 0; a < tab.n_Y; ++a) {
       const double s = wave_sum(sDY[a * kLanes + lane]);
       if (lane == 0) dY_partial[(static_cast<size_t>(cb) * n_edges + e) * tab.n_Y + a] = static_cast<T>(s);
@@ -99,38 +110,28 @@ __global__ __launch_bounds__(kLanes) void generic_backward_recv_kernel(
   }
 }
 
-// Sender side of the backward: dh[j] = sum over the edges sent by j.
+// dh[j] = sum of the shares of the edges sent by j, in the order of send_edge.  One lane per
+// (channel, component) pair: consecutive lanes read consecutive elements of an edge's row.
 template <typename T>
-__global__ __launch_bounds__(kLanes) void generic_backward_send_kernel(
-    TermTable tab, int K, int chblocks, const T* __restrict__ Y, const T* __restrict__ R,
-    const int32_t* __restrict__ receiver, const int32_t* __restrict__ send_ptr,
-    const int32_t* __restrict__ send_edge, const T* __restrict__ dA, T* __restrict__ dh) {
-  extern __shared__ unsigned char lds_raw[];
-  double* sR = reinterpret_cast<double*>(lds_raw);  // [P][64]
-  double* sG = sR + tab.num_paths * kLanes;         // [n_out][64]
-  double* sDH = sG + tab.n_out * kLanes;            // [n_h][64]
-  const int lane = threadIdx.x;
-  const size_t node = blockIdx.x / chblocks;
-  const int cb = blockIdx.x % chblocks;
-  const int ch = cb * kLanes + lane;
-  const bool active = ch < K;
-  for (int b = 0; b < tab.n_h; ++b) sDH[b * kLanes + lane] = 0.0;
+__global__ __launch_bounds__(256) void dh_sum_kernel(int row, int64_t n_rows, const int32_t* __restrict__ send_ptr,
+                                                     const int32_t* __restrict__ send_edge,
+                                                     const T* __restrict__ dh_edge, T* __restrict__ dh) {
+  // row = K * n_h elements per node; blockIdx.y walks the row in pieces of 256 elements
+  const size_t node = blockIdx.x;
+  const int i = blockIdx.y * 256 + threadIdx.x;
+  if (node >= static_cast<size_t>(n_rows) || i >= row) return;
   const int q0 = send_ptr[node], q1 = send_ptr[node + 1];
-  for (int q = q0; q < q1; ++q) {
-    const size_t e = send_edge[q];
-    const size_t i = receiver[e];
-    for (int c = 0; c < tab.n_out; ++c)
-      sG[c * kLanes + lane] = active ? static_cast<double>(dA[(i * K + ch) * tab.n_out + c]) : 0.0;
-    for (int p = 0; p < tab.num_paths; ++p)
-      sR[p * kLanes + lane] = active ? static_cast<double>(R[(e * tab.num_paths + p) * K + ch]) : 0.0;
-    const T* y = Y + e * tab.n_Y;
-    for (int t = 0; t < tab.n_terms; ++t) {
-      const int4 ix = tab.idx[t];
-      sDH[ix.z * kLanes + lane] += tab.coef[t] * sR[ix.x * kLanes + lane] * static_cast<double>(y[ix.y]) * sG[ix.w * kLanes + lane];
-    }
+  T s0 = T(0), s1 = T(0), s2 = T(0), s3 = T(0);
+  int q = q0;
+  for (; q + 4 <= q1; q += 4) {  // four independent loads in flight; the order of the additions is fixed
+    const T v0 = dh_edge[static_cast<size_t>(send_edge[q]) * row + i];
+    const T v1 = dh_edge[static_cast<size_t>(send_edge[q + 1]) * row + i];
+    const T v2 = dh_edge[static_cast<size_t>(send_edge[q + 2]) * row + i];
+    const T v3 = dh_edge[static_cast<size_t>(send_edge[q + 3]) * row + i];
+    s0 += v0; s1 += v1; s2 += v2; s3 += v3;
   }
-  if (active)
-    for (int b = 0; b < tab.n_h; ++b) dh[(node * K + ch) * tab.n_h + b] = static_cast<T>(sDH[b * kLanes + lane]);
+  for (; q < q1; ++q) s0 += dh_edge[static_cast<size_t>(send_edge[q]) * row + i];
+  dh[node * row + i] = (s0 + s1) + (s2 + s3);
 }
 
 // dY[e][a] = sum over the channel blocks of the partials, in block order.
@@ -155,25 +156,22 @@ hipError_t fwd_t(const tp_plan* plan, const FwdArgs& a, hipStream_t stream) {
 }
 
 template <typename T>
-hipError_t bwd_recv_t(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+hipError_t bwd_t(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   const TermTable& t = plan->tab;
   const int K = plan->cfg.num_channels, chblocks = (K + kLanes - 1) / kLanes;
-  const size_t lds = static_cast<size_t>(t.n_h + 2 * t.num_paths + t.n_out + t.n_Y) * kLanes * sizeof(double);
-  hipLaunchKernelGGL(generic_backward_recv_kernel<T>, dim3(static_cast<unsigned>(a.n_out_nodes * chblocks)), dim3(kLanes),
-                     lds, stream, t, K, chblocks, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
+  const size_t lds = static_cast<size_t>(2 * t.n_h + 2 * t.num_paths + t.n_out + t.n_Y) * kLanes * sizeof(double);
+  hipLaunchKernelGGL(generic_backward_kernel<T>, dim3(static_cast<unsigned>(a.n_out_nodes * chblocks)), dim3(kLanes), lds,
+                     stream, t, K, chblocks, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
                      static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<const T*>(a.dA),
-                     static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial));
+                     static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh_edge));
   return hipGetLastError();
 }
 
 template <typename T>
-hipError_t bwd_send_t(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
-  const TermTable& t = plan->tab;
-  const int K = plan->cfg.num_channels, chblocks = (K + kLanes - 1) / kLanes;
-  const size_t lds = static_cast<size_t>(t.num_paths + t.n_out + t.n_h) * kLanes * sizeof(double);
-  hipLaunchKernelGGL(generic_backward_send_kernel<T>, dim3(static_cast<unsigned>(a.n_in * chblocks)), dim3(kLanes), lds,
-                     stream, t, K, chblocks, static_cast<const T*>(a.Y), static_cast<const T*>(a.R), a.receiver,
-                     a.send_ptr, a.send_edge, static_cast<const T*>(a.dA), static_cast<T*>(a.dh));
+hipError_t dh_sum_t(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  const int row = plan->cfg.num_channels * plan->n_h;
+  hipLaunchKernelGGL(dh_sum_kernel<T>, dim3(static_cast<unsigned>(a.n_in), (row + 255) / 256), dim3(256), 0, stream, row,
+                     a.n_in, a.send_ptr, a.send_edge, static_cast<const T*>(a.dh_edge), static_cast<T*>(a.dh));
   return hipGetLastError();
 }
 
@@ -192,11 +190,11 @@ hipError_t dY_sum_t(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
 hipError_t launch_generic_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream) {
   return plan->cfg.dtype == SC_F64 ? fwd_t<double>(plan, a, stream) : fwd_t<float>(plan, a, stream);
 }
-hipError_t launch_generic_backward_recv(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
-  return plan->cfg.dtype == SC_F64 ? bwd_recv_t<double>(plan, a, stream) : bwd_recv_t<float>(plan, a, stream);
+hipError_t launch_generic_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  return plan->cfg.dtype == SC_F64 ? bwd_t<double>(plan, a, stream) : bwd_t<float>(plan, a, stream);
 }
-hipError_t launch_generic_backward_send(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
-  return plan->cfg.dtype == SC_F64 ? bwd_send_t<double>(plan, a, stream) : bwd_send_t<float>(plan, a, stream);
+hipError_t launch_dh_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  return plan->cfg.dtype == SC_F64 ? dh_sum_t<double>(plan, a, stream) : dh_sum_t<float>(plan, a, stream);
 }
 hipError_t launch_dY_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   return plan->cfg.dtype == SC_F64 ? dY_sum_t<double>(plan, a, stream) : dY_sum_t<float>(plan, a, stream);

@@ -55,22 +55,22 @@ struct FwdArgs {
 struct BwdArgs {
   int64_t n_in, n_out_nodes, n_edges;
   const void *Y, *h, *R;
-  const int32_t *sender, *receiver, *row_ptr, *send_ptr, *send_edge;
+  const int32_t *sender, *row_ptr, *send_ptr, *send_edge;
   const void* dA;
   void *dY, *dh, *dR;
   void* dY_partial;  // [chblocks][n_edges][n_Y] of the plan's dtype
+  void* dh_edge;     // [n_edges][K][n_h]: every edge's share of its sender's dh
 };
 
 hipError_t launch_generic_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream);
-hipError_t launch_generic_backward_recv(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
-hipError_t launch_generic_backward_send(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_generic_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
 hipError_t launch_dY_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_dh_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
 
 // generated kernels (tp_spec.hip)
 int spec_lookup(const tp_plan* plan);
-void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]);
+void spec_op_counts(int id, int32_t ops[2], int32_t flops[2]);
 hipError_t launch_spec_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream);
-hipError_t launch_spec_backward_recv(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
-hipError_t launch_spec_backward_send(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_spec_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
 
 }  // namespace tp

@@ -6,14 +6,16 @@
 // sums the edges of a receiver):
 //   lane      = channel (64 consecutive channels per wave): a path's weights R[e][p][:] are one
 //               contiguous 256 B row per wave, the sender's features h[j][k][:] 16 B per lane
-//   wave      = one (atom, 64-channel block): it walks the atom's edges - the edges it receives
-//               (forward, dR/dY) or the edges it sends (dh) - and keeps the atom's sum in
-//               registers: no atomics, a fixed summation order, one store per atom
+//   wave      = one (receiving atom, 64-channel block): it walks the edges the atom receives and
+//               keeps the atom's sum (forward) or its dA row (backward) in registers: no
+//               atomics, a fixed summation order, one store per atom.  The backward writes per
+//               edge: dR, the channel block's partial of dY, and the edge's share of its
+//               sender's dh, which a small second kernel sums per sender.
 //   Y[e][:]   is the same for all lanes: it is read with scalar loads and enters the
 //               arithmetic as scalar operands
 // The next edge's rows are requested before the current edge is evaluated (two register sets
-// in turn); the index chain (sender / receiver of the edge after next) is read one step
-// further ahead so that no row load waits for an index.
+// in turn); the sender index of the edge after next is read one step further ahead so that
+// no row load waits for an index.
 #include "tp_internal.h"
 
 namespace tp {
@@ -130,12 +132,13 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, 
   store_row<T, G::kNout>(A + (node * K + ch) * G::kNout, acc);
 }
 
-// dR of every edge and this channel block's partial of dY; walks the edges grouped by receiver.
+// dR of every edge, this channel block's partial of dY and the edge's share of dh; walks the
+// edges grouped by receiver.
 template <typename T, typename G>
-__global__ __launch_bounds__(kThreads) void backward_recv_kernel(
+__global__ __launch_bounds__(kThreads) void backward_kernel(
     int K, int chblocks, int64_t n_units, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
     const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
-    const T* __restrict__ dA, T* __restrict__ dR, T* __restrict__ dY_partial) {
+    const T* __restrict__ dA, T* __restrict__ dR, T* __restrict__ dY_partial, T* __restrict__ dh_edge) {
   __shared__ T stage_all[kWaves][G::kNY * kStageStride];
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = uniform(threadIdx.x / kLanes);
@@ -158,12 +161,13 @@ __global__ __launch_bounds__(kThreads) void backward_recv_kernel(
   // 4a+q adds the sixteen lanes 16q..16q+15 of component a from an LDS transpose, then the
   // four quarters are combined with two exchanges).
   auto finish_edge = [&](int e, const T (&r)[G::kP], const T (&hh)[G::kNh]) {
-    T y[G::kNY], dr[G::kP], dy[G::kNY];
+    T y[G::kNY], dr[G::kP], dy[G::kNY], dhe[G::kNh];
     load_uniform<T, G::kNY>(Y, e, y);
-    G::backward_recv(y, hh, r, g, dr, dy);
+    G::backward(y, hh, r, g, dr, dy, dhe);
     T* out = dR + static_cast<size_t>(e) * G::kP * K + ch;
 #pragma unroll
     for (int p = 0; p < G::kP; ++p) out[static_cast<size_t>(p) * K] = dr[p];
+    store_row<T, G::kNh>(dh_edge + (static_cast<size_t>(e) * K + ch) * G::kNh, dhe);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the previous edge's reads of the stage are done
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -200,64 +204,6 @@ __global__ __launch_bounds__(kThreads) void backward_recv_kernel(
   }
 }
 
-// dh of every atom: walks the edges grouped by sender.
-template <typename T, typename G>
-__global__ __launch_bounds__(kThreads) void backward_send_kernel(
-    int K, int chblocks, int64_t n_units, const T* __restrict__ Y, const T* __restrict__ R,
-    const int32_t* __restrict__ receiver, const int32_t* __restrict__ send_ptr,
-    const int32_t* __restrict__ send_edge, const T* __restrict__ dA, T* __restrict__ dh) {
-  const int lane = threadIdx.x & (kLanes - 1);
-  const int wave = uniform(threadIdx.x / kLanes);
-  const int64_t unit = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
-  if (unit >= n_units) return;
-  const size_t node = unit / chblocks;
-  const int cb = static_cast<int>(unit % chblocks);
-  const int ch = cb * kLanes + lane;
-  const int q0 = uniform(send_ptr[node]), q1 = uniform(send_ptr[node + 1]);
-  T acc[G::kNh];
-#pragma unroll
-  for (int b = 0; b < G::kNh; ++b) acc[b] = T(0);
-  if (q0 < q1) {
-    T r0[G::kP], r1[G::kP], g0[G::kNout], g1[G::kNout], y[G::kNY];
-    int ea = send_edge[q0];                     // edge of buffer set 0
-    load_weights<T, G::kP>(R, ea, K, ch, r0);
-    load_row<T, G::kNout>(dA + (static_cast<size_t>(receiver[ea]) * K + ch) * G::kNout, g0);
-    int eb = 0, ib = 0;                         // edge of buffer set 1 and its receiver, read one step ahead
-    if (q0 + 1 < q1) {
-      eb = send_edge[q0 + 1];
-      ib = receiver[eb];
-    }
-    for (int q = q0; q < q1; q += 2) {
-      int en = 0, in = 0;                       // edge q+2 and its receiver
-      if (q + 1 < q1) {
-        load_weights<T, G::kP>(R, eb, K, ch, r1);
-        load_row<T, G::kNout>(dA + (static_cast<size_t>(ib) * K + ch) * G::kNout, g1);
-        if (q + 2 < q1) {
-          en = send_edge[q + 2];
-          in = receiver[en];
-        }
-      }
-      load_uniform<T, G::kNY>(Y, ea, y);
-      G::backward_send(y, r0, g0, acc);
-      if (q + 1 < q1) {
-        const int ecur = eb;
-        if (q + 2 < q1) {
-          load_weights<T, G::kP>(R, en, K, ch, r0);
-          load_row<T, G::kNout>(dA + (static_cast<size_t>(in) * K + ch) * G::kNout, g0);
-          ea = en;
-          if (q + 3 < q1) {
-            eb = send_edge[q + 3];
-            ib = receiver[eb];
-          }
-        }
-        load_uniform<T, G::kNY>(Y, ecur, y);
-        G::backward_send(y, r1, g1, acc);
-      }
-    }
-  }
-  store_row<T, G::kNh>(dh + (node * K + ch) * G::kNh, acc);
-}
-
 template <typename G>
 bool matches(const tp_plan* plan) {
   const tp_config& c = plan->cfg;
@@ -278,29 +224,19 @@ hipError_t fwd_launch(const tp_plan* plan, const FwdArgs& a, hipStream_t stream)
 }
 
 template <typename T, typename G>
-hipError_t recv_launch(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+hipError_t bwd_launch(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   const int K = plan->cfg.num_channels, chblocks = K / kLanes;
   const int64_t n_units = a.n_out_nodes * chblocks;
-  hipLaunchKernelGGL((backward_recv_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
+  hipLaunchKernelGGL((backward_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
                      n_units, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
                      static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<const T*>(a.dA),
-                     static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial));
-  return hipGetLastError();
-}
-
-template <typename T, typename G>
-hipError_t send_launch(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
-  const int K = plan->cfg.num_channels, chblocks = K / kLanes;
-  const int64_t n_units = a.n_in * chblocks;
-  hipLaunchKernelGGL((backward_send_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
-                     n_units, static_cast<const T*>(a.Y), static_cast<const T*>(a.R), a.receiver, a.send_ptr,
-                     a.send_edge, static_cast<const T*>(a.dA), static_cast<T*>(a.dh));
+                     static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh_edge));
   return hipGetLastError();
 }
 
 template <typename G>
-void op_counts(int32_t ops[3], int32_t flops[3]) {
-  for (int i = 0; i < 3; ++i) {
+void op_counts(int32_t ops[2], int32_t flops[2]) {
+  for (int i = 0; i < 2; ++i) {
     ops[i] = G::kOps[i];
     flops[i] = G::kFlops[i];
   }
@@ -314,8 +250,8 @@ int spec_lookup(const tp_plan* plan) {
   return 0;
 }
 
-void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
-  for (int i = 0; i < 3; ++i) ops[i] = flops[i] = 0;
+void spec_op_counts(int id, int32_t ops[2], int32_t flops[2]) {
+  for (int i = 0; i < 2; ++i) ops[i] = flops[i] = 0;
   if (id == 1) op_counts<GenTP_y3h0o3>(ops, flops);
   if (id == 2) op_counts<GenTP_y3h1o3>(ops, flops);
 }
@@ -329,11 +265,8 @@ void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
 hipError_t launch_spec_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream) {
   TP_DISPATCH(fwd_launch, (plan, a, stream))
 }
-hipError_t launch_spec_backward_recv(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
-  TP_DISPATCH(recv_launch, (plan, a, stream))
-}
-hipError_t launch_spec_backward_send(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
-  TP_DISPATCH(send_launch, (plan, a, stream))
+hipError_t launch_spec_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  TP_DISPATCH(bwd_launch, (plan, a, stream))
 }
 
 }  // namespace tp

@@ -22,7 +22,7 @@ class tp_config(C.Structure):
 
 class tp_info(C.Structure):
     _fields_ = [("n_Y", C.c_int32), ("n_h", C.c_int32), ("n_out", C.c_int32), ("num_paths", C.c_int32),
-                ("specialised", C.c_int32), ("ops", C.c_int32 * 3), ("flops", C.c_int32 * 3)]
+                ("specialised", C.c_int32), ("ops", C.c_int32 * 2), ("flops", C.c_int32 * 2)]
 
 
 def _declare() -> None:
@@ -35,7 +35,7 @@ def _declare() -> None:
     lib.tp_plan_terms.argtypes = [vp, i32, pi32, pi32, pi32, pi32, pi32, C.POINTER(C.c_double)]
     lib.tp_forward.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.tp_workspace_bytes.argtypes = [vp, i64, C.POINTER(C.c_size_t)]
-    lib.tp_backward.argtypes = [vp, i64, i64, i64] + [vp] * 13 + [C.c_size_t, vp]
+    lib.tp_backward.argtypes = [vp, i64, i64, i64] + [vp] * 12 + [C.c_size_t, vp]
     lib.tp_profile_enable.argtypes = [vp, i32]
     lib.tp_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float)]
     for name in EXPORTS:
@@ -113,11 +113,11 @@ def tp_workspace_bytes(plan: Plan, n_edges: int) -> int:
     return n.value
 
 
-def tp_backward(plan: Plan, n_nodes_in: int, n_nodes_out: int, n_edges: int, Y, h, R, sender, receiver, row_ptr,
-                send_ptr, send_edge, dA, dY, dh, dR, workspace, workspace_bytes: int, stream=None) -> None:
+def tp_backward(plan: Plan, n_nodes_in: int, n_nodes_out: int, n_edges: int, Y, h, R, sender, row_ptr, send_ptr,
+                send_edge, dA, dY, dh, dR, workspace, workspace_bytes: int, stream=None) -> None:
     _check(lib.tp_backward(plan.handle, n_nodes_in, n_nodes_out, n_edges, _ptr(Y), _ptr(h), _ptr(R), _ptr(sender),
-                           _ptr(receiver), _ptr(row_ptr), _ptr(send_ptr), _ptr(send_edge), _ptr(dA), _ptr(dY),
-                           _ptr(dh), _ptr(dR), _ptr(workspace), workspace_bytes, _stream(stream)))
+                           _ptr(row_ptr), _ptr(send_ptr), _ptr(send_edge), _ptr(dA), _ptr(dY), _ptr(dh), _ptr(dR),
+                           _ptr(workspace), workspace_bytes, _stream(stream)))
 
 
 def tp_profile_enable(plan: Plan, on: bool) -> None:
@@ -125,7 +125,7 @@ def tp_profile_enable(plan: Plan, on: bool) -> None:
 
 
 def tp_profile_read(plan: Plan) -> Tuple[float, float, float]:
-    """(forward, receiver-side backward, sender-side backward) kernel durations in ms."""
+    """(forward, edge-walking backward, per-sender dh sum) kernel durations in ms."""
     f, r, s = C.c_float(), C.c_float(), C.c_float()
     _check(lib.tp_profile_read(plan.handle, C.byref(f), C.byref(r), C.byref(s)))
     return f.value, r.value, s.value

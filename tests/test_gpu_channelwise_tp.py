@@ -39,7 +39,7 @@ class TPRun:
         f = lambda x: torch.tensor(x, dtype=self.tdt, device=dev)
         i = lambda x: torch.tensor(x, dtype=torch.int32, device=dev)
         self.Y, self.h, self.R, self.dA = f(inp.Y), f(inp.h), f(inp.R), f(inp.dA)
-        self.sender, self.receiver, self.row_ptr = i(inp.sender), i(inp.receiver), i(inp.row_ptr)
+        self.sender, self.row_ptr = i(inp.sender), i(inp.row_ptr)
         self.send_ptr, self.send_edge = i(inp.send_ptr), i(inp.send_edge)
         self.A = torch.full((self.N, wl.num_channels, wl.n_out), float("nan"), dtype=self.tdt, device=dev)
         self.dY, self.dh, self.dR = (torch.full_like(x, float("nan")) for x in (self.Y, self.h, self.R))
@@ -52,9 +52,8 @@ class TPRun:
         return self.A.cpu().numpy()
 
     def backward(self):
-        self.tp.tp_backward(self.plan, self.N, self.N, self.E, self.Y, self.h, self.R, self.sender, self.receiver,
-                            self.row_ptr, self.send_ptr, self.send_edge, self.dA, self.dY, self.dh, self.dR, self.ws,
-                            self.ws_bytes)
+        self.tp.tp_backward(self.plan, self.N, self.N, self.E, self.Y, self.h, self.R, self.sender, self.row_ptr,
+                            self.send_ptr, self.send_edge, self.dA, self.dY, self.dh, self.dR, self.ws, self.ws_bytes)
         self.torch.cuda.synchronize()
         return self.dY.cpu().numpy(), self.dh.cpu().numpy(), self.dR.cpu().numpy()
 
@@ -166,7 +165,7 @@ def test_empty_graph_and_argument_errors(tp):
     # no edges: A and dh are zeroed
     zeros = torch.zeros(run.N + 1, dtype=torch.int32, device="cuda:0")
     tp.tp_forward(run.plan, run.N, run.N, 0, None, run.h, None, None, zeros, run.A)
-    tp.tp_backward(run.plan, run.N, run.N, 0, None, run.h, None, None, None, zeros, zeros, None, run.dA, None, run.dh,
+    tp.tp_backward(run.plan, run.N, run.N, 0, None, run.h, None, None, zeros, zeros, None, run.dA, None, run.dh,
                    None, None, 0)
     torch.cuda.synchronize()
     assert not run.A.cpu().numpy().any() and not run.dh.cpu().numpy().any()
@@ -178,7 +177,7 @@ def test_empty_graph_and_argument_errors(tp):
         tp.tp_forward(run.plan, run.N, run.N, run.E, run.Y.data_ptr() + 4, run.h, run.R, run.sender, run.row_ptr, run.A)
     assert e.value.status == 1
     with pytest.raises(tp.ScError) as e:
-        tp.tp_backward(run.plan, run.N, run.N, run.E, run.Y, run.h, run.R, run.sender, run.receiver, run.row_ptr,
+        tp.tp_backward(run.plan, run.N, run.N, run.E, run.Y, run.h, run.R, run.sender, run.row_ptr,
                        run.send_ptr, run.send_edge, run.dA, run.dY, run.dh, run.dR, run.ws, 16)
     assert e.value.status == 3
     # the plan still works
