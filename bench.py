@@ -325,6 +325,12 @@ def measure_tp(wl, steps, warmup):
     bwd_rate = (bwd_bytes + bwd_ws_bytes) / (bwd_ms * 1e-3) / 1e9
     step_bytes = fwd_bytes + bwd_bytes + E * wl.n_Y * elem + node_h   # + dY and dh out
     k_ops = info.ops[1]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath) and info.specialised:
+        ent = json.load(open(tpath)).get("tp:" + wl.name)
+        if ent:
+            traffic = 1024.0 * (ent["fetch_kib"] * ent["fetch_scale"] + ent["write_kib"] * ent["write_scale"])
     del Rs, dRs, R0, ws
     torch.cuda.empty_cache()
     return {
@@ -336,7 +342,7 @@ def measure_tp(wl, steps, warmup):
         "step_hbm_fraction": step_bytes / (dt / steps) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "backward over the edges (dR, dY partials, per-edge dh shares)",
                      "achieved": bwd_rate, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_rate / HBM_PEAK_GBS,
-                     "traffic": None, "kernel_ms": bwd_ms, "algorithmic_bytes_per_launch": bwd_bytes + bwd_ws_bytes,
+                     "traffic": traffic, "kernel_ms": bwd_ms, "algorithmic_bytes_per_launch": bwd_bytes + bwd_ws_bytes,
                      "valu_issue_frac": E * K * k_ops / (bwd_ms * 1e-3) / VALU_ISSUE_PEAK if k_ops else None,
                      "forward": {"kernel_ms": fwd_ms, "algorithmic_bytes_per_launch": fwd_bytes,
                                  "achieved": fwd_bytes / (fwd_ms * 1e-3) / 1e9},

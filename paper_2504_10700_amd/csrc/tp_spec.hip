@@ -87,6 +87,15 @@ __device__ __forceinline__ void load_uniform(const T* __restrict__ Y, int e, T (
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// blockIdx -> logical block such that the blocks an XCD receives (round-robin by blockIdx) form
+// one contiguous range of atoms: the atoms of one structure, which share their senders' rows of
+// h, then meet in one XCD's L2.  gridDim.x is a multiple of kXcds.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int64_t xcd_contiguous_block() {
+  const int64_t per = gridDim.x / kXcds;
+  return (blockIdx.x % kXcds) * per + blockIdx.x / kXcds;
+}
+
 template <typename T, typename G>
 __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, int64_t n_units,
                                                            const T* __restrict__ Y, const T* __restrict__ h,
@@ -95,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, 
                                                            const int32_t* __restrict__ row_ptr, T* __restrict__ A) {
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = uniform(threadIdx.x / kLanes);
-  const int64_t unit = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+  const int64_t unit = xcd_contiguous_block() * kWaves + wave;
   if (unit >= n_units) return;
   const size_t node = unit / chblocks;
   const int cb = static_cast<int>(unit % chblocks);
@@ -143,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = uniform(threadIdx.x / kLanes);
   T* stage = stage_all[wave];
-  const int64_t unit = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+  const int64_t unit = xcd_contiguous_block() * kWaves + wave;
   if (unit >= n_units) return;
   const size_t node = unit / chblocks;
   const int cb = static_cast<int>(unit % chblocks);
@@ -211,7 +220,10 @@ bool matches(const tp_plan* plan) {
          static_cast<int>(plan->paths.size()) == G::kP;
 }
 
-unsigned grid_for(int64_t n_units) { return static_cast<unsigned>((n_units + kWaves - 1) / kWaves); }
+unsigned grid_for(int64_t n_units) {
+  const int64_t blocks = (n_units + kWaves - 1) / kWaves;
+  return static_cast<unsigned>((blocks + kXcds - 1) / kXcds * kXcds);
+}
 
 template <typename T, typename G>
 hipError_t fwd_launch(const tp_plan* plan, const FwdArgs& a, hipStream_t stream) {

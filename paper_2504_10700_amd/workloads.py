@@ -130,10 +130,13 @@ def make_cotangent(wl: Workload, num_nodes: Optional[int] = None) -> np.ndarray:
 # Channelwise tensor product (Algorithm 1): a graph, per-edge Y and R, per-node h.
 #
 # The paper's graphs come from a 4 Angstrom cutoff on molecules, liquids and crystals
-# (Evaluation, dataset description): a few to a few tens of neighbours per atom.  The
-# stand-in draws the in-degree of every atom from Poisson(mean_degree) (clipped to
-# 4 * mean_degree, and about 1% of the atoms receive nothing), senders uniformly among the
-# other atoms, edges grouped by receiver as neighbour lists are.  Y, h, dA ~ N(0,1) (the
+# (Evaluation, dataset description): a few to a few tens of neighbours per atom, and a batch
+# is many small structures (1..768 atoms) whose edges never cross structure boundaries.  The
+# stand-in cuts the atoms into structures of 10..190 atoms (as for `large_batch`), draws the
+# in-degree of every atom from Poisson(mean_degree) (clipped to 4 * mean_degree, and about 1%
+# of the atoms receive nothing), senders uniformly among the other atoms of the same
+# structure (several edges between one pair stand for periodic images), edges grouped by
+# receiver as neighbour lists are.  Y, h, dA ~ N(0,1) (the
 # components of spherical harmonics in the usual "component" normalisation have unit rms);
 # R ~ N(0,1) / sqrt(mean_degree * #paths into the same l3) so that A is O(1).
 
@@ -166,6 +169,7 @@ TP_WORKLOADS = {
     "tp_tiny": TPWorkload("tp_tiny", 40, 5, 8, 1, 1, 1, "f64", 4001),
     "tp_first_layer": TPWorkload("tp_first_layer", 10_000, 20, 128, 3, 0, 3, "f32", 4002),
     "tp_training_step": TPWorkload("tp_training_step", 10_000, 20, 128, 3, 1, 3, "f32", 4003),
+    "tp_large_batch": TPWorkload("tp_large_batch", 50_000, 20, 128, 3, 1, 3, "f32", 4004),
 }
 
 
@@ -201,9 +205,18 @@ def make_tp_inputs(wl: TPWorkload, paths: Sequence[Sequence[int]]) -> TPInputs:
     deg[rng.random(N) < 0.01] = 0
     if N == 1:
         deg[:] = 0
+    # structures: consecutive runs of atoms; small graphs are one structure
+    if N >= 400:
+        sizes = structure_sizes(rng, max(1, N // 100), N)
+    else:
+        sizes = np.array([N])
+    first = np.repeat(np.cumsum(sizes) - sizes, sizes)    # first atom of every atom's structure
+    size_of = np.repeat(sizes, sizes)
+    deg[size_of == 1] = 0
     receiver = np.repeat(np.arange(N, dtype=np.int32), deg)
     E = int(receiver.size)
-    sender = rng.integers(0, max(N - 1, 1), size=E).astype(np.int32)
+    lo, span = first[receiver], size_of[receiver]
+    sender = (lo + rng.integers(0, 1 << 30, size=E) % np.maximum(span - 1, 1)).astype(np.int32)
     sender += (sender >= receiver).astype(np.int32)      # never the receiver itself
     paths = np.asarray(paths, dtype=np.int64).reshape(-1, 3)
     per_l3 = np.bincount(paths[:, 2], minlength=wl.L_max + 1)
