@@ -214,6 +214,18 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
 
 // Second-order pass: the backward skeleton with one more input row (H) and one more output
 // row (ddB) per node; its dW2' rows leave through the same per-tile partial rows.
+//
+// The generated program keeps about 290 values live.  Two kernels:
+//  * spec_double_backward_kernel keeps everything in registers (256 VGPRs + AGPRs, one wave
+//    per SIMD);
+//  * spec_double_backward_lds_kernel keeps the folded weights w' and the dW2' accumulators
+//    (2 x kS values per lane) in LDS columns - w' is re-read and the accumulators are updated
+//    once per node - which brings it under 256 registers without scratch, so that two waves
+//    share a SIMD (measured on MI355X, fp32, 0e+1o: 80 us instead of 106 us at 10k nodes,
+//    1.24 ms instead of 1.45 ms at 200k).  It is used where it fits (kUseLdsState): for the
+//    larger basis or fp64 it would spill.  Small changes to its text move the register
+//    allocation across the spill threshold: check the compiler's resource report
+//    (-Rpass-analysis=kernel-resource-usage) after touching it.
 template <typename T, typename G>
 __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
     int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
@@ -271,6 +283,81 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
     out[i] = acc;
   }
 }
+
+// See above.  LDS: w' [kSpecWaves][kS][64] | sums [kSpecWaves][kS][64] | stage [kSpecWaves][64][kNlm].
+template <typename T, typename G>
+__global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void spec_double_backward_lds_kernel(
+    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
+    const T* __restrict__ H, T* __restrict__ ddB, T* __restrict__ dA2, T* __restrict__ partial,
+    const TileDesc* __restrict__ tiles, const int32_t* __restrict__ perm) {
+  extern __shared__ unsigned char lds_raw[];
+  T* red = reinterpret_cast<T*>(lds_raw);  // [kSpecWaves][kS][64]: every wave's w' columns
+  T* acc_all = red + kSpecWaves * G::kS * kLanes;                         // [kSpecWaves][kS][64] dW2' sums
+  T* stage = acc_all + kSpecWaves * G::kS * kLanes + wave_of_thread() * kLanes * G::kNlm;  // [64][kNlm] per wave
+  constexpr bool kStageB = G::kNLM * sizeof(T) != 16;
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int logical = xcd_contiguous_block();
+  if (logical >= n_blocks) return;  // uniform per workgroup
+  const int tile = logical / chblocks, cb = logical % chblocks;
+  const TileDesc td = tiles[tile];
+  if (td.count == 0) return;        // unused descriptor; uniform per workgroup
+  const int j0 = td.start + td.count * wave / kSpecWaves;
+  const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
+  const int ch = cb * kLanes + lane;
+  T* dwl = acc_all + wave * G::kS * kLanes + lane;
+#pragma unroll
+  for (int s = 0; s < G::kS; ++s) dwl[s * kLanes] = T(0);
+  if (j0 < j1) {
+    T* wl = red + wave * G::kS * kLanes + lane;   // this wave's slice of red holds w' until the end
+    {
+      T w0[G::kS];
+      G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w0);
+#pragma unroll
+      for (int s = 0; s < G::kS; ++s) wl[s * kLanes] = w0[s];
+    }
+    // one register set of inputs: the next node's rows are requested right after the
+    // arithmetic of the current one has consumed them, ahead of its stores
+    T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
+    size_t node = perm[j0];
+    Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+    Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+    Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+    for (int j = j0; j < j1; ++j) {
+      T w[G::kS];
+      asm volatile("" ::: "memory");  // keep the reads of w' inside the loop (registers are short)
+#pragma unroll
+      for (int s = 0; s < G::kS; ++s) w[s] = wl[s * kLanes];
+      T dw[G::kS];
+#pragma unroll
+      for (int s = 0; s < G::kS; ++s) dw[s] = T(0);
+      G::double_backward(a, w, g, h, ddb, da, dw);
+#pragma unroll
+      for (int s = 0; s < G::kS; ++s) dwl[s * kLanes] += dw[s];
+      const size_t cur = node;
+      if (j + 1 < j1) {
+        node = perm[j + 1];
+        Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+        Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+        Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+      }
+      store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da);
+      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb);
+      else Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+    }
+  }
+  __syncthreads();
+  T* out = partial + (static_cast<size_t>(tile) * chblocks + cb) * G::kS * kLanes;
+  for (int i = threadIdx.x; i < G::kS * kLanes; i += kSpecThreads) {
+    T acc = acc_all[i];
+#pragma unroll
+    for (int v = 1; v < kSpecWaves; ++v) acc += acc_all[v * G::kS * kLanes + i];
+    out[i] = acc;
+  }
+}
+
+template <typename T, typename G>
+constexpr bool kUseLdsState = sizeof(T) == 4 && G::kS <= 32;
 
 // Second stage of the dW reduction, two small launches (device-scope fences, which a
 // single-launch "last wave finishes the job" scheme needs, flush the per-XCD L2s and cost
@@ -388,16 +475,19 @@ hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const v
                       void* dA2, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
-  const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
-  if (lds > 64 * 1024) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&spec_double_backward_kernel<T, G>),
+  constexpr bool kLds = kUseLdsState<T, G>;
+  const size_t lds = sizeof(T) * kSpecWaves * ((kLds ? 2 : 1) * G::kS + G::kNlm) * kLanes;
+  auto kernel = &spec_double_backward_kernel<T, G>;
+  if constexpr (kLds) kernel = &spec_double_backward_lds_kernel<T, G>;
+  if (lds > 64 * 1024) {  // above the default dynamic LDS limit: raise it for this kernel
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((spec_double_backward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
-                     plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
-                     static_cast<const T*>(W), static_cast<const T*>(dB), static_cast<const T*>(H),
-                     static_cast<T*>(ddB), static_cast<T*>(dA2), static_cast<T*>(ws.partial), ws.tiles, ws.perm);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpecThreads), lds, stream, plan->cfg.num_channels, shape.chblocks,
+                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(W), static_cast<const T*>(dB),
+                     static_cast<const T*>(H), static_cast<T*>(ddB), static_cast<T*>(dA2),
+                     static_cast<T*>(ws.partial), ws.tiles, ws.perm);
   return hipGetLastError();
 }
 
