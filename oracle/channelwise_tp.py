@@ -116,3 +116,44 @@ def backward(cfg: TPConfig, Y, h, R, sender, receiver, dA):
     dh = np.zeros_like(h)
     np.add.at(dh, sender, dhj)
     return dY, dh, dR
+
+
+def double_backward(cfg: TPConfig, Y, h, R, sender, receiver, dA, HY, Hh, HR):
+    """Second-order pass needed when a loss depends on the gradients (forces are derivatives of
+    the energy, Section 2.2, and reach the loss through dY).
+
+    With (dY, dh, dR) = backward(..., dA) and psi = sum(HY*dY) + sum(Hh*dh) + sum(HR*dR) returns
+        ddA = dpsi/d(dA)  (N, K, n_out)      d2Y = dpsi/dY  (E, n_Y)
+        d2h = dpsi/dh     (N, K, n_h)        d2R = dpsi/dR  (E, P, K)
+    written out from the definition: every message is linear in each of Y, h and R, so psi is
+    the sum over edges of dA[receiver] contracted with the message in which, in turn, Y, h or R
+    is replaced by its cotangent, and the gradients differentiate those three terms.
+    """
+    Y, h, R, dA, HY, Hh, HR = (np.asarray(x, dtype=np.float64) for x in (Y, h, R, dA, HY, Hh, HR))
+    sender, receiver = np.asarray(sender), np.asarray(receiver)
+    g = dA[receiver]                                     # (E, K, n_out)
+    x, hx = h[sender], Hh[sender]                        # (E, K, n_h)
+    E = Y.shape[0]
+    tdot = np.zeros((E, cfg.num_channels, cfg.n_out))    # derivative of every message along (HY, Hh, HR)
+    d2Y = np.zeros_like(Y)
+    d2R = np.zeros_like(R)
+    d2x = np.zeros_like(x)
+    for p, (l1, l2, l3) in enumerate(enumerate_paths(cfg)):
+        C = coupling_tensor(l1, l2, l3)
+        s1, s2, s3 = irrep_slice(l1), irrep_slice(l2), irrep_slice(l3)
+        y, hy, xx, hxx, r, hr, gg = Y[:, s1], HY[:, s1], x[:, :, s2], hx[:, :, s2], R[:, p, :], HR[:, p, :], g[:, :, s3]
+        tdot[:, :, s3] += (np.einsum("abc,ek,ea,ekb->ekc", C, r, hy, xx, optimize=True)
+                           + np.einsum("abc,ek,ea,ekb->ekc", C, r, y, hxx, optimize=True)
+                           + np.einsum("abc,ek,ea,ekb->ekc", C, hr, y, xx, optimize=True))
+        # psi_e = sum_c g[c] * tdot[c]; its derivatives with respect to y, x and r
+        d2Y[:, s1] += (np.einsum("abc,ek,ekb,ekc->ea", C, r, hxx, gg, optimize=True)
+                       + np.einsum("abc,ek,ekb,ekc->ea", C, hr, xx, gg, optimize=True))
+        d2x[:, :, s2] += (np.einsum("abc,ek,ea,ekc->ekb", C, r, hy, gg, optimize=True)
+                          + np.einsum("abc,ek,ea,ekc->ekb", C, hr, y, gg, optimize=True))
+        d2R[:, p, :] = (np.einsum("abc,ea,ekb,ekc->ek", C, hy, xx, gg, optimize=True)
+                        + np.einsum("abc,ea,ekb,ekc->ek", C, y, hxx, gg, optimize=True))
+    ddA = np.zeros_like(dA)
+    np.add.at(ddA, receiver, tdot)
+    d2h = np.zeros_like(h)
+    np.add.at(d2h, sender, d2x)
+    return ddA, d2Y, d2h, d2R

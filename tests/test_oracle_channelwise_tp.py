@@ -182,3 +182,63 @@ def test_backward_against_finite_differences_and_euler():
     # senders without outgoing edges and edges-less receivers
     unused = np.setdiff1d(np.arange(N), sender)
     assert not dh[unused].any()
+
+
+def test_double_backward_against_finite_differences_of_the_backward():
+    cfg = otp.TPConfig(3, 3, 1, 3)
+    N, E = 5, 13
+    Y, h, R, sender, receiver = random_case(cfg, N, E, 11)
+    rng = np.random.default_rng(12)
+    dA = rng.standard_normal((N, cfg.num_channels, cfg.n_out))
+    HY, Hh, HR = rng.standard_normal(Y.shape), rng.standard_normal(h.shape), rng.standard_normal(R.shape)
+    ddA, d2Y, d2h, d2R = otp.double_backward(cfg, Y, h, R, sender, receiver, dA, HY, Hh, HR)
+
+    def psi(Y_, h_, R_, dA_):
+        dY, dh, dR = otp.backward(cfg, Y_, h_, R_, sender, receiver, dA_)
+        return float((HY * dY).sum() + (Hh * dh).sum() + (HR * dR).sum())
+    eps = 1e-6
+    base = {"Y": Y, "h": h, "R": R, "dA": dA}
+    for name, grad in (("Y", d2Y), ("h", d2h), ("R", d2R), ("dA", ddA)):
+        for _ in range(10):
+            idx = tuple(rng.integers(0, s) for s in base[name].shape)
+            ap, am = dict(base), dict(base)
+            ap[name], am[name] = base[name].copy(), base[name].copy()
+            ap[name][idx] += eps
+            am[name][idx] -= eps
+            fd = (psi(ap["Y"], ap["h"], ap["R"], ap["dA"]) - psi(am["Y"], am["h"], am["R"], am["dA"])) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 2e-7 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
+
+
+def test_double_backward_identities():
+    cfg = otp.TPConfig(2, 3, 1, 3)
+    N, E = 6, 17
+    Y, h, R, sender, receiver = random_case(cfg, N, E, 13)
+    rng = np.random.default_rng(14)
+    dA = rng.standard_normal((N, cfg.num_channels, cfg.n_out))
+    HY, Hh, HR = rng.standard_normal(Y.shape), rng.standard_normal(h.shape), rng.standard_normal(R.shape)
+    ddA, d2Y, d2h, d2R = otp.double_backward(cfg, Y, h, R, sender, receiver, dA, HY, Hh, HR)
+    dY, dh, dR = otp.backward(cfg, Y, h, R, sender, receiver, dA)
+    psi = (HY * dY).sum() + (Hh * dh).sum() + (HR * dR).sum()
+    # psi is linear in dA, and of degree two in (Y, h, R) jointly with the cotangents taking one
+    # slot: Euler gives sum(Y*d2Y) + sum(h*d2h) + sum(R*d2R) = 2 * psi
+    assert np.isclose((dA * ddA).sum(), psi, rtol=1e-12)
+    assert np.isclose((Y * d2Y).sum() + (h * d2h).sum() + (R * d2R).sum(), 2 * psi, rtol=1e-12)
+    # choosing the cotangents equal to the inputs makes ddA three times the forward result
+    A = otp.forward(cfg, Y, h, R, sender, receiver, N)
+    ddA_same = otp.double_backward(cfg, Y, h, R, sender, receiver, dA, Y, h, R)[0]
+    assert np.allclose(ddA_same, 3.0 * A, atol=1e-12)
+    # a cotangent on one argument only leaves that argument's second derivative at zero
+    only_Y = otp.double_backward(cfg, Y, h, R, sender, receiver, dA, HY, 0 * Hh, 0 * HR)
+    assert not only_Y[1].any() and only_Y[2].any() and only_Y[3].any()
+    # rotating Y, h and their cotangents rotates ddA and d2Y, d2h; d2R is invariant
+    theta = np.array([-0.4, 0.9, 1.3])
+    D = [oc.wigner_D_real(l, theta) for l in range(4)]
+
+    def rot(x, lmax):
+        out = np.empty_like(x)
+        for l in range(lmax + 1):
+            out[..., l * l:(l + 1) ** 2] = x[..., l * l:(l + 1) ** 2] @ D[l].T
+        return out
+    r = otp.double_backward(cfg, rot(Y, 3), rot(h, 1), R, sender, receiver, rot(dA, 3), rot(HY, 3), rot(Hh, 1), HR)
+    assert np.allclose(r[0], rot(ddA, 3), atol=1e-12) and np.allclose(r[1], rot(d2Y, 3), atol=1e-12)
+    assert np.allclose(r[2], rot(d2h, 1), atol=1e-12) and np.allclose(r[3], d2R, atol=1e-12)
