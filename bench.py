@@ -351,6 +351,75 @@ def measure_tp(wl, steps, warmup):
     }
 
 
+def measure_tp_double_backward(wl, steps, warmup):
+    """Second-order pass of the channelwise tensor product alone: one step = tp_double_backward."""
+    import numpy as np
+    import torch
+    from paper_2504_10700_amd import tp_binding as tp
+    from paper_2504_10700_amd import workloads
+
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if wl.dtype == "f32" else torch.float64
+    elem = 4 if wl.dtype == "f32" else 8
+    plan = tp.tp_plan_create(wl.num_channels, wl.l_Y, wl.l_h, wl.L_max, tp.SC_F32 if wl.dtype == "f32" else tp.SC_F64, 0)
+    info = tp.tp_plan_info(plan)
+    inp = workloads.make_tp_inputs(wl, tp.tp_plan_paths(plan))
+    cot = workloads.make_tp_cotangents(wl, inp)
+    N, K, E, P = wl.num_nodes, wl.num_channels, int(inp.Y.shape[0]), int(info.num_paths)
+    f = lambda x: torch.tensor(x, dtype=tdt, device=dev)
+    i32 = lambda x: torch.tensor(x, dtype=torch.int32, device=dev)
+    Y, h, dA, HY, Hh = f(inp.Y), f(inp.h), f(inp.dA), f(cot[0]), f(cot[1])
+    sender, row_ptr, send_ptr, send_edge = i32(inp.sender), i32(inp.row_ptr), i32(inp.send_ptr), i32(inp.send_edge)
+    R0, HR0 = f(inp.R), f(cot[2])
+    del inp, cot
+    Rs, HRs = [R0, R0.clone()], [HR0, HR0.clone()]    # rotated: no reuse of the last step's rows from cache
+    d2Rs = [torch.empty_like(R0), torch.empty_like(R0)]
+    ddA, d2Y, d2h = torch.empty((N, K, wl.n_out), dtype=tdt, device=dev), torch.empty_like(Y), torch.empty_like(h)
+    ws_bytes = tp.tp_workspace_bytes(plan, E)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step(i):
+        tp.tp_double_backward(plan, N, N, E, Y, h, Rs[i % 2], sender, row_ptr, send_ptr, send_edge, dA, HY, Hh,
+                              HRs[i % 2], ddA, d2Y, d2h, d2Rs[i % 2], ws, ws_bytes)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tp.tp_profile_enable(plan, True)
+    ms = []
+    for i in range(min(steps, 30)):
+        step(i)
+        ms.append(tp.tp_profile_read_double_backward(plan))
+    tp.tp_profile_enable(plan, False)
+    tp.tp_plan_destroy(plan)
+    k_ms = float(np.mean(ms))
+    chblocks = (K + 63) // 64
+    # R, HR in and d2R out per edge, Y, HY, index; h, Hh, dA in and ddA out per node; plus the
+    # workspace rows this kernel writes (d2h shares, d2Y partials)
+    k_bytes = (E * (3 * P * K * elem + 2 * wl.n_Y * elem + 4) + N * K * (2 * wl.n_h + 2 * wl.n_out) * elem
+               + E * (K * wl.n_h + chblocks * wl.n_Y) * elem)
+    rate = k_bytes / (k_ms * 1e-3) / 1e9
+    k_ops = info.ops[2]
+    del Rs, HRs, d2Rs, R0, HR0, ws
+    torch.cuda.empty_cache()
+    return {
+        "metric": "edges/sec channelwise tensor product, second-order pass", "value": E / (dt / steps),
+        "unit": "edges/s", "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3, "dtype": wl.dtype,
+        "config": {"workload": f"{wl.name}: {N} nodes, {E} edges, {K} channels, l_Y={wl.l_Y}, l_h={wl.l_h}, "
+                               f"L_max={wl.L_max}, {P} paths, second-order pass only",
+                   "kernel": "generated" if info.specialised else "table-driven"},
+        "roofline": {"bound": "hbm", "kernel": "second-order pass over the edges", "achieved": rate,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rate / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_ms": k_ms, "algorithmic_bytes_per_launch": k_bytes,
+                     "valu_issue_frac": E * K * k_ops / (k_ms * 1e-3) / VALU_ISSUE_PEAK if k_ops else None},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -375,7 +444,8 @@ def main():
 
     if args.tp:
         name = args.workload if args.workload in workloads.TP_WORKLOADS else "tp_training_step"
-        print(json.dumps(measure_tp(workloads.TP_WORKLOADS[name], args.steps, args.warmup)))
+        fn = measure_tp_double_backward if args.double_backward else measure_tp
+        print(json.dumps(fn(workloads.TP_WORKLOADS[name], args.steps, args.warmup)))
         return
     wl = workloads.WORKLOADS[args.workload]
     if args.double_backward:
@@ -396,6 +466,8 @@ def main():
         out["also"]["double_backward_training_step"] = measure_double_backward(wl, 100, 10)
         out["also"]["double_backward_large_batch"] = measure_double_backward(workloads.WORKLOADS["large_batch"], 20, 3)
         out["also"]["channelwise_tp_training_step"] = measure_tp(workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
+        out["also"]["channelwise_tp_double_backward_training_step"] = measure_tp_double_backward(
+            workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
     print(json.dumps(out))
 
 

@@ -66,9 +66,10 @@ typedef struct {
   int32_t num_paths;   /* P: second extent of R */
   int32_t specialised; /* 1 if generated straight-line kernels serve this plan */
   /* generated kernels only (else 0): vector instructions / floating-point operations (a fused
-   * multiply-add counts as two) per (edge, channel) of the forward and the backward kernel */
-  int32_t ops[2];
-  int32_t flops[2];
+   * multiply-add counts as two) per (edge, channel) of the forward, the backward and the
+   * second-order kernel */
+  int32_t ops[3];
+  int32_t flops[3];
 } tp_info;
 
 /* Section 4.1, inputs of Algorithm 1: fixes K and the three l ranges, derives the sparse
@@ -97,7 +98,7 @@ sc_status tp_forward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, int
                      const void* h, const void* R, const int32_t* sender, const int32_t* row_ptr, void* A,
                      void* hip_stream);
 
-/* Bytes of device workspace tp_backward needs (partial sums of dY per 64-channel block and
+/* Bytes of device workspace tp_backward and tp_double_backward need (partial sums of dY per 64-channel block and
  * the per-edge shares of dh: about n_edges * (K * n_h + ceil(K/64) * n_Y) elements). */
 sc_status tp_workspace_bytes(const tp_plan* plan, int64_t n_edges, size_t* bytes);
 
@@ -115,12 +116,30 @@ sc_status tp_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, in
                       const int32_t* send_ptr, const int32_t* send_edge, const void* dA, void* dY, void* dh,
                       void* dR, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Second-order pass (Section 2.2: forces are derivatives of the energy and reach a force loss
+ * through dY, so that loss differentiates tp_backward once more).  With (dY, dh, dR) as
+ * returned by tp_backward for dA and
+ *   psi = sum(HY * dY) + sum(Hh * dh) + sum(HR * dR)
+ * it returns the gradients of psi with respect to the four arguments of the backward:
+ *   HY  dev [n_edges][n_Y]   Hh dev [n_nodes_in][K][n_h]   HR dev [n_edges][num_paths][K]   (cotangents, inputs)
+ *   ddA dev [n_nodes_out][K][n_out]   d2Y dev [n_edges][n_Y]   d2h dev [n_nodes_in][K][n_h]
+ *   d2R dev [n_edges][num_paths][K]                                                   (all overwritten)
+ * Everything else (graph arrays, workspace of tp_workspace_bytes, zero rows for atoms without
+ * edges, fixed summation orders) is as for tp_backward. */
+sc_status tp_double_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, int64_t n_edges, const void* Y,
+                             const void* h, const void* R, const int32_t* sender, const int32_t* row_ptr,
+                             const int32_t* send_ptr, const int32_t* send_edge, const void* dA, const void* HY,
+                             const void* Hh, const void* HR, void* ddA, void* d2Y, void* d2h, void* d2R,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Measurement helper as in sc.h: while enabled, tp_forward / tp_backward bracket their
  * main kernels with HIP events; tp_profile_read returns the durations in milliseconds of
  * the forward kernel, the edge-walking backward kernel and the per-sender sum of dh of the
  * most recent calls (negative if none). */
 sc_status tp_profile_enable(tp_plan* plan, int32_t on);
 sc_status tp_profile_read(tp_plan* plan, float* forward_ms, float* backward_ms, float* dh_sum_ms);
+/* Same for the edge-walking kernel of the most recent tp_double_backward call. */
+sc_status tp_profile_read_double_backward(tp_plan* plan, float* ms);
 
 #ifdef __cplusplus
 }

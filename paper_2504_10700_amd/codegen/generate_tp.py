@@ -11,6 +11,10 @@ bilinear couplings through the same sparse tensors with a different free index:
   backward  q[l1]    = C . h_l2 . g_l3 ;  dR[p] = Y_l1 . q ;  dY_l1 += R[p] q
             s[l2]    = C . Y_l1 . g_l3 ;  dh_l2 += R[p] s      (the edge's share of its sender's dh)
 
+A third program, the second-order pass, is derived from the forward one (autodiff.py): the
+message's derivative along the cotangents (hy, hh, hr) of (dY, dh, dR) is added to ddA, and
+the reverse-mode derivative of sum(g * that derivative) gives d2Y, d2h and d2R.
+
 The sparse terms come from the library's host tables (tp_plan_terms on a host-only plan);
 every coupling tensor is divided by its most frequent |coefficient| (the factor is folded
 into the one multiplication by R[p]) so that most terms need no constant.  The programs are
@@ -26,6 +30,7 @@ from typing import Dict, List, Optional, Tuple
 
 import numpy as np
 
+from .autodiff import replay_with_tangent, reverse
 from .program import Program
 from .scheme import couple_into
 from .tables import HOST_LIB
@@ -61,7 +66,7 @@ class TPTables:
             if st != 0:
                 raise RuntimeError(lib.sc_last_error().decode())
         check(lib.tp_plan_create(C.byref(cfg), C.byref(plan)))
-        info = (C.c_int32 * 9)()
+        info = (C.c_int32 * 11)()
         check(lib.tp_plan_info(plan, info))
         self.n_Y, self.n_h, self.n_out, self.P = info[0], info[1], info[2], info[3]
         paths = np.zeros((self.P, 3), dtype=np.int32)
@@ -156,6 +161,76 @@ def build_programs(tab: TPTables) -> Tuple[Program, Program]:
     return F, Bq
 
 
+def build_double_backward(tab: TPTables, F: Program) -> Program:
+    """psi = sum_c g[c] * (derivative of the edge's message along (hy, hh, hr)):
+    dda += that derivative; d2y, d2h, d2r = d psi / d (y, h, r) (overwritten)."""
+    P = Program()
+    y = [P.inp(f"y[{a}]") for a in range(tab.n_Y)]
+    hy = [P.inp(f"hy[{a}]") for a in range(tab.n_Y)]
+    h = [P.inp(f"h[{b}]") for b in range(tab.n_h)]
+    hh = [P.inp(f"hh[{b}]") for b in range(tab.n_h)]
+    r = [P.inp(f"r[{p}]") for p in range(tab.P)]
+    hr = [P.inp(f"hr[{p}]") for p in range(tab.P)]
+    g = [P.inp(f"g[{c}]") for c in range(tab.n_out)]
+    dda = [P.inp(f"dda[{c}]") for c in range(tab.n_out)]
+    unused = P.inp("T(0)")     # primal value of the forward accumulator: never live
+    inputs = {f"y[{a}]": (y[a], hy[a]) for a in range(tab.n_Y)}
+    inputs.update({f"h[{b}]": (h[b], hh[b]) for b in range(tab.n_h)})
+    inputs.update({f"r[{p}]": (r[p], hr[p]) for p in range(tab.P)})
+    inputs.update({f"acc[{c}]": (unused, None) for c in range(tab.n_out)})
+    outs = replay_with_tangent(F, P, inputs)
+    seeds: Dict[int, int] = {}
+    for c in range(tab.n_out):
+        t = outs[f"acc[{c}]"][1]
+        if t is not None:
+            seeds[t] = P.add(seeds.get(t), g[c])
+    adj = reverse(P, seeds)
+    for c in range(tab.n_out):
+        P.out(f"dda[{c}]", P.add(dda[c], outs[f"acc[{c}]"][1]))
+    for p in range(tab.P):
+        P.out(f"d2r[{p}]", adj.get(r[p]))
+    for a in range(tab.n_Y):
+        P.out(f"d2y[{a}]", adj.get(y[a]))
+    for b in range(tab.n_h):
+        P.out(f"d2h[{b}]", adj.get(h[b]))
+    return P
+
+
+def self_check_double(tab: TPTables, D: Program, dtype=np.float64) -> Dict[str, float]:
+    rng = np.random.default_rng(1357)
+    n = 1500
+    shapes = {"y": tab.n_Y, "hy": tab.n_Y, "h": tab.n_h, "hh": tab.n_h, "r": tab.P, "hr": tab.P, "g": tab.n_out}
+    v = {k: rng.standard_normal((n, m)).astype(dtype).astype(np.float64) for k, m in shapes.items()}
+    p, a, b, c, coef = tab.terms
+    dda = np.zeros((n, tab.n_out))
+    d2r = np.zeros((n, tab.P))
+    d2y = np.zeros((n, tab.n_Y))
+    d2h = np.zeros((n, tab.n_h))
+    for t in range(len(coef)):
+        Y, HY, X, HX, R, HR, G = (v["y"][:, a[t]], v["hy"][:, a[t]], v["h"][:, b[t]], v["hh"][:, b[t]],
+                                  v["r"][:, p[t]], v["hr"][:, p[t]], v["g"][:, c[t]])
+        dda[:, c[t]] += coef[t] * (HR * Y * X + R * HY * X + R * Y * HX)
+        d2r[:, p[t]] += coef[t] * G * (HY * X + Y * HX)
+        d2y[:, a[t]] += coef[t] * G * (HR * X + R * HX)
+        d2h[:, b[t]] += coef[t] * G * (HR * Y + R * HY)
+    inputs = {f"{k}[{i}]": v[k][:, i] for k, m in shapes.items() for i in range(m)}
+    inputs.update({f"dda[{i}]": np.zeros(n) for i in range(tab.n_out)})
+    inputs["T(0)"] = np.zeros(n)
+    res = D.evaluate(inputs, dtype)
+
+    def col(x):
+        return np.zeros(n) if x is None else x.astype(np.float64)
+
+    def err(x, ref):
+        return float(np.abs(x - ref).max() / np.sqrt((ref ** 2).mean()))
+    return {
+        "ddA": err(np.stack([col(res[f"dda[{i}]"]) for i in range(tab.n_out)], 1), dda),
+        "d2R": err(np.stack([col(res[f"d2r[{i}]"]) for i in range(tab.P)], 1), d2r),
+        "d2Y": err(np.stack([col(res[f"d2y[{i}]"]) for i in range(tab.n_Y)], 1), d2y),
+        "d2h": err(np.stack([col(res[f"d2h[{i}]"]) for i in range(tab.n_h)], 1), d2h),
+    }
+
+
 def self_check(tab: TPTables, F: Program, Bq: Program, dtype=np.float64) -> Dict[str, float]:
     rng = np.random.default_rng(2468)
     n = 1500
@@ -198,9 +273,9 @@ def flops(c: Dict[str, int]) -> int:
     return 2 * (c.get("fma", 0) + c.get("fnma", 0) + c.get("cfma", 0)) + sum(c.get(k, 0) for k in ("mul", "add", "sub", "cmul"))
 
 
-def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program) -> str:
+def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program, D: Program) -> str:
     l_Y, l_h, L_max = spec
-    cs = [F.count(), Bq.count()]
+    cs = [F.count(), Bq.count(), D.count()]
     L = []
     L.append(f"// GENERATED by paper_2504_10700_amd/codegen/generate_tp.py for l_Y={l_Y}, l_h={l_h}, L_max={L_max}.  Do not edit.")
     L.append("//")
@@ -210,9 +285,9 @@ def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program) -> str:
     L.append(f"  static constexpr int kLY = {l_Y}, kLh = {l_h}, kLout = {L_max};")
     L.append(f"  static constexpr int kNY = {tab.n_Y}, kNh = {tab.n_h}, kNout = {tab.n_out}, kP = {tab.P};")
     L.append("  // vector instructions / flops (a fused multiply-add counts twice) per (edge, channel):")
-    L.append("  // forward, backward")
-    L.append("  static constexpr int kOps[2] = {" + ", ".join(str(c["total"]) for c in cs) + "};")
-    L.append("  static constexpr int kFlops[2] = {" + ", ".join(str(flops(c)) for c in cs) + "};")
+    L.append("  // forward, backward, second-order pass")
+    L.append("  static constexpr int kOps[3] = {" + ", ".join(str(c["total"]) for c in cs) + "};")
+    L.append("  static constexpr int kFlops[3] = {" + ", ".join(str(flops(c)) for c in cs) + "};")
     L.append("")
     L.append("  // acc += message of one edge")
     L.append("  template <typename T>")
@@ -228,6 +303,18 @@ def emit_inc(tag: str, spec, tab: TPTables, F: Program, Bq: Program) -> str:
     L.append("                                                  const T (&g)[kNout], T (&dr)[kP], T (&dy)[kNY], T (&dh)[kNh]) {")
     L.append(Bq.emit("T", "    "))
     L.append("  }")
+    L.append("")
+    L.append("  // Second-order pass of one edge.  hy, hh, hr: cotangents of (dY, dh, dR); g = dA of the receiver.")
+    L.append("  // dda += derivative of the edge's message along (hy, hh, hr); with psi = sum(g * that derivative):")
+    L.append("  // d2r = d psi / d r, d2y = this channel's share of d psi / d y, d2h = the edge's share of d psi / d h")
+    L.append("  // (all three overwritten).")
+    L.append("  template <typename T>")
+    L.append("  static __device__ __forceinline__ void double_backward(const T (&y)[kNY], const T (&hy)[kNY], const T (&h)[kNh],")
+    L.append("                                                         const T (&hh)[kNh], const T (&r)[kP], const T (&hr)[kP],")
+    L.append("                                                         const T (&g)[kNout], T (&dda)[kNout], T (&d2r)[kP],")
+    L.append("                                                         T (&d2y)[kNY], T (&d2h)[kNh]) {")
+    L.append(D.emit("T", "    "))
+    L.append("  }")
     L.append("};")
     return "\n".join(L) + "\n"
 
@@ -236,14 +323,19 @@ def generate(tag: str, lib_path: str = HOST_LIB, verbose: bool = True) -> str:
     spec = SPECS[tag]
     tab = TPTables(lib_path, *spec)
     F, Bq = build_programs(tab)
+    D = build_double_backward(tab, F)
     e64 = self_check(tab, F, Bq, np.float64)
     assert max(e64.values()) < 1e-12, e64
+    d64 = self_check_double(tab, D, np.float64)
+    assert max(d64.values()) < 1e-12, d64
     if verbose:
         e32 = self_check(tab, F, Bq, np.float32)
-        print(f"[tp {tag}] P={tab.P} terms={len(tab.terms[4])} ops fwd={F.count()['total']} bwd={Bq.count()['total']}")
-        print(f"[tp {tag}] fp64 self-check max|err|/rms: {e64}")
-        print(f"[tp {tag}] fp32 emulation  max|err|/rms: {e32}")
-    return emit_inc(tag, spec, tab, F, Bq)
+        d32 = self_check_double(tab, D, np.float32)
+        print(f"[tp {tag}] P={tab.P} terms={len(tab.terms[4])} ops fwd={F.count()['total']} bwd={Bq.count()['total']} "
+              f"second-order={D.count()['total']}")
+        print(f"[tp {tag}] fp64 self-check max|err|/rms: {e64} {d64}")
+        print(f"[tp {tag}] fp32 emulation  max|err|/rms: {e32} {d32}")
+    return emit_inc(tag, spec, tab, F, Bq, D)
 
 
 def main(argv=None) -> int:

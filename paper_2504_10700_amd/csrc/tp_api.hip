@@ -130,7 +130,7 @@ sc_status tp_plan_create(const tp_config* cfg, tp_plan** out_plan) {
 sc_status tp_plan_destroy(tp_plan* plan) {
   if (!plan) return SC_OK;
   sc_status st = SC_OK;
-  for (int i = 0; i < 6; ++i)
+  for (int i = 0; i < 8; ++i)
     if (plan->ev[i]) (void)hipEventDestroy(plan->ev[i]);
   if (plan->dev_blob) {
     DeviceGuard guard(plan->cfg.device);
@@ -179,13 +179,13 @@ sc_status tp_profile_enable(tp_plan* plan, int32_t on) {
   DeviceGuard guard(plan->cfg.device);
   if (!guard.ok) return set_error(SC_ERR_HIP, "tp_profile_enable: cannot make the plan's device current");
   if (on && !plan->ev[0]) {
-    for (int i = 0; i < 6; ++i) {
+    for (int i = 0; i < 8; ++i) {
       const hipError_t e = hipEventCreate(&plan->ev[i]);
       if (e != hipSuccess) return fail_hip(e, "tp_profile_enable: hipEventCreate");
     }
   }
   plan->profile = on != 0;
-  plan->ev_used[0] = plan->ev_used[1] = plan->ev_used[2] = false;
+  plan->ev_used[0] = plan->ev_used[1] = plan->ev_used[2] = plan->ev_used[3] = false;
   return SC_OK;
 }
 
@@ -200,6 +200,16 @@ sc_status tp_profile_read(tp_plan* plan, float* forward_ms, float* backward_ms, 
     if (e == hipSuccess) e = hipEventElapsedTime(out[k], plan->ev[2 * k], plan->ev[2 * k + 1]);
     if (e != hipSuccess) return fail_hip(e, "tp_profile_read");
   }
+  return SC_OK;
+}
+
+sc_status tp_profile_read_double_backward(tp_plan* plan, float* ms) {
+  if (!plan || !ms) return set_error(SC_ERR_INVALID_ARG, "tp_profile_read_double_backward: NULL argument");
+  *ms = -1.0f;
+  if (!plan->ev_used[3]) return SC_OK;
+  hipError_t e = hipEventSynchronize(plan->ev[7]);
+  if (e == hipSuccess) e = hipEventElapsedTime(ms, plan->ev[6], plan->ev[7]);
+  if (e != hipSuccess) return fail_hip(e, "tp_profile_read_double_backward");
   return SC_OK;
 }
 
@@ -287,6 +297,61 @@ sc_status tp_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, in
       (void)hipEventRecord(plan->ev[5], stream);
       plan->ev_used[2] = true;
     }
+  }
+  return SC_OK;
+}
+
+sc_status tp_double_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, int64_t n_edges, const void* Y,
+                             const void* h, const void* R, const int32_t* sender, const int32_t* row_ptr,
+                             const int32_t* send_ptr, const int32_t* send_edge, const void* dA, const void* HY,
+                             const void* Hh, const void* HR, void* ddA, void* d2Y, void* d2h, void* d2R,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+  sc_status st = check_sizes("tp_double_backward", plan, n_nodes_in, n_nodes_out, n_edges);
+  if (st != SC_OK) return st;
+  if (n_nodes_in > 0 && (!d2h || !send_ptr))
+    return set_error(SC_ERR_INVALID_ARG, "tp_double_backward: d2h or send_ptr is NULL");
+  if (n_nodes_out > 0 && (!row_ptr || !ddA))
+    return set_error(SC_ERR_INVALID_ARG, "tp_double_backward: row_ptr or ddA is NULL");
+  if (n_edges > 0) {
+    if (!Y || !h || !R || !sender || !send_edge || !dA || !HY || !Hh || !HR || !d2Y || !d2R)
+      return set_error(SC_ERR_INVALID_ARG, "tp_double_backward: NULL tensor argument");
+    size_t need = 0;
+    (void)tp_workspace_bytes(plan, n_edges, &need);
+    if (!workspace || workspace_bytes < need)
+      return set_error(SC_ERR_WORKSPACE, "tp_double_backward: workspace missing or smaller than tp_workspace_bytes()");
+    if (misaligned(workspace, 256))
+      return set_error(SC_ERR_WORKSPACE, "tp_double_backward: workspace not 256-byte aligned");
+  }
+  if (misaligned(Y, 16) || misaligned(h, 16) || misaligned(R, 16) || misaligned(dA, 16) || misaligned(HY, 16) ||
+      misaligned(Hh, 16) || misaligned(HR, 16) || misaligned(ddA, 16) || misaligned(d2Y, 16) || misaligned(d2h, 16) ||
+      misaligned(d2R, 16) || misaligned(sender, 4) || misaligned(row_ptr, 4) || misaligned(send_ptr, 4) ||
+      misaligned(send_edge, 4))
+    return set_error(SC_ERR_INVALID_ARG, "tp_double_backward: tensor pointer not 16-byte aligned");
+  DeviceGuard guard(plan->cfg.device);
+  if (!guard.ok) return set_error(SC_ERR_HIP, "tp_double_backward: cannot make the plan's device current");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  char* dh_edge = workspace ? static_cast<char*>(workspace) +
+                                  align_up(static_cast<size_t>(chblocks_of(plan)) * n_edges * plan->n_Y * elem_size(plan), 256)
+                            : nullptr;
+  const tp::DblArgs a{{n_nodes_in, n_nodes_out, n_edges, Y, h, R, sender, row_ptr, send_ptr, send_edge, dA, d2Y, d2h,
+                       d2R, workspace, dh_edge},
+                      HY, Hh, HR, ddA};
+  hipError_t e = hipSuccess;
+  if (n_nodes_out > 0) {  // also with no edges: ddA is zeroed
+    if (plan->profile) (void)hipEventRecord(plan->ev[6], stream);
+    e = plan->specialised ? tp::launch_spec_double_backward(plan, a, stream)
+                          : tp::launch_generic_double_backward(plan, a, stream);
+    if (e != hipSuccess) return fail_hip(e, "tp_double_backward: edge kernel launch");
+    if (plan->profile) {
+      (void)hipEventRecord(plan->ev[7], stream);
+      plan->ev_used[3] = true;
+    }
+    e = tp::launch_dY_sum(plan, a.b, stream);
+    if (e != hipSuccess) return fail_hip(e, "tp_double_backward: d2Y sum launch");
+  }
+  if (n_nodes_in > 0) {
+    e = tp::launch_dh_sum(plan, a.b, stream);
+    if (e != hipSuccess) return fail_hip(e, "tp_double_backward: d2h sum launch");
   }
   return SC_OK;
 }

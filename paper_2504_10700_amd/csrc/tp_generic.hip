@@ -110,6 +110,80 @@ __global__ __launch_bounds__(kLanes) void generic_backward_kernel(
   }
 }
 
+// Second-order pass over the edges grouped by receiver.  hy, hx, hr: cotangents of (dY, dh,
+// dR).  Per term the derivative of the message along the cotangents is
+// coef * (hr*y*x + r*hy*x + r*y*hx); ddA of the receiver sums it over the edges, and with
+// psi = sum_c g[c] * (that derivative) the kernel writes d psi / d r (d2R), this channel block's
+// partial of d psi / d y (d2Y) and the edge's share of d psi / d x (d2h).
+template <typename T>
+__global__ __launch_bounds__(kLanes) void generic_double_backward_kernel(
+    TermTable tab, int K, int chblocks, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
+    const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
+    const T* __restrict__ dA, const T* __restrict__ HY, const T* __restrict__ Hh, const T* __restrict__ HR,
+    T* __restrict__ ddA, T* __restrict__ d2R, T* __restrict__ d2Y_partial, T* __restrict__ d2h_edge) {
+  extern __shared__ unsigned char lds_raw[];
+  double* sH = reinterpret_cast<double*>(lds_raw);  // [n_h][64]
+  double* sHH = sH + tab.n_h * kLanes;              // [n_h][64]   cotangent of dh at the sender
+  double* sR = sHH + tab.n_h * kLanes;              // [P][64]
+  double* sHR = sR + tab.num_paths * kLanes;        // [P][64]     cotangent of dR
+  double* sG = sHR + tab.num_paths * kLanes;        // [n_out][64] dA of the receiver
+  double* sDDA = sG + tab.n_out * kLanes;           // [n_out][64]
+  double* sDR = sDDA + tab.n_out * kLanes;          // [P][64]
+  double* sDY = sDR + tab.num_paths * kLanes;       // [n_Y][64]
+  double* sDH = sDY + tab.n_Y * kLanes;             // [n_h][64]
+  const int lane = threadIdx.x;
+  const size_t node = blockIdx.x / chblocks;
+  const int cb = blockIdx.x % chblocks;
+  const int ch = cb * kLanes + lane;
+  const bool active = ch < K;
+  for (int c = 0; c < tab.n_out; ++c) {
+    sG[c * kLanes + lane] = active ? static_cast<double>(dA[(node * K + ch) * tab.n_out + c]) : 0.0;
+    sDDA[c * kLanes + lane] = 0.0;
+  }
+  const int e0 = row_ptr[node], e1 = row_ptr[node + 1];
+  for (int e = e0; e < e1; ++e) {
+    const size_t j = sender[e];
+    for (int b = 0; b < tab.n_h; ++b) {
+      sH[b * kLanes + lane] = active ? static_cast<double>(h[(j * K + ch) * tab.n_h + b]) : 0.0;
+      sHH[b * kLanes + lane] = active ? static_cast<double>(Hh[(j * K + ch) * tab.n_h + b]) : 0.0;
+      sDH[b * kLanes + lane] = 0.0;
+    }
+    for (int p = 0; p < tab.num_paths; ++p) {
+      const size_t at = (static_cast<size_t>(e) * tab.num_paths + p) * K + ch;
+      sR[p * kLanes + lane] = active ? static_cast<double>(R[at]) : 0.0;
+      sHR[p * kLanes + lane] = active ? static_cast<double>(HR[at]) : 0.0;
+      sDR[p * kLanes + lane] = 0.0;
+    }
+    for (int a = 0; a < tab.n_Y; ++a) sDY[a * kLanes + lane] = 0.0;
+    const T* y = Y + static_cast<size_t>(e) * tab.n_Y;
+    const T* hy = HY + static_cast<size_t>(e) * tab.n_Y;
+    for (int t = 0; t < tab.n_terms; ++t) {
+      const int4 ix = tab.idx[t];
+      const double c = tab.coef[t];
+      const double ya = static_cast<double>(y[ix.y]), hya = static_cast<double>(hy[ix.y]);
+      const double x = sH[ix.z * kLanes + lane], hx = sHH[ix.z * kLanes + lane];
+      const double r = sR[ix.x * kLanes + lane], hr = sHR[ix.x * kLanes + lane];
+      const double cg = c * sG[ix.w * kLanes + lane];
+      sDDA[ix.w * kLanes + lane] += c * (hr * ya * x + r * (hya * x + ya * hx));
+      sDR[ix.x * kLanes + lane] += cg * (hya * x + ya * hx);
+      sDY[ix.y * kLanes + lane] += cg * (hr * x + r * hx);
+      sDH[ix.z * kLanes + lane] += cg * (hr * ya + r * hya);
+    }
+    if (active) {
+      for (int p = 0; p < tab.num_paths; ++p)
+        d2R[(static_cast<size_t>(e) * tab.num_paths + p) * K + ch] = static_cast<T>(sDR[p * kLanes + lane]);
+      for (int b = 0; b < tab.n_h; ++b)
+        d2h_edge[(static_cast<size_t>(e) * K + ch) * tab.n_h + b] = static_cast<T>(sDH[b * kLanes + lane]);
+    }
+    for (int a = 0; a < tab.n_Y; ++a) {
+      const double s = wave_sum(sDY[a * kLanes + lane]);
+      if (lane == 0) d2Y_partial[(static_cast<size_t>(cb) * n_edges + e) * tab.n_Y + a] = static_cast<T>(s);
+    }
+  }
+  if (active)
+    for (int c = 0; c < tab.n_out; ++c) ddA[(node * K + ch) * tab.n_out + c] = static_cast<T>(sDDA[c * kLanes + lane]);
+}
+
 // dh[j] = sum of the shares of the edges sent by j, in the order of send_edge.  One lane per
 // (channel, component) pair: consecutive lanes read consecutive elements of an edge's row.
 template <typename T>
@@ -160,10 +234,35 @@ hipError_t bwd_t(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   const TermTable& t = plan->tab;
   const int K = plan->cfg.num_channels, chblocks = (K + kLanes - 1) / kLanes;
   const size_t lds = static_cast<size_t>(2 * t.n_h + 2 * t.num_paths + t.n_out + t.n_Y) * kLanes * sizeof(double);
+  if (lds > 64 * 1024) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&generic_backward_kernel<T>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(generic_backward_kernel<T>, dim3(static_cast<unsigned>(a.n_out_nodes * chblocks)), dim3(kLanes), lds,
                      stream, t, K, chblocks, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
                      static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<const T*>(a.dA),
                      static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh_edge));
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t dbl_t(const tp_plan* plan, const DblArgs& d, hipStream_t stream) {
+  const TermTable& t = plan->tab;
+  const BwdArgs& a = d.b;
+  const int K = plan->cfg.num_channels, chblocks = (K + kLanes - 1) / kLanes;
+  const size_t lds = static_cast<size_t>(3 * t.n_h + 3 * t.num_paths + 2 * t.n_out + t.n_Y) * kLanes * sizeof(double);
+  if (lds > 64 * 1024) {  // above the default dynamic LDS limit (largest l ranges): raise it for this kernel
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&generic_double_backward_kernel<T>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(generic_double_backward_kernel<T>, dim3(static_cast<unsigned>(a.n_out_nodes * chblocks)),
+                     dim3(kLanes), lds, stream, t, K, chblocks, a.n_edges, static_cast<const T*>(a.Y),
+                     static_cast<const T*>(a.h), static_cast<const T*>(a.R), a.sender, a.row_ptr,
+                     static_cast<const T*>(a.dA), static_cast<const T*>(d.HY), static_cast<const T*>(d.Hh),
+                     static_cast<const T*>(d.HR), static_cast<T*>(d.ddA), static_cast<T*>(a.dR),
+                     static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh_edge));
   return hipGetLastError();
 }
 
@@ -192,6 +291,9 @@ hipError_t launch_generic_forward(const tp_plan* plan, const FwdArgs& a, hipStre
 }
 hipError_t launch_generic_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   return plan->cfg.dtype == SC_F64 ? bwd_t<double>(plan, a, stream) : bwd_t<float>(plan, a, stream);
+}
+hipError_t launch_generic_double_backward(const tp_plan* plan, const DblArgs& a, hipStream_t stream) {
+  return plan->cfg.dtype == SC_F64 ? dbl_t<double>(plan, a, stream) : dbl_t<float>(plan, a, stream);
 }
 hipError_t launch_dh_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   return plan->cfg.dtype == SC_F64 ? dh_sum_t<double>(plan, a, stream) : dh_sum_t<float>(plan, a, stream);

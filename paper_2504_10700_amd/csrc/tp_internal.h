@@ -37,8 +37,9 @@ struct tp_plan {
   int specialised = 0;
   int n_Y = 0, n_h = 0, n_out = 0;
   bool profile = false;
-  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-  bool ev_used[3] = {false, false, false};
+  // start/stop pairs: forward, backward, dh sum, second-order kernel
+  hipEvent_t ev[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  bool ev_used[4] = {false, false, false, false};
   void* dev_blob = nullptr;
   tp::TermTable tab{};
 };
@@ -62,14 +63,24 @@ struct BwdArgs {
   void* dh_edge;     // [n_edges][K][n_h]: every edge's share of its sender's dh
 };
 
+// Second-order pass: the backward's arguments (dY, dh, dR of BwdArgs receive d2Y, d2h, d2R)
+// plus the cotangents and ddA.
+struct DblArgs {
+  BwdArgs b;
+  const void *HY, *Hh, *HR;
+  void* ddA;
+};
+
 hipError_t launch_generic_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream);
+hipError_t launch_generic_double_backward(const tp_plan* plan, const DblArgs& a, hipStream_t stream);
+hipError_t launch_spec_double_backward(const tp_plan* plan, const DblArgs& a, hipStream_t stream);
 hipError_t launch_generic_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
 hipError_t launch_dY_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
 hipError_t launch_dh_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
 
 // generated kernels (tp_spec.hip)
 int spec_lookup(const tp_plan* plan);
-void spec_op_counts(int id, int32_t ops[2], int32_t flops[2]);
+void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]);
 hipError_t launch_spec_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream);
 hipError_t launch_spec_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
 

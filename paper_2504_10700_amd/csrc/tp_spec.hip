@@ -96,6 +96,29 @@ __device__ __forceinline__ int64_t xcd_contiguous_block() {
   return (blockIdx.x % kXcds) * per + blockIdx.x / kXcds;
 }
 
+// Sum of dy[a] over the 64 lanes in a fixed order, written to out[a] (a < N): lane 4a+q adds the
+// sixteen lanes 16q..16q+15 of component a from an LDS transpose (stage: N * kStageStride
+// elements owned by this wave), then the four quarters are combined with two exchanges.
+template <typename T, int N>
+__device__ __forceinline__ void lane_sum_store(T* stage, int lane, const T (&dy)[N], T* __restrict__ out) {
+  static_assert(N <= 16, "one lane quartet per component");
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the previous edge's reads of the stage are done
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int a = 0; a < N; ++a) stage[a * kStageStride + lane] = dy[a];
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const int a = lane >> 2, q = lane & 3;
+  T s = T(0);
+  if (a < N) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += stage[a * kStageStride + q * 16 + i];
+  }
+  s += __shfl_xor(s, 1);
+  s += __shfl_xor(s, 2);
+  if (q == 0 && a < N) out[a] = s;
+}
+
 template <typename T, typename G>
 __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, int64_t n_units,
                                                            const T* __restrict__ Y, const T* __restrict__ h,
@@ -166,9 +189,7 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
   load_row<T, G::kNh>(h + (static_cast<size_t>(sender[e0]) * K + ch) * G::kNh, h0);
   int jn = (e0 + 1 < e1) ? sender[e0 + 1] : 0;
 
-  // One edge: arithmetic, dR row stores, dY summed over the 64 lanes in a fixed order (lane
-  // 4a+q adds the sixteen lanes 16q..16q+15 of component a from an LDS transpose, then the
-  // four quarters are combined with two exchanges).
+  // One edge: arithmetic, dR row stores, dY summed over the 64 lanes in a fixed order.
   auto finish_edge = [&](int e, const T (&r)[G::kP], const T (&hh)[G::kNh]) {
     T y[G::kNY], dr[G::kP], dy[G::kNY], dhe[G::kNh];
     load_uniform<T, G::kNY>(Y, e, y);
@@ -177,21 +198,7 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
 #pragma unroll
     for (int p = 0; p < G::kP; ++p) out[static_cast<size_t>(p) * K] = dr[p];
     store_row<T, G::kNh>(dh_edge + (static_cast<size_t>(e) * K + ch) * G::kNh, dhe);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the previous edge's reads of the stage are done
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int a = 0; a < G::kNY; ++a) stage[a * kStageStride + lane] = dy[a];
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    const int a = lane >> 2, q = lane & 3;
-    T s = T(0);
-    if (a < G::kNY) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s += stage[a * kStageStride + q * 16 + i];
-    }
-    s += __shfl_xor(s, 1);
-    s += __shfl_xor(s, 2);
-    if (q == 0 && a < G::kNY) dY_partial[(static_cast<size_t>(cb) * n_edges + e) * G::kNY + a] = s;
+    lane_sum_store<T, G::kNY>(stage, lane, dy, dY_partial + (static_cast<size_t>(cb) * n_edges + e) * G::kNY);
   };
 
   for (int e = e0; e < e1; e += 2) {
@@ -211,6 +218,79 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
       finish_edge(e + 1, r1, h1);
     }
   }
+}
+
+// Second-order pass: the backward's walk with the cotangents HR (per edge and path), Hh (at the
+// sender) and HY (wave-uniform) as additional inputs; ddA of the receiver is summed in registers
+// and stored once, d2R / d2Y partial / d2h share leave per edge like dR / dY / dh.
+template <typename T, typename G>
+__global__ __launch_bounds__(kThreads) void double_backward_kernel(
+    int K, int chblocks, int64_t n_units, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
+    const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
+    const T* __restrict__ dA, const T* __restrict__ HY, const T* __restrict__ Hh, const T* __restrict__ HR,
+    T* __restrict__ ddA, T* __restrict__ d2R, T* __restrict__ d2Y_partial, T* __restrict__ d2h_edge) {
+  __shared__ T stage_all[kWaves][G::kNY * kStageStride];
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = uniform(threadIdx.x / kLanes);
+  T* stage = stage_all[wave];
+  const int64_t unit = xcd_contiguous_block() * kWaves + wave;
+  if (unit >= n_units) return;
+  const size_t node = unit / chblocks;
+  const int cb = static_cast<int>(unit % chblocks);
+  const int ch = cb * kLanes + lane;
+  const int e0 = uniform(row_ptr[node]), e1 = uniform(row_ptr[node + 1]);
+  T dda[G::kNout];
+#pragma unroll
+  for (int c = 0; c < G::kNout; ++c) dda[c] = T(0);
+  if (e0 < e1) {
+    T g[G::kNout];
+    load_row<T, G::kNout>(dA + (node * K + ch) * G::kNout, g);
+    T r0[G::kP], r1[G::kP], q0[G::kP], q1[G::kP], h0[G::kNh], h1[G::kNh], x0[G::kNh], x1[G::kNh];
+    {
+      const size_t j = sender[e0];
+      load_weights<T, G::kP>(R, e0, K, ch, r0);
+      load_weights<T, G::kP>(HR, e0, K, ch, q0);
+      load_row<T, G::kNh>(h + (j * K + ch) * G::kNh, h0);
+      load_row<T, G::kNh>(Hh + (j * K + ch) * G::kNh, x0);
+    }
+    int jn = (e0 + 1 < e1) ? sender[e0 + 1] : 0;
+
+    auto finish_edge = [&](int e, const T (&r)[G::kP], const T (&hr)[G::kP], const T (&hh)[G::kNh],
+                           const T (&hx)[G::kNh]) {
+      T y[G::kNY], hy[G::kNY], d2r[G::kP], d2y[G::kNY], d2h[G::kNh];
+      load_uniform<T, G::kNY>(Y, e, y);
+      load_uniform<T, G::kNY>(HY, e, hy);
+      G::double_backward(y, hy, hh, hx, r, hr, g, dda, d2r, d2y, d2h);
+      T* out = d2R + static_cast<size_t>(e) * G::kP * K + ch;
+#pragma unroll
+      for (int p = 0; p < G::kP; ++p) out[static_cast<size_t>(p) * K] = d2r[p];
+      store_row<T, G::kNh>(d2h_edge + (static_cast<size_t>(e) * K + ch) * G::kNh, d2h);
+      lane_sum_store<T, G::kNY>(stage, lane, d2y, d2Y_partial + (static_cast<size_t>(cb) * n_edges + e) * G::kNY);
+    };
+
+    for (int e = e0; e < e1; e += 2) {
+      int jn2 = 0;
+      if (e + 1 < e1) {
+        load_weights<T, G::kP>(R, e + 1, K, ch, r1);
+        load_weights<T, G::kP>(HR, e + 1, K, ch, q1);
+        load_row<T, G::kNh>(h + (static_cast<size_t>(jn) * K + ch) * G::kNh, h1);
+        load_row<T, G::kNh>(Hh + (static_cast<size_t>(jn) * K + ch) * G::kNh, x1);
+        if (e + 2 < e1) jn2 = sender[e + 2];
+      }
+      finish_edge(e, r0, q0, h0, x0);
+      if (e + 1 < e1) {
+        if (e + 2 < e1) {
+          load_weights<T, G::kP>(R, e + 2, K, ch, r0);
+          load_weights<T, G::kP>(HR, e + 2, K, ch, q0);
+          load_row<T, G::kNh>(h + (static_cast<size_t>(jn2) * K + ch) * G::kNh, h0);
+          load_row<T, G::kNh>(Hh + (static_cast<size_t>(jn2) * K + ch) * G::kNh, x0);
+          if (e + 3 < e1) jn = sender[e + 3];
+        }
+        finish_edge(e + 1, r1, q1, h1, x1);
+      }
+    }
+  }
+  store_row<T, G::kNout>(ddA + (node * K + ch) * G::kNout, dda);
 }
 
 template <typename G>
@@ -246,9 +326,23 @@ hipError_t bwd_launch(const tp_plan* plan, const BwdArgs& a, hipStream_t stream)
   return hipGetLastError();
 }
 
+template <typename T, typename G>
+hipError_t dbl_launch(const tp_plan* plan, const DblArgs& d, hipStream_t stream) {
+  const BwdArgs& a = d.b;
+  const int K = plan->cfg.num_channels, chblocks = K / kLanes;
+  const int64_t n_units = a.n_out_nodes * chblocks;
+  hipLaunchKernelGGL((double_backward_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
+                     n_units, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
+                     static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<const T*>(a.dA),
+                     static_cast<const T*>(d.HY), static_cast<const T*>(d.Hh), static_cast<const T*>(d.HR),
+                     static_cast<T*>(d.ddA), static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial),
+                     static_cast<T*>(a.dh_edge));
+  return hipGetLastError();
+}
+
 template <typename G>
-void op_counts(int32_t ops[2], int32_t flops[2]) {
-  for (int i = 0; i < 2; ++i) {
+void op_counts(int32_t ops[3], int32_t flops[3]) {
+  for (int i = 0; i < 3; ++i) {
     ops[i] = G::kOps[i];
     flops[i] = G::kFlops[i];
   }
@@ -262,8 +356,8 @@ int spec_lookup(const tp_plan* plan) {
   return 0;
 }
 
-void spec_op_counts(int id, int32_t ops[2], int32_t flops[2]) {
-  for (int i = 0; i < 2; ++i) ops[i] = flops[i] = 0;
+void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
+  for (int i = 0; i < 3; ++i) ops[i] = flops[i] = 0;
   if (id == 1) op_counts<GenTP_y3h0o3>(ops, flops);
   if (id == 2) op_counts<GenTP_y3h1o3>(ops, flops);
 }
@@ -279,6 +373,9 @@ hipError_t launch_spec_forward(const tp_plan* plan, const FwdArgs& a, hipStream_
 }
 hipError_t launch_spec_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   TP_DISPATCH(bwd_launch, (plan, a, stream))
+}
+hipError_t launch_spec_double_backward(const tp_plan* plan, const DblArgs& a, hipStream_t stream) {
+  TP_DISPATCH(dbl_launch, (plan, a, stream))
 }
 
 }  // namespace tp

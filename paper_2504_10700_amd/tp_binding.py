@@ -12,7 +12,8 @@ from . import binding as _b
 from .binding import SC_F32, SC_F64, SC_PLAN_FORCE_GENERIC, SC_PLAN_HOST_ONLY, ScError, _check, _ptr, _stream, lib  # noqa: F401
 
 EXPORTS = ("tp_plan_create", "tp_plan_destroy", "tp_plan_info", "tp_plan_paths", "tp_plan_terms", "tp_forward",
-           "tp_workspace_bytes", "tp_backward", "tp_profile_enable", "tp_profile_read")
+           "tp_workspace_bytes", "tp_backward", "tp_double_backward", "tp_profile_enable", "tp_profile_read",
+           "tp_profile_read_double_backward")
 
 
 class tp_config(C.Structure):
@@ -22,7 +23,7 @@ class tp_config(C.Structure):
 
 class tp_info(C.Structure):
     _fields_ = [("n_Y", C.c_int32), ("n_h", C.c_int32), ("n_out", C.c_int32), ("num_paths", C.c_int32),
-                ("specialised", C.c_int32), ("ops", C.c_int32 * 2), ("flops", C.c_int32 * 2)]
+                ("specialised", C.c_int32), ("ops", C.c_int32 * 3), ("flops", C.c_int32 * 3)]
 
 
 def _declare() -> None:
@@ -36,6 +37,8 @@ def _declare() -> None:
     lib.tp_forward.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.tp_workspace_bytes.argtypes = [vp, i64, C.POINTER(C.c_size_t)]
     lib.tp_backward.argtypes = [vp, i64, i64, i64] + [vp] * 12 + [C.c_size_t, vp]
+    lib.tp_double_backward.argtypes = [vp, i64, i64, i64] + [vp] * 16 + [C.c_size_t, vp]
+    lib.tp_profile_read_double_backward.argtypes = [vp, C.POINTER(C.c_float)]
     lib.tp_profile_enable.argtypes = [vp, i32]
     lib.tp_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float)]
     for name in EXPORTS:
@@ -118,6 +121,21 @@ def tp_backward(plan: Plan, n_nodes_in: int, n_nodes_out: int, n_edges: int, Y, 
     _check(lib.tp_backward(plan.handle, n_nodes_in, n_nodes_out, n_edges, _ptr(Y), _ptr(h), _ptr(R), _ptr(sender),
                            _ptr(row_ptr), _ptr(send_ptr), _ptr(send_edge), _ptr(dA), _ptr(dY), _ptr(dh), _ptr(dR),
                            _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def tp_double_backward(plan: Plan, n_nodes_in: int, n_nodes_out: int, n_edges: int, Y, h, R, sender, row_ptr,
+                       send_ptr, send_edge, dA, HY, Hh, HR, ddA, d2Y, d2h, d2R, workspace, workspace_bytes: int,
+                       stream=None) -> None:
+    _check(lib.tp_double_backward(plan.handle, n_nodes_in, n_nodes_out, n_edges, _ptr(Y), _ptr(h), _ptr(R),
+                                  _ptr(sender), _ptr(row_ptr), _ptr(send_ptr), _ptr(send_edge), _ptr(dA), _ptr(HY),
+                                  _ptr(Hh), _ptr(HR), _ptr(ddA), _ptr(d2Y), _ptr(d2h), _ptr(d2R), _ptr(workspace),
+                                  workspace_bytes, _stream(stream)))
+
+
+def tp_profile_read_double_backward(plan: Plan) -> float:
+    t = C.c_float()
+    _check(lib.tp_profile_read_double_backward(plan.handle, C.byref(t)))
+    return t.value
 
 
 def tp_profile_enable(plan: Plan, on: bool) -> None:

@@ -227,3 +227,11 @@ def make_tp_inputs(wl: TPWorkload, paths: Sequence[Sequence[int]]) -> TPInputs:
     dA = rng.standard_normal((N, wl.num_channels, wl.n_out))
     row_ptr, send_ptr, send_edge = graph_indices(sender, receiver, N)
     return TPInputs(Y, h, R, dA, sender, receiver, row_ptr, send_ptr, send_edge)
+
+
+def make_tp_cotangents(wl: TPWorkload, inp: TPInputs):
+    """HY, Hh, HR: cotangents of (dY, dh, dR) for the second-order pass, N(0,1) of the shapes of
+    Y, h, R, from their own stream default_rng(seed + 7919)."""
+    rng = np.random.default_rng(wl.seed + 7919)
+    return rng.standard_normal(inp.Y.shape), rng.standard_normal(inp.h.shape), rng.standard_normal(inp.R.shape)
+

@@ -57,6 +57,17 @@ class TPRun:
         self.torch.cuda.synchronize()
         return self.dY.cpu().numpy(), self.dh.cpu().numpy(), self.dR.cpu().numpy()
 
+    def double_backward(self, HY, Hh, HR):
+        """Returns (ddA, d2Y, d2h, d2R) and the cotangents as computed (fp64 numpy)."""
+        torch = self.torch
+        H = [torch.tensor(x, dtype=self.tdt, device=self.A.device) for x in (HY, Hh, HR)]
+        out = [torch.full_like(x, float("nan")) for x in (self.A, self.Y, self.h, self.R)]
+        self.tp.tp_double_backward(self.plan, self.N, self.N, self.E, self.Y, self.h, self.R, self.sender, self.row_ptr,
+                                   self.send_ptr, self.send_edge, self.dA, H[0], H[1], H[2], out[0], out[1], out[2],
+                                   out[3], self.ws, self.ws_bytes)
+        torch.cuda.synchronize()
+        return [x.cpu().numpy() for x in out], [x.double().cpu().numpy() for x in H]
+
     def inputs_as_computed(self):
         return tuple(x.double().cpu().numpy() for x in (self.Y, self.h, self.R, self.dA))
 
@@ -96,6 +107,16 @@ def full_parity(tp, wl, flags=0, mutate=None):
     A2 = run.forward()
     again = run.backward()
     assert np.array_equal(A, A2) and all(np.array_equal(x, y) for x, y in zip((dY, dh, dR), again))
+    # second-order pass
+    got, (HY, Hh, HR) = run.double_backward(*workloads.make_tp_cotangents(wl, inp))
+    ref = otp.double_backward(cfg, Y, h, R, inp.sender, inp.receiver, dA, HY, Hh, HR)
+    assert not got[0][no_edges].any() and not got[2][silent].any()
+    check("ddA", got[0][~no_edges], ref[0][~no_edges], wl.dtype)
+    check("d2Y", got[1], ref[1], wl.dtype)
+    check("d2h", got[2][~silent], ref[2][~silent], wl.dtype)
+    check("d2R", got[3], ref[3], wl.dtype)
+    got2, _ = run.double_backward(HY, Hh, HR)
+    assert all(np.array_equal(x, y) for x, y in zip(got, got2))
     info = tp.tp_plan_info(run.plan)
     run.close()
     return info
@@ -219,4 +240,13 @@ def test_full_size_sampled(tp, name):
     A2 = run.forward()
     again = run.backward()
     assert np.array_equal(A, A2) and all(np.array_equal(x, y) for x, y in zip((dY, dh, dR), again)), "not reproducible"
+    # second-order pass on the same samples
+    (ddA, d2Y, d2h, d2R), (HY, Hh, HR) = run.double_backward(*workloads.make_tp_cotangents(wl, inp))
+    assert all(np.isfinite(x).all() for x in (ddA, d2Y, d2h, d2R))
+    r = otp.double_backward(cfg, Y[em], h, R[em], inp.sender[em], inp.receiver[em], dA, HY[em], Hh, HR[em])
+    check("ddA(sample)", ddA[S], r[0][S], wl.dtype)
+    check("d2Y(sample)", d2Y[em], r[1], wl.dtype)
+    check("d2R(sample)", d2R[em], r[3], wl.dtype)
+    r = otp.double_backward(cfg, Y[sm], h, R[sm], inp.sender[sm], inp.receiver[sm], dA, HY[sm], Hh, HR[sm])
+    check("d2h(sample)", d2h[Tn], r[2][Tn], wl.dtype)
     run.close()
