@@ -420,6 +420,31 @@ def measure_tp_double_backward(wl, steps, warmup):
     }
 
 
+def measure_balanced_batches(n_graphs=1_000_000, capacity=3072, n_gpus=8, oracle_sample=200_000):
+    """Load balancer (host code): graphs/s of the C++ implementation, the oracle beside it."""
+    import numpy as np
+    from oracle import balanced_batches as obb
+    from paper_2504_10700_amd import bb_binding as bb
+    from paper_2504_10700_amd import workloads
+
+    sizes = workloads.make_graph_sizes(n_graphs)
+    bb.bb_create_balanced_batches(sizes[:1000], capacity, n_gpus)
+    t0 = time.perf_counter()
+    bins, slots, n_bins = bb.bb_create_balanced_batches(sizes, capacity, n_gpus)
+    dt = time.perf_counter() - t0
+    loads = np.bincount(bins, weights=sizes, minlength=n_bins)
+    t0 = time.perf_counter()
+    obb.create_balanced_batches(sizes[:oracle_sample], capacity, n_gpus)
+    dto = time.perf_counter() - t0
+    return {"metric": "graphs/sec CREATE-BALANCED-BATCHES (host)", "value": n_graphs / dt, "unit": "graphs/s",
+            "seconds": dt,
+            "config": {"workload": f"{n_graphs} graphs of 1..768 vertices, capacity {capacity}, {n_gpus} GPUs",
+                       "bins": int(n_bins), "lower_bound_bins": int(np.ceil(sizes.sum() / capacity)),
+                       "mean_fill": float(loads.mean() / capacity), "min_fill": float(loads.min() / capacity)},
+            "cpu_baseline": {"value": oracle_sample / dto, "unit": "graphs/s", "cores": 1, "kind": "oracle",
+                             "sample": f"first {oracle_sample} graphs, {dto:.1f} s"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -430,6 +455,8 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
     ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
     ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
+    ap.add_argument("--balanced-batches", action="store_true",
+                    help="measure only the host load balancer (1M graphs) and print its object")
     ap.add_argument("--tp", action="store_true",
                     help="measure only the channelwise tensor product (--workload tp_training_step|tp_first_layer|tp_tiny)")
     ap.add_argument("--double-backward", action="store_true",
@@ -442,6 +469,9 @@ def main():
 
     from paper_2504_10700_amd import workloads
 
+    if args.balanced_batches:
+        print(json.dumps(measure_balanced_batches()))
+        return
     if args.tp:
         name = args.workload if args.workload in workloads.TP_WORKLOADS else "tp_training_step"
         fn = measure_tp_double_backward if args.double_backward else measure_tp
@@ -468,6 +498,7 @@ def main():
         out["also"]["channelwise_tp_training_step"] = measure_tp(workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
         out["also"]["channelwise_tp_double_backward_training_step"] = measure_tp_double_backward(
             workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
+        out["also"]["balanced_batches"] = measure_balanced_batches()
     print(json.dumps(out))
 
 

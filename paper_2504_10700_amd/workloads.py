@@ -235,3 +235,14 @@ def make_tp_cotangents(wl: TPWorkload, inp: TPInputs):
     rng = np.random.default_rng(wl.seed + 7919)
     return rng.standard_normal(inp.Y.shape), rng.standard_normal(inp.h.shape), rng.standard_normal(inp.R.shape)
 
+
+def make_graph_sizes(n_graphs: int, seed: int = 6001, max_size: int = 768) -> np.ndarray:
+    """Vertex counts for the load balancer: half small molecules (1..39 atoms), 40% mid-sized
+    cells (40..199), 10% large systems (200..max_size); the paper's combined data set spans
+    1..768 atoms per structure with most structures small (Evaluation, data set description)."""
+    rng = np.random.default_rng(seed)
+    kind = rng.random(n_graphs)
+    sizes = np.where(kind < 0.5, rng.integers(1, 40, n_graphs),
+                     np.where(kind < 0.9, rng.integers(40, 200, n_graphs), rng.integers(200, max_size + 1, n_graphs)))
+    return sizes.astype(np.int32)
+
