@@ -1,0 +1,58 @@
+/*
+ * el.h - C ABI of the per-order channel-mixing linear (same library, libsc_mi355x.so).
+ *
+ * Section 4.1 of arXiv 2504.10700 (the paragraph before Algorithm 2): after the pooling over
+ * the neighbours "a further linear combination (between terms k of the same order)" is applied
+ * to the atomic-basis features before the symmetric contraction.  For every atom i, output
+ * channel k', order l = 0..l_max and component m
+ *
+ *   Y[i,k',(l,m)] = sum_k W[l,k,k'] * X[i,k,(l,m)]
+ *
+ * one K_in x K_out matrix per order l, shared by the 2l+1 components of that order; component
+ * index l*l + l + m as in sc.h.  No bias and no normalisation factor inside the operation.
+ * This is a dense contraction: the kernels run on the matrix cores (MFMA, fp32 or fp64
+ * inputs and accumulation) when K_in is a multiple of 4 and K_out a multiple of 64, and on a
+ * plain vector kernel otherwise.
+ *
+ * Conventions as in sc.h: device pointers, dense row-major, 16-byte aligned; calls enqueue on
+ * the given HIP stream and never synchronise; outputs are overwritten; errors by return code
+ * with sc_last_error().  Layouts:
+ *   X  [n_nodes][K_in][(l_max+1)^2]     W  [l_max+1][K_in][K_out]     Y  [n_nodes][K_out][(l_max+1)^2]
+ */
+#ifndef EL_MI355X_H
+#define EL_MI355X_H
+
+#include "sc.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+  int32_t struct_size; /* = sizeof(el_config), ABI guard */
+  int32_t k_in;        /* K_in >= 1                        */
+  int32_t k_out;       /* K_out >= 1                       */
+  int32_t l_max;       /* 0..SC_MAX_L                      */
+  int32_t dtype;       /* sc_dtype of X, W, Y and the gradients */
+  int32_t device;      /* HIP device ordinal               */
+} el_config;
+
+/* Forward.  n_nodes == 0 is valid and does nothing. */
+sc_status el_forward(const el_config* cfg, int64_t n_nodes, const void* X, const void* W, void* Y, void* hip_stream);
+
+/* Bytes of device workspace el_backward needs (partial sums of dW per range of atoms). */
+sc_status el_workspace_bytes(const el_config* cfg, int64_t n_nodes, size_t* bytes);
+
+/* Backward for an upstream gradient dY [n_nodes][K_out][(l_max+1)^2] (training, Section 2.2):
+ *   dX [n_nodes][K_in][(l_max+1)^2] = sum_k' W[l,k,k'] dY[.,k',.]          (overwritten)
+ *   dW [l_max+1][K_in][K_out]       = sum over atoms and m of X[.,k,.] dY[.,k',.]   (overwritten)
+ * workspace: device memory, 256-byte aligned, at least el_workspace_bytes().  dW is summed in a
+ * fixed order (per range of atoms, then over the ranges): bitwise reproducible.
+ * n_nodes == 0 zeroes dW. */
+sc_status el_backward(const el_config* cfg, int64_t n_nodes, const void* X, const void* W, const void* dY, void* dX,
+                      void* dW, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EL_MI355X_H */

@@ -1,0 +1,451 @@
+// Per-order channel-mixing linear (see include/el.h): Y[i,k',(l,m)] = sum_k W[l,k,k'] X[i,k,(l,m)]
+// (Section 4.1 of arXiv 2504.10700, the linear combination between the pooling and the
+// symmetric contraction), forward and backward, on the matrix cores.
+//
+// One MFMA 16x16x4 multiplies a 16x4 by a 4x16 block; lane L supplies A[i = L%16][kk = L/16]
+// and B[kk = L/16][j = L%16] and receives four entries of column j = L%16 of the 16x16 result
+// (rows 4*(L/16)+r in fp32, 4*r + L/16 in fp64; r = 0..3).
+//
+// Forward (and dX, which is the same product with W transposed): rows = 16 atoms, reduction =
+// input channels, columns = 16 output channels, one accumulator block per component (l,m); the
+// 2l+1 components of an order share their B operand.  With the layout X[atom][channel][lm]
+// the A operands of all components of one (atom, channel) are 64 contiguous bytes, so every
+// lane reads its operands for a reduction step with four 16-byte loads straight from global
+// memory (no LDS staging needed), and the result of all components of one (atom, output
+// channel) leaves as 64 contiguous bytes per lane.
+// dW: rows = 16 input channels, columns = 16 output channels, reduction = atoms (four per
+// MFMA) and the components of the order; A and B operands are again 64 contiguous bytes per
+// lane.  The atoms are cut into ranges, every range writes a partial dW, a second kernel adds
+// the partials in range order (fixed order, no atomics).
+#include <algorithm>
+#include <string>
+
+#include "../../include/el.h"
+#include "sc_internal.h"
+
+namespace el {
+namespace {
+
+using sc::kLanes;
+using sc::set_error;
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * kLanes;
+
+template <typename T>
+struct Mma;
+template <>
+struct Mma<float> {
+  typedef float acc_t __attribute__((ext_vector_type(4)));
+  static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ int row(int lane, int r) { return 4 * (lane / 16) + r; }
+};
+template <>
+struct Mma<double> {
+  typedef double acc_t __attribute__((ext_vector_type(4)));
+  static __device__ __forceinline__ acc_t mma(double a, double b, acc_t c) {
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ int row(int lane, int r) { return 4 * r + lane / 16; }
+};
+
+__host__ __device__ constexpr int order_of(int c) { return c >= 9 ? 3 : c >= 4 ? 2 : c >= 1 ? 1 : 0; }
+
+// N consecutive elements (16-byte accesses when the row is a multiple of 16 bytes).
+template <typename T, int N>
+__device__ __forceinline__ void load_row(const T* __restrict__ p, T (&v)[N]) {
+  constexpr int V = 16 / sizeof(T);
+  if constexpr ((N * sizeof(T)) % 16 == 0) {
+    typedef T Vec __attribute__((ext_vector_type(V)));
+#pragma unroll
+    for (int i = 0; i < N; i += V) {
+      const Vec x = *reinterpret_cast<const Vec*>(p + i);
+#pragma unroll
+      for (int k = 0; k < V; ++k) v[i + k] = x[k];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = p[i];
+  }
+}
+
+template <typename T, int N>
+__device__ __forceinline__ void store_row(T* __restrict__ p, const T (&v)[N]) {
+  constexpr int V = 16 / sizeof(T);
+  if constexpr ((N * sizeof(T)) % 16 == 0) {
+    typedef T Vec __attribute__((ext_vector_type(V)));
+#pragma unroll
+    for (int i = 0; i < N; i += V) {
+      Vec x;
+#pragma unroll
+      for (int k = 0; k < V; ++k) x[k] = v[i + k];
+      *reinterpret_cast<Vec*>(p + i) = x;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) p[i] = v[i];
+  }
+}
+
+// Y[n][j][c] = sum_k X[n][k][c] * B_l(c)[k][j] with B_l[k][j] = W[l][k][j] (kTrans = false,
+// W is [L][k_red][k_cols]) or W[l][j][k] (kTrans = true, W is [L][k_cols][k_red]).
+// One workgroup = 16 atoms; wave w owns the column tiles w, w+4, ... and works on CT of them
+// at a time.  k_red % 4 == 0, k_cols % (64 * CT) == 0.
+template <typename T, int LMAX, int CT, bool kTrans>
+__global__ __launch_bounds__(kThreads) void mfma_forward_kernel(int64_t n_nodes, int k_red, int k_cols,
+                                                                const T* __restrict__ X, const T* __restrict__ W,
+                                                                T* __restrict__ Y) {
+  constexpr int NC = (LMAX + 1) * (LMAX + 1), L = LMAX + 1;
+  typedef typename Mma<T>::acc_t acc_t;
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int64_t n0 = static_cast<int64_t>(blockIdx.x) * 16;
+  int64_t na = n0 + (lane & 15);               // the atom whose A operands this lane supplies
+  if (na >= n_nodes) na = n_nodes - 1;         // rows past the end compute on a valid atom and are not stored
+  const int kq = lane / 16;                    // position inside the reduction step
+  const T* xrow = X + (static_cast<size_t>(na) * k_red + kq) * NC;
+  const int steps = k_red / 4;
+  const int tiles_per_wave = k_cols / (16 * kWaves);
+  for (int g = 0; g < tiles_per_wave; g += CT) {
+    int jc[CT];                                // this lane's column in every tile of the group
+#pragma unroll
+    for (int t = 0; t < CT; ++t) jc[t] = ((g + t) * kWaves + wave) * 16 + (lane & 15);
+    acc_t acc[NC][CT];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int t = 0; t < CT; ++t) acc[c][t] = acc_t{0, 0, 0, 0};
+
+    auto load = [&](int s, T (&a)[NC], T (&b)[L][CT]) {
+      load_row<T, NC>(xrow + static_cast<size_t>(s) * 4 * NC, a);
+      const int k = s * 4 + kq;
+#pragma unroll
+      for (int l = 0; l < L; ++l)
+#pragma unroll
+        for (int t = 0; t < CT; ++t)
+          b[l][t] = kTrans ? W[(static_cast<size_t>(l) * k_cols + jc[t]) * k_red + k]
+                           : W[(static_cast<size_t>(l) * k_red + k) * k_cols + jc[t]];
+    };
+    auto multiply = [&](const T (&a)[NC], const T (&b)[L][CT]) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int t = 0; t < CT; ++t) acc[c][t] = Mma<T>::mma(a[c], b[order_of(c)][t], acc[c][t]);
+    };
+    T a0[NC], a1[NC], b0[L][CT], b1[L][CT];    // two operand sets in turn
+    load(0, a0, b0);
+    for (int s = 0; s < steps; s += 2) {
+      if (s + 1 < steps) load(s + 1, a1, b1);
+      multiply(a0, b0);
+      if (s + 1 < steps) {
+        if (s + 2 < steps) load(s + 2, a0, b0);
+        multiply(a1, b1);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < CT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t n = n0 + Mma<T>::row(lane, r);
+        if (n < n_nodes) {
+          T y[NC];
+#pragma unroll
+          for (int c = 0; c < NC; ++c) y[c] = acc[c][t][r];
+          store_row<T, NC>(Y + (static_cast<size_t>(n) * k_cols + jc[t]) * NC, y);
+        }
+      }
+  }
+}
+
+// Partial dW of a range of atoms: part[range][l][k][j] = sum_{n in range} sum_{m in l} X[n][k][c] dY[n][j][c].
+// Workgroup = (range, group of 4 row tiles, group of NT column tiles); wave w owns row tile
+// 4*kgroup + w.  k_in % 64 == 0, k_out % (16 * NT) == 0, nodes_per_range % 4 == 0.
+template <typename T, int LMAX, int NT>
+__global__ __launch_bounds__(kThreads) void mfma_dw_kernel(int64_t n_nodes, int nodes_per_range, int k_in, int k_out,
+                                                           const T* __restrict__ X, const T* __restrict__ dY,
+                                                           T* __restrict__ part) {
+  constexpr int NC = (LMAX + 1) * (LMAX + 1), L = LMAX + 1;
+  typedef typename Mma<T>::acc_t acc_t;
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int jgroups = k_out / (16 * NT), kgroups = k_in / 64;
+  const int jg = blockIdx.x % jgroups;
+  const int kg = (blockIdx.x / jgroups) % kgroups;
+  const int64_t range = blockIdx.x / (jgroups * kgroups);
+  const int64_t r0 = range * nodes_per_range;
+  const int64_t r1 = (r0 + nodes_per_range < n_nodes) ? r0 + nodes_per_range : n_nodes;
+  const int k = (kg * kWaves + wave) * 16 + (lane & 15);   // row (input channel) of this lane's A operands
+  const int j0 = jg * NT * 16 + (lane & 15);               // column of this lane in the group's first tile
+  acc_t acc[L][NT];
+#pragma unroll
+  for (int l = 0; l < L; ++l)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[l][t] = acc_t{0, 0, 0, 0};
+  for (int64_t n4 = r0; n4 < r1; n4 += 4) {
+    const int64_t n = n4 + lane / 16;          // the atom of this lane's position in the reduction step
+    const bool valid = n < r1;
+    const int64_t nc = valid ? n : r1 - 1;
+    T a[NC];
+    load_row<T, NC>(X + (static_cast<size_t>(nc) * k_in + k) * NC, a);
+    if (!valid) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) a[c] = T(0);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      T b[NC];
+      load_row<T, NC>(dY + (static_cast<size_t>(nc) * k_out + j0 + t * 16) * NC, b);
+#pragma unroll
+      for (int c = 0; c < NC; ++c) acc[order_of(c)][t] = Mma<T>::mma(a[c], b[c], acc[order_of(c)][t]);
+    }
+  }
+  T* out = part + static_cast<size_t>(range) * L * k_in * k_out;
+  const int kt = (kg * kWaves + wave) * 16;
+#pragma unroll
+  for (int l = 0; l < L; ++l)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        out[(static_cast<size_t>(l) * k_in + kt + Mma<T>::row(lane, r)) * k_out + j0 + t * 16] = acc[l][t][r];
+}
+
+// dW[idx] = sum over the ranges, in range order.
+template <typename T>
+__global__ void dw_reduce_kernel(int64_t n_elems, int n_ranges, const T* __restrict__ part, T* __restrict__ dW) {
+  const int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
+  if (i >= n_elems) return;
+  T s = T(0);
+  for (int r = 0; r < n_ranges; ++r) s += part[static_cast<size_t>(r) * n_elems + i];
+  dW[i] = s;
+}
+
+// ---- plain vector kernels for channel counts the MFMA tiling does not cover (fp64 accumulation)
+template <typename T, bool kTrans>
+__global__ void plain_forward_kernel(int64_t n_nodes, int k_red, int k_cols, int l_max, const T* __restrict__ X,
+                                     const T* __restrict__ W, T* __restrict__ Y) {
+  const int nc = (l_max + 1) * (l_max + 1);
+  const int64_t idx = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
+  if (idx >= n_nodes * k_cols) return;
+  const int64_t n = idx / k_cols;
+  const int j = static_cast<int>(idx % k_cols);
+  double y[16];
+  for (int c = 0; c < nc; ++c) y[c] = 0.0;
+  for (int k = 0; k < k_red; ++k) {
+    const T* x = X + (static_cast<size_t>(n) * k_red + k) * nc;
+    for (int c = 0; c < nc; ++c) {
+      const int l = order_of(c);
+      const T w = kTrans ? W[(static_cast<size_t>(l) * k_cols + j) * k_red + k]
+                         : W[(static_cast<size_t>(l) * k_red + k) * k_cols + j];
+      y[c] += static_cast<double>(x[c]) * static_cast<double>(w);
+    }
+  }
+  for (int c = 0; c < nc; ++c) Y[idx * nc + c] = static_cast<T>(y[c]);
+}
+
+// one thread per (l, k, j): sums over all atoms in atom order
+template <typename T>
+__global__ void plain_dw_kernel(int64_t n_nodes, int k_in, int k_out, int l_max, const T* __restrict__ X,
+                                const T* __restrict__ dY, T* __restrict__ dW) {
+  const int nc = (l_max + 1) * (l_max + 1);
+  const int64_t idx = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
+  if (idx >= static_cast<int64_t>(l_max + 1) * k_in * k_out) return;
+  const int j = static_cast<int>(idx % k_out);
+  const int k = static_cast<int>((idx / k_out) % k_in);
+  const int l = static_cast<int>(idx / (static_cast<int64_t>(k_out) * k_in));
+  double s = 0.0;
+  for (int64_t n = 0; n < n_nodes; ++n)
+    for (int c = l * l; c < (l + 1) * (l + 1); ++c)
+      s += static_cast<double>(X[(static_cast<size_t>(n) * k_in + k) * nc + c]) *
+           static_cast<double>(dY[(static_cast<size_t>(n) * k_out + j) * nc + c]);
+  dW[idx] = static_cast<T>(s);
+}
+
+__global__ void zero_kernel(unsigned int* p, size_t n_words) {
+  for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n_words;
+       i += static_cast<size_t>(gridDim.x) * blockDim.x)
+    p[i] = 0u;
+}
+
+// ---- host side
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int device) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == device) || hipSetDevice(device) == hipSuccess;
+    if (prev == device) prev = -1;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
+size_t elem_size(const el_config* c) { return c->dtype == SC_F64 ? 8 : 4; }
+
+sc_status check_config(const char* fn, const el_config* cfg, int64_t n) {
+  if (!cfg) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": cfg is NULL");
+  if (cfg->struct_size != static_cast<int32_t>(sizeof(el_config)))
+    return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": struct_size does not match this library's el_config");
+  if (cfg->k_in < 1 || cfg->k_out < 1) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": k_in or k_out < 1");
+  if (cfg->l_max < 0 || cfg->l_max > SC_MAX_L) return set_error(SC_ERR_UNSUPPORTED, std::string(fn) + ": l_max outside 0..3");
+  if (cfg->dtype != SC_F32 && cfg->dtype != SC_F64) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": bad dtype");
+  if (n < 0 || n > (int64_t(1) << 30)) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": n_nodes outside 0..2^30");
+  return SC_OK;
+}
+
+// Is the product with k_red reduction channels and k_cols output channels served by the MFMA kernel?
+bool mfma_forward_ok(int k_red, int k_cols) { return k_red % 4 == 0 && k_cols % 64 == 0; }
+bool mfma_dw_ok(const el_config* c) { return c->k_in % 64 == 0 && c->k_out % 64 == 0; }
+
+// Atoms per range of the dW kernel: enough ranges to fill the chip about once, a multiple of 4.
+int nodes_per_range(const el_config* cfg, int64_t n) {
+  const int groups = (cfg->k_in / 64) * (cfg->k_out / 64);
+  int64_t ranges = std::max<int64_t>(1, 256 / std::max(1, groups));
+  int64_t per = (n + ranges - 1) / ranges;
+  per = std::max<int64_t>(16, (per + 3) / 4 * 4);
+  return static_cast<int>(std::min<int64_t>(per, int64_t(1) << 20));
+}
+
+template <typename T, int LMAX, bool kTrans>
+hipError_t forward_l(int64_t n, int k_red, int k_cols, const void* X, const void* W, void* Y, hipStream_t stream) {
+  if (mfma_forward_ok(k_red, k_cols)) {
+    const unsigned grid = static_cast<unsigned>((n + 15) / 16);
+    // two column tiles at a time when the accumulators fit (fp32 and at least two tiles per wave)
+    if (sizeof(T) == 4 && k_cols % 128 == 0)
+      hipLaunchKernelGGL((mfma_forward_kernel<T, LMAX, 2, kTrans>), dim3(grid), dim3(kThreads), 0, stream, n, k_red,
+                         k_cols, static_cast<const T*>(X), static_cast<const T*>(W), static_cast<T*>(Y));
+    else
+      hipLaunchKernelGGL((mfma_forward_kernel<T, LMAX, 1, kTrans>), dim3(grid), dim3(kThreads), 0, stream, n, k_red,
+                         k_cols, static_cast<const T*>(X), static_cast<const T*>(W), static_cast<T*>(Y));
+  } else {
+    const int64_t total = n * k_cols;
+    hipLaunchKernelGGL((plain_forward_kernel<T, kTrans>), dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,
+                       stream, n, k_red, k_cols, LMAX, static_cast<const T*>(X), static_cast<const T*>(W),
+                       static_cast<T*>(Y));
+  }
+  return hipGetLastError();
+}
+
+template <typename T, bool kTrans>
+hipError_t forward_t(int l_max, int64_t n, int k_red, int k_cols, const void* X, const void* W, void* Y,
+                     hipStream_t stream) {
+  switch (l_max) {
+    case 0: return forward_l<T, 0, kTrans>(n, k_red, k_cols, X, W, Y, stream);
+    case 1: return forward_l<T, 1, kTrans>(n, k_red, k_cols, X, W, Y, stream);
+    case 2: return forward_l<T, 2, kTrans>(n, k_red, k_cols, X, W, Y, stream);
+    default: return forward_l<T, 3, kTrans>(n, k_red, k_cols, X, W, Y, stream);
+  }
+}
+
+template <typename T, int LMAX>
+hipError_t dw_l(const el_config* cfg, int64_t n, const void* X, const void* dY, void* dW, void* ws,
+                hipStream_t stream) {
+  const int64_t elems = static_cast<int64_t>(LMAX + 1) * cfg->k_in * cfg->k_out;
+  if (!mfma_dw_ok(cfg)) {
+    hipLaunchKernelGGL((plain_dw_kernel<T>), dim3(static_cast<unsigned>((elems + 255) / 256)), dim3(256), 0, stream, n,
+                       cfg->k_in, cfg->k_out, LMAX, static_cast<const T*>(X), static_cast<const T*>(dY),
+                       static_cast<T*>(dW));
+    return hipGetLastError();
+  }
+  const int per = nodes_per_range(cfg, n);
+  const int ranges = static_cast<int>((n + per - 1) / per);
+  // column tiles per workgroup: the accumulators (orders x tiles x 4 values) must fit the registers
+  constexpr int NT = sizeof(T) == 4 ? 4 : 2;
+  const unsigned grid = static_cast<unsigned>(static_cast<int64_t>(ranges) * (cfg->k_in / 64) * (cfg->k_out / (16 * NT)));
+  hipLaunchKernelGGL((mfma_dw_kernel<T, LMAX, NT>), dim3(grid), dim3(kThreads), 0, stream, n, per, cfg->k_in,
+                     cfg->k_out, static_cast<const T*>(X), static_cast<const T*>(dY), static_cast<T*>(ws));
+  hipLaunchKernelGGL((dw_reduce_kernel<T>), dim3(static_cast<unsigned>((elems + 255) / 256)), dim3(256), 0, stream, elems,
+                     ranges, static_cast<const T*>(ws), static_cast<T*>(dW));
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t dw_t(const el_config* cfg, int64_t n, const void* X, const void* dY, void* dW, void* ws,
+                hipStream_t stream) {
+  switch (cfg->l_max) {
+    case 0: return dw_l<T, 0>(cfg, n, X, dY, dW, ws, stream);
+    case 1: return dw_l<T, 1>(cfg, n, X, dY, dW, ws, stream);
+    case 2: return dw_l<T, 2>(cfg, n, X, dY, dW, ws, stream);
+    default: return dw_l<T, 3>(cfg, n, X, dY, dW, ws, stream);
+  }
+}
+
+size_t workspace_bytes(const el_config* cfg, int64_t n) {
+  if (n == 0 || !mfma_dw_ok(cfg)) return 256;
+  const int per = nodes_per_range(cfg, n);
+  const int64_t ranges = (n + per - 1) / per;
+  const size_t bytes = static_cast<size_t>(ranges) * (cfg->l_max + 1) * cfg->k_in * cfg->k_out * elem_size(cfg);
+  return (bytes + 255) / 256 * 256 + 256;
+}
+
+}  // namespace
+}  // namespace el
+
+extern "C" {
+
+sc_status el_forward(const el_config* cfg, int64_t n_nodes, const void* X, const void* W, void* Y, void* hip_stream) {
+  using namespace el;
+  sc_status st = check_config("el_forward", cfg, n_nodes);
+  if (st != SC_OK) return st;
+  if (n_nodes == 0) return SC_OK;
+  if (!X || !W || !Y) return set_error(SC_ERR_INVALID_ARG, "el_forward: NULL tensor argument");
+  if (misaligned(X, 16) || misaligned(W, 16) || misaligned(Y, 16))
+    return set_error(SC_ERR_INVALID_ARG, "el_forward: tensor pointer not 16-byte aligned");
+  DeviceGuard guard(cfg->device);
+  if (!guard.ok) return set_error(SC_ERR_HIP, "el_forward: cannot make cfg->device current");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = cfg->dtype == SC_F64
+                           ? forward_t<double, false>(cfg->l_max, n_nodes, cfg->k_in, cfg->k_out, X, W, Y, stream)
+                           : forward_t<float, false>(cfg->l_max, n_nodes, cfg->k_in, cfg->k_out, X, W, Y, stream);
+  if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_forward: kernel launch: ") + hipGetErrorString(e));
+  return SC_OK;
+}
+
+sc_status el_workspace_bytes(const el_config* cfg, int64_t n_nodes, size_t* bytes) {
+  using namespace el;
+  sc_status st = check_config("el_workspace_bytes", cfg, n_nodes);
+  if (st != SC_OK) return st;
+  if (!bytes) return set_error(SC_ERR_INVALID_ARG, "el_workspace_bytes: bytes is NULL");
+  *bytes = workspace_bytes(cfg, n_nodes);
+  return SC_OK;
+}
+
+sc_status el_backward(const el_config* cfg, int64_t n_nodes, const void* X, const void* W, const void* dY, void* dX,
+                      void* dW, void* workspace, size_t workspace_bytes_given, void* hip_stream) {
+  using namespace el;
+  sc_status st = check_config("el_backward", cfg, n_nodes);
+  if (st != SC_OK) return st;
+  if (!dW) return set_error(SC_ERR_INVALID_ARG, "el_backward: dW is NULL");
+  if (misaligned(dW, 16)) return set_error(SC_ERR_INVALID_ARG, "el_backward: dW not 16-byte aligned");
+  DeviceGuard guard(cfg->device);
+  if (!guard.ok) return set_error(SC_ERR_HIP, "el_backward: cannot make cfg->device current");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (n_nodes == 0) {
+    const size_t words = elem_size(cfg) / 4 * static_cast<size_t>(cfg->l_max + 1) * cfg->k_in * cfg->k_out;
+    hipLaunchKernelGGL(zero_kernel, dim3(64), dim3(256), 0, stream, static_cast<unsigned int*>(dW), words);
+    const hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_backward: fill launch: ") + hipGetErrorString(e0));
+    return SC_OK;
+  }
+  if (!X || !W || !dY || !dX) return set_error(SC_ERR_INVALID_ARG, "el_backward: NULL tensor argument");
+  if (misaligned(X, 16) || misaligned(W, 16) || misaligned(dY, 16) || misaligned(dX, 16))
+    return set_error(SC_ERR_INVALID_ARG, "el_backward: tensor pointer not 16-byte aligned");
+  if (!workspace || workspace_bytes_given < workspace_bytes(cfg, n_nodes))
+    return set_error(SC_ERR_WORKSPACE, "el_backward: workspace missing or smaller than el_workspace_bytes()");
+  if (misaligned(workspace, 256)) return set_error(SC_ERR_WORKSPACE, "el_backward: workspace not 256-byte aligned");
+  // dX = dY times W transposed: reduction over the output channels, columns = input channels
+  hipError_t e = cfg->dtype == SC_F64
+                     ? forward_t<double, true>(cfg->l_max, n_nodes, cfg->k_out, cfg->k_in, dY, W, dX, stream)
+                     : forward_t<float, true>(cfg->l_max, n_nodes, cfg->k_out, cfg->k_in, dY, W, dX, stream);
+  if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_backward: dX launch: ") + hipGetErrorString(e));
+  e = cfg->dtype == SC_F64 ? dw_t<double>(cfg, n_nodes, X, dY, dW, workspace, stream)
+                           : dw_t<float>(cfg, n_nodes, X, dY, dW, workspace, stream);
+  if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_backward: dW launch: ") + hipGetErrorString(e));
+  return SC_OK;
+}
+
+}  // extern "C"

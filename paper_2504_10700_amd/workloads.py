@@ -246,3 +246,13 @@ def make_graph_sizes(n_graphs: int, seed: int = 6001, max_size: int = 768) -> np
                      np.where(kind < 0.9, rng.integers(40, 200, n_graphs), rng.integers(200, max_size + 1, n_graphs)))
     return sizes.astype(np.int32)
 
+
+def make_linear_inputs(n_nodes: int, k_in: int, k_out: int, l_max: int, seed: int):
+    """X, W, dY for the per-order channel-mixing linear: X, dY ~ N(0,1), W ~ N(0,1)/sqrt(k_in)."""
+    rng = np.random.default_rng(seed)
+    nc = (l_max + 1) ** 2
+    X = rng.standard_normal((n_nodes, k_in, nc))
+    W = rng.standard_normal((l_max + 1, k_in, k_out)) / np.sqrt(k_in)
+    dY = rng.standard_normal((n_nodes, k_out, nc))
+    return X, W, dY
+
