@@ -420,6 +420,69 @@ def measure_tp_double_backward(wl, steps, warmup):
     }
 
 
+def measure_linear(n_nodes=10_000, k_in=128, k_out=128, l_max=3, steps=50, warmup=5):
+    """Per-order channel-mixing linear on the matrix cores: one step = el_forward + el_backward."""
+    import numpy as np
+    import torch
+    from paper_2504_10700_amd import el_binding as el
+    from paper_2504_10700_amd import workloads
+
+    dev = torch.device("cuda:0")
+    X, W, dY = (torch.tensor(x, dtype=torch.float32, device=dev)
+                for x in workloads.make_linear_inputs(n_nodes, k_in, k_out, l_max, 9001))
+    cfg = el.make_config(k_in, k_out, l_max, el.SC_F32)
+    nc = (l_max + 1) ** 2
+    n_sets = 6     # rotated so that a step does not find the previous step's tensors in the last-level cache
+    Xs = [X] + [X.clone() for _ in range(n_sets - 1)]
+    dYs = [dY] + [dY.clone() for _ in range(n_sets - 1)]
+    Ys = [torch.empty((n_nodes, k_out, nc), dtype=torch.float32, device=dev) for _ in range(n_sets)]
+    dXs = [torch.empty_like(X) for _ in range(n_sets)]
+    dW = torch.empty_like(W)
+    nbytes = el.el_workspace_bytes(cfg, n_nodes)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    def fwd(i):
+        el.el_forward(cfg, n_nodes, Xs[i % n_sets], W, Ys[i % n_sets])
+
+    def bwd(i):
+        j = (i + n_sets // 2) % n_sets
+        el.el_backward(cfg, n_nodes, Xs[j], W, dYs[j], dXs[j], dW, ws, nbytes)
+
+    for i in range(warmup):
+        fwd(i)
+        bwd(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fwd(i)
+        bwd(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    f_ms, b_ms = [], []
+    for i in range(min(steps, 30)):      # the library launches on torch's current stream: its events see the kernels
+        ev[0].record()
+        fwd(i)
+        ev[1].record()
+        bwd(i)
+        ev[2].record()
+        torch.cuda.synchronize()
+        f_ms.append(ev[0].elapsed_time(ev[1]))
+        b_ms.append(ev[1].elapsed_time(ev[2]))
+    f_ms, b_ms = float(np.mean(f_ms)), float(np.mean(b_ms))
+    gemm_flops = 2.0 * n_nodes * nc * k_in * k_out          # one product; the backward is two of them
+    tf = gemm_flops / (f_ms * 1e-3) / 1e12
+    return {"metric": "atoms/sec per-order channel-mixing linear fwd+bwd", "value": n_nodes / (dt / steps),
+            "unit": "nodes/s", "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3, "dtype": "f32",
+            "config": {"workload": f"{n_nodes} nodes, {k_in} -> {k_out} channels, l_max={l_max}, forward+backward",
+                       "kernel": "MFMA 16x16x4 f32"},
+            "roofline": {"bound": "mfma", "kernel": "forward (Y = X W per order)", "achieved": tf,
+                         "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS, "traffic": None,
+                         "kernel_ms": f_ms, "flops_per_launch": gemm_flops,
+                         "backward": {"ms": b_ms, "flops": 2 * gemm_flops,
+                                      "achieved": 2 * gemm_flops / (b_ms * 1e-3) / 1e12}}}
+
+
 def measure_balanced_batches(n_graphs=1_000_000, capacity=3072, n_gpus=8, oracle_sample=200_000):
     """Load balancer (host code): graphs/s of the C++ implementation, the oracle beside it."""
     import numpy as np
@@ -455,6 +518,8 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
     ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
     ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
+    ap.add_argument("--linear", action="store_true",
+                    help="measure only the channel-mixing linear (10k nodes, 128 -> 128 channels, l <= 3)")
     ap.add_argument("--balanced-batches", action="store_true",
                     help="measure only the host load balancer (1M graphs) and print its object")
     ap.add_argument("--tp", action="store_true",
@@ -471,6 +536,9 @@ def main():
 
     if args.balanced_batches:
         print(json.dumps(measure_balanced_batches()))
+        return
+    if args.linear:
+        print(json.dumps(measure_linear()))
         return
     if args.tp:
         name = args.workload if args.workload in workloads.TP_WORKLOADS else "tp_training_step"
@@ -498,6 +566,7 @@ def main():
         out["also"]["channelwise_tp_training_step"] = measure_tp(workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
         out["also"]["channelwise_tp_double_backward_training_step"] = measure_tp_double_backward(
             workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
+        out["also"]["channel_mixing_linear"] = measure_linear()
         out["also"]["balanced_batches"] = measure_balanced_batches()
     print(json.dumps(out))
 

@@ -11,8 +11,8 @@
  * one K_in x K_out matrix per order l, shared by the 2l+1 components of that order; component
  * index l*l + l + m as in sc.h.  No bias and no normalisation factor inside the operation.
  * This is a dense contraction: the kernels run on the matrix cores (MFMA, fp32 or fp64
- * inputs and accumulation) when K_in is a multiple of 4 and K_out a multiple of 64, and on a
- * plain vector kernel otherwise.
+ * inputs and accumulation) when K_in and K_out are multiples of 64 (forward alone: K_in a
+ * multiple of 16), and on plain vector kernels otherwise.
  *
  * Conventions as in sc.h: device pointers, dense row-major, 16-byte aligned; calls enqueue on
  * the given HIP stream and never synchronise; outputs are overwritten; errors by return code

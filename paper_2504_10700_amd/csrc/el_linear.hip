@@ -91,8 +91,15 @@ __device__ __forceinline__ void store_row(T* __restrict__ p, const T (&v)[N]) {
 
 // Y[n][j][c] = sum_k X[n][k][c] * B_l(c)[k][j] with B_l[k][j] = W[l][k][j] (kTrans = false,
 // W is [L][k_red][k_cols]) or W[l][j][k] (kTrans = true, W is [L][k_cols][k_red]).
-// One workgroup = 16 atoms; wave w owns the column tiles w, w+4, ... and works on CT of them
-// at a time.  k_red % 4 == 0, k_cols % (64 * CT) == 0.
+// One row tile = 16 atoms; wave w owns the column tiles w, w+4, ... and works on CT of them
+// at a time.  The grid is persistent: every workgroup walks the row tiles blockIdx.x,
+// blockIdx.x + gridDim.x, ...  With one workgroup resident per CU (the accumulators and the
+// operand pipeline fill the register file) a grid of one workgroup per row tile would pay the
+// launch of a workgroup, the first loads and the drain of the stores once per tile with
+// nothing to overlap them (measured 27 us per workgroup against 15 us of matrix time).
+// k_red % (4 * kDepth) == 0, k_cols % (64 * CT) == 0.
+constexpr int kDepth = 4;  // operand sets of the forward kernel's software pipeline
+
 template <typename T, int LMAX, int CT, bool kTrans>
 __global__ __launch_bounds__(kThreads) void mfma_forward_kernel(int64_t n_nodes, int k_red, int k_cols,
                                                                 const T* __restrict__ X, const T* __restrict__ W,
@@ -101,14 +108,16 @@ __global__ __launch_bounds__(kThreads) void mfma_forward_kernel(int64_t n_nodes,
   typedef typename Mma<T>::acc_t acc_t;
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
-  const int64_t n0 = static_cast<int64_t>(blockIdx.x) * 16;
-  int64_t na = n0 + (lane & 15);               // the atom whose A operands this lane supplies
-  if (na >= n_nodes) na = n_nodes - 1;         // rows past the end compute on a valid atom and are not stored
   const int kq = lane / 16;                    // position inside the reduction step
-  const T* xrow = X + (static_cast<size_t>(na) * k_red + kq) * NC;
   const int steps = k_red / 4;
   const int tiles_per_wave = k_cols / (16 * kWaves);
+  const int64_t row_tiles = (n_nodes + 15) / 16;
+  for (int64_t tile = blockIdx.x; tile < row_tiles; tile += gridDim.x)
   for (int g = 0; g < tiles_per_wave; g += CT) {
+    const int64_t n0 = tile * 16;
+    int64_t na = n0 + (lane & 15);             // the atom whose A operands this lane supplies
+    if (na >= n_nodes) na = n_nodes - 1;       // rows past the end compute on a valid atom and are not stored
+    const T* xrow = X + (static_cast<size_t>(na) * k_red + kq) * NC;
     int jc[CT];                                // this lane's column in every tile of the group
 #pragma unroll
     for (int t = 0; t < CT; ++t) jc[t] = ((g + t) * kWaves + wave) * 16 + (lane & 15);
@@ -134,14 +143,25 @@ __global__ __launch_bounds__(kThreads) void mfma_forward_kernel(int64_t n_nodes,
 #pragma unroll
         for (int t = 0; t < CT; ++t) acc[c][t] = Mma<T>::mma(a[c], b[order_of(c)][t], acc[c][t]);
     };
-    T a0[NC], a1[NC], b0[L][CT], b1[L][CT];    // two operand sets in turn
-    load(0, a0, b0);
-    for (int s = 0; s < steps; s += 2) {
-      if (s + 1 < steps) load(s + 1, a1, b1);
-      multiply(a0, b0);
-      if (s + 1 < steps) {
-        if (s + 2 < steps) load(s + 2, a0, b0);
-        multiply(a1, b1);
+    // kDepth operand sets in turn: the loads of step s + kDepth - 1 are issued before the
+    // products of step s, so that kDepth - 1 steps of matrix work cover the load latency.
+    // The loop body has no branch (steps is a multiple of kDepth; prefetches past the end
+    // re-read the last step): with branches inside, the compiler's wait-count bookkeeping
+    // falls back to waiting for every outstanding load at each step, which serialises the
+    // pipeline (measured: 33 us instead of 15 us of matrix time per workgroup).  The scheduling
+    // barriers keep the instruction scheduler from regrouping the loads of several steps, which
+    // has the same effect (a wait for the newest loads at the top of every iteration).
+    T a[kDepth][NC], b[kDepth][L][CT];
+#pragma unroll
+    for (int q = 0; q < kDepth - 1; ++q) load(q < steps ? q : steps - 1, a[q], b[q]);
+    for (int s = 0; s < steps; s += kDepth) {
+#pragma unroll
+      for (int q = 0; q < kDepth; ++q) {
+        const int nxt = s + q + kDepth - 1;
+        load(nxt < steps ? nxt : steps - 1, a[(q + kDepth - 1) % kDepth], b[(q + kDepth - 1) % kDepth]);
+        __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of this step's products ...
+        multiply(a[q], b[q]);
+        __builtin_amdgcn_sched_barrier(0);   // ... and the next step's loads behind them
       }
     }
 #pragma unroll
@@ -154,6 +174,123 @@ __global__ __launch_bounds__(kThreads) void mfma_forward_kernel(int64_t n_nodes,
 #pragma unroll
           for (int c = 0; c < NC; ++c) y[c] = acc[c][t][r];
           store_row<T, NC>(Y + (static_cast<size_t>(n) * k_cols + jc[t]) * NC, y);
+        }
+      }
+  }
+}
+
+// The same product for fp32 and l_max = 3 (64-byte rows) with the A operands shared through
+// LDS.  In the kernel above each of the four waves reads the whole X tile itself; those
+// 16-byte accesses to 32 cache lines per instruction keep the vector memory path as busy as the
+// matrix cores (measured: 30 us per row tile against 15 us of matrix time).  Here the
+// workgroup stages X in chunks of 16 reduction channels (16 atoms x 16 channels x 64 B = 16 KB,
+// two buffers): every thread loads 64 contiguous bytes once, all waves read their A operands
+// from LDS (rows padded by 16 B against bank conflicts).  B operands (this wave's columns of
+// W) are read from global memory one MFMA step ahead.  k_red % 16 == 0, k_cols % 128 == 0.
+constexpr int kChunk = 16;                       // reduction channels per LDS chunk
+constexpr int kRowPad = kChunk * 16 + 4;         // floats per atom row in LDS
+
+template <bool kTrans>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_forward_lds_kernel(int64_t n_nodes, int k_red, int k_cols,
+                                                                    const float* __restrict__ X,
+                                                                    const float* __restrict__ W,
+                                                                    float* __restrict__ Y) {
+  constexpr int NC = 16, L = 4, CT = 2, SPC = kChunk / 4;   // SPC: MFMA steps per chunk
+  typedef Mma<float>::acc_t acc_t;
+  typedef float V4 __attribute__((ext_vector_type(4)));
+  __shared__ __attribute__((aligned(16))) float xs[2][16 * kRowPad];
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int kq = lane / 16;
+  const int chunks = k_red / kChunk;
+  const int tiles_per_wave = k_cols / (16 * kWaves);
+  const int64_t row_tiles = (n_nodes + 15) / 16;
+  // staging role of this thread: atom tid/16 of the tile, reduction channel tid%16 of the chunk
+  const int sn = threadIdx.x / 16, sk = threadIdx.x % 16;
+  float* const swr = &xs[0][sn * kRowPad + sk * 16];
+  const float* const ard = &xs[0][(lane & 15) * kRowPad + kq * 16];   // A operands of MFMA step 0 of a chunk
+
+  for (int64_t tile = blockIdx.x; tile < row_tiles; tile += gridDim.x)
+  for (int g = 0; g < tiles_per_wave; g += CT) {
+    const int64_t n0 = tile * 16;
+    int64_t ns = n0 + sn;
+    if (ns >= n_nodes) ns = n_nodes - 1;       // rows past the end stage a valid atom and are not stored
+    const float* xsrc = X + (static_cast<size_t>(ns) * k_red + sk) * NC;
+    int jc[CT];
+#pragma unroll
+    for (int t = 0; t < CT; ++t) jc[t] = ((g + t) * kWaves + wave) * 16 + (lane & 15);
+    acc_t acc[NC][CT];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int t = 0; t < CT; ++t) acc[c][t] = acc_t{0, 0, 0, 0};
+
+    auto gload = [&](int chunk, V4 (&x)[4]) {
+      const V4* p = reinterpret_cast<const V4*>(xsrc + static_cast<size_t>(chunk) * kChunk * NC);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) x[i] = p[i];
+    };
+    auto stage = [&](int buf, const V4 (&x)[4]) {
+      V4* p = reinterpret_cast<V4*>(swr + buf * 16 * kRowPad);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) p[i] = x[i];
+    };
+    // B operands: a wave-uniform base (order, reduction step) plus a 32-bit per-lane offset, so
+    // that the loads need no per-lane 64-bit address registers
+    int boff[CT];
+#pragma unroll
+    for (int t = 0; t < CT; ++t) boff[t] = kTrans ? jc[t] * k_red + kq : kq * k_cols + jc[t];
+    const int steps = chunks * SPC;
+    auto bload = [&](int step, float (&b)[L][CT]) {   // B operands of one MFMA step
+      const int k = (step < steps ? step : steps - 1) * 4;   // wave-uniform; past the end: re-read the last step
+#pragma unroll
+      for (int l = 0; l < L; ++l) {
+        const float* base = kTrans ? W + static_cast<size_t>(l) * k_cols * k_red + k
+                                   : W + (static_cast<size_t>(l) * k_red + k) * k_cols;
+#pragma unroll
+        for (int t = 0; t < CT; ++t) b[l][t] = base[boff[t]];
+      }
+    };
+
+    V4 xr[4];
+    float b[2][L][CT];                         // B operands of the current and of the next step
+    __syncthreads();                           // the previous tile's reads of both buffers are done
+    gload(0, xr);
+    bload(0, b[0]);
+    stage(0, xr);
+    if (chunks > 1) gload(1, xr);
+    __syncthreads();
+    for (int c = 0; c < chunks; ++c) {
+      const float* abuf = ard + (c & 1) * 16 * kRowPad;
+#pragma unroll
+      for (int st = 0; st < SPC; ++st) {       // SPC is even: the roles of b[0] and b[1] repeat per chunk
+        bload(c * SPC + st + 1, b[(st + 1) & 1]);
+        const V4* p = reinterpret_cast<const V4*>(abuf + st * 4 * 16);
+        V4 a4[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a4[i] = p[i];
+#pragma unroll
+        for (int cc = 0; cc < NC; ++cc)
+#pragma unroll
+          for (int t = 0; t < CT; ++t)
+            acc[cc][t] = Mma<float>::mma(a4[cc / 4][cc % 4], b[st & 1][order_of(cc)][t], acc[cc][t]);
+      }
+      if (c + 1 < chunks) {
+        stage((c + 1) & 1, xr);
+        if (c + 2 < chunks) gload(c + 2, xr);
+      }
+      __syncthreads();
+    }
+#pragma unroll
+    for (int t = 0; t < CT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t n = n0 + Mma<float>::row(lane, r);
+        if (n < n_nodes) {
+          float y[NC];
+#pragma unroll
+          for (int c = 0; c < NC; ++c) y[c] = acc[c][t][r];
+          store_row<float, NC>(Y + (static_cast<size_t>(n) * k_cols + jc[t]) * NC, y);
         }
       }
   }
@@ -297,8 +434,21 @@ sc_status check_config(const char* fn, const el_config* cfg, int64_t n) {
   return SC_OK;
 }
 
+// Compute units of the current device (asked once per device).
+int compute_units() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 // Is the product with k_red reduction channels and k_cols output channels served by the MFMA kernel?
-bool mfma_forward_ok(int k_red, int k_cols) { return k_red % 4 == 0 && k_cols % 64 == 0; }
+bool mfma_forward_ok(int k_red, int k_cols) { return k_red % (4 * kDepth) == 0 && k_cols % 64 == 0; }
 bool mfma_dw_ok(const el_config* c) { return c->k_in % 64 == 0 && c->k_out % 64 == 0; }
 
 // Atoms per range of the dW kernel: enough ranges to fill the chip about once, a multiple of 4.
@@ -313,7 +463,15 @@ int nodes_per_range(const el_config* cfg, int64_t n) {
 template <typename T, int LMAX, bool kTrans>
 hipError_t forward_l(int64_t n, int k_red, int k_cols, const void* X, const void* W, void* Y, hipStream_t stream) {
   if (mfma_forward_ok(k_red, k_cols)) {
-    const unsigned grid = static_cast<unsigned>((n + 15) / 16);
+    const unsigned grid = static_cast<unsigned>(std::min<int64_t>((n + 15) / 16, compute_units()));
+    if constexpr (sizeof(T) == 4 && LMAX == 3) {
+      if (k_cols % 128 == 0) {   // the LDS-staged variant: two workgroups fit a CU
+        const unsigned grid2 = static_cast<unsigned>(std::min<int64_t>((n + 15) / 16, 2 * compute_units()));
+        hipLaunchKernelGGL((mfma_forward_lds_kernel<kTrans>), dim3(grid2), dim3(kThreads), 0, stream, n, k_red, k_cols,
+                           static_cast<const float*>(X), static_cast<const float*>(W), static_cast<float*>(Y));
+        return hipGetLastError();
+      }
+    }
     // two column tiles at a time when the accumulators fit (fp32 and at least two tiles per wave)
     if (sizeof(T) == 4 && k_cols % 128 == 0)
       hipLaunchKernelGGL((mfma_forward_kernel<T, LMAX, 2, kTrans>), dim3(grid), dim3(kThreads), 0, stream, n, k_red,
