@@ -2,8 +2,8 @@
  * el.h - C ABI of the per-order channel-mixing linear (same library, libsc_mi355x.so).
  *
  * Section 4.1 of arXiv 2504.10700 (the paragraph before Algorithm 2): after the pooling over
- * the neighbours "a further linear combination (between terms k of the same order)" is applied
- * to the atomic-basis features before the symmetric contraction.  For every atom i, output
+ * the neighbours the channels k that belong to one order l are mixed linearly once more, and the
+ * result is what the symmetric contraction takes.  For every atom i, output
  * channel k', order l = 0..l_max and component m
  *
  *   Y[i,k',(l,m)] = sum_k W[l,k,k'] * X[i,k,(l,m)]

@@ -12,9 +12,9 @@ Readings of what the paper leaves open (all listed in the design notes):
 * the sort of the bins takes the listing's line (stable, by remaining capacity, descending:
   the emptiest bin receives the next - largest remaining - graph); the prose next to it speaks
   of prioritising fuller bins, which contradicts the listing and the stated goal of balance;
-* "any non-full bin has less remaining capacity than a full bin" compares the smallest
-  remaining capacity among the bins still active after the sweep with the largest among the
-  bins marked full in that sweep;
+* the second-chance test (some bin still accepting graphs has less room left than some bin
+  already given up on) compares the smallest remaining capacity among the bins still active
+  after the sweep with the largest among the bins marked full in that sweep;
 * a bin keeps the identity it was created with: bins of the first call are numbered 0..M-1,
   bins created by the recursive call for the remaining graphs continue the numbering; bins that
   stay empty (M is rounded up to a multiple of G) are kept, so that every call contributes a

@@ -3,8 +3,8 @@
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
 Section 4.1 (the paragraph before Algorithm 2): after the messages are summed over the
-neighbours, "a further linear combination (between terms k of the same order)" is applied
-before the symmetric contraction.  For every atom i, output channel k', order l and m
+neighbours, the channels k belonging to one order l are mixed linearly once more before the
+symmetric contraction.  For every atom i, output channel k', order l and m
 
     Y[i,k',(l,m)] = sum_k W[l,k,k'] * X[i,k,(l,m)]
 
