@@ -483,6 +483,67 @@ def measure_linear(n_nodes=10_000, k_in=128, k_out=128, l_max=3, steps=50, warmu
                                       "achieved": 2 * gemm_flops / (b_ms * 1e-3) / 1e12}}}
 
 
+def measure_fused_forward(wl, steps=50, warmup=5):
+    """Forward of linear + contraction: el_sc_forward (one kernel, A stays in registers) next to the two calls
+    el_forward + sc_forward through A in memory."""
+    import numpy as np
+    import torch
+    from paper_2504_10700_amd import binding as sc
+    from paper_2504_10700_amd import el_binding as el
+    from paper_2504_10700_amd import workloads
+
+    dev = torch.device("cuda:0")
+    N, K, k_in = wl.num_nodes, wl.num_channels, wl.num_channels
+    plan = sc.sc_plan_create(K, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps, sc.SC_F32, 0)
+    paths = sc.sc_plan_paths(plan)
+    inp = workloads.make_inputs(wl, paths)
+    Xn, Wln, _ = workloads.make_linear_inputs(N, k_in, K, wl.l_max, wl.seed + 1)
+    f = lambda x: torch.tensor(x, dtype=torch.float32, device=dev)
+    W, Wl, z = f(inp.W), f(Wln), torch.tensor(inp.z, dtype=torch.int32, device=dev)
+    n_sets = 6
+    Xs = [f(Xn)]
+    Xs += [Xs[0].clone() for _ in range(n_sets - 1)]
+    Bs = [torch.empty((N, K, wl.n_LM), dtype=torch.float32, device=dev) for _ in range(n_sets)]
+    A = torch.empty((N, K, wl.n_lm), dtype=torch.float32, device=dev)
+    fused = el.el_sc_is_fused(plan, k_in)
+    fb = el.el_sc_workspace_bytes(plan, k_in, N)
+    fws = torch.empty(fb, dtype=torch.uint8, device=dev)
+    sb = sc.sc_workspace_bytes(plan, N)
+    sws = torch.empty(sb, dtype=torch.uint8, device=dev)
+    cfg = el.make_config(k_in, K, wl.l_max, el.SC_F32)
+
+    def one(i):
+        el.el_sc_forward(plan, k_in, N, Xs[i % n_sets], Wl, z, W, Bs[i % n_sets], fws, fb)
+
+    def two(i):
+        el.el_forward(cfg, N, Xs[i % n_sets], Wl, A)
+        sc.sc_forward(plan, N, A, z, W, Bs[i % n_sets], sws, sb)
+
+    def timed(fn):
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    t_one, t_two = timed(one), timed(two)
+    sc.sc_plan_destroy(plan)
+    nc = wl.n_lm
+    gemm_flops = 2.0 * N * nc * k_in * K
+    tf = gemm_flops / t_one / 1e12
+    return {"metric": "atoms/sec channel-mixing linear + symmetric contraction, forward", "value": N / t_one,
+            "unit": "nodes/s", "steps": steps, "warmup": warmup, "ms_per_step": t_one * 1e3, "dtype": "f32",
+            "config": {"workload": wl.name, "k_in": k_in, "single_kernel": bool(fused)},
+            "two_calls": {"value": N / t_two, "ms_per_step": t_two * 1e3},
+            "roofline": {"bound": "mfma", "kernel": "linear on MFMA + contraction from the accumulators",
+                         "achieved": tf, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS,
+                         "traffic": None, "flops_per_launch": gemm_flops,
+                         "note": "flops of the matrix product only, duration of the whole call (fold + kernel)"}}
+
+
 def measure_balanced_batches(n_graphs=1_000_000, capacity=3072, n_gpus=8, oracle_sample=200_000):
     """Load balancer (host code): graphs/s of the C++ implementation, the oracle beside it."""
     import numpy as np
@@ -520,6 +581,8 @@ def main():
     ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
     ap.add_argument("--linear", action="store_true",
                     help="measure only the channel-mixing linear (10k nodes, 128 -> 128 channels, l <= 3)")
+    ap.add_argument("--fused", action="store_true",
+                    help="measure only the forward of linear + contraction as one call (--workload)")
     ap.add_argument("--balanced-batches", action="store_true",
                     help="measure only the host load balancer (1M graphs) and print its object")
     ap.add_argument("--tp", action="store_true",
@@ -546,6 +609,9 @@ def main():
         print(json.dumps(fn(workloads.TP_WORKLOADS[name], args.steps, args.warmup)))
         return
     wl = workloads.WORKLOADS[args.workload]
+    if args.fused:
+        print(json.dumps(measure_fused_forward(wl, args.steps, args.warmup)))
+        return
     if args.double_backward:
         print(json.dumps(measure_double_backward(wl, args.steps, args.warmup, args.tile_nodes)))
         return
@@ -567,6 +633,7 @@ def main():
         out["also"]["channelwise_tp_double_backward_training_step"] = measure_tp_double_backward(
             workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
         out["also"]["channel_mixing_linear"] = measure_linear()
+        out["also"]["linear_plus_contraction_forward"] = measure_fused_forward(wl, 50, 5)
         out["also"]["balanced_batches"] = measure_balanced_batches()
     print(json.dumps(out))
 

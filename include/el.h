@@ -40,7 +40,7 @@ typedef struct {
 /* Forward.  n_nodes == 0 is valid and does nothing. */
 sc_status el_forward(const el_config* cfg, int64_t n_nodes, const void* X, const void* W, void* Y, void* hip_stream);
 
-/* Bytes of device workspace el_backward needs (partial sums of dW per range of atoms). */
+/* Bytes of device workspace el_backward needs (W transposed for the dX product, partial sums of dW per range of atoms). */
 sc_status el_workspace_bytes(const el_config* cfg, int64_t n_nodes, size_t* bytes);
 
 /* Backward for an upstream gradient dY [n_nodes][K_out][(l_max+1)^2] (training, Section 2.2):
@@ -51,6 +51,27 @@ sc_status el_workspace_bytes(const el_config* cfg, int64_t n_nodes, size_t* byte
  * n_nodes == 0 zeroes dW. */
 sc_status el_backward(const el_config* cfg, int64_t n_nodes, const void* X, const void* W, const void* dY, void* dX,
                       void* dW, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The linear and the contraction as one forward call (Section 4.1: the channel mixing and
+ * Algorithm 2 are consecutive steps on the receiving atom):
+ *
+ *   B = sc_forward(A, z, W)   with   A[i,k',(l,m)] = sum_k W_lin[l,k,k'] X[i,k,(l,m)]
+ *
+ * plan: a contraction plan (sc.h); its num_channels is K_out of the linear, its l_max the l_max
+ * of X, its dtype the dtype of every tensor.  k_in: input channels of the linear.
+ *   X [n_nodes][k_in][(l_max+1)^2]   W_lin [l_max+1][k_in][K]   z [n_nodes] int32   W [Z][num_paths][K]
+ *   B [n_nodes][K][n_LM]  (overwritten)
+ * For fp32 plans served by the generated 0e+1o kernel with K a multiple of 128 and k_in a multiple
+ * of 16, one kernel computes the tile of A on the matrix cores and evaluates the contraction from
+ * the accumulators: A is never written (el_sc_is_fused returns 1).  Every other plan runs
+ * el_forward into the workspace and then sc_forward, with the same result up to rounding.
+ * workspace: device memory, 256-byte aligned, at least el_sc_workspace_bytes().  Same conventions
+ * as sc_forward (stream, no synchronisation, z not range-checked); n_nodes == 0 does nothing. */
+int32_t el_sc_is_fused(const sc_plan* plan, int32_t k_in);
+sc_status el_sc_workspace_bytes(const sc_plan* plan, int32_t k_in, int64_t n_nodes, size_t* bytes);
+sc_status el_sc_forward(sc_plan* plan, int32_t k_in, int64_t n_nodes, const void* X, const void* W_lin,
+                        const int32_t* z, const void* W, void* B, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
 
 #ifdef __cplusplus
 }

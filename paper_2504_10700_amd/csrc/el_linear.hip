@@ -21,76 +21,16 @@
 #include <string>
 
 #include "../../include/el.h"
+#include "el_tile.h"
 #include "sc_internal.h"
 
 namespace el {
 namespace {
 
-using sc::kLanes;
 using sc::set_error;
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * kLanes;
-
-template <typename T>
-struct Mma;
-template <>
-struct Mma<float> {
-  typedef float acc_t __attribute__((ext_vector_type(4)));
-  static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-  }
-  static __device__ __forceinline__ int row(int lane, int r) { return 4 * (lane / 16) + r; }
-};
-template <>
-struct Mma<double> {
-  typedef double acc_t __attribute__((ext_vector_type(4)));
-  static __device__ __forceinline__ acc_t mma(double a, double b, acc_t c) {
-    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
-  }
-  static __device__ __forceinline__ int row(int lane, int r) { return 4 * r + lane / 16; }
-};
-
-__host__ __device__ constexpr int order_of(int c) { return c >= 9 ? 3 : c >= 4 ? 2 : c >= 1 ? 1 : 0; }
-
-// N consecutive elements (16-byte accesses when the row is a multiple of 16 bytes).
-template <typename T, int N>
-__device__ __forceinline__ void load_row(const T* __restrict__ p, T (&v)[N]) {
-  constexpr int V = 16 / sizeof(T);
-  if constexpr ((N * sizeof(T)) % 16 == 0) {
-    typedef T Vec __attribute__((ext_vector_type(V)));
-#pragma unroll
-    for (int i = 0; i < N; i += V) {
-      const Vec x = *reinterpret_cast<const Vec*>(p + i);
-#pragma unroll
-      for (int k = 0; k < V; ++k) v[i + k] = x[k];
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < N; ++i) v[i] = p[i];
-  }
-}
-
-template <typename T, int N>
-__device__ __forceinline__ void store_row(T* __restrict__ p, const T (&v)[N]) {
-  constexpr int V = 16 / sizeof(T);
-  if constexpr ((N * sizeof(T)) % 16 == 0) {
-    typedef T Vec __attribute__((ext_vector_type(V)));
-#pragma unroll
-    for (int i = 0; i < N; i += V) {
-      Vec x;
-#pragma unroll
-      for (int k = 0; k < V; ++k) x[k] = v[i + k];
-      *reinterpret_cast<Vec*>(p + i) = x;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < N; ++i) p[i] = v[i];
-  }
-}
-
-// Y[n][j][c] = sum_k X[n][k][c] * B_l(c)[k][j] with B_l[k][j] = W[l][k][j] (kTrans = false,
-// W is [L][k_red][k_cols]) or W[l][j][k] (kTrans = true, W is [L][k_cols][k_red]).
+// Y[n][j][c] = sum_k X[n][k][c] * W[l(c)][k][j], W is [L][k_red][k_cols] (the dX product of the
+// backward passes W transposed, so that both read their B operands along rows of W).
 // One row tile = 16 atoms; wave w owns the column tiles w, w+4, ... and works on CT of them
 // at a time.  The grid is persistent: every workgroup walks the row tiles blockIdx.x,
 // blockIdx.x + gridDim.x, ...  With one workgroup resident per CU (the accumulators and the
@@ -100,7 +40,7 @@ __device__ __forceinline__ void store_row(T* __restrict__ p, const T (&v)[N]) {
 // k_red % (4 * kDepth) == 0, k_cols % (64 * CT) == 0.
 constexpr int kDepth = 4;  // operand sets of the forward kernel's software pipeline
 
-template <typename T, int LMAX, int CT, bool kTrans>
+template <typename T, int LMAX, int CT>
 __global__ __launch_bounds__(kThreads) void mfma_forward_kernel(int64_t n_nodes, int k_red, int k_cols,
                                                                 const T* __restrict__ X, const T* __restrict__ W,
                                                                 T* __restrict__ Y) {
@@ -134,8 +74,7 @@ __global__ __launch_bounds__(kThreads) void mfma_forward_kernel(int64_t n_nodes,
       for (int l = 0; l < L; ++l)
 #pragma unroll
         for (int t = 0; t < CT; ++t)
-          b[l][t] = kTrans ? W[(static_cast<size_t>(l) * k_cols + jc[t]) * k_red + k]
-                           : W[(static_cast<size_t>(l) * k_red + k) * k_cols + jc[t]];
+          b[l][t] = W[(static_cast<size_t>(l) * k_red + k) * k_cols + jc[t]];
     };
     auto multiply = [&](const T (&a)[NC], const T (&b)[L][CT]) {
 #pragma unroll
@@ -179,121 +118,42 @@ __global__ __launch_bounds__(kThreads) void mfma_forward_kernel(int64_t n_nodes,
   }
 }
 
-// The same product for fp32 and l_max = 3 (64-byte rows) with the A operands shared through
-// LDS.  In the kernel above each of the four waves reads the whole X tile itself; those
-// 16-byte accesses to 32 cache lines per instruction keep the vector memory path as busy as the
-// matrix cores (measured: 30 us per row tile against 15 us of matrix time).  Here the
-// workgroup stages X in chunks of 16 reduction channels (16 atoms x 16 channels x 64 B = 16 KB,
-// two buffers): every thread loads 64 contiguous bytes once, all waves read their A operands
-// from LDS (rows padded by 16 B against bank conflicts).  B operands (this wave's columns of
-// W) are read from global memory one MFMA step ahead.  k_red % 16 == 0, k_cols % 128 == 0.
-constexpr int kChunk = 16;                       // reduction channels per LDS chunk
-constexpr int kRowPad = kChunk * 16 + 4;         // floats per atom row in LDS
-
-template <bool kTrans>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_forward_lds_kernel(int64_t n_nodes, int k_red, int k_cols,
-                                                                    const float* __restrict__ X,
-                                                                    const float* __restrict__ W,
-                                                                    float* __restrict__ Y) {
-  constexpr int NC = 16, L = 4, CT = 2, SPC = kChunk / 4;   // SPC: MFMA steps per chunk
-  typedef Mma<float>::acc_t acc_t;
-  typedef float V4 __attribute__((ext_vector_type(4)));
-  __shared__ __attribute__((aligned(16))) float xs[2][16 * kRowPad];
+// fp32, l_max = 3: the LDS-staged product of el_tile.h.  A full work unit = a row tile x 128
+// columns (two column tiles per wave, 128 accumulator registers); see UnitSchedule for the halves.
+template <int CT>
+__device__ __forceinline__ void forward_lds_unit(int64_t n_nodes, int64_t n0, int g, int k_red, int k_cols,
+                                                 const float* __restrict__ X, const float* __restrict__ W,
+                                                 float* __restrict__ Y, float* xs) {
+  constexpr int NC = 16;
   const int lane = threadIdx.x & (kLanes - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
-  const int kq = lane / 16;
-  const int chunks = k_red / kChunk;
-  const int tiles_per_wave = k_cols / (16 * kWaves);
-  const int64_t row_tiles = (n_nodes + 15) / 16;
-  // staging role of this thread: atom tid/16 of the tile, reduction channel tid%16 of the chunk
-  const int sn = threadIdx.x / 16, sk = threadIdx.x % 16;
-  float* const swr = &xs[0][sn * kRowPad + sk * 16];
-  const float* const ard = &xs[0][(lane & 15) * kRowPad + kq * 16];   // A operands of MFMA step 0 of a chunk
-
-  for (int64_t tile = blockIdx.x; tile < row_tiles; tile += gridDim.x)
-  for (int g = 0; g < tiles_per_wave; g += CT) {
-    const int64_t n0 = tile * 16;
-    int64_t ns = n0 + sn;
-    if (ns >= n_nodes) ns = n_nodes - 1;       // rows past the end stage a valid atom and are not stored
-    const float* xsrc = X + (static_cast<size_t>(ns) * k_red + sk) * NC;
-    int jc[CT];
+  Mma<float>::acc_t acc[NC][CT];
+  int jc[CT];
+  lds_tile_product<CT>(n_nodes, n0, g, k_red, k_cols, X, W, xs, acc, jc);
 #pragma unroll
-    for (int t = 0; t < CT; ++t) jc[t] = ((g + t) * kWaves + wave) * 16 + (lane & 15);
-    acc_t acc[NC][CT];
+  for (int t = 0; t < CT; ++t)
 #pragma unroll
-    for (int c = 0; c < NC; ++c)
+    for (int r = 0; r < 4; ++r) {
+      const int64_t n = n0 + Mma<float>::row(lane, r);
+      if (n < n_nodes) {
+        float y[NC];
 #pragma unroll
-      for (int t = 0; t < CT; ++t) acc[c][t] = acc_t{0, 0, 0, 0};
-
-    auto gload = [&](int chunk, V4 (&x)[4]) {
-      const V4* p = reinterpret_cast<const V4*>(xsrc + static_cast<size_t>(chunk) * kChunk * NC);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) x[i] = p[i];
-    };
-    auto stage = [&](int buf, const V4 (&x)[4]) {
-      V4* p = reinterpret_cast<V4*>(swr + buf * 16 * kRowPad);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) p[i] = x[i];
-    };
-    // B operands: a wave-uniform base (order, reduction step) plus a 32-bit per-lane offset, so
-    // that the loads need no per-lane 64-bit address registers
-    int boff[CT];
-#pragma unroll
-    for (int t = 0; t < CT; ++t) boff[t] = kTrans ? jc[t] * k_red + kq : kq * k_cols + jc[t];
-    const int steps = chunks * SPC;
-    auto bload = [&](int step, float (&b)[L][CT]) {   // B operands of one MFMA step
-      const int k = (step < steps ? step : steps - 1) * 4;   // wave-uniform; past the end: re-read the last step
-#pragma unroll
-      for (int l = 0; l < L; ++l) {
-        const float* base = kTrans ? W + static_cast<size_t>(l) * k_cols * k_red + k
-                                   : W + (static_cast<size_t>(l) * k_red + k) * k_cols;
-#pragma unroll
-        for (int t = 0; t < CT; ++t) b[l][t] = base[boff[t]];
+        for (int c = 0; c < NC; ++c) y[c] = acc[c][t][r];
+        store_row<float, NC>(Y + (static_cast<size_t>(n) * k_cols + jc[t]) * NC, y);
       }
-    };
-
-    V4 xr[4];
-    float b[2][L][CT];                         // B operands of the current and of the next step
-    __syncthreads();                           // the previous tile's reads of both buffers are done
-    gload(0, xr);
-    bload(0, b[0]);
-    stage(0, xr);
-    if (chunks > 1) gload(1, xr);
-    __syncthreads();
-    for (int c = 0; c < chunks; ++c) {
-      const float* abuf = ard + (c & 1) * 16 * kRowPad;
-#pragma unroll
-      for (int st = 0; st < SPC; ++st) {       // SPC is even: the roles of b[0] and b[1] repeat per chunk
-        bload(c * SPC + st + 1, b[(st + 1) & 1]);
-        const V4* p = reinterpret_cast<const V4*>(abuf + st * 4 * 16);
-        V4 a4[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) a4[i] = p[i];
-#pragma unroll
-        for (int cc = 0; cc < NC; ++cc)
-#pragma unroll
-          for (int t = 0; t < CT; ++t)
-            acc[cc][t] = Mma<float>::mma(a4[cc / 4][cc % 4], b[st & 1][order_of(cc)][t], acc[cc][t]);
-      }
-      if (c + 1 < chunks) {
-        stage((c + 1) & 1, xr);
-        if (c + 2 < chunks) gload(c + 2, xr);
-      }
-      __syncthreads();
     }
-#pragma unroll
-    for (int t = 0; t < CT; ++t)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int64_t n = n0 + Mma<float>::row(lane, r);
-        if (n < n_nodes) {
-          float y[NC];
-#pragma unroll
-          for (int c = 0; c < NC; ++c) y[c] = acc[c][t][r];
-          store_row<float, NC>(Y + (static_cast<size_t>(n) * k_cols + jc[t]) * NC, y);
-        }
-      }
-  }
+}
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_forward_lds_kernel(
+    int64_t n_nodes, int k_red, int k_cols, const float* __restrict__ X, const float* __restrict__ W,
+    float* __restrict__ Y) {
+  __shared__ __attribute__((aligned(16))) float xs[kBuffers * 16 * kRowPad];
+  const int groups = k_cols / 128;                       // full units per row tile
+  const UnitSchedule u = unit_schedule((n_nodes + 15) / 16 * groups, true);
+  if (u.has_half)
+    forward_lds_unit<1>(n_nodes, u.half_unit / groups * 16, static_cast<int>(u.half_unit % groups) * 2 + u.half, k_red,
+                        k_cols, X, W, Y, xs);
+  for (int64_t unit = blockIdx.x; unit < u.n_full; unit += gridDim.x)
+    forward_lds_unit<2>(n_nodes, unit / groups * 16, static_cast<int>(unit % groups) * 2, k_red, k_cols, X, W, Y, xs);
 }
 
 // Partial dW of a range of atoms: part[range][l][k][j] = sum_{n in range} sum_{m in l} X[n][k][c] dY[n][j][c].
@@ -406,6 +266,17 @@ __global__ void zero_kernel(unsigned int* p, size_t n_words) {
     p[i] = 0u;
 }
 
+// Wt[l][j][k] = W[l][k][j]: the dX product then reads its B operands along rows like the forward.
+template <typename T>
+__global__ void transpose_w_kernel(int n_l, int k_in, int k_out, const T* __restrict__ W, T* __restrict__ Wt) {
+  const int64_t idx = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
+  if (idx >= static_cast<int64_t>(n_l) * k_in * k_out) return;
+  const int k = static_cast<int>(idx % k_in);
+  const int j = static_cast<int>((idx / k_in) % k_out);
+  const int l = static_cast<int>(idx / (static_cast<int64_t>(k_in) * k_out));
+  Wt[idx] = W[(static_cast<size_t>(l) * k_in + k) * k_out + j];
+}
+
 // ---- host side
 struct DeviceGuard {
   int prev = -1;
@@ -462,29 +333,34 @@ int nodes_per_range(const el_config* cfg, int64_t n) {
 
 template <typename T, int LMAX, bool kTrans>
 hipError_t forward_l(int64_t n, int k_red, int k_cols, const void* X, const void* W, void* Y, hipStream_t stream) {
-  if (mfma_forward_ok(k_red, k_cols)) {
-    const unsigned grid = static_cast<unsigned>(std::min<int64_t>((n + 15) / 16, compute_units()));
-    if constexpr (sizeof(T) == 4 && LMAX == 3) {
-      if (k_cols % 128 == 0) {   // the LDS-staged variant: two workgroups fit a CU
-        const unsigned grid2 = static_cast<unsigned>(std::min<int64_t>((n + 15) / 16, 2 * compute_units()));
-        hipLaunchKernelGGL((mfma_forward_lds_kernel<kTrans>), dim3(grid2), dim3(kThreads), 0, stream, n, k_red, k_cols,
-                           static_cast<const float*>(X), static_cast<const float*>(W), static_cast<float*>(Y));
-        return hipGetLastError();
+  // The MFMA kernels read B operands along rows of W (the backward hands them W transposed).
+  if constexpr (!kTrans) {
+    if (mfma_forward_ok(k_red, k_cols)) {
+      const int64_t tiles = (n + 15) / 16;
+      const unsigned grid = static_cast<unsigned>(std::min<int64_t>(tiles, compute_units()));
+      // (the LDS-staged kernel addresses W through a buffer descriptor: its bytes must fit 31 bits)
+      if (sizeof(T) == 4 && LMAX == 3 && k_cols % 128 == 0 && static_cast<int64_t>(k_red) * k_cols < (int64_t(1) << 26)) {
+        if constexpr (sizeof(T) == 4 && LMAX == 3) {   // the LDS-staged variant: two workgroups fit a CU
+          const int64_t units = tiles * (k_cols / 128);
+          const unsigned grid2 = static_cast<unsigned>(std::min<int64_t>(units, 2 * compute_units()));
+          hipLaunchKernelGGL(mfma_forward_lds_kernel, dim3(grid2), dim3(kThreads), 0, stream, n, k_red, k_cols,
+                             static_cast<const float*>(X), static_cast<const float*>(W), static_cast<float*>(Y));
+        }
+      } else if (sizeof(T) == 4 && k_cols % 128 == 0) {
+        // two column tiles at a time when the accumulators fit (fp32 and at least two tiles per wave)
+        hipLaunchKernelGGL((mfma_forward_kernel<T, LMAX, 2>), dim3(grid), dim3(kThreads), 0, stream, n, k_red, k_cols,
+                           static_cast<const T*>(X), static_cast<const T*>(W), static_cast<T*>(Y));
+      } else {
+        hipLaunchKernelGGL((mfma_forward_kernel<T, LMAX, 1>), dim3(grid), dim3(kThreads), 0, stream, n, k_red, k_cols,
+                           static_cast<const T*>(X), static_cast<const T*>(W), static_cast<T*>(Y));
       }
+      return hipGetLastError();
     }
-    // two column tiles at a time when the accumulators fit (fp32 and at least two tiles per wave)
-    if (sizeof(T) == 4 && k_cols % 128 == 0)
-      hipLaunchKernelGGL((mfma_forward_kernel<T, LMAX, 2, kTrans>), dim3(grid), dim3(kThreads), 0, stream, n, k_red,
-                         k_cols, static_cast<const T*>(X), static_cast<const T*>(W), static_cast<T*>(Y));
-    else
-      hipLaunchKernelGGL((mfma_forward_kernel<T, LMAX, 1, kTrans>), dim3(grid), dim3(kThreads), 0, stream, n, k_red,
-                         k_cols, static_cast<const T*>(X), static_cast<const T*>(W), static_cast<T*>(Y));
-  } else {
-    const int64_t total = n * k_cols;
-    hipLaunchKernelGGL((plain_forward_kernel<T, kTrans>), dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,
-                       stream, n, k_red, k_cols, LMAX, static_cast<const T*>(X), static_cast<const T*>(W),
-                       static_cast<T*>(Y));
   }
+  const int64_t total = n * k_cols;
+  hipLaunchKernelGGL((plain_forward_kernel<T, kTrans>), dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,
+                     stream, n, k_red, k_cols, LMAX, static_cast<const T*>(X), static_cast<const T*>(W),
+                     static_cast<T*>(Y));
   return hipGetLastError();
 }
 
@@ -532,11 +408,21 @@ hipError_t dw_t(const el_config* cfg, int64_t n, const void* X, const void* dY, 
   }
 }
 
+// Workspace: [ W transposed, rounded up to 256 bytes ][ partial dW per range of atoms ].
+size_t wt_bytes(const el_config* cfg) {
+  if (!mfma_forward_ok(cfg->k_out, cfg->k_in)) return 0;   // the plain dX kernel reads W as it is
+  const size_t bytes = static_cast<size_t>(cfg->l_max + 1) * cfg->k_in * cfg->k_out * elem_size(cfg);
+  return (bytes + 255) / 256 * 256;
+}
+
 size_t workspace_bytes(const el_config* cfg, int64_t n) {
-  if (n == 0 || !mfma_dw_ok(cfg)) return 256;
-  const int per = nodes_per_range(cfg, n);
-  const int64_t ranges = (n + per - 1) / per;
-  const size_t bytes = static_cast<size_t>(ranges) * (cfg->l_max + 1) * cfg->k_in * cfg->k_out * elem_size(cfg);
+  if (n == 0) return 256;
+  size_t bytes = wt_bytes(cfg);
+  if (mfma_dw_ok(cfg)) {
+    const int per = nodes_per_range(cfg, n);
+    const int64_t ranges = (n + per - 1) / per;
+    bytes += static_cast<size_t>(ranges) * (cfg->l_max + 1) * cfg->k_in * cfg->k_out * elem_size(cfg);
+  }
   return (bytes + 255) / 256 * 256 + 256;
 }
 
@@ -595,13 +481,32 @@ sc_status el_backward(const el_config* cfg, int64_t n_nodes, const void* X, cons
   if (!workspace || workspace_bytes_given < workspace_bytes(cfg, n_nodes))
     return set_error(SC_ERR_WORKSPACE, "el_backward: workspace missing or smaller than el_workspace_bytes()");
   if (misaligned(workspace, 256)) return set_error(SC_ERR_WORKSPACE, "el_backward: workspace not 256-byte aligned");
-  // dX = dY times W transposed: reduction over the output channels, columns = input channels
-  hipError_t e = cfg->dtype == SC_F64
-                     ? forward_t<double, true>(cfg->l_max, n_nodes, cfg->k_out, cfg->k_in, dY, W, dX, stream)
-                     : forward_t<float, true>(cfg->l_max, n_nodes, cfg->k_out, cfg->k_in, dY, W, dX, stream);
+  // dX = dY times W transposed: reduction over the output channels, columns = input channels.  The MFMA
+  // kernels take W transposed once into the workspace (strided B operands cost a third more time).
+  hipError_t e;
+  if (mfma_forward_ok(cfg->k_out, cfg->k_in)) {
+    const int64_t elems = static_cast<int64_t>(cfg->l_max + 1) * cfg->k_in * cfg->k_out;
+    const unsigned tgrid = static_cast<unsigned>((elems + 255) / 256);
+    if (cfg->dtype == SC_F64)
+      hipLaunchKernelGGL((transpose_w_kernel<double>), dim3(tgrid), dim3(256), 0, stream, cfg->l_max + 1, cfg->k_in,
+                         cfg->k_out, static_cast<const double*>(W), static_cast<double*>(workspace));
+    else
+      hipLaunchKernelGGL((transpose_w_kernel<float>), dim3(tgrid), dim3(256), 0, stream, cfg->l_max + 1, cfg->k_in,
+                         cfg->k_out, static_cast<const float*>(W), static_cast<float*>(workspace));
+    e = hipGetLastError();
+    if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_backward: transpose launch: ") + hipGetErrorString(e));
+    e = cfg->dtype == SC_F64
+            ? forward_t<double, false>(cfg->l_max, n_nodes, cfg->k_out, cfg->k_in, dY, workspace, dX, stream)
+            : forward_t<float, false>(cfg->l_max, n_nodes, cfg->k_out, cfg->k_in, dY, workspace, dX, stream);
+  } else {
+    e = cfg->dtype == SC_F64
+            ? forward_t<double, true>(cfg->l_max, n_nodes, cfg->k_out, cfg->k_in, dY, W, dX, stream)
+            : forward_t<float, true>(cfg->l_max, n_nodes, cfg->k_out, cfg->k_in, dY, W, dX, stream);
+  }
   if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_backward: dX launch: ") + hipGetErrorString(e));
-  e = cfg->dtype == SC_F64 ? dw_t<double>(cfg, n_nodes, X, dY, dW, workspace, stream)
-                           : dw_t<float>(cfg, n_nodes, X, dY, dW, workspace, stream);
+  void* partials = static_cast<char*>(workspace) + wt_bytes(cfg);
+  e = cfg->dtype == SC_F64 ? dw_t<double>(cfg, n_nodes, X, dY, dW, partials, stream)
+                           : dw_t<float>(cfg, n_nodes, X, dY, dW, partials, stream);
   if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_backward: dW launch: ") + hipGetErrorString(e));
   return SC_OK;
 }

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "el.h")).read()
-    declared = set(re.findall(r"^sc_status\s+(el_\w+)\s*\(", header, flags=re.M))
+    declared = set(re.findall(r"^(?:sc_status|int32_t)\s+(el_\w+)\s*\(", header, flags=re.M))
     assert declared == set(el.EXPORTS)
     for name in declared:
         assert getattr(el.lib, name) is not None

@@ -1,0 +1,125 @@
+"""Parity of el_sc_forward (channel-mixing linear fused into the forward of the symmetric
+contraction, through the C ABI) with the chain of the two fp64 oracles
+B = contraction(linear(X, W_lin), z, W).  Covers the single-kernel path (fp32, generated 0e+1o
+kernel, K a multiple of 128) and the two-step path of every other plan.
+
+Tolerance of the composition: each of the two operations is held to 1e-5 (fp32; 1e-12 fp64)
+against its oracle on exact inputs.  B is a polynomial of degree <= 3 in A, so a relative error
+e_A in A shows up as at most 3 e_A in B (first order), next to the contraction's own 1e-5:
+the chain is held to (3 + 1) x the single-operation bar, same error measures."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import equivariant_linear as oel
+from oracle import symmetric_contraction as osc
+from paper_2504_10700_amd import workloads
+from gpu_util import F32_TOL, F64_TOL, rel_err_f32, rel_err_f64
+
+pytestmark = pytest.mark.gpu
+
+CHAIN = 4.0   # see the module docstring
+
+
+def check(name, got, ref, dtype):
+    err = rel_err_f32(got, ref) if dtype == "f32" else rel_err_f64(got, ref)
+    tol = CHAIN * (F32_TOL if dtype == "f32" else F64_TOL)
+    assert err <= tol, f"{name}: error {err:.3e} exceeds {tol:.1e}"
+    return err
+
+
+O01 = ((0, 1), (1, -1))
+O012 = ((0, 1), (1, -1), (2, 1))
+
+
+@pytest.fixture(scope="module")
+def mods():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2504_10700_amd import binding, el_binding
+    return binding, el_binding
+
+
+def run_case(mods, N, k_in, K, Z, l_max, nu_max, out, dtype, seed, expect_fused, z_mode="skewed", sample=None):
+    import torch
+    sc, el = mods
+    print(f"case N={N} k_in={k_in} K={K} Z={Z} l_max={l_max} nu={nu_max} out={out} {dtype}", flush=True)
+    sys.stdout.flush()
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if dtype == "f32" else torch.float64
+    wl = workloads.Workload("fused", N, Z, K, l_max, nu_max, out, dtype, seed, z_mode=z_mode)
+    T = osc.build_tables(osc.OracleConfig(K, l_max, nu_max, Z, out))
+    inp = workloads.make_inputs(wl, T.paths)
+    X, Wlin, _ = workloads.make_linear_inputs(N, k_in, K, l_max, seed + 1)
+    Xd, Wl = (torch.tensor(x, dtype=tdt, device=dev) for x in (X, Wlin))
+    W = torch.tensor(inp.W, dtype=tdt, device=dev)
+    z = torch.tensor(inp.z, dtype=torch.int32, device=dev)
+    plan = sc.sc_plan_create(K, l_max, nu_max, Z, out, sc.SC_F32 if dtype == "f32" else sc.SC_F64, 0)
+    try:
+        assert el.el_sc_is_fused(plan, k_in) == expect_fused
+        nbytes = el.el_sc_workspace_bytes(plan, k_in, N)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        B = torch.full((N, K, wl.n_LM), float("nan"), dtype=tdt, device=dev)
+        el.el_sc_forward(plan, k_in, N, Xd, Wl, z, W, B, ws, nbytes)
+        torch.cuda.synchronize()
+        B2 = torch.full_like(B, float("nan"))
+        el.el_sc_forward(plan, k_in, N, Xd, Wl, z, W, B2, ws, nbytes)
+        torch.cuda.synchronize()
+        assert torch.equal(B, B2), "not reproducible"
+    finally:
+        sc.sc_plan_destroy(plan)
+    X64, Wl64, W64 = (x.double().cpu().numpy() for x in (Xd, Wl, W))
+    got = B.cpu().numpy()
+    if sample is None:
+        ref = osc.forward(T, oel.forward(X64, Wl64), inp.z, W64)
+        check("B", got, ref, dtype)
+    else:
+        # full size: a sample of nodes one by one; the rms of the tolerance comes from the sample
+        idx = np.unique(np.concatenate([np.arange(16), np.arange(N - 17, N),
+                                        np.random.default_rng(seed).integers(0, N, sample)]))
+        ref = osc.forward(T, oel.forward(X64[idx], Wl64), inp.z[idx], W64)
+        check("B (sampled nodes)", got[idx], ref, dtype)
+        assert np.isfinite(got).all()
+
+
+def test_single_kernel_path_small(mods):
+    # 333 atoms: 20 full row tiles and a ragged one, all 89 elements mixed inside the tiles
+    run_case(mods, 333, 128, 128, 89, 3, 3, O01, "f32", 9001, True)
+
+
+@pytest.mark.parametrize("N", [1, 15, 16, 17])
+def test_single_kernel_path_tiny(mods, N):
+    run_case(mods, N, 128, 128, 3, 3, 3, O01, "f32", 9010 + N, True, z_mode="uniform")
+
+
+@pytest.mark.parametrize("k_in,K", [(64, 128), (256, 128), (128, 256), (16, 256)])
+def test_single_kernel_path_other_channel_counts(mods, k_in, K):
+    run_case(mods, 100, k_in, K, 7, 3, 3, O01, "f32", 9100 + k_in + K, True)
+
+
+def test_two_step_path(mods):
+    run_case(mods, 70, 128, 128, 5, 3, 3, O01, "f64", 9201, False)          # fp64
+    run_case(mods, 70, 128, 64, 5, 3, 3, O01, "f32", 9202, False)           # K not a multiple of 128
+    run_case(mods, 40, 24, 128, 5, 3, 3, O01, "f32", 9203, False)           # k_in not a multiple of 16
+    run_case(mods, 40, 64, 128, 4, 3, 3, O012, "f32", 9204, False)          # outputs with 2e
+    run_case(mods, 40, 8, 8, 2, 1, 2, ((0, 1),), "f64", 9205, False)        # the tiny configuration
+
+
+def test_full_size_sampled(mods):
+    run_case(mods, 10_000, 128, 128, 89, 3, 3, O01, "f32", 9301, True, sample=96)
+
+
+def test_empty_and_errors(mods):
+    import torch
+    sc, el = mods
+    plan = sc.sc_plan_create(128, 3, 3, 89, O01, sc.SC_F32, 0)
+    try:
+        el.el_sc_forward(plan, 128, 0, None, None, None, None, None, None, 0)
+        x = torch.zeros(16, device="cuda:0")
+        with pytest.raises(sc.ScError):
+            el.el_sc_forward(plan, 128, 4, x, x, x, x, x, None, 0)       # no workspace
+        with pytest.raises(sc.ScError):
+            el.el_sc_forward(plan, 0, 4, x, x, x, x, x, x, 64)           # k_in < 1
+    finally:
+        sc.sc_plan_destroy(plan)
