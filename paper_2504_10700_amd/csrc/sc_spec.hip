@@ -52,7 +52,11 @@ struct Row {
       Vec x;
 #pragma unroll
       for (int k = 0; k < V; ++k) x[k] = v[i + k];
-      *reinterpret_cast<Vec*>(p + i) = x;
+      // A row of one 16-byte piece makes the wave's store one contiguous KB: streamed past the
+      // cache (measured faster).  Longer rows are written by several instructions that each touch
+      // a part of every line: left to the L2 to merge (streaming them measured slower).
+      if constexpr (N * sizeof(T) == 16) __builtin_nontemporal_store(x, reinterpret_cast<Vec*>(p + i));
+      else *reinterpret_cast<Vec*>(p + i) = x;
     }
 #pragma unroll
     for (int i = N / V * V; i < N; ++i) p[i] = v[i];
@@ -66,7 +70,11 @@ struct Row {
 // (four times fewer, four times larger write requests to L2; measured -10% on the whole
 // backward kernel; the same trick on the loads of A gained nothing).  stage: 64*N elements
 // of LDS owned by this wave; block: where lane 0's row goes (16-byte aligned).
-template <typename T, int N>
+// kStream: non-temporal stores (the rows are not read again soon and each instruction writes
+// whole lines).  Measured: faster for B (forward 28 -> 25.5 us at 10k nodes, 437 -> 421 us at
+// 200k) and for the second-order outputs at every size, a wash for the backward's dA at 10k
+// nodes and 1% slower at 200k, so the backward leaves it off.
+template <typename T, int N, bool kStream = true>
 __device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* stage, int lane, const T (&v)[N]) {
   constexpr int V = 16 / sizeof(T);
   typedef T Vec __attribute__((ext_vector_type(V)));
@@ -92,7 +100,8 @@ __device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* s
     const int q = q0 + lane;
     if (q0 + kLanes <= kPieces || q < kPieces) {
       const Vec x = *reinterpret_cast<const Vec*>(stage + q * V);
-      *reinterpret_cast<Vec*>(block + q * V) = x;
+      if constexpr (kStream) __builtin_nontemporal_store(x, reinterpret_cast<Vec*>(block + q * V));
+      else *reinterpret_cast<Vec*>(block + q * V) = x;
     }
   }
 }
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
         Row<T, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
       }
       G::backward(a0, w, g0, da, dw);
-      store_rows_coalesced<T, G::kNlm>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da);
+      store_rows_coalesced<T, G::kNlm, false>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da);
       if (j + 1 < j1) {
         if (j + 2 < j1) {
           node0 = perm[j + 2];
@@ -195,7 +204,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int 
           Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
         }
         G::backward(a1, w, g1, da, dw);
-        store_rows_coalesced<T, G::kNlm>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da);
+        store_rows_coalesced<T, G::kNlm, false>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da);
       }
     }
   }
@@ -458,15 +467,15 @@ hipError_t bwd_launch(const sc_plan* plan, const void* A, const void* W, const v
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
   const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
+  auto kernel = &spec_backward_kernel<T, G>;
   if (lds > 64 * 1024) {  // above the default dynamic LDS limit: raise it for this kernel
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&spec_backward_kernel<T, G>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((spec_backward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
-                     plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
-                     static_cast<const T*>(W), static_cast<const T*>(dB), static_cast<T*>(dA),
-                     static_cast<T*>(ws.partial), ws.tiles, ws.perm);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpecThreads), lds, stream, plan->cfg.num_channels, shape.chblocks,
+                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(W), static_cast<const T*>(dB),
+                     static_cast<T*>(dA), static_cast<T*>(ws.partial), ws.tiles, ws.perm);
   return hipGetLastError();
 }
 

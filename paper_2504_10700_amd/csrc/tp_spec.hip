@@ -61,7 +61,11 @@ __device__ __forceinline__ void store_row(T* __restrict__ p, const T (&v)[N]) {
       Vec x;
 #pragma unroll
       for (int k = 0; k < V; ++k) x[k] = v[i + k];
-      *reinterpret_cast<Vec*>(p + i) = x;
+      // A row of one 16-byte piece makes the wave's store one contiguous KB: streamed past the
+      // cache (measured faster).  Longer rows are written by several instructions that each touch
+      // a part of every line: left to the L2 to merge (streaming them measured slower).
+      if constexpr (N * sizeof(T) == 16) __builtin_nontemporal_store(x, reinterpret_cast<Vec*>(p + i));
+      else *reinterpret_cast<Vec*>(p + i) = x;
     }
   } else {
 #pragma unroll
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
     G::backward(y, hh, r, g, dr, dy, dhe);
     T* out = dR + static_cast<size_t>(e) * G::kP * K + ch;
 #pragma unroll
-    for (int p = 0; p < G::kP; ++p) out[static_cast<size_t>(p) * K] = dr[p];
+    for (int p = 0; p < G::kP; ++p) __builtin_nontemporal_store(dr[p], out + static_cast<size_t>(p) * K);
     store_row<T, G::kNh>(dh_edge + (static_cast<size_t>(e) * K + ch) * G::kNh, dhe);
     lane_sum_store<T, G::kNY>(stage, lane, dy, dY_partial + (static_cast<size_t>(cb) * n_edges + e) * G::kNY);
   };
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void double_backward_kernel(
       G::double_backward(y, hy, hh, hx, r, hr, g, dda, d2r, d2y, d2h);
       T* out = d2R + static_cast<size_t>(e) * G::kP * K + ch;
 #pragma unroll
-      for (int p = 0; p < G::kP; ++p) out[static_cast<size_t>(p) * K] = d2r[p];
+      for (int p = 0; p < G::kP; ++p) __builtin_nontemporal_store(d2r[p], out + static_cast<size_t>(p) * K);
       store_row<T, G::kNh>(d2h_edge + (static_cast<size_t>(e) * K + ch) * G::kNh, d2h);
       lane_sum_store<T, G::kNY>(stage, lane, d2y, d2Y_partial + (static_cast<size_t>(cb) * n_edges + e) * G::kNY);
     };
