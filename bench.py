@@ -544,6 +544,60 @@ def measure_fused_forward(wl, steps=50, warmup=5):
                          "note": "flops of the matrix product only, duration of the whole call (fold + kernel)"}}
 
 
+def measure_graph_step(n_nodes=3072, steps=300, warmup=20):
+    """The paper's per-GPU batch (capacity 3072 atoms, Section 5) is launch-bound: contraction forward + backward
+    as eager calls and as one captured HIP graph (the entry points only enqueue kernels)."""
+    import torch
+    from paper_2504_10700_amd import binding as sc
+    from paper_2504_10700_amd import workloads
+
+    dev = torch.device("cuda:0")
+    base = workloads.WORKLOADS["training_step"]
+    wl = workloads.Workload("paper_batch", n_nodes, base.num_elements, base.num_channels, base.l_max, base.nu_max,
+                            base.out_irreps, "f32", 1007)
+    plan = sc.sc_plan_create(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps, sc.SC_F32, 0)
+    inp = workloads.make_inputs(wl, sc.sc_plan_paths(plan))
+    f = lambda x: torch.tensor(x, dtype=torch.float32, device=dev)
+    A, W, dB = f(inp.A), f(inp.W), f(inp.dB)
+    z = torch.tensor(inp.z, dtype=torch.int32, device=dev)
+    B = torch.empty((n_nodes, wl.num_channels, wl.n_LM), dtype=torch.float32, device=dev)
+    dA, dW = torch.empty_like(A), torch.empty_like(W)
+    nb = sc.sc_workspace_bytes(plan, n_nodes)
+    ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+
+    def step():
+        sc.sc_forward(plan, n_nodes, A, z, W, B, ws, nb)
+        sc.sc_backward(plan, n_nodes, A, z, W, dB, dA, dW, ws, nb, sc.SC_REUSE_GROUPING)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    t_eager = timed(step)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    t_graph = timed(graph.replay)
+    sc.sc_plan_destroy(plan)
+    return {"metric": METRIC, "value": n_nodes / t_graph, "unit": "nodes/s", "steps": steps, "warmup": warmup,
+            "ms_per_step": t_graph * 1e3, "dtype": "f32",
+            "config": {"workload": f"{n_nodes} nodes (the paper's batch capacity), otherwise training_step; "
+                                   "forward+backward replayed as one HIP graph, inputs resident in cache"},
+            "eager": {"value": n_nodes / t_eager, "ms_per_step": t_eager * 1e3}}
+
+
 def measure_balanced_batches(n_graphs=1_000_000, capacity=3072, n_gpus=8, oracle_sample=200_000):
     """Load balancer (host code): graphs/s of the C++ implementation, the oracle beside it."""
     import numpy as np
@@ -581,6 +635,8 @@ def main():
     ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
     ap.add_argument("--linear", action="store_true",
                     help="measure only the channel-mixing linear (10k nodes, 128 -> 128 channels, l <= 3)")
+    ap.add_argument("--graph", action="store_true",
+                    help="measure only the 3072-atom step as eager calls and as a replayed HIP graph")
     ap.add_argument("--fused", action="store_true",
                     help="measure only the forward of linear + contraction as one call (--workload)")
     ap.add_argument("--balanced-batches", action="store_true",
@@ -602,6 +658,9 @@ def main():
         return
     if args.linear:
         print(json.dumps(measure_linear()))
+        return
+    if args.graph:
+        print(json.dumps(measure_graph_step()))
         return
     if args.tp:
         name = args.workload if args.workload in workloads.TP_WORKLOADS else "tp_training_step"
@@ -634,6 +693,7 @@ def main():
             workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
         out["also"]["channel_mixing_linear"] = measure_linear()
         out["also"]["linear_plus_contraction_forward"] = measure_fused_forward(wl, 50, 5)
+        out["also"]["paper_batch_3072_atoms_graph"] = measure_graph_step()
         out["also"]["balanced_batches"] = measure_balanced_batches()
     print(json.dumps(out))
 
