@@ -66,7 +66,8 @@ sc_status el_backward(const el_config* cfg, int64_t n_nodes, const void* X, cons
  * the accumulators: A is never written (el_sc_is_fused returns 1).  Every other plan runs
  * el_forward into the workspace and then sc_forward, with the same result up to rounding.
  * workspace: device memory, 256-byte aligned, at least el_sc_workspace_bytes().  Same conventions
- * as sc_forward (stream, no synchronisation, z not range-checked); n_nodes == 0 does nothing. */
+ * as sc_forward (stream, no synchronisation); z is not validated: an index outside 0..Z-1 gives an
+ * undefined B row for that atom, never an access outside the buffers.  n_nodes == 0 does nothing. */
 int32_t el_sc_is_fused(const sc_plan* plan, int32_t k_in);
 sc_status el_sc_workspace_bytes(const sc_plan* plan, int32_t k_in, int64_t n_nodes, size_t* bytes);
 sc_status el_sc_forward(sc_plan* plan, int32_t k_in, int64_t n_nodes, const void* X, const void* W_lin,

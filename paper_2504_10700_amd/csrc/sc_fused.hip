@@ -57,19 +57,21 @@ __global__ __launch_bounds__(kLanes) void fold_table_kernel(int K, const float* 
 }
 
 template <int CT>
-__device__ __forceinline__ void fused_unit(int64_t n_nodes, int64_t n0, int g, int k_in, int K,
+__device__ __forceinline__ void fused_unit(int64_t n_nodes, int64_t n0, int g, int k_in, int K, int Z,
                                            const float* __restrict__ X, const float* __restrict__ Wlin,
                                            const int32_t* __restrict__ z, const float* __restrict__ wf,
                                            float* __restrict__ B, float* xs) {
   typedef float V4 __attribute__((ext_vector_type(4)));
   typedef el::Mma<float> M;
   const int lane = threadIdx.x & (kLanes - 1);
-  // elements of this lane's four atoms (rows past the end: element 0, nothing is stored)
+  // elements of this lane's four atoms (rows past the end: element 0, nothing is stored); an
+  // element index outside 0..Z-1 is clamped, so that it gives a wrong B row but no wild read
   int zr[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int64_t n = n0 + M::row(lane, r);
-    zr[r] = n < n_nodes ? z[n] : 0;
+    const int ze = n < n_nodes ? z[n] : 0;
+    zr[r] = ze < 0 ? 0 : ze >= Z ? Z - 1 : ze;
   }
   M::acc_t acc[16][CT];
   int jc[CT];
@@ -104,16 +106,16 @@ __device__ __forceinline__ void fused_unit(int64_t n_nodes, int64_t n0, int g, i
 }
 
 __global__ __launch_bounds__(el::kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(
-    int64_t n_nodes, int k_in, int K, const float* __restrict__ X, const float* __restrict__ Wlin,
+    int64_t n_nodes, int k_in, int K, int Z, const float* __restrict__ X, const float* __restrict__ Wlin,
     const int32_t* __restrict__ z, const float* __restrict__ wf, float* __restrict__ B) {
   __shared__ __attribute__((aligned(16))) float xs[el::kBuffers * 16 * el::kRowPad];
   const int groups = K / 128;                            // full units per row tile
   const el::UnitSchedule u = el::unit_schedule((n_nodes + 15) / 16 * groups, true);
   if (u.has_half)
-    fused_unit<1>(n_nodes, u.half_unit / groups * 16, static_cast<int>(u.half_unit % groups) * 2 + u.half, k_in, K, X,
-                  Wlin, z, wf, B, xs);
+    fused_unit<1>(n_nodes, u.half_unit / groups * 16, static_cast<int>(u.half_unit % groups) * 2 + u.half, k_in, K, Z,
+                  X, Wlin, z, wf, B, xs);
   for (int64_t unit = blockIdx.x; unit < u.n_full; unit += gridDim.x)
-    fused_unit<2>(n_nodes, unit / groups * 16, static_cast<int>(unit % groups) * 2, k_in, K, X, Wlin, z, wf, B, xs);
+    fused_unit<2>(n_nodes, unit / groups * 16, static_cast<int>(unit % groups) * 2, k_in, K, Z, X, Wlin, z, wf, B, xs);
 }
 
 bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
@@ -228,7 +230,7 @@ sc_status el_sc_forward(sc_plan* plan, int32_t k_in, int64_t n_nodes, const void
   if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_sc_forward: fold launch: ") + hipGetErrorString(e));
   const int64_t units = (n_nodes + 15) / 16 * (K / 128);
   const unsigned grid = static_cast<unsigned>(std::min<int64_t>(units, 2 * static_cast<int64_t>(plan->num_cus)));
-  hipLaunchKernelGGL(fused_forward_kernel, dim3(grid), dim3(el::kThreads), 0, stream, n_nodes, k_in, K,
+  hipLaunchKernelGGL(fused_forward_kernel, dim3(grid), dim3(el::kThreads), 0, stream, n_nodes, k_in, K, Z,
                      static_cast<const float*>(X), static_cast<const float*>(W_lin), z, wf, static_cast<float*>(B));
   e = hipGetLastError();
   if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("el_sc_forward: kernel launch: ") + hipGetErrorString(e));

@@ -123,3 +123,34 @@ def test_empty_and_errors(mods):
             el.el_sc_forward(plan, 0, 4, x, x, x, x, x, x, 64)           # k_in < 1
     finally:
         sc.sc_plan_destroy(plan)
+
+
+def test_element_index_out_of_range_is_clamped(mods):
+    """z is not validated, but the kernel clamps it: the rows of the other atoms are unaffected and
+    nothing outside the buffers is touched (the clamped rows equal those of elements 0 / Z-1)."""
+    import torch
+    sc, el = mods
+    dev = torch.device("cuda:0")
+    N, K, Z = 100, 128, 5
+    wl = workloads.Workload("fused_z", N, Z, K, 3, 3, O01, "f32", 9401, z_mode="uniform")
+    plan = sc.sc_plan_create(K, 3, 3, Z, O01, sc.SC_F32, 0)
+    try:
+        inp = workloads.make_inputs(wl, sc.sc_plan_paths(plan))
+        X, Wlin, _ = workloads.make_linear_inputs(N, K, K, 3, 9402)
+        f = lambda x: torch.tensor(x, dtype=torch.float32, device=dev)
+        Xd, Wl, W = f(X), f(Wlin), f(inp.W)
+        bad = inp.z.copy()
+        bad[[3, 40]] = [-7, Z + 1000]
+        good = inp.z.copy()
+        good[[3, 40]] = [0, Z - 1]
+        nbytes = el.el_sc_workspace_bytes(plan, K, N)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        out = []
+        for zz in (bad, good):
+            B = torch.full((N, K, 4), float("nan"), device=dev)
+            el.el_sc_forward(plan, K, N, Xd, Wl, torch.tensor(zz, dtype=torch.int32, device=dev), W, B, ws, nbytes)
+            torch.cuda.synchronize()
+            out.append(B)
+        assert torch.equal(out[0], out[1])
+    finally:
+        sc.sc_plan_destroy(plan)
