@@ -209,14 +209,160 @@ __global__ __launch_bounds__(kThreads) void mfma_dw_kernel(int64_t n_nodes, int 
         out[(static_cast<size_t>(l) * k_in + kt + Mma<T>::row(lane, r)) * k_out + j0 + t * 16] = acc[l][t][r];
 }
 
-// dW[idx] = sum over the ranges, in range order.
+// The same partial dW for fp32, l_max = 3 and k_in a multiple of 128, with more reuse per loaded
+// byte: the workgroup owns 128 input channels x 64 output channels (wave w: two row tiles, 32
+// input channels, against all four column tiles: 32 accumulator blocks), the dY rows of a
+// reduction step (4 atoms x 64 channels x 64 B = 16 KB) are loaded once per workgroup and shared
+// through LDS (two buffers, rows padded to 80 B against bank conflicts), X rows come straight from
+// global memory; both are requested one step ahead.  Per MFMA a wave reads 96 B instead of 320 B.
+// One workgroup per CU (the accumulators and two operand sets fill the register file).
+constexpr int kDwRow = 20;   // floats per (atom, output channel) row of dY in LDS
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void mfma_dw_lds_kernel(
+    int64_t n_nodes, int nodes_per_range, int k_in, int k_out, const float* __restrict__ X,
+    const float* __restrict__ dY, float* __restrict__ part) {
+  constexpr int NC = 16, L = 4, NT = 4, NU = 2;
+  typedef Mma<float>::acc_t acc_t;
+  typedef float V4 __attribute__((ext_vector_type(4)));
+  __shared__ __attribute__((aligned(16))) float ys[2][4 * 64 * kDwRow];
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  const int jgroups = k_out / 64, kgroups = k_in / 128;
+  const int jg = blockIdx.x % jgroups;
+  const int kg = (blockIdx.x / jgroups) % kgroups;
+  const int64_t range = blockIdx.x / (jgroups * kgroups);
+  const int64_t r0 = range * nodes_per_range;
+  const int64_t r1 = (r0 + nodes_per_range < n_nodes) ? r0 + nodes_per_range : n_nodes;
+  const int steps = static_cast<int>((r1 - r0 + 3) / 4);
+  const int kt = kg * 128 + wave * 32;                       // first input channel of this wave
+  const int j0 = jg * 64;                                    // first output channel of the workgroup
+  const int la = lane / 16;                                  // this lane's atom within a reduction step
+  // staging role of this thread: atom tid/64 of the step, output channel tid%64 of the group
+  const int sa = threadIdx.x / 64, sj = threadIdx.x % 64;
+  float* const swr = &ys[0][(sa * 64 + sj) * kDwRow];
+  const float* const brd = &ys[0][(la * 64 + (lane & 15)) * kDwRow];   // column tile 0, this lane's row
+
+  acc_t acc[L][NU][NT];
+#pragma unroll
+  for (int l = 0; l < L; ++l)
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) acc[l][u][t] = acc_t{0, 0, 0, 0};
+
+  // rows past the end of the range: a valid atom's address, A operands zeroed
+  auto aload = [&](int step, V4 (&a)[NU][4]) {
+    const int64_t n = r0 + step * 4 + la;
+    const int64_t nc = n < r1 ? n : r1 - 1;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const V4* p = reinterpret_cast<const V4*>(X + (static_cast<size_t>(nc) * k_in + kt + u * 16 + (lane & 15)) * NC);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[u][i] = n < r1 ? p[i] : V4{0, 0, 0, 0};
+    }
+  };
+  auto yload = [&](int step, V4 (&y)[4]) {
+    const int64_t n = r0 + step * 4 + sa;
+    const int64_t nc = n < r1 ? n : r1 - 1;
+    const V4* p = reinterpret_cast<const V4*>(dY + (static_cast<size_t>(nc) * k_out + j0 + sj) * NC);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) y[i] = p[i];
+  };
+  auto ystage = [&](int buf, const V4 (&y)[4]) {
+    V4* p = reinterpret_cast<V4*>(swr + buf * 4 * 64 * kDwRow);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[i] = y[i];
+  };
+  auto multiply = [&](int buf, const V4 (&a)[NU][4]) {
+    const float* bb = brd + buf * 4 * 64 * kDwRow;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {             // a quarter of the components at a time
+      V4 b[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) b[t] = *reinterpret_cast<const V4*>(bb + t * 16 * kDwRow + q * 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)             // component c = 4 q + i; consecutive MFMAs use different accumulators
+#pragma unroll
+        for (int u = 0; u < NU; ++u)
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[order_of(4 * q + i)][u][t] = Mma<float>::mma(a[u][q][i], b[t][i], acc[order_of(4 * q + i)][u][t]);
+    }
+  };
+
+  if (steps > 0) {
+    V4 a[2][NU][4], yr[4];
+    aload(0, a[0]);
+    yload(0, yr);
+    ystage(0, yr);
+    __syncthreads();
+    for (int s = 0; s < steps; s += 2) {
+      // even step: operands in a[0] and buffer 0; the next step's are requested first
+      if (s + 1 < steps) {
+        aload(s + 1, a[1]);
+        yload(s + 1, yr);
+      }
+      multiply(0, a[0]);
+      if (s + 1 < steps) ystage(1, yr);
+      __syncthreads();
+      if (s + 1 < steps) {                    // odd step (uniform branch)
+        if (s + 2 < steps) {
+          aload(s + 2, a[0]);
+          yload(s + 2, yr);
+        }
+        multiply(1, a[1]);
+        if (s + 2 < steps) ystage(0, yr);
+        __syncthreads();
+      }
+    }
+  }
+  float* out = part + static_cast<size_t>(range) * L * k_in * k_out;
+#pragma unroll
+  for (int l = 0; l < L; ++l)
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          out[(static_cast<size_t>(l) * k_in + kt + u * 16 + Mma<float>::row(lane, r)) * k_out + j0 + t * 16 + (lane & 15)] =
+              acc[l][u][t][r];
+}
+
+// dW[i] = sum of part[r][i] over the ranges r.  A workgroup of four waves owns 64 elements; wave
+// q adds the q-th quarter of the ranges (eight independent loads in flight, partial sums
+// combined in a fixed tree), the four quarter sums are added in wave order: a fixed order
+// altogether, so the result is bitwise reproducible.
 template <typename T>
-__global__ void dw_reduce_kernel(int64_t n_elems, int n_ranges, const T* __restrict__ part, T* __restrict__ dW) {
-  const int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
-  if (i >= n_elems) return;
-  T s = T(0);
-  for (int r = 0; r < n_ranges; ++r) s += part[static_cast<size_t>(r) * n_elems + i];
-  dW[i] = s;
+__global__ __launch_bounds__(256) void dw_reduce_kernel(int64_t n_elems, int n_ranges, const T* __restrict__ part,
+                                                        T* __restrict__ dW) {
+  __shared__ T quarter[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int64_t i = blockIdx.x * int64_t(64) + lane;
+  const int ra = n_ranges * q / 4, rb = n_ranges * (q + 1) / 4;
+  constexpr int U = 8;
+  T a[U];
+#pragma unroll
+  for (int k = 0; k < U; ++k) a[k] = T(0);
+  if (i < n_elems) {
+    const T* src = part + i;
+    int r = ra;
+    for (; r + U <= rb; r += U) {
+      T v[U];
+#pragma unroll
+      for (int k = 0; k < U; ++k) v[k] = src[static_cast<size_t>(r + k) * n_elems];
+#pragma unroll
+      for (int k = 0; k < U; ++k) a[k] += v[k];
+    }
+    for (; r < rb; ++r) a[0] += src[static_cast<size_t>(r) * n_elems];
+  }
+#pragma unroll
+  for (int w = U / 2; w >= 1; w /= 2)
+#pragma unroll
+    for (int k = 0; k < w; ++k) a[k] += a[k + w];
+  quarter[q][lane] = a[0];
+  __syncthreads();
+  if (q == 0 && i < n_elems) dW[i] = ((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane];
 }
 
 // ---- plain vector kernels for channel counts the MFMA tiling does not cover (fp64 accumulation)
@@ -322,9 +468,12 @@ int compute_units() {
 bool mfma_forward_ok(int k_red, int k_cols) { return k_red % (4 * kDepth) == 0 && k_cols % 64 == 0; }
 bool mfma_dw_ok(const el_config* c) { return c->k_in % 64 == 0 && c->k_out % 64 == 0; }
 
+// Is the LDS-staged dW kernel the one for this configuration?
+bool dw_lds_ok(const el_config* c) { return c->dtype == SC_F32 && c->l_max == 3 && c->k_in % 128 == 0 && c->k_out % 64 == 0; }
+
 // Atoms per range of the dW kernel: enough ranges to fill the chip about once, a multiple of 4.
 int nodes_per_range(const el_config* cfg, int64_t n) {
-  const int groups = (cfg->k_in / 64) * (cfg->k_out / 64);
+  const int groups = (dw_lds_ok(cfg) ? cfg->k_in / 128 : cfg->k_in / 64) * (cfg->k_out / 64);
   int64_t ranges = std::max<int64_t>(1, 256 / std::max(1, groups));
   int64_t per = (n + ranges - 1) / ranges;
   per = std::max<int64_t>(16, (per + 3) / 4 * 4);
@@ -387,12 +536,22 @@ hipError_t dw_l(const el_config* cfg, int64_t n, const void* X, const void* dY, 
   }
   const int per = nodes_per_range(cfg, n);
   const int ranges = static_cast<int>((n + per - 1) / per);
+  if constexpr (sizeof(T) == 4 && LMAX == 3) {
+    if (dw_lds_ok(cfg)) {
+      const unsigned grid = static_cast<unsigned>(static_cast<int64_t>(ranges) * (cfg->k_in / 128) * (cfg->k_out / 64));
+      hipLaunchKernelGGL(mfma_dw_lds_kernel, dim3(grid), dim3(kThreads), 0, stream, n, per, cfg->k_in, cfg->k_out,
+                         static_cast<const float*>(X), static_cast<const float*>(dY), static_cast<float*>(ws));
+      hipLaunchKernelGGL((dw_reduce_kernel<T>), dim3(static_cast<unsigned>((elems + 63) / 64)), dim3(256), 0, stream,
+                         elems, ranges, static_cast<const T*>(ws), static_cast<T*>(dW));
+      return hipGetLastError();
+    }
+  }
   // column tiles per workgroup: the accumulators (orders x tiles x 4 values) must fit the registers
   constexpr int NT = sizeof(T) == 4 ? 4 : 2;
   const unsigned grid = static_cast<unsigned>(static_cast<int64_t>(ranges) * (cfg->k_in / 64) * (cfg->k_out / (16 * NT)));
   hipLaunchKernelGGL((mfma_dw_kernel<T, LMAX, NT>), dim3(grid), dim3(kThreads), 0, stream, n, per, cfg->k_in,
                      cfg->k_out, static_cast<const T*>(X), static_cast<const T*>(dY), static_cast<T*>(ws));
-  hipLaunchKernelGGL((dw_reduce_kernel<T>), dim3(static_cast<unsigned>((elems + 255) / 256)), dim3(256), 0, stream, elems,
+  hipLaunchKernelGGL((dw_reduce_kernel<T>), dim3(static_cast<unsigned>((elems + 63) / 64)), dim3(256), 0, stream, elems,
                      ranges, static_cast<const T*>(ws), static_cast<T*>(dW));
   return hipGetLastError();
 }
