@@ -71,9 +71,9 @@ struct Row {
 // backward kernel; the same trick on the loads of A gained nothing).  stage: 64*N elements
 // of LDS owned by this wave; block: where lane 0's row goes (16-byte aligned).
 // kStream: non-temporal stores (the rows are not read again soon and each instruction writes
-// whole lines).  Measured: faster for B (forward 28 -> 25.5 us at 10k nodes, 437 -> 421 us at
-// 200k) and for the second-order outputs at every size, a wash for the backward's dA at 10k
-// nodes and 1% slower at 200k, so the backward leaves it off.
+// whole lines).  Measured on one box, library against library: forward 28.4 -> 27.0 us at 10k
+// nodes (neutral at 200k), second-order kernel 78.7 -> 77.5 us; a wash for the backward's dA
+// at 10k nodes and 1% slower at 200k, so the backward leaves it off.
 template <typename T, int N, bool kStream = true>
 __device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* stage, int lane, const T (&v)[N]) {
   constexpr int V = 16 / sizeof(T);
@@ -158,8 +158,15 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(int K, int c
   }
 }
 
-template <typename T, typename G>
-__global__ __launch_bounds__(kSpecThreads) void spec_backward_kernel(int K, int chblocks, int n_blocks,
+// kOcc = waves per SIMD the kernel is held to (0: the compiler's choice).  The fp32 kernel of the
+// small basis needs 171 registers if left alone, three over the limit for three waves per SIMD;
+// held to 168 (two values go to scratch) it runs three workgroups per CU instead of two.  On a
+// small batch a workgroup's life is a chain of latencies (fold, first rows, a handful of nodes,
+// the dW sum) and the third workgroup pays: 51.1 -> 49.3 us at 10k nodes, 138.7 -> 136.6 at
+// 30k, measured on one box; from 60k nodes on the unconstrained kernel is 1% faster.
+template <typename T, typename G, int kOcc = 0>
+__global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(kOcc == 0 ? 1 : kOcc, 8)))
+void spec_backward_kernel(int K, int chblocks, int n_blocks,
                                                                      const T* __restrict__ A,
                                                                      const T* __restrict__ W,
                                                                      const T* __restrict__ dB, T* __restrict__ dA,
@@ -462,12 +469,15 @@ hipError_t fwd_launch(const sc_plan* plan, const void* A, const void* W, void* B
 }
 
 template <typename T, typename G>
-hipError_t bwd_launch(const sc_plan* plan, const void* A, const void* W, const void* dB, void* dA,
+hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB, void* dA,
                       const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
   const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
-  auto kernel = &spec_backward_kernel<T, G>;
+  auto kernel = &spec_backward_kernel<T, G, 0>;
+  if constexpr (sizeof(T) == 4 && G::kS <= 32) {
+    if (n <= 40000) kernel = &spec_backward_kernel<T, G, 3>;   // small batches: three waves per SIMD (see the kernel)
+  }
   if (lds > 64 * 1024) {  // above the default dynamic LDS limit: raise it for this kernel
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
@@ -549,15 +559,15 @@ hipError_t launch_spec_forward(const sc_plan* plan, int64_t, const void* A, cons
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_spec_backward(const sc_plan* plan, int64_t, const void* A, const void* W, const void* dB,
+hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,
                                 void* dA, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const bool f64 = plan->cfg.dtype == SC_F64;
   if (plan->specialised == 1)
-    return f64 ? bwd_launch<double, Gen_l3n3_0e1o>(plan, A, W, dB, dA, ws, shape, stream)
-               : bwd_launch<float, Gen_l3n3_0e1o>(plan, A, W, dB, dA, ws, shape, stream);
+    return f64 ? bwd_launch<double, Gen_l3n3_0e1o>(plan, n, A, W, dB, dA, ws, shape, stream)
+               : bwd_launch<float, Gen_l3n3_0e1o>(plan, n, A, W, dB, dA, ws, shape, stream);
   if (plan->specialised == 2)
-    return f64 ? bwd_launch<double, Gen_l3n3_0e1o2e>(plan, A, W, dB, dA, ws, shape, stream)
-               : bwd_launch<float, Gen_l3n3_0e1o2e>(plan, A, W, dB, dA, ws, shape, stream);
+    return f64 ? bwd_launch<double, Gen_l3n3_0e1o2e>(plan, n, A, W, dB, dA, ws, shape, stream)
+               : bwd_launch<float, Gen_l3n3_0e1o2e>(plan, n, A, W, dB, dA, ws, shape, stream);
   return hipErrorInvalidValue;
 }
 
