@@ -27,6 +27,8 @@
 namespace el {
 namespace {
 
+using sc::DeviceGuard;
+using sc::misaligned;
 using sc::set_error;
 
 // Y[n][j][c] = sum_k X[n][k][c] * W[l(c)][k][j], W is [L][k_red][k_cols] (the dX product of the
@@ -424,20 +426,7 @@ __global__ void transpose_w_kernel(int n_l, int k_in, int k_out, const T* __rest
 }
 
 // ---- host side
-struct DeviceGuard {
-  int prev = -1;
-  bool ok = false;
-  explicit DeviceGuard(int device) {
-    if (hipGetDevice(&prev) != hipSuccess) return;
-    ok = (prev == device) || hipSetDevice(device) == hipSuccess;
-    if (prev == device) prev = -1;
-  }
-  ~DeviceGuard() {
-    if (prev >= 0) (void)hipSetDevice(prev);
-  }
-};
 
-bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
 size_t elem_size(const el_config* c) { return c->dtype == SC_F64 ? 8 : 4; }
 
 sc_status check_config(const char* fn, const el_config* cfg, int64_t n) {

@@ -10,6 +10,10 @@
 
 namespace {
 
+using sc::align_up;
+using sc::DeviceGuard;
+using sc::misaligned;
+
 thread_local std::string g_last_error;
 
 sc_status fail(sc_status code, const std::string& msg) {
@@ -21,22 +25,6 @@ sc_status fail_hip(hipError_t e, const char* what) {
   return fail(SC_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-// Makes `device` current for the lifetime of the guard.
-struct DeviceGuard {
-  int prev = -1;
-  bool ok = false;
-  explicit DeviceGuard(int device) {
-    if (hipGetDevice(&prev) != hipSuccess) return;
-    ok = (prev == device) || hipSetDevice(device) == hipSuccess;
-    if (prev == device) prev = -1;
-  }
-  ~DeviceGuard() {
-    if (prev >= 0) (void)hipSetDevice(prev);
-  }
-};
-
 __global__ void fill_zero_kernel(unsigned int* p, size_t n_words) {
   for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n_words;
        i += static_cast<size_t>(gridDim.x) * blockDim.x)
@@ -45,7 +33,6 @@ __global__ void fill_zero_kernel(unsigned int* p, size_t n_words) {
 
 size_t elem_size(const sc_plan* plan) { return plan->cfg.dtype == SC_F64 ? 8 : 4; }
 
-bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
 
 }  // namespace
 

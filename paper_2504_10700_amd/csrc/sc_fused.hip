@@ -118,20 +118,7 @@ __global__ __launch_bounds__(el::kThreads) __attribute__((amdgpu_waves_per_eu(2,
     fused_unit<2>(n_nodes, unit / groups * 16, static_cast<int>(unit % groups) * 2, k_in, K, Z, X, Wlin, z, wf, B, xs);
 }
 
-bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
 
-struct DeviceGuard {
-  int prev = -1;
-  bool ok = false;
-  explicit DeviceGuard(int device) {
-    if (hipGetDevice(&prev) != hipSuccess) return;
-    ok = (prev == device) || hipSetDevice(device) == hipSuccess;
-    if (prev == device) prev = -1;
-  }
-  ~DeviceGuard() {
-    if (prev >= 0) (void)hipSetDevice(prev);
-  }
-};
 
 // Does the fused kernel serve this plan and this number of input channels?
 bool fused_ok(const sc_plan* plan, int k_in) {

@@ -75,6 +75,24 @@ struct sc_plan {
 
 namespace sc {
 
+// Makes `device` the current HIP device for the lifetime of the object and restores the caller's
+// device afterwards; ok is false if that failed.
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int device) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == device) || hipSetDevice(device) == hipSuccess;
+    if (prev == device) prev = -1;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
+
 // Records the calling thread's error message (what sc_last_error returns) and returns code.
 sc_status set_error(sc_status code, const std::string& msg);
 

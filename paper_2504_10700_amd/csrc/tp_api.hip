@@ -9,29 +9,18 @@
 
 namespace {
 
+using sc::align_up;
+using sc::DeviceGuard;
+using sc::misaligned;
 using sc::set_error;
 
 sc_status fail_hip(hipError_t e, const char* what) {
   return set_error(SC_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
 size_t elem_size(const tp_plan* plan) { return plan->cfg.dtype == SC_F64 ? 8 : 4; }
 int chblocks_of(const tp_plan* plan) { return (plan->cfg.num_channels + sc::kLanes - 1) / sc::kLanes; }
 
-struct DeviceGuard {
-  int prev = -1;
-  bool ok = false;
-  explicit DeviceGuard(int device) {
-    if (hipGetDevice(&prev) != hipSuccess) return;
-    ok = (prev == device) || hipSetDevice(device) == hipSuccess;
-    if (prev == device) prev = -1;
-  }
-  ~DeviceGuard() {
-    if (prev >= 0) (void)hipSetDevice(prev);
-  }
-};
 
 sc_status check_sizes(const char* fn, const tp_plan* plan, int64_t n_in, int64_t n_out, int64_t n_edges) {
   if (!plan) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": plan is NULL");
