@@ -127,22 +127,13 @@ __device__ __forceinline__ void forward_lds_unit(int64_t n_nodes, int64_t n0, in
                                                  const float* __restrict__ X, const float* __restrict__ W,
                                                  float* __restrict__ Y, float* xs) {
   constexpr int NC = 16;
-  const int lane = threadIdx.x & (kLanes - 1);
   Mma<float>::acc_t acc[NC][CT];
   int jc[CT];
   lds_tile_product<CT>(n_nodes, n0, g, k_red, k_cols, X, W, xs, acc, jc);
-#pragma unroll
-  for (int t = 0; t < CT; ++t)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int64_t n = n0 + Mma<float>::row(lane, r);
-      if (n < n_nodes) {
-        float y[NC];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) y[c] = acc[c][t][r];
-        store_row<float, NC>(Y + (static_cast<size_t>(n) * k_cols + jc[t]) * NC, y);
-      }
-    }
+  // (the product ends with a workgroup barrier: its buffers are free for the store stages)
+  static_assert(kWaves * kStoreStageFloats <= kBuffers * 16 * kRowPad, "the store stages reuse the product's buffers");
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+  store_tile_coalesced<CT>(Y, n_nodes, n0, k_cols, jc, acc, xs + wave * kStoreStageFloats);
 }
 
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_forward_lds_kernel(

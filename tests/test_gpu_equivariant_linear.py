@@ -38,10 +38,11 @@ def run_case(el, N, k_in, k_out, l_max, dtype, seed):
     el.el_backward(cfg, N, Xd, Wd, dYd, dX, dW, ws, nbytes)
     torch.cuda.synchronize()
     X64, W64, dY64 = (x.double().cpu().numpy() for x in (Xd, Wd, dYd))
-    check("Y", Y.cpu().numpy(), oel.forward(X64, W64), dtype)
+    errs = [check("Y", Y.cpu().numpy(), oel.forward(X64, W64), dtype)]
     dX_ref, dW_ref = oel.backward(X64, W64, dY64)
-    check("dX", dX.cpu().numpy(), dX_ref, dtype)
-    check("dW", dW.cpu().numpy(), dW_ref, dtype)
+    errs.append(check("dX", dX.cpu().numpy(), dX_ref, dtype))
+    errs.append(check("dW", dW.cpu().numpy(), dW_ref, dtype))
+    print("  errors Y, dX, dW: " + ", ".join(f"{e:.2e}" for e in errs), flush=True)
     Y2, dX2, dW2 = torch.empty_like(Y), torch.empty_like(dX), torch.empty_like(dW)
     el.el_forward(cfg, N, Xd, Wd, Y2)
     el.el_backward(cfg, N, Xd, Wd, dYd, dX2, dW2, ws, nbytes)
