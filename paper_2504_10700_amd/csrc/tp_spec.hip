@@ -123,12 +123,43 @@ __device__ __forceinline__ void lane_sum_store(T* stage, int lane, const T (&dy)
   if (q == 0 && a < N) out[a] = s;
 }
 
+// Store of a wave's rows (N elements per lane, lane rows N elements apart = one contiguous block
+// of 64*N elements) as whole lines: every lane's row goes through an LDS block of the same
+// layout and comes back so that store instruction k writes the k-th contiguous KB of the block
+// instead of 64 pieces of 16 bytes (partial lines, N*sizeof(T)/16 times the write requests);
+// streamed past the cache.  stage: 64*N elements of LDS owned by this wave; block: where lane
+// 0's row goes (16-byte aligned).  N*sizeof(T) is a multiple of 16.
+template <typename T, int N>
+__device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* stage, int lane, const T (&v)[N]) {
+  constexpr int V = 16 / sizeof(T);
+  static_assert(N % V == 0, "rows are whole 16-byte pieces");
+  typedef T Vec __attribute__((ext_vector_type(V)));
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // earlier reads of the stage are done
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int j = 0; j < N / V; ++j) {
+    Vec x;
+#pragma unroll
+    for (int k = 0; k < V; ++k) x[k] = v[j * V + k];
+    *reinterpret_cast<Vec*>(stage + lane * N + j * V) = x;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the other lanes' pieces are visible
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int q0 = 0; q0 < kLanes * N / V; q0 += kLanes) {
+    const int q = q0 + lane;
+    const Vec x = *reinterpret_cast<const Vec*>(stage + q * V);
+    __builtin_nontemporal_store(x, reinterpret_cast<Vec*>(block + q * V));
+  }
+}
+
 template <typename T, typename G>
 __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, int64_t n_units,
                                                            const T* __restrict__ Y, const T* __restrict__ h,
                                                            const T* __restrict__ R,
                                                            const int32_t* __restrict__ sender,
                                                            const int32_t* __restrict__ row_ptr, T* __restrict__ A) {
+  __shared__ __attribute__((aligned(16))) T out_stage[kWaves][kLanes * G::kNout];
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = uniform(threadIdx.x / kLanes);
   const int64_t unit = xcd_contiguous_block() * kWaves + wave;
@@ -165,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, 
       }
     }
   }
-  store_row<T, G::kNout>(A + (node * K + ch) * G::kNout, acc);
+  store_rows_coalesced<T, G::kNout>(A + (node * K + cb * kLanes) * G::kNout, out_stage[wave], lane, acc);
 }
 
 // dR of every edge, this channel block's partial of dY and the edge's share of dh; walks the
