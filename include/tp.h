@@ -30,9 +30,11 @@
  * Conventions: as in sc.h (device pointers for tensors and index arrays, dense row-major,
  * 16-byte aligned tensors, 4-byte aligned index arrays; calls enqueue on the given HIP
  * stream and never synchronise; outputs are overwritten; errors by return code with
- * sc_last_error()).  Index arrays are NOT validated on the device: sender values
- * outside [0, n_nodes_in), a row_ptr that is not ascending from 0 to n_edges, or a send_edge
- * that is not a permutation of the edge ids give undefined results.
+ * sc_last_error()).  Index arrays are not validated (they live on the device and the calls do
+ * not synchronise): sender values outside [0, n_nodes_in), a row_ptr that is not ascending
+ * from 0 to n_edges, or a send_edge that is not a permutation of the edge ids give undefined
+ * VALUES; every index is clamped into its range where the kernels read it, so such a list never
+ * makes them touch memory outside the buffers.
  * No entry point allocates; no workspace is needed except for tp_backward (see there).
  */
 #ifndef TP_MI355X_H

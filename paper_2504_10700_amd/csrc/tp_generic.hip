@@ -25,8 +25,7 @@ template <typename T>
 __global__ __launch_bounds__(kLanes) void generic_forward_kernel(TermTable tab, int K, int chblocks,
                                                                  const T* __restrict__ Y, const T* __restrict__ h,
                                                                  const T* __restrict__ R,
-                                                                 const int32_t* __restrict__ sender,
-                                                                 const int32_t* __restrict__ row_ptr,
+                                                                 const EdgeList el,
                                                                  T* __restrict__ A) {
   extern __shared__ unsigned char lds_raw[];
   double* sH = reinterpret_cast<double*>(lds_raw);  // [n_h][64]
@@ -38,9 +37,9 @@ __global__ __launch_bounds__(kLanes) void generic_forward_kernel(TermTable tab, 
   const int ch = cb * kLanes + lane;
   const bool active = ch < K;
   for (int c = 0; c < tab.n_out; ++c) sA[c * kLanes + lane] = 0.0;
-  const int e0 = row_ptr[node], e1 = row_ptr[node + 1];
+  const int e0 = el.first(node), e1 = el.first(node + 1);
   for (int e = e0; e < e1; ++e) {
-    const size_t j = sender[e];
+    const size_t j = el.snd(e);
     for (int b = 0; b < tab.n_h; ++b) sH[b * kLanes + lane] = active ? static_cast<double>(h[(j * K + ch) * tab.n_h + b]) : 0.0;
     for (int p = 0; p < tab.num_paths; ++p)
       sR[p * kLanes + lane] = active ? static_cast<double>(R[(static_cast<size_t>(e) * tab.num_paths + p) * K + ch]) : 0.0;
@@ -59,7 +58,7 @@ __global__ __launch_bounds__(kLanes) void generic_forward_kernel(TermTable tab, 
 template <typename T>
 __global__ __launch_bounds__(kLanes) void generic_backward_kernel(
     TermTable tab, int K, int chblocks, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
-    const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
+    const T* __restrict__ R, const EdgeList el,
     const T* __restrict__ dA, T* __restrict__ dR, T* __restrict__ dY_partial, T* __restrict__ dh_edge) {
   extern __shared__ unsigned char lds_raw[];
   double* sH = reinterpret_cast<double*>(lds_raw);  // [n_h][64]
@@ -75,9 +74,9 @@ __global__ __launch_bounds__(kLanes) void generic_backward_kernel(
   const bool active = ch < K;
   for (int c = 0; c < tab.n_out; ++c)
     sG[c * kLanes + lane] = active ? static_cast<double>(dA[(node * K + ch) * tab.n_out + c]) : 0.0;
-  const int e0 = row_ptr[node], e1 = row_ptr[node + 1];
+  const int e0 = el.first(node), e1 = el.first(node + 1);
   for (int e = e0; e < e1; ++e) {
-    const size_t j = sender[e];
+    const size_t j = el.snd(e);
     for (int b = 0; b < tab.n_h; ++b) {
       sH[b * kLanes + lane] = active ? static_cast<double>(h[(j * K + ch) * tab.n_h + b]) : 0.0;
       sDH[b * kLanes + lane] = 0.0;
@@ -118,7 +117,7 @@ __global__ __launch_bounds__(kLanes) void generic_backward_kernel(
 template <typename T>
 __global__ __launch_bounds__(kLanes) void generic_double_backward_kernel(
     TermTable tab, int K, int chblocks, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
-    const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
+    const T* __restrict__ R, const EdgeList el,
     const T* __restrict__ dA, const T* __restrict__ HY, const T* __restrict__ Hh, const T* __restrict__ HR,
     T* __restrict__ ddA, T* __restrict__ d2R, T* __restrict__ d2Y_partial, T* __restrict__ d2h_edge) {
   extern __shared__ unsigned char lds_raw[];
@@ -140,9 +139,9 @@ __global__ __launch_bounds__(kLanes) void generic_double_backward_kernel(
     sG[c * kLanes + lane] = active ? static_cast<double>(dA[(node * K + ch) * tab.n_out + c]) : 0.0;
     sDDA[c * kLanes + lane] = 0.0;
   }
-  const int e0 = row_ptr[node], e1 = row_ptr[node + 1];
+  const int e0 = el.first(node), e1 = el.first(node + 1);
   for (int e = e0; e < e1; ++e) {
-    const size_t j = sender[e];
+    const size_t j = el.snd(e);
     for (int b = 0; b < tab.n_h; ++b) {
       sH[b * kLanes + lane] = active ? static_cast<double>(h[(j * K + ch) * tab.n_h + b]) : 0.0;
       sHH[b * kLanes + lane] = active ? static_cast<double>(Hh[(j * K + ch) * tab.n_h + b]) : 0.0;
@@ -187,24 +186,31 @@ __global__ __launch_bounds__(kLanes) void generic_double_backward_kernel(
 // dh[j] = sum of the shares of the edges sent by j, in the order of send_edge.  One lane per
 // (channel, component) pair: consecutive lanes read consecutive elements of an edge's row.
 template <typename T>
-__global__ __launch_bounds__(256) void dh_sum_kernel(int row, int64_t n_rows, const int32_t* __restrict__ send_ptr,
+__global__ __launch_bounds__(256) void dh_sum_kernel(int row, int64_t n_rows, int n_edges,
+                                                     const int32_t* __restrict__ send_ptr,
                                                      const int32_t* __restrict__ send_edge,
                                                      const T* __restrict__ dh_edge, T* __restrict__ dh) {
   // row = K * n_h elements per node; blockIdx.y walks the row in pieces of 256 elements
   const size_t node = blockIdx.x;
   const int i = blockIdx.y * 256 + threadIdx.x;
   if (node >= static_cast<size_t>(n_rows) || i >= row) return;
-  const int q0 = send_ptr[node], q1 = send_ptr[node + 1];
+  // indices clamped into their ranges (see EdgeList): no access outside the buffers for a wrong list
+  auto pos = [&](int v) { return v < 0 ? 0 : (v > n_edges ? n_edges : v); };
+  auto edge = [&](int q) {
+    const int e = send_edge[q];
+    return static_cast<size_t>(e < 0 ? 0 : (e >= n_edges ? n_edges - 1 : e));
+  };
+  const int q0 = pos(send_ptr[node]), q1 = pos(send_ptr[node + 1]);
   T s0 = T(0), s1 = T(0), s2 = T(0), s3 = T(0);
   int q = q0;
   for (; q + 4 <= q1; q += 4) {  // four independent loads in flight; the order of the additions is fixed
-    const T v0 = dh_edge[static_cast<size_t>(send_edge[q]) * row + i];
-    const T v1 = dh_edge[static_cast<size_t>(send_edge[q + 1]) * row + i];
-    const T v2 = dh_edge[static_cast<size_t>(send_edge[q + 2]) * row + i];
-    const T v3 = dh_edge[static_cast<size_t>(send_edge[q + 3]) * row + i];
+    const T v0 = dh_edge[edge(q) * row + i];
+    const T v1 = dh_edge[edge(q + 1) * row + i];
+    const T v2 = dh_edge[edge(q + 2) * row + i];
+    const T v3 = dh_edge[edge(q + 3) * row + i];
     s0 += v0; s1 += v1; s2 += v2; s3 += v3;
   }
-  for (; q < q1; ++q) s0 += dh_edge[static_cast<size_t>(send_edge[q]) * row + i];
+  for (; q < q1; ++q) s0 += dh_edge[edge(q) * row + i];
   dh[node * row + i] = (s0 + s1) + (s2 + s3);
 }
 
@@ -225,7 +231,7 @@ hipError_t fwd_t(const tp_plan* plan, const FwdArgs& a, hipStream_t stream) {
   const size_t lds = static_cast<size_t>(t.n_h + t.num_paths + t.n_out) * kLanes * sizeof(double);
   hipLaunchKernelGGL(generic_forward_kernel<T>, dim3(static_cast<unsigned>(a.n_out_nodes * chblocks)), dim3(kLanes), lds,
                      stream, t, K, chblocks, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
-                     static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<T*>(a.A));
+                     static_cast<const T*>(a.R), EdgeList{a.sender, a.row_ptr, static_cast<int>(a.n_in), static_cast<int>(a.n_edges)}, static_cast<T*>(a.A));
   return hipGetLastError();
 }
 
@@ -241,7 +247,7 @@ hipError_t bwd_t(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   }
   hipLaunchKernelGGL(generic_backward_kernel<T>, dim3(static_cast<unsigned>(a.n_out_nodes * chblocks)), dim3(kLanes), lds,
                      stream, t, K, chblocks, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
-                     static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<const T*>(a.dA),
+                     static_cast<const T*>(a.R), EdgeList{a.sender, a.row_ptr, static_cast<int>(a.n_in), static_cast<int>(a.n_edges)}, static_cast<const T*>(a.dA),
                      static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh_edge));
   return hipGetLastError();
 }
@@ -259,7 +265,7 @@ hipError_t dbl_t(const tp_plan* plan, const DblArgs& d, hipStream_t stream) {
   }
   hipLaunchKernelGGL(generic_double_backward_kernel<T>, dim3(static_cast<unsigned>(a.n_out_nodes * chblocks)),
                      dim3(kLanes), lds, stream, t, K, chblocks, a.n_edges, static_cast<const T*>(a.Y),
-                     static_cast<const T*>(a.h), static_cast<const T*>(a.R), a.sender, a.row_ptr,
+                     static_cast<const T*>(a.h), static_cast<const T*>(a.R), EdgeList{a.sender, a.row_ptr, static_cast<int>(a.n_in), static_cast<int>(a.n_edges)},
                      static_cast<const T*>(a.dA), static_cast<const T*>(d.HY), static_cast<const T*>(d.Hh),
                      static_cast<const T*>(d.HR), static_cast<T*>(d.ddA), static_cast<T*>(a.dR),
                      static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh_edge));
@@ -270,7 +276,8 @@ template <typename T>
 hipError_t dh_sum_t(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   const int row = plan->cfg.num_channels * plan->n_h;
   hipLaunchKernelGGL(dh_sum_kernel<T>, dim3(static_cast<unsigned>(a.n_in), (row + 255) / 256), dim3(256), 0, stream, row,
-                     a.n_in, a.send_ptr, a.send_edge, static_cast<const T*>(a.dh_edge), static_cast<T*>(a.dh));
+                     a.n_in, static_cast<int>(a.n_edges), a.send_ptr, a.send_edge, static_cast<const T*>(a.dh_edge),
+                     static_cast<T*>(a.dh));
   return hipGetLastError();
 }
 

@@ -46,6 +46,25 @@ struct tp_plan {
 
 namespace tp {
 
+// The caller's edge list as the kernels read it.  The index arrays are not validated on the host
+// (they live on the device and the calls never synchronise); every index is clamped into its
+// range where it is read, so that a wrong index gives wrong numbers for that edge but never an
+// access outside the buffers.
+struct EdgeList {
+  const int32_t* sender;   // [n_edges]
+  const int32_t* row_ptr;  // [n_out_nodes + 1]
+  int n_in, n_edges;
+  // A sender index is clamped where it is USED (node), not where it is read (raw): the kernels read
+  // it one or two edges ahead, and a clamp at the read would wait for the load at once.
+  __device__ __forceinline__ int raw(int e) const { return sender[e]; }
+  __device__ __forceinline__ size_t node(int j) const { return static_cast<size_t>(j < 0 ? 0 : (j >= n_in ? n_in - 1 : j)); }
+  __device__ __forceinline__ size_t snd(int e) const { return node(sender[e]); }
+  __device__ __forceinline__ int first(size_t node) const {
+    const int e = row_ptr[node];
+    return e < 0 ? 0 : (e > n_edges ? n_edges : e);
+  }
+};
+
 struct FwdArgs {
   int64_t n_in, n_out_nodes, n_edges;
   const void *Y, *h, *R;

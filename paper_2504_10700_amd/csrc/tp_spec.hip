@@ -157,8 +157,7 @@ template <typename T, typename G>
 __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, int64_t n_units,
                                                            const T* __restrict__ Y, const T* __restrict__ h,
                                                            const T* __restrict__ R,
-                                                           const int32_t* __restrict__ sender,
-                                                           const int32_t* __restrict__ row_ptr, T* __restrict__ A) {
+                                                           const EdgeList el, T* __restrict__ A) {
   __shared__ __attribute__((aligned(16))) T out_stage[kWaves][kLanes * G::kNout];
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = uniform(threadIdx.x / kLanes);
@@ -167,29 +166,29 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, 
   const size_t node = unit / chblocks;
   const int cb = static_cast<int>(unit % chblocks);
   const int ch = cb * kLanes + lane;
-  const int e0 = uniform(row_ptr[node]), e1 = uniform(row_ptr[node + 1]);
+  const int e0 = uniform(el.first(node)), e1 = uniform(el.first(node + 1));
   T acc[G::kNout];
 #pragma unroll
   for (int c = 0; c < G::kNout; ++c) acc[c] = T(0);
   if (e0 < e1) {
     T r0[G::kP], r1[G::kP], h0[G::kNh], h1[G::kNh], y[G::kNY];
     load_weights<T, G::kP>(R, e0, K, ch, r0);
-    load_row<T, G::kNh>(h + (static_cast<size_t>(sender[e0]) * K + ch) * G::kNh, h0);
-    int jn = (e0 + 1 < e1) ? sender[e0 + 1] : 0;  // sender of the next edge, read one step ahead
+    load_row<T, G::kNh>(h + (el.snd(e0) * K + ch) * G::kNh, h0);
+    int jn = (e0 + 1 < e1) ? el.raw(e0 + 1) : 0;  // sender of the next edge, read one step ahead
     for (int e = e0; e < e1; e += 2) {
       int jn2 = 0;
       if (e + 1 < e1) {
         load_weights<T, G::kP>(R, e + 1, K, ch, r1);
-        load_row<T, G::kNh>(h + (static_cast<size_t>(jn) * K + ch) * G::kNh, h1);
-        if (e + 2 < e1) jn2 = sender[e + 2];
+        load_row<T, G::kNh>(h + (el.node(jn) * K + ch) * G::kNh, h1);
+        if (e + 2 < e1) jn2 = el.raw(e + 2);
       }
       load_uniform<T, G::kNY>(Y, e, y);
       G::forward(y, h0, r0, acc);
       if (e + 1 < e1) {
         if (e + 2 < e1) {
           load_weights<T, G::kP>(R, e + 2, K, ch, r0);
-          load_row<T, G::kNh>(h + (static_cast<size_t>(jn2) * K + ch) * G::kNh, h0);
-          if (e + 3 < e1) jn = sender[e + 3];
+          load_row<T, G::kNh>(h + (el.node(jn2) * K + ch) * G::kNh, h0);
+          if (e + 3 < e1) jn = el.raw(e + 3);
         }
         load_uniform<T, G::kNY>(Y, e + 1, y);
         G::forward(y, h1, r1, acc);
@@ -204,7 +203,7 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, 
 template <typename T, typename G>
 __global__ __launch_bounds__(kThreads) void backward_kernel(
     int K, int chblocks, int64_t n_units, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
-    const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
+    const T* __restrict__ R, const EdgeList el,
     const T* __restrict__ dA, T* __restrict__ dR, T* __restrict__ dY_partial, T* __restrict__ dh_edge) {
   __shared__ T stage_all[kWaves][G::kNY * kStageStride];
   const int lane = threadIdx.x & (kLanes - 1);
@@ -215,14 +214,14 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
   const size_t node = unit / chblocks;
   const int cb = static_cast<int>(unit % chblocks);
   const int ch = cb * kLanes + lane;
-  const int e0 = uniform(row_ptr[node]), e1 = uniform(row_ptr[node + 1]);
+  const int e0 = uniform(el.first(node)), e1 = uniform(el.first(node + 1));
   if (e0 >= e1) return;
   T g[G::kNout];
   load_row<T, G::kNout>(dA + (node * K + ch) * G::kNout, g);
   T r0[G::kP], r1[G::kP], h0[G::kNh], h1[G::kNh];
   load_weights<T, G::kP>(R, e0, K, ch, r0);
-  load_row<T, G::kNh>(h + (static_cast<size_t>(sender[e0]) * K + ch) * G::kNh, h0);
-  int jn = (e0 + 1 < e1) ? sender[e0 + 1] : 0;
+  load_row<T, G::kNh>(h + (el.snd(e0) * K + ch) * G::kNh, h0);
+  int jn = (e0 + 1 < e1) ? el.raw(e0 + 1) : 0;
 
   // One edge: arithmetic, dR row stores, dY summed over the 64 lanes in a fixed order.
   auto finish_edge = [&](int e, const T (&r)[G::kP], const T (&hh)[G::kNh]) {
@@ -240,15 +239,15 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
     int jn2 = 0;
     if (e + 1 < e1) {
       load_weights<T, G::kP>(R, e + 1, K, ch, r1);
-      load_row<T, G::kNh>(h + (static_cast<size_t>(jn) * K + ch) * G::kNh, h1);
-      if (e + 2 < e1) jn2 = sender[e + 2];
+      load_row<T, G::kNh>(h + (el.node(jn) * K + ch) * G::kNh, h1);
+      if (e + 2 < e1) jn2 = el.raw(e + 2);
     }
     finish_edge(e, r0, h0);
     if (e + 1 < e1) {
       if (e + 2 < e1) {
         load_weights<T, G::kP>(R, e + 2, K, ch, r0);
-        load_row<T, G::kNh>(h + (static_cast<size_t>(jn2) * K + ch) * G::kNh, h0);
-        if (e + 3 < e1) jn = sender[e + 3];
+        load_row<T, G::kNh>(h + (el.node(jn2) * K + ch) * G::kNh, h0);
+        if (e + 3 < e1) jn = el.raw(e + 3);
       }
       finish_edge(e + 1, r1, h1);
     }
@@ -261,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
 template <typename T, typename G>
 __global__ __launch_bounds__(kThreads) void double_backward_kernel(
     int K, int chblocks, int64_t n_units, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
-    const T* __restrict__ R, const int32_t* __restrict__ sender, const int32_t* __restrict__ row_ptr,
+    const T* __restrict__ R, const EdgeList el,
     const T* __restrict__ dA, const T* __restrict__ HY, const T* __restrict__ Hh, const T* __restrict__ HR,
     T* __restrict__ ddA, T* __restrict__ d2R, T* __restrict__ d2Y_partial, T* __restrict__ d2h_edge) {
   __shared__ T stage_all[kWaves][G::kNY * kStageStride];
@@ -273,7 +272,7 @@ __global__ __launch_bounds__(kThreads) void double_backward_kernel(
   const size_t node = unit / chblocks;
   const int cb = static_cast<int>(unit % chblocks);
   const int ch = cb * kLanes + lane;
-  const int e0 = uniform(row_ptr[node]), e1 = uniform(row_ptr[node + 1]);
+  const int e0 = uniform(el.first(node)), e1 = uniform(el.first(node + 1));
   T dda[G::kNout];
 #pragma unroll
   for (int c = 0; c < G::kNout; ++c) dda[c] = T(0);
@@ -282,13 +281,13 @@ __global__ __launch_bounds__(kThreads) void double_backward_kernel(
     load_row<T, G::kNout>(dA + (node * K + ch) * G::kNout, g);
     T r0[G::kP], r1[G::kP], q0[G::kP], q1[G::kP], h0[G::kNh], h1[G::kNh], x0[G::kNh], x1[G::kNh];
     {
-      const size_t j = sender[e0];
+      const size_t j = el.snd(e0);
       load_weights<T, G::kP>(R, e0, K, ch, r0);
       load_weights<T, G::kP>(HR, e0, K, ch, q0);
       load_row<T, G::kNh>(h + (j * K + ch) * G::kNh, h0);
       load_row<T, G::kNh>(Hh + (j * K + ch) * G::kNh, x0);
     }
-    int jn = (e0 + 1 < e1) ? sender[e0 + 1] : 0;
+    int jn = (e0 + 1 < e1) ? el.raw(e0 + 1) : 0;
 
     auto finish_edge = [&](int e, const T (&r)[G::kP], const T (&hr)[G::kP], const T (&hh)[G::kNh],
                            const T (&hx)[G::kNh]) {
@@ -308,18 +307,18 @@ __global__ __launch_bounds__(kThreads) void double_backward_kernel(
       if (e + 1 < e1) {
         load_weights<T, G::kP>(R, e + 1, K, ch, r1);
         load_weights<T, G::kP>(HR, e + 1, K, ch, q1);
-        load_row<T, G::kNh>(h + (static_cast<size_t>(jn) * K + ch) * G::kNh, h1);
-        load_row<T, G::kNh>(Hh + (static_cast<size_t>(jn) * K + ch) * G::kNh, x1);
-        if (e + 2 < e1) jn2 = sender[e + 2];
+        load_row<T, G::kNh>(h + (el.node(jn) * K + ch) * G::kNh, h1);
+        load_row<T, G::kNh>(Hh + (el.node(jn) * K + ch) * G::kNh, x1);
+        if (e + 2 < e1) jn2 = el.raw(e + 2);
       }
       finish_edge(e, r0, q0, h0, x0);
       if (e + 1 < e1) {
         if (e + 2 < e1) {
           load_weights<T, G::kP>(R, e + 2, K, ch, r0);
           load_weights<T, G::kP>(HR, e + 2, K, ch, q0);
-          load_row<T, G::kNh>(h + (static_cast<size_t>(jn2) * K + ch) * G::kNh, h0);
-          load_row<T, G::kNh>(Hh + (static_cast<size_t>(jn2) * K + ch) * G::kNh, x0);
-          if (e + 3 < e1) jn = sender[e + 3];
+          load_row<T, G::kNh>(h + (el.node(jn2) * K + ch) * G::kNh, h0);
+          load_row<T, G::kNh>(Hh + (el.node(jn2) * K + ch) * G::kNh, x0);
+          if (e + 3 < e1) jn = el.raw(e + 3);
         }
         finish_edge(e + 1, r1, q1, h1, x1);
       }
@@ -345,8 +344,7 @@ hipError_t fwd_launch(const tp_plan* plan, const FwdArgs& a, hipStream_t stream)
   const int K = plan->cfg.num_channels, chblocks = K / kLanes;
   const int64_t n_units = a.n_out_nodes * chblocks;
   hipLaunchKernelGGL((forward_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks, n_units,
-                     static_cast<const T*>(a.Y), static_cast<const T*>(a.h), static_cast<const T*>(a.R), a.sender,
-                     a.row_ptr, static_cast<T*>(a.A));
+                     static_cast<const T*>(a.Y), static_cast<const T*>(a.h), static_cast<const T*>(a.R), EdgeList{a.sender, a.row_ptr, static_cast<int>(a.n_in), static_cast<int>(a.n_edges)}, static_cast<T*>(a.A));
   return hipGetLastError();
 }
 
@@ -356,7 +354,7 @@ hipError_t bwd_launch(const tp_plan* plan, const BwdArgs& a, hipStream_t stream)
   const int64_t n_units = a.n_out_nodes * chblocks;
   hipLaunchKernelGGL((backward_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
                      n_units, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
-                     static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<const T*>(a.dA),
+                     static_cast<const T*>(a.R), EdgeList{a.sender, a.row_ptr, static_cast<int>(a.n_in), static_cast<int>(a.n_edges)}, static_cast<const T*>(a.dA),
                      static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh_edge));
   return hipGetLastError();
 }
@@ -368,7 +366,7 @@ hipError_t dbl_launch(const tp_plan* plan, const DblArgs& d, hipStream_t stream)
   const int64_t n_units = a.n_out_nodes * chblocks;
   hipLaunchKernelGGL((double_backward_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
                      n_units, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
-                     static_cast<const T*>(a.R), a.sender, a.row_ptr, static_cast<const T*>(a.dA),
+                     static_cast<const T*>(a.R), EdgeList{a.sender, a.row_ptr, static_cast<int>(a.n_in), static_cast<int>(a.n_edges)}, static_cast<const T*>(a.dA),
                      static_cast<const T*>(d.HY), static_cast<const T*>(d.Hh), static_cast<const T*>(d.HR),
                      static_cast<T*>(d.ddA), static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial),
                      static_cast<T*>(a.dh_edge));

@@ -250,3 +250,41 @@ def test_full_size_sampled(tp, name):
     r = otp.double_backward(cfg, Y[sm], h, R[sm], inp.sender[sm], inp.receiver[sm], dA, HY[sm], Hh, HR[sm])
     check("d2h(sample)", d2h[Tn], r[2][Tn], wl.dtype)
     run.close()
+
+
+@pytest.mark.parametrize("flags", [0, 2])
+def test_wrong_index_arrays_stay_inside_the_buffers(tp, flags):
+    """The index arrays are not validated, but every index is clamped where it is read: a list with
+    senders, offsets and edge ids out of range gives meaningless numbers for the edges concerned and
+    leaves the device healthy - the correct list gives the oracle's result right afterwards."""
+    import torch
+    wl = wl_of("bad_indices", 40, 6, 128, 3, 1, 3, "f32", 5301)
+    cfg = oracle_cfg(wl)
+    inp = workloads.make_tp_inputs(wl, otp.enumerate_paths(cfg))
+    run = TPRun(tp, wl, inp, flags)
+    good = [x.clone() for x in (run.sender, run.row_ptr, run.send_ptr, run.send_edge)]
+    E = run.E
+    say(f"case bad_indices: N={run.N} E={E} flags={flags}")
+    run.sender[::7] = -5
+    run.sender[3::11] = run.N + 1000
+    run.row_ptr[5] = E + 12345
+    run.row_ptr[9] = -4
+    run.send_ptr[7] = 2 * E
+    run.send_edge[::5] = E + 7
+    run.send_edge[2::9] = -1
+    run.forward()
+    run.backward()
+    HY, Hh, HR = workloads.make_tp_cotangents(wl, inp)
+    run.double_backward(HY, Hh, HR)
+    for dst, src in zip((run.sender, run.row_ptr, run.send_ptr, run.send_edge), good):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    Y, h, R, dA = run.inputs_as_computed()
+    no_edges = np.diff(inp.row_ptr) == 0
+    A = run.forward()
+    check("A", A[~no_edges], otp.forward(cfg, Y, h, R, inp.sender, inp.receiver, run.N)[~no_edges], wl.dtype)
+    dY, dh, dR = run.backward()
+    dY_ref, dh_ref, dR_ref = otp.backward(cfg, Y, h, R, inp.sender, inp.receiver, dA)
+    check("dY", dY, dY_ref, wl.dtype)
+    check("dR", dR, dR_ref, wl.dtype)
+    run.close()
