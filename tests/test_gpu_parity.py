@@ -96,6 +96,13 @@ def test_other_configurations(sc, l_max, nu_max, outs):
     full_parity(sc, wl_of("other", 40, 4, 64, l_max, nu_max, outs, "f64", 2200, z_mode="uniform"))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f64"])
+def test_outputs_up_to_L3(sc, dtype):
+    # four output irreps 0e+1o+2e+3o (16 output components) at l_max = 3, nu_max = 3: the table-driven kernels
+    full_parity(sc, wl_of("out_L3", 48, 5, 64, 3, 3, ((0, 1), (1, -1), (2, 1), (3, -1)), dtype, 2300,
+                          z_mode="uniform"))
+
+
 def test_degenerate_batches(sc):
     # one node; all nodes of one element; most elements absent
     full_parity(sc, wl_of("one_node", 1, 89, 128, 3, 3, O01, "f32", 2301))
