@@ -6,17 +6,21 @@
 // and B[kk = L/16][j = L%16] and receives four entries of column j = L%16 of the 16x16 result
 // (rows 4*(L/16)+r in fp32, 4*r + L/16 in fp64; r = 0..3).
 //
-// Forward (and dX, which is the same product with W transposed): rows = 16 atoms, reduction =
+// Forward (and dX, which is the same product on W transposed): rows = 16 atoms, reduction =
 // input channels, columns = 16 output channels, one accumulator block per component (l,m); the
 // 2l+1 components of an order share their B operand.  With the layout X[atom][channel][lm]
-// the A operands of all components of one (atom, channel) are 64 contiguous bytes, so every
-// lane reads its operands for a reduction step with four 16-byte loads straight from global
-// memory (no LDS staging needed), and the result of all components of one (atom, output
-// channel) leaves as 64 contiguous bytes per lane.
+// the A operands of all components of one (atom, channel) are 64 contiguous bytes, and a lane
+// ends up with whole 64-byte rows of the result.  Kernels: mfma_forward_lds_kernel (fp32,
+// l_max = 3: X staged through LDS once per workgroup, B through a buffer descriptor, result
+// rows stored as whole lines through an LDS transpose; the product lives in el_tile.h and is
+// shared with the fused linear + contraction kernel) and mfma_forward_kernel (every other
+// shape: operands straight from global memory through a four-deep register pipeline).
 // dW: rows = 16 input channels, columns = 16 output channels, reduction = atoms (four per
 // MFMA) and the components of the order; A and B operands are again 64 contiguous bytes per
-// lane.  The atoms are cut into ranges, every range writes a partial dW, a second kernel adds
-// the partials in range order (fixed order, no atomics).
+// lane.  The atoms are cut into ranges, every range writes a partial dW (mfma_dw_lds_kernel:
+// dY rows shared through LDS, two row tiles per wave; mfma_dw_kernel: every other shape), a
+// second kernel adds the partials in a fixed order (no atomics).
+// Channel counts outside the MFMA tilings run on plain vector kernels with fp64 accumulation.
 #include <algorithm>
 #include <string>
 
