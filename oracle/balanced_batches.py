@@ -8,7 +8,7 @@ capacity, G the number of GPUs, c(B_j) the remaining capacity of bin j, p the po
 sorted list.  Plain Python lists and the language's stable sort; nothing is reorganised for
 speed.
 
-Readings of what the paper leaves open (all listed in the design notes):
+Readings of what the paper leaves open:
 * the sort of the bins takes the listing's line (stable, by remaining capacity, descending:
   the emptiest bin receives the next - largest remaining - graph); the prose next to it speaks
   of prioritising fuller bins, which contradicts the listing and the stated goal of balance;

@@ -13,7 +13,7 @@ describes before Algorithm 2 (the messages are summed over j on the receiving ve
 
     A[i,k,(l3,m3)] = sum over the edges ji with receiver i of msg[ji,k,(l3,m3)].
 
-Readings of what the paper leaves open (all listed in the design notes):
+Readings of what the paper leaves open:
 * Y carries l1 = 0..l_Y, h carries l2 = 0..l_h, the output l3 = 0..L_max, all in the real
   basis with component index l*l + l + m and parity (-1)^l (spherical harmonics and the
   irreps MACE keeps have this "natural" parity);

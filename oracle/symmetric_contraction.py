@@ -12,7 +12,7 @@ for every atom i, channel k and output component (L,M)
 with dense generalized coupling tensors U, no sparsity, no symmetrisation.
 The backward is the analytic derivative of that expression.
 
-Readings of what the paper leaves open (all listed in the design notes):
+Readings of what the paper leaves open:
 * component index a = l*l + l + m; A carries l = 0..l_max with parity (-1)^l;
 * a coupling path eta is an ORDERED l-tuple plus, for nu = 3, the intermediate
   L2 of the chain ((l1 (x) l2) -> L2) (x) l3 -> L; all paths allowed by the
