@@ -1,8 +1,8 @@
 /*
  * bb.h - C ABI of the load balancer (same library, libsc_mi355x.so; host code only).
  *
- * Algorithm CREATE-BALANCED-BATCHES of arXiv 2504.10700 (Section 3, "Iterative Algorithm for
- * Multi-Objective Bin Packing"): distributes N graphs with given sizes (vertex counts) over
+ * Algorithm CREATE-BALANCED-BATCHES of arXiv 2504.10700 (Section 3, the subsection on the iterative
+ * multi-objective bin packing): distributes N graphs with given sizes (vertex counts) over
  * bins (mini-batches) of capacity C, the number of bins a multiple of the number of GPUs G,
  * by dealing the graphs in descending size order to the bins in descending order of remaining
  * capacity, one graph per bin and sweep; bins that cannot take the current graph are set

@@ -1,7 +1,7 @@
 /*
  * sc.h - C ABI of the MI355X symmetric tensor contraction library (libsc_mi355x.so).
  *
- * The operation is the "higher-order feature computation" of MACE, Algorithm 2 of
+ * The operation is the product-basis step of MACE (symmetric contraction), Algorithm 2 of
  * arXiv 2504.10700 (Section 4.1) together with the message equation of Section 2.2:
  * for every atom i, channel k and output component (L,M)
  *

@@ -1,7 +1,7 @@
 /*
  * tp.h - C ABI of the MI355X channelwise tensor product (same library, libsc_mi355x.so).
  *
- * The operation is the "construction of original messages" of MACE, Algorithm 1 of
+ * The operation is the message construction of MACE (channelwise tensor product), Algorithm 1 of
  * arXiv 2504.10700 (Section 4.1), fused with the pooling over the neighbours of the
  * receiving atom that the same section describes before Algorithm 2: for every atom i,
  * channel k and output component (l3,m3)

@@ -2,8 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
-Follows Algorithm CREATE-BALANCED-BATCHES (Section 3, "Iterative Algorithm for Multi-Objective
-Bin Packing") step by step, in its notation: L the graph sizes (vertex counts), C the bin
+Follows Algorithm CREATE-BALANCED-BATCHES (Section 3, the subsection on the iterative
+multi-objective bin packing) step by step, in its notation: L the graph sizes (vertex counts), C the bin
 capacity, G the number of GPUs, c(B_j) the remaining capacity of bin j, p the pointer into the
 sorted list.  Plain Python lists and the language's stable sort; nothing is reorganised for
 speed.

@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
-Follows Algorithm 1 of the paper ("Construction of original messages in MACE"): for
+Follows Algorithm 1 of the paper (the message construction of MACE, Section 4.1): for
 every edge ji (sender j, receiver i), channel k and output component (l3, m3)
 
     msg[ji,k,(l3,m3)] = sum over (l1,m1), (l2,m2) of

@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
-Follows Algorithm 2 of the paper ("Higher-order feature computation in MACE")
+Follows Algorithm 2 of the paper (the product-basis step of MACE, Section 4.1)
 and the message equation of Section 2.2 (m = sum_nu sum_eta W^(nu)_{k,eta} B^(nu)_{eta,kLM}):
 for every atom i, channel k and output component (L,M)
 
