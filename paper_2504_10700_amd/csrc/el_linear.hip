@@ -287,28 +287,27 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     }
   };
 
+  // Operands are requested TWO steps before their use (a step is ~2 us of matrix work, about the
+  // memory latency under load; one step of lead left ~1.5 us of stall per step).  Four A sets and
+  // two dY register sets rotate with period four: the loop is unrolled by four and has no branch
+  // inside (past the end of the range the A operands are zero and the addresses clamped, so the
+  // padding steps add nothing), which keeps the compiler's wait counts exact.
   if (steps > 0) {
-    V4 a[2][NU][4], yr[4];
+    const int padded = (steps + 3) / 4 * 4;
+    V4 a[4][NU][4], yr[2][4];
     aload(0, a[0]);
-    yload(0, yr);
-    ystage(0, yr);
+    yload(0, yr[0]);
+    aload(1, a[1]);
+    yload(1, yr[1]);
+    ystage(0, yr[0]);
     __syncthreads();
-    for (int s = 0; s < steps; s += 2) {
-      // even step: operands in a[0] and buffer 0; the next step's are requested first
-      if (s + 1 < steps) {
-        aload(s + 1, a[1]);
-        yload(s + 1, yr);
-      }
-      multiply(0, a[0]);
-      if (s + 1 < steps) ystage(1, yr);
-      __syncthreads();
-      if (s + 1 < steps) {                    // odd step (uniform branch)
-        if (s + 2 < steps) {
-          aload(s + 2, a[0]);
-          yload(s + 2, yr);
-        }
-        multiply(1, a[1]);
-        if (s + 2 < steps) ystage(0, yr);
+    for (int s = 0; s < padded; s += 4) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        aload(s + i + 2, a[(i + 2) & 3]);
+        yload(s + i + 2, yr[i & 1]);              // (the set that held step s+i, staged a step ago)
+        multiply(i & 1, a[i]);
+        ystage((i + 1) & 1, yr[(i + 1) & 1]);     // step s+i+1, requested a step ago
         __syncthreads();
       }
     }
