@@ -22,6 +22,7 @@
 // second kernel adds the partials in a fixed order (no atomics).
 // Channel counts outside the MFMA tilings run on plain vector kernels with fp64 accumulation.
 #include <algorithm>
+#include <atomic>
 #include <string>
 
 #include "../../include/el.h"
@@ -436,15 +437,15 @@ sc_status check_config(const char* fn, const el_config* cfg, int64_t n) {
 
 // Compute units of the current device (asked once per device).
 int compute_units() {
-  static int cached[64] = {0};
+  static std::atomic<int> cached[64];   // zero-initialised; any thread may fill an entry, all with the same value
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    cached[dev] = n;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return cached[dev];
+  return n;
 }
 
 // Is the product with k_red reduction channels and k_cols output channels served by the MFMA kernel?
