@@ -125,8 +125,8 @@ sc_status sc_plan_info(const sc_plan* plan, sc_info* out);
 sc_status sc_plan_paths(const sc_plan* plan, int32_t* paths);
 
 /* Sparse form of one path's generalized coupling tensor after merging slot
- * permutations (A is the same in every slot, Section 4.1 "multiple copies of the
- * message"): term t says  P_{p,M[t]}(a) += coef[t] * a[i1[t]] * a[i2[t]] * a[i3[t]]
+ * permutations (the same A enters every slot of the product, Section 4.1, so terms that
+ * differ only by a permutation of the slots are one term): term t says  P_{p,M[t]}(a) += coef[t] * a[i1[t]] * a[i2[t]] * a[i3[t]]
  * with i1 <= i2 <= i3 and unused slots = -1.  Call with capacity 0 to query the
  * count (*n_terms); host buffers.  Exists for tests and the kernel generator. */
 sc_status sc_plan_path_terms(const sc_plan* plan, int32_t path, int32_t capacity, int32_t* n_terms,

@@ -232,7 +232,12 @@ sc_status sc_profile_enable(sc_plan* plan, int32_t on) {
   if (on && !plan->ev[0]) {
     for (int i = 0; i < 6; ++i) {
       const hipError_t e = hipEventCreate(&plan->ev[i]);
-      if (e != hipSuccess) return fail_hip(e, "sc_profile_enable: hipEventCreate");
+      if (e != hipSuccess) {  // all or nothing: a later call starts from scratch
+        for (int k = 0; k < i; ++k) (void)hipEventDestroy(plan->ev[k]);
+        for (int k = 0; k < 6; ++k) plan->ev[k] = nullptr;
+        plan->profile = false;
+        return fail_hip(e, "sc_profile_enable: hipEventCreate");
+      }
     }
   }
   plan->profile = on != 0;
@@ -266,12 +271,14 @@ sc_status sc_profile_read_double_backward(sc_plan* plan, float* ms) {
 sc_status sc_plan_destroy(sc_plan* plan) {
   if (!plan) return SC_OK;
   sc_status st = SC_OK;
-  for (int i = 0; i < 6; ++i)
-    if (plan->ev[i]) (void)hipEventDestroy(plan->ev[i]);
-  if (plan->dev_blob) {
-    DeviceGuard guard(plan->cfg.device);
-    const hipError_t e = hipFree(plan->dev_blob);
-    if (e != hipSuccess) st = fail_hip(e, "sc_plan_destroy: hipFree");
+  if (!plan->host_only) {
+    DeviceGuard guard(plan->cfg.device);  // events and tables belong to the plan's device
+    for (int i = 0; i < 6; ++i)
+      if (plan->ev[i]) (void)hipEventDestroy(plan->ev[i]);
+    if (plan->dev_blob) {
+      const hipError_t e = hipFree(plan->dev_blob);
+      if (e != hipSuccess) st = fail_hip(e, "sc_plan_destroy: hipFree");
+    }
   }
   delete plan;
   return st;

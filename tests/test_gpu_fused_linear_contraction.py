@@ -3,10 +3,11 @@ contraction, through the C ABI) with the chain of the two fp64 oracles
 B = contraction(linear(X, W_lin), z, W).  Covers the single-kernel path (fp32, generated 0e+1o
 kernel, K a multiple of 128) and the two-step path of every other plan.
 
-Tolerance of the composition: each of the two operations is held to 1e-5 (fp32; 1e-12 fp64)
-against its oracle on exact inputs.  B is a polynomial of degree <= 3 in A, so a relative error
-e_A in A shows up as at most 3 e_A in B (first order), next to the contraction's own 1e-5:
-the chain is held to (3 + 1) x the single-operation bar, same error measures."""
+Tolerance: the bar of a single operation, 1e-5 (fp32; 1e-12 fp64), same error measures, for the
+composition as well.  Only the cases listed in WIDER get more, each with the reason and the error
+measured on MI355X: B is a polynomial of degree <= 3 in A, so a relative error e_A of the linear
+step shows up as up to 3 e_A in B next to the contraction's own error, and e_A itself grows with
+the length of the channel sum."""
 import sys
 
 import numpy as np
@@ -15,16 +16,18 @@ import pytest
 from oracle import equivariant_linear as oel
 from oracle import symmetric_contraction as osc
 from paper_2504_10700_amd import workloads
-from gpu_util import F32_TOL, F64_TOL, rel_err_f32, rel_err_f64
+from gpu_util import F32_TOL, F64_TOL, rel_err_f32, rel_err_f64, oracle_forward
 
 pytestmark = pytest.mark.gpu
 
-CHAIN = 4.0   # see the module docstring
+# (k_in, K) -> factor on the bar, for the cases that do not meet the bar itself
+WIDER = {}
 
 
-def check(name, got, ref, dtype):
+def check(name, got, ref, dtype, factor=1.0):
     err = rel_err_f32(got, ref) if dtype == "f32" else rel_err_f64(got, ref)
-    tol = CHAIN * (F32_TOL if dtype == "f32" else F64_TOL)
+    tol = factor * (F32_TOL if dtype == "f32" else F64_TOL)
+    print(f"{name}: error {err:.3e} (bar {tol:.1e})", flush=True)
     assert err <= tol, f"{name}: error {err:.3e} exceeds {tol:.1e}"
     return err
 
@@ -41,7 +44,7 @@ def mods():
     return binding, el_binding
 
 
-def run_case(mods, N, k_in, K, Z, l_max, nu_max, out, dtype, seed, expect_fused, z_mode="skewed", sample=None):
+def run_case(mods, N, k_in, K, Z, l_max, nu_max, out, dtype, seed, expect_fused, z_mode="skewed"):
     import torch
     sc, el = mods
     print(f"case N={N} k_in={k_in} K={K} Z={Z} l_max={l_max} nu={nu_max} out={out} {dtype}", flush=True)
@@ -71,16 +74,8 @@ def run_case(mods, N, k_in, K, Z, l_max, nu_max, out, dtype, seed, expect_fused,
         sc.sc_plan_destroy(plan)
     X64, Wl64, W64 = (x.double().cpu().numpy() for x in (Xd, Wl, W))
     got = B.cpu().numpy()
-    if sample is None:
-        ref = osc.forward(T, oel.forward(X64, Wl64), inp.z, W64)
-        check("B", got, ref, dtype)
-    else:
-        # full size: a sample of nodes one by one; the rms of the tolerance comes from the sample
-        idx = np.unique(np.concatenate([np.arange(16), np.arange(N - 17, N),
-                                        np.random.default_rng(seed).integers(0, N, sample)]))
-        ref = osc.forward(T, oel.forward(X64[idx], Wl64), inp.z[idx], W64)
-        check("B (sampled nodes)", got[idx], ref, dtype)
-        assert np.isfinite(got).all()
+    ref = oracle_forward(osc, T, oel.forward(X64, Wl64), inp.z, W64)
+    check(f"B (N={N}, {k_in}->{K}, {dtype})", got, ref, dtype, WIDER.get((k_in, K, dtype), 1.0))
 
 
 def test_single_kernel_path_small(mods):
@@ -106,8 +101,8 @@ def test_two_step_path(mods):
     run_case(mods, 40, 8, 8, 2, 1, 2, ((0, 1),), "f64", 9205, False)        # the tiny configuration
 
 
-def test_full_size_sampled(mods):
-    run_case(mods, 10_000, 128, 128, 89, 3, 3, O01, "f32", 9301, True, sample=96)
+def test_full_size_all_nodes(mods):
+    run_case(mods, 10_000, 128, 128, 89, 3, 3, O01, "f32", 9301, True)
 
 
 def test_empty_and_errors(mods):
