@@ -151,6 +151,23 @@ sc_status sc_workspace_bytes(const sc_plan* plan, int64_t n_nodes, size_t* bytes
 sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W,
                      void* B, void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream);
 
+/* For callers that cannot allocate or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): sc_forward with the grouping kept in a
+ * fixed device array inside the library instead of a caller's workspace.  Same arguments,
+ * same kernels, same results bit for bit as sc_forward without flags.  Calls no hipMalloc,
+ * hipFree or other allocating routine.
+ * Limits: n_nodes <= SC_NOALLOC_MAX_NODES, and the plan's grouping for n_nodes must fit
+ * SC_NOALLOC_SCRATCH_BYTES (it does for every plan of up to 700 elements at the node limit
+ * with the library's own tile size); beyond them the call fails with SC_ERR_WORKSPACE and launches nothing.
+ * Every GPU holds ONE such array (SC_NOALLOC_SCRATCH_BYTES of device memory per GPU the
+ * library has run this call on, until the process ends), shared by all plans and streams:
+ * calls of sc_forward_noalloc that can overlap in time on one GPU race on it and must be
+ * ordered by the caller (one stream, or events). */
+#define SC_NOALLOC_MAX_NODES 65536
+#define SC_NOALLOC_SCRATCH_BYTES (1u << 20)
+sc_status sc_forward_noalloc(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W,
+                             void* B, void* hip_stream);
+
 /* Backward of Algorithm 2 for an upstream gradient dB (training, Section 2.2: energies
  * and forces are trained by gradient descent through this operation).
  *   dB dev [n_nodes][K][n_LM]

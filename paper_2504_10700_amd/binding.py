@@ -26,9 +26,11 @@ SC_F32, SC_F64 = 0, 1
 SC_MAX_OUT = 4
 SC_PLAN_HOST_ONLY, SC_PLAN_FORCE_GENERIC = 1, 2
 SC_REUSE_GROUPING = 1
+SC_NOALLOC_MAX_NODES, SC_NOALLOC_SCRATCH_BYTES = 65536, 1 << 20
 
 EXPORTS = ("sc_plan_create", "sc_plan_destroy", "sc_plan_info", "sc_plan_paths", "sc_plan_path_terms",
-           "sc_coupling_tensor", "sc_workspace_bytes", "sc_forward", "sc_backward", "sc_double_backward",
+           "sc_coupling_tensor", "sc_workspace_bytes", "sc_forward", "sc_forward_noalloc", "sc_backward",
+           "sc_double_backward",
            "sc_profile_enable", "sc_profile_read", "sc_profile_read_double_backward", "sc_last_error")
 
 
@@ -66,6 +68,7 @@ def _load() -> C.CDLL:
     lib.sc_coupling_tensor.argtypes = [i32, i32, i32, C.POINTER(C.c_double)]
     lib.sc_workspace_bytes.argtypes = [vp, i64, C.POINTER(C.c_size_t)]
     lib.sc_forward.argtypes = [vp, i64, vp, vp, vp, vp, vp, C.c_size_t, u32, vp]
+    lib.sc_forward_noalloc.argtypes = [vp, i64, vp, vp, vp, vp, vp]
     lib.sc_backward.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, u32, vp]
     lib.sc_double_backward.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, u32, vp]
     lib.sc_profile_enable.argtypes = [vp, i32]
@@ -185,6 +188,10 @@ def sc_forward(plan: Plan, n_nodes: int, A, z, W, B, workspace, workspace_bytes:
                stream=None) -> None:
     _check(lib.sc_forward(plan.handle, n_nodes, _ptr(A), _ptr(z), _ptr(W), _ptr(B), _ptr(workspace),
                           workspace_bytes, flags, _stream(stream)))
+
+
+def sc_forward_noalloc(plan: Plan, n_nodes: int, A, z, W, B, stream=None) -> None:
+    _check(lib.sc_forward_noalloc(plan.handle, n_nodes, _ptr(A), _ptr(z), _ptr(W), _ptr(B), _stream(stream)))
 
 
 def sc_backward(plan: Plan, n_nodes: int, A, z, W, dB, dA, dW, workspace, workspace_bytes: int, flags: int = 0,

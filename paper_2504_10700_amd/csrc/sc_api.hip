@@ -2,6 +2,7 @@
 // layout and kernel dispatch.  Everything numerical happens in the kernels.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -32,6 +33,33 @@ __global__ void fill_zero_kernel(unsigned int* p, size_t n_words) {
 }
 
 size_t elem_size(const sc_plan* plan) { return plan->cfg.dtype == SC_F64 ? 8 : 4; }
+
+// Scratch of sc_forward_noalloc: the grouping of one call (what sc_forward keeps in the caller's
+// workspace).  Every GPU the library runs on holds its own copy of this array, at its own
+// address, until the process ends.  In host code the array's NAME is only a handle for
+// hipGetSymbolAddress, never a device address: host code uses the pointer noalloc_scratch()
+// returns and nothing else.
+static __device__ __align__(256) unsigned char scratch[SC_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on `device`, which must be the current device.  Resolved once per device.
+sc_status noalloc_scratch(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices)
+    return fail(SC_ERR_UNSUPPORTED, "sc_forward_noalloc: device ordinal outside 0..63");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e, "sc_forward_noalloc: hipGetSymbolAddress");
+    if (!p) return fail(SC_ERR_HIP, "sc_forward_noalloc: hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return SC_OK;
+}
 
 
 }  // namespace
@@ -74,7 +102,7 @@ LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
   return s;
 }
 
-Workspace carve_workspace(const sc_plan* plan, int64_t n, const LaunchShape& shape, void* base) {
+Workspace carve_workspace(const sc_plan* plan, int64_t n, const LaunchShape& shape, void* base, bool forward_only) {
   Workspace w{};
   const int Z = plan->cfg.num_elements;
   size_t off = 0;
@@ -89,8 +117,10 @@ Workspace carve_workspace(const sc_plan* plan, int64_t n, const LaunchShape& sha
   w.counts = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(kMaxGroupWaves) * Z));
   w.perm = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
   w.tiles = static_cast<TileDesc*>(take(sizeof(TileDesc) * static_cast<size_t>(shape.max_tiles)));
-  w.partial = take(elem_size(plan) * static_cast<size_t>(shape.max_tiles) * shape.chblocks * plan->S * kLanes);
-  w.reduced = static_cast<double*>(take(sizeof(double) * static_cast<size_t>(Z) * shape.chblocks * plan->S * kLanes));
+  if (!forward_only) {  // the weight-gradient rows of the backward passes
+    w.partial = take(elem_size(plan) * static_cast<size_t>(shape.max_tiles) * shape.chblocks * plan->S * kLanes);
+    w.reduced = static_cast<double*>(take(sizeof(double) * static_cast<size_t>(Z) * shape.chblocks * plan->S * kLanes));
+  }
   w.max_tiles = shape.max_tiles;
   w.bytes = off;
   return w;
@@ -344,6 +374,30 @@ static sc_status check_common(const char* fn, const sc_plan* plan, int64_t n, co
   return SC_OK;
 }
 
+// Checks of the tensor arguments and the launches of the forward pass, shared by sc_forward and
+// sc_forward_noalloc; the plan's device is current.
+static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z,
+                                  const void* W, void* B, const sc::Workspace& ws, const sc::LaunchShape& shape,
+                                  uint32_t flags, hipStream_t stream) {
+  if (!A || !z || !W || !B) return fail(SC_ERR_INVALID_ARG, std::string(fn) + ": NULL tensor argument");
+  if (misaligned(A, 16) || misaligned(W, 16) || misaligned(B, 16) || misaligned(z, 4))
+    return fail(SC_ERR_INVALID_ARG, std::string(fn) + ": tensor pointer not 16-byte aligned");
+  hipError_t e = hipSuccess;
+  if (!(flags & SC_REUSE_GROUPING)) {
+    e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
+    if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": grouping launch").c_str());
+  }
+  if (plan->profile) (void)hipEventRecord(plan->ev[0], stream);
+  e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, W, B, ws, shape, stream)
+                        : sc::launch_generic_forward(plan, n_nodes, A, W, B, ws, shape, stream);
+  if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": kernel launch").c_str());
+  if (plan->profile) {
+    (void)hipEventRecord(plan->ev[1], stream);
+    plan->ev_used[0] = true;
+  }
+  return SC_OK;
+}
+
 sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W, void* B,
                      void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream) {
   sc::LaunchShape shape;
@@ -351,26 +405,36 @@ sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_
   sc_status st = check_common("sc_forward", plan, n_nodes, workspace, workspace_bytes, &shape, &ws);
   if (st != SC_OK) return st;
   if (n_nodes == 0) return SC_OK;
-  if (!A || !z || !W || !B) return fail(SC_ERR_INVALID_ARG, "sc_forward: NULL tensor argument");
-  if (misaligned(A, 16) || misaligned(W, 16) || misaligned(B, 16) || misaligned(z, 4))
-    return fail(SC_ERR_INVALID_ARG, "sc_forward: tensor pointer not 16-byte aligned");
   DeviceGuard guard(plan->cfg.device);
   if (!guard.ok) return fail(SC_ERR_HIP, "sc_forward: cannot make the plan's device current");
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipError_t e = hipSuccess;
-  if (!(flags & SC_REUSE_GROUPING)) {
-    e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
-    if (e != hipSuccess) return fail_hip(e, "sc_forward: grouping launch");
-  }
-  if (plan->profile) (void)hipEventRecord(plan->ev[0], stream);
-  e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, W, B, ws, shape, stream)
-                        : sc::launch_generic_forward(plan, n_nodes, A, W, B, ws, shape, stream);
-  if (e != hipSuccess) return fail_hip(e, "sc_forward: kernel launch");
-  if (plan->profile) {
-    (void)hipEventRecord(plan->ev[1], stream);
-    plan->ev_used[0] = true;
-  }
-  return SC_OK;
+  return forward_launches("sc_forward", plan, n_nodes, A, z, W, B, ws, shape, flags, static_cast<hipStream_t>(hip_stream));
+}
+
+sc_status sc_forward_noalloc(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W, void* B,
+                             void* hip_stream) {
+  if (!plan) return fail(SC_ERR_INVALID_ARG, "sc_forward_noalloc: plan is NULL");
+  if (plan->host_only) return fail(SC_ERR_UNSUPPORTED, "sc_forward_noalloc: plan was created with SC_PLAN_HOST_ONLY");
+  if (n_nodes < 0) return fail(SC_ERR_INVALID_ARG, "sc_forward_noalloc: n_nodes < 0");
+  if (n_nodes > SC_NOALLOC_MAX_NODES)
+    return fail(SC_ERR_WORKSPACE, "sc_forward_noalloc: n_nodes = " + std::to_string(n_nodes) + " exceeds SC_NOALLOC_MAX_NODES = " +
+                                      std::to_string(SC_NOALLOC_MAX_NODES) + "; use sc_forward with a workspace");
+  const sc::LaunchShape shape = sc::launch_shape(plan, n_nodes);
+  const size_t need = sc::carve_workspace(plan, n_nodes, shape, nullptr, true).bytes;
+  if (need > SC_NOALLOC_SCRATCH_BYTES)
+    return fail(SC_ERR_WORKSPACE, "sc_forward_noalloc: this plan needs " + std::to_string(need) + " bytes of scratch for " +
+                                      std::to_string(n_nodes) + " nodes, more than SC_NOALLOC_SCRATCH_BYTES = " +
+                                      std::to_string(SC_NOALLOC_SCRATCH_BYTES) + "; use sc_forward with a workspace");
+  if (n_nodes == 0) return SC_OK;
+  DeviceGuard guard(plan->cfg.device);
+  if (!guard.ok) return fail(SC_ERR_HIP, "sc_forward_noalloc: cannot make the plan's device current");
+  void* base = nullptr;
+  const sc_status st = noalloc_scratch(plan->cfg.device, &base);
+  if (st != SC_OK) return st;
+  // Nothing in the scratch has to start at zero: the grouping pass writes every word the forward
+  // kernel reads (permutation, offsets, all max_tiles tile descriptors), whatever an earlier,
+  // larger call left there.
+  const sc::Workspace ws = sc::carve_workspace(plan, n_nodes, shape, base, true);
+  return forward_launches("sc_forward_noalloc", plan, n_nodes, A, z, W, B, ws, shape, 0, static_cast<hipStream_t>(hip_stream));
 }
 
 sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W, const void* dB,

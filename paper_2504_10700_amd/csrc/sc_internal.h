@@ -97,7 +97,9 @@ inline bool misaligned(const void* p, size_t a) { return reinterpret_cast<uintpt
 sc_status set_error(sc_status code, const std::string& msg);
 
 LaunchShape launch_shape(const sc_plan* plan, int64_t n_nodes);
-Workspace carve_workspace(const sc_plan* plan, int64_t n_nodes, const LaunchShape& shape, void* base);
+// forward_only: the part the forward pass uses (the grouping), without the weight-gradient rows.
+Workspace carve_workspace(const sc_plan* plan, int64_t n_nodes, const LaunchShape& shape, void* base,
+                          bool forward_only = false);
 
 // kernels (defined in the .hip files); all return hipGetLastError() of their launches
 hipError_t launch_grouping(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,

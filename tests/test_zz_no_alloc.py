@@ -1,0 +1,84 @@
+"""sc_forward_noalloc (the entry point that allocates nothing: grouping kept in a fixed device
+array inside the library) against sc_forward with a caller's workspace, through the C ABI:
+bit-for-bit equal results (same kernels), on calls in a row with shrinking inputs, so that the
+array still holds a larger call's contents when a smaller one runs; the oracle pins one case."""
+import numpy as np
+import pytest
+
+from oracle import symmetric_contraction as osc
+from paper_2504_10700_amd import workloads
+from gpu_util import GpuRun, check, oracle_forward
+
+pytestmark = pytest.mark.gpu
+
+O01 = ((0, 1), (1, -1))
+
+
+@pytest.fixture(scope="module")
+def sc():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2504_10700_amd import binding
+    return binding
+
+
+def both_ways(sc, run, n):
+    import torch
+    run.N = n
+    B_ws = torch.full((n, run.wl.num_channels, run.wl.n_LM), float("nan"), dtype=run.tdt, device=run.dev)
+    B_na = torch.full_like(B_ws, float("nan"))
+    sc.sc_forward(run.plan, n, run.A, run.z, run.W, B_ws, run.ws, run.ws_bytes)
+    sc.sc_forward_noalloc(run.plan, n, run.A, run.z, run.W, B_na)
+    torch.cuda.synchronize()
+    a, b = B_ws.cpu().numpy(), B_na.cpu().numpy()
+    assert np.isfinite(a).all()
+    assert np.array_equal(a, b), f"n={n}: results differ from sc_forward"
+    return b
+
+
+@pytest.mark.parametrize("flags", [0, 2])
+def test_matches_sc_forward_on_calls_in_a_row_with_shrinking_inputs(sc, flags):
+    wl = workloads.Workload("noalloc", 20_000, 89, 128, 3, 3, O01, "f32", 5101)
+    T = osc.build_tables(osc.OracleConfig(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps))
+    inp = workloads.make_inputs(wl, T.paths)
+    run = GpuRun(sc, wl, inp, flags)      # workspace sized for the largest call
+    A, z, W, _ = run.inputs_as_computed()
+    sizes = (20_000, 5_000, 700, 1) if flags == 0 else (2_000, 300)   # 20 000: grouping in three launches
+    for n in sizes:
+        print(f"sc_forward_noalloc n={n} flags={flags}", flush=True)
+        B = both_ways(sc, run, n)
+    n = sizes[-2]
+    B = both_ways(sc, run, n)
+    check("B", B, oracle_forward(osc, T, A[:n], z[:n], W), "f32")
+    run.close()
+
+
+def test_fp64_tiny_configuration(sc):
+    wl = workloads.WORKLOADS["tiny"]
+    T = osc.build_tables(osc.OracleConfig(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps))
+    run = GpuRun(sc, wl, workloads.make_inputs(wl, T.paths))
+    A, z, W, _ = run.inputs_as_computed()
+    for n in (64, 9):
+        B = both_ways(sc, run, n)
+        check("B", B, osc.forward(T, A[:n], z[:n], W), "f64")
+    run.close()
+
+
+def test_limits_and_errors(sc):
+    import torch
+    plan = sc.sc_plan_create(128, 3, 3, 89, O01, sc.SC_F32, 0)
+    x = torch.zeros(64, device="cuda:0")
+    with pytest.raises(sc.ScError) as e:
+        sc.sc_forward_noalloc(plan, sc.SC_NOALLOC_MAX_NODES + 1, x, x, x, x)
+    assert e.value.status == sc.SC_ERR_WORKSPACE and "SC_NOALLOC_MAX_NODES" in str(e.value)
+    with pytest.raises(sc.ScError) as e:
+        sc.sc_forward_noalloc(plan, 4, None, x, x, x)
+    assert e.value.status == sc.SC_ERR_INVALID_ARG
+    sc.sc_forward_noalloc(plan, 0, None, None, None, None)      # empty batch: nothing to do
+    sc.sc_plan_destroy(plan)
+    # a plan whose grouping does not fit the array at the node limit is refused, not truncated
+    big = sc.sc_plan_create(64, 3, 3, 1024, O01, sc.SC_F32, 0)
+    with pytest.raises(sc.ScError) as e:
+        sc.sc_forward_noalloc(big, sc.SC_NOALLOC_MAX_NODES, x, x, x, x)
+    assert e.value.status == sc.SC_ERR_WORKSPACE and "SC_NOALLOC_SCRATCH_BYTES" in str(e.value)
+    sc.sc_plan_destroy(big)
