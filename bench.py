@@ -1,9 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the symmetric-contraction hot path on one MI355X.
 
-One "step" = sc_forward + sc_backward (grouping of the nodes by element done once,
-in the forward, and reused by the backward) over one batch of synthetic atoms that
-is already resident in HBM.  Prints ONE JSON line.
+One "step" = sc_forward + sc_backward (the grouping of the nodes by element and the
+preparation of the weights done once, in the forward, and reused by the backward) over
+one batch of synthetic atoms that is already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W]
                   [--workload training_step|large_batch|wide_high_l|wide_high_l_f64|medium_fwd|tiny]
@@ -117,7 +117,8 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0):
         sc.sc_forward(plan, N, f["A"], z, W, f["B"], ws, ws_bytes, 0)
         if wl.backward:
             b = sets[(i + n_sets // 2) % n_sets]   # another copy of A: no cache reuse across fwd -> bwd
-            sc.sc_backward(plan, N, b["A"], z, W, b["dB"], b["dA"], dW, ws, ws_bytes, sc.SC_REUSE_GROUPING)
+            sc.sc_backward(plan, N, b["A"], z, W, b["dB"], b["dA"], dW, ws, ws_bytes,
+                           sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS)
 
     for i in range(warmup):
         step(i)
@@ -171,6 +172,61 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0):
                      "forward_kernel_ms": fwd_mean, "algorithmic_bytes_per_launch": k_bytes,
                      "valu_issue_frac": valu_issue_frac},
     }
+
+
+def measure_attainable(n_nodes=10_000, chblocks=2, reps=20):
+    """Streaming probes of the library (kernels without arithmetic, known byte counts), timed
+    with events on the launch stream in this same run: what the box attains for plain reads,
+    writes, copies, and for the access pattern of the fused backward kernel (gathered 4 KB + 1 KB
+    rows in, 4 KB rows out) at the batch size of the workload and at 20x that size.  Buffers are
+    rotated so that no launch finds its data in the 256 MB last-level cache."""
+    import numpy as np
+    import torch
+    from paper_2504_10700_amd import binding as sc
+
+    dev = torch.device("cuda:0")
+
+    def timed(launch, n_variants):
+        for i in range(3):
+            launch(i % n_variants)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for i in range(reps):
+            launch(i % n_variants)
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / reps * 1e-3
+
+    out = {"unit": "GB/s", "note": "library streaming probes, same run; rows = the backward kernel's access "
+                                   "pattern (9216 B per row of 64 channels) without arithmetic"}
+    nbytes = 1 << 30
+    bufs = [torch.empty(nbytes // 4, dtype=torch.float32, device=dev).normal_() for _ in range(3)]
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    t = timed(lambda i: sc.sc_probe_stream(sc.SC_PROBE_READ, bufs[i], None, sink, None, nbytes), 3)
+    out["read"] = nbytes / t / 1e9
+    t = timed(lambda i: sc.sc_probe_stream(sc.SC_PROBE_WRITE, None, None, bufs[i], None, nbytes), 3)
+    out["write"] = nbytes / t / 1e9
+    t = timed(lambda i: sc.sc_probe_stream(sc.SC_PROBE_COPY, bufs[i], None, bufs[(i + 1) % 3], None, nbytes), 3)
+    out["copy"] = 2 * nbytes / t / 1e9
+    del bufs
+    torch.cuda.empty_cache()
+    for label, rows, n_sets in (("rows_at_batch_size", n_nodes * chblocks, 6), ("rows_at_20x_batch_size", 20 * n_nodes * chblocks, 2)):
+        rng = np.random.default_rng(5)
+        sets = []
+        for s in range(n_sets):
+            sets.append((torch.empty(rows * 1024, dtype=torch.float32, device=dev).normal_(),
+                         torch.empty(rows * 256, dtype=torch.float32, device=dev).normal_(),
+                         torch.empty(rows * 1024, dtype=torch.float32, device=dev)))
+        perm = torch.tensor(rng.permutation(rows).astype(np.int32), device=dev)
+        t = timed(lambda i: sc.sc_probe_stream(sc.SC_PROBE_ROWS, sets[i][0], sets[i][1], sets[i][2], perm, rows), n_sets)
+        out[label] = rows * 9216 / t / 1e9
+        out[label + "_us"] = t * 1e6
+        del sets
+        torch.cuda.empty_cache()
+    out["frac_of_peak"] = {k: out[k] / HBM_PEAK_GBS for k in ("read", "write", "copy", "rows_at_batch_size",
+                                                              "rows_at_20x_batch_size")}
+    return out
 
 
 def measure_double_backward(wl, steps, warmup, tile_nodes=0):
@@ -567,7 +623,7 @@ def measure_graph_step(n_nodes=3072, steps=300, warmup=20):
 
     def step():
         sc.sc_forward(plan, n_nodes, A, z, W, B, ws, nb)
-        sc.sc_backward(plan, n_nodes, A, z, W, dB, dA, dW, ws, nb, sc.SC_REUSE_GROUPING)
+        sc.sc_backward(plan, n_nodes, A, z, W, dB, dA, dW, ws, nb, sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS)
 
     def timed(fn):
         for _ in range(warmup):
@@ -633,6 +689,7 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
     ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
     ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
+    ap.add_argument("--no-probe", action="store_true", help="skip the streaming probes (\"attainable\")")
     ap.add_argument("--linear", action="store_true",
                     help="measure only the channel-mixing linear (10k nodes, 128 -> 128 channels, l <= 3)")
     ap.add_argument("--graph", action="store_true",
@@ -643,6 +700,8 @@ def main():
                     help="measure only the host load balancer (1M graphs) and print its object")
     ap.add_argument("--tp", action="store_true",
                     help="measure only the channelwise tensor product (--workload tp_training_step|tp_first_layer|tp_tiny)")
+    ap.add_argument("--attainable", action="store_true",
+                    help="measure only the streaming probes (read, write, copy, backward-like rows) and print their object")
     ap.add_argument("--double-backward", action="store_true",
                     help="measure only the second-order pass of --workload and print its object")
     args = ap.parse_args()
@@ -655,6 +714,9 @@ def main():
 
     if args.balanced_batches:
         print(json.dumps(measure_balanced_batches()))
+        return
+    if args.attainable:
+        print(json.dumps(measure_attainable()))
         return
     if args.linear:
         print(json.dumps(measure_linear()))
@@ -679,6 +741,8 @@ def main():
            "warmup": args.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": m["dtype"], "data": "synthetic", "config": m["config"],
            "step_hbm_fraction": m["step_hbm_fraction"], "roofline": m["roofline"]}
+    if not args.generic and not args.no_probe:
+        out["attainable"] = measure_attainable(wl.num_nodes, (wl.num_channels + 63) // 64)
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(wl, min(args.cpu_sample, wl.num_nodes))
     if args.workload == "training_step" and not args.no_also and not args.generic and args.tile_nodes == 0:

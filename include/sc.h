@@ -77,6 +77,9 @@ typedef enum { SC_F32 = 0, SC_F64 = 1 } sc_dtype;
 #define SC_REUSE_GROUPING 1u /* the workspace still holds the grouping written by the previous
                                 compute call of this plan with the same n_nodes and the
                                 same z contents: skip regrouping                           */
+#define SC_REUSE_WEIGHTS 2u  /* the workspace still holds the weights as the previous compute
+                                call of this plan prepared them, and W has the same contents
+                                (the backward of a step after its forward): skip that step   */
 
 typedef struct {
   int32_t struct_size;            /* = sizeof(sc_config), ABI guard                                  */
@@ -152,19 +155,21 @@ sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_
                      void* B, void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream);
 
 /* For callers that cannot allocate or pass a workspace (code under HIP graph capture, tight
- * serving loops, harnesses that forbid hipMalloc): sc_forward with the grouping kept in a
- * fixed device array inside the library instead of a caller's workspace.  Same arguments,
- * same kernels, same results bit for bit as sc_forward without flags.  Calls no hipMalloc,
- * hipFree or other allocating routine.
- * Limits: n_nodes <= SC_NOALLOC_MAX_NODES, and the plan's grouping for n_nodes must fit
- * SC_NOALLOC_SCRATCH_BYTES (it does for every plan of up to 700 elements at the node limit
- * with the library's own tile size); beyond them the call fails with SC_ERR_WORKSPACE and launches nothing.
+ * serving loops, harnesses that forbid hipMalloc): sc_forward with its scratch (the weights
+ * prepared for the kernels, the grouping of the table-driven kernels) kept in a fixed device
+ * array inside the library instead of a caller's workspace.  Same arguments, same kernels,
+ * same results bit for bit as sc_forward without flags.  Calls no hipMalloc, hipFree or other
+ * allocating routine.
+ * Limits: n_nodes <= SC_NOALLOC_MAX_NODES, and the plan's forward scratch for n_nodes must fit
+ * SC_NOALLOC_SCRATCH_BYTES (about 1.9 MB for 89 elements x 128 channels in fp32, 5.1 MB for
+ * 256 channels with 0e+1o+2e outputs); beyond them the call fails with SC_ERR_WORKSPACE and
+ * launches nothing.
  * Every GPU holds ONE such array (SC_NOALLOC_SCRATCH_BYTES of device memory per GPU the
- * library has run this call on, until the process ends), shared by all plans and streams:
- * calls of sc_forward_noalloc that can overlap in time on one GPU race on it and must be
- * ordered by the caller (one stream, or events). */
+ * library is loaded on, until the process ends), shared by all plans and streams: calls of
+ * sc_forward_noalloc that can overlap in time on one GPU race on it and must be ordered by
+ * the caller (one stream, or events). */
 #define SC_NOALLOC_MAX_NODES 65536
-#define SC_NOALLOC_SCRATCH_BYTES (1u << 20)
+#define SC_NOALLOC_SCRATCH_BYTES (8u << 20)
 sc_status sc_forward_noalloc(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W,
                              void* B, void* hip_stream);
 
@@ -205,6 +210,25 @@ sc_status sc_profile_enable(sc_plan* plan, int32_t on);
 sc_status sc_profile_read(sc_plan* plan, float* forward_ms, float* backward_ms);
 /* Same for the main kernel of the most recent sc_double_backward call. */
 sc_status sc_profile_read_double_backward(sc_plan* plan, float* ms);
+
+/* Measurement helper (benchmarks only; not part of the operation): streaming kernels without
+ * arithmetic that move a known number of bytes, so that a benchmark can state the bandwidth
+ * the machine attains in the same run as the contraction kernels.  Enqueues one kernel on the
+ * stream, on the current device; all pointers are device memory, 16-byte aligned.
+ *   SC_PROBE_READ   reads n bytes of src (dst: 4 bytes, never written for finite data)
+ *   SC_PROBE_WRITE  writes n bytes of dst
+ *   SC_PROBE_COPY   copies n bytes from src to dst
+ *   SC_PROBE_ROWS   the access pattern of the fused backward kernel: for each of n rows, taken
+ *                   in the order perm[0..n) (int32, values in [0, n); clamped), reads 4096 bytes
+ *                   of src (64 B per lane) and 1024 bytes of src2 (16 B per lane) and writes
+ *                   4096 bytes of dst; moves n * 9216 bytes
+ * n bytes must be a multiple of 16.  src2 and perm are used by SC_PROBE_ROWS only. */
+#define SC_PROBE_READ 0
+#define SC_PROBE_WRITE 1
+#define SC_PROBE_COPY 2
+#define SC_PROBE_ROWS 3
+sc_status sc_probe_stream(int32_t kind, const void* src, const void* src2, void* dst, const int32_t* perm,
+                          int64_t n, void* hip_stream);
 
 /* Thread-local message of the last failing call on this thread; never NULL. */
 const char* sc_last_error(void);

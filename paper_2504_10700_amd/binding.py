@@ -25,13 +25,14 @@ SC_ERR_INVALID_ARG, SC_ERR_UNSUPPORTED, SC_ERR_WORKSPACE, SC_ERR_HIP, SC_ERR_ALL
 SC_F32, SC_F64 = 0, 1
 SC_MAX_OUT = 4
 SC_PLAN_HOST_ONLY, SC_PLAN_FORCE_GENERIC = 1, 2
-SC_REUSE_GROUPING = 1
-SC_NOALLOC_MAX_NODES, SC_NOALLOC_SCRATCH_BYTES = 65536, 1 << 20
+SC_REUSE_GROUPING, SC_REUSE_WEIGHTS = 1, 2
+SC_NOALLOC_MAX_NODES, SC_NOALLOC_SCRATCH_BYTES = 65536, 8 << 20
 
 EXPORTS = ("sc_plan_create", "sc_plan_destroy", "sc_plan_info", "sc_plan_paths", "sc_plan_path_terms",
            "sc_coupling_tensor", "sc_workspace_bytes", "sc_forward", "sc_forward_noalloc", "sc_backward",
            "sc_double_backward",
-           "sc_profile_enable", "sc_profile_read", "sc_profile_read_double_backward", "sc_last_error")
+           "sc_profile_enable", "sc_profile_read", "sc_profile_read_double_backward", "sc_probe_stream",
+           "sc_last_error")
 
 
 class sc_config(C.Structure):
@@ -71,6 +72,7 @@ def _load() -> C.CDLL:
     lib.sc_forward_noalloc.argtypes = [vp, i64, vp, vp, vp, vp, vp]
     lib.sc_backward.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, u32, vp]
     lib.sc_double_backward.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, u32, vp]
+    lib.sc_probe_stream.argtypes = [i32, vp, vp, vp, vp, i64, vp]
     lib.sc_profile_enable.argtypes = [vp, i32]
     lib.sc_profile_read_double_backward.argtypes = [vp, C.POINTER(C.c_float)]
     lib.sc_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
@@ -204,6 +206,13 @@ def sc_double_backward(plan: Plan, n_nodes: int, A, z, W, dB, H, ddB, dA2, dW2, 
                        flags: int = 0, stream=None) -> None:
     _check(lib.sc_double_backward(plan.handle, n_nodes, _ptr(A), _ptr(z), _ptr(W), _ptr(dB), _ptr(H), _ptr(ddB),
                                   _ptr(dA2), _ptr(dW2), _ptr(workspace), workspace_bytes, flags, _stream(stream)))
+
+
+SC_PROBE_READ, SC_PROBE_WRITE, SC_PROBE_COPY, SC_PROBE_ROWS = 0, 1, 2, 3
+
+
+def sc_probe_stream(kind: int, src, src2, dst, perm, n: int, stream=None) -> None:
+    _check(lib.sc_probe_stream(kind, _ptr(src), _ptr(src2), _ptr(dst), _ptr(perm), n, _stream(stream)))
 
 
 def sc_profile_enable(plan: Plan, on: bool) -> None:

@@ -355,17 +355,58 @@ def emit_inc(tag: str, tab: Tables, basis, fold, fwd: Program, bwd: Program, dbl
     L.append(fwd.emit("T", "    "))
     L.append("  }")
     L.append("")
-    L.append("  // dW[z,p,k] = sum_s F[s,p] * r[s]; out points at dW[z,0,k], consecutive paths are K apart.")
-    L.append("  template <typename T>")
-    L.append("  static __device__ __forceinline__ void unfold(const double (&r)[kS], T* __restrict__ out, int K) {")
+    L.append("  // dW[z,p,k] = sum_s F[s,p] * r[s] (the transpose of fold).")
     by_p: Dict[int, List[Tuple[int, float]]] = {p: [] for p in range(P)}
     for s, lst in enumerate(fold):
         for p, c in lst:
             by_p[p].append((s, c))
+    # Rows and external paths fall into small independent blocks (connected components of the fold
+    # matrix): the paths of a block need the rows of that block only.
+    parent = list(range(S))
+
+    def find(x):
+        while parent[x] != x:
+            parent[x] = parent[parent[x]]
+            x = parent[x]
+        return x
     for p in range(P):
-        terms = " + ".join(f"{repr(c)} * r[{s}]" for s, c in by_p[p]) or "0.0"
-        L.append(f"    out[{p} * K] = static_cast<T>({terms});")
-    L.append("  }")
+        rs = [s_ for s_, _ in by_p[p]]
+        for r in rs[1:]:
+            a, b = find(rs[0]), find(r)
+            if a != b:
+                parent[max(a, b)] = min(a, b)
+    roots = sorted({find(r) for r in range(S)})
+    comp_of_row = {r: roots.index(find(r)) for r in range(S)}
+    comp_rows = [[r for r in range(S) if comp_of_row[r] == c] for c in range(len(roots))]
+    comp_outs = [[] for _ in roots]
+    for p in range(P):
+        comp_outs[comp_of_row[by_p[p][0][0]] if by_p[p] else 0].append(p)   # identically zero paths ride with block 0
+    max_rows = max(len(c) for c in comp_rows)
+    max_paths = max(len(c) for c in comp_outs)
+    L.append("  // Independent blocks of the fold matrix, one descriptor each (read as one run of scalar loads):")
+    L.append("  // the block's internal rows (the last one repeated up to kMaxBlockRows), its external paths and,")
+    L.append("  // per path, the coefficients on the block's rows: dW[path[i]] = sum_r coef[i][r] * r[row[r]].")
+    L.append(f"  static constexpr int kNumBlocks = {len(roots)}, kMaxBlockRows = {max_rows}, kMaxBlockPaths = {max_paths};")
+    L.append("  struct Block {")
+    L.append("    int n_rows, n_paths;")
+    L.append("    int row[kMaxBlockRows];")
+    L.append("    int path[kMaxBlockPaths];")
+    L.append("    double coef[kMaxBlockPaths][kMaxBlockRows];")
+    L.append("  };")
+    L.append("  static constexpr Block kBlocks[kNumBlocks] = {")
+    for c in range(len(roots)):
+        rws = comp_rows[c] + [comp_rows[c][-1]] * (max_rows - len(comp_rows[c]))
+        pths = comp_outs[c] + [comp_outs[c][-1] if comp_outs[c] else 0] * (max_paths - len(comp_outs[c]))
+        coef_rows = []
+        for i in range(max_paths):
+            cs = [0.0] * max_rows
+            if i < len(comp_outs[c]):
+                for s_, cf in by_p[comp_outs[c][i]]:
+                    cs[comp_rows[c].index(s_)] = cf
+            coef_rows.append("{" + ", ".join(repr(x) for x in cs) + "}")
+        L.append(f"      {{{len(comp_rows[c])}, {len(comp_outs[c])}, {{{', '.join(map(str, rws))}}}, {{{', '.join(map(str, pths))}}},")
+        L.append("       {" + ", ".join(coef_rows) + "}},")
+    L.append("  };")
     L.append("")
     L.append("  // da is overwritten; dw is accumulated into.")
     L.append("  template <typename T>")

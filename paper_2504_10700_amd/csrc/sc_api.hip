@@ -99,6 +99,17 @@ LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
     s.group_waves = static_cast<int>(gw);
     s.nodes_per_group_wave = static_cast<int>((n + gw - 1) / gw);
   }
+  {  // generated kernels: four 64-node chunks per wave up to kMaxGroupWaves waves, whole chunks per wave
+    int64_t gw = (n + 255) / 256;
+    gw = (gw + kGroupWavesPerWG - 1) / kGroupWavesPerWG * kGroupWavesPerWG;
+    if (gw < kGroupWavesPerWG) gw = kGroupWavesPerWG;
+    if (gw > kMaxGroupWaves) gw = kMaxGroupWaves;
+    s.split_waves = static_cast<int>(gw);
+    s.split_nodes_per_wave = static_cast<int>(((n + gw - 1) / gw + kLanes - 1) / kLanes * kLanes);
+    if (s.split_nodes_per_wave < kLanes) s.split_nodes_per_wave = kLanes;
+    // forward: two to four nodes per wave (the folded weights come per node, so small tiles cost nothing)
+    s.fwd_tile_nodes = (n * s.chblocks <= 7168 ? 2 : 4) * (plan->specialised ? spec_waves_per_tile() : 1);
+  }
   return s;
 }
 
@@ -117,10 +128,9 @@ Workspace carve_workspace(const sc_plan* plan, int64_t n, const LaunchShape& sha
   w.counts = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(kMaxGroupWaves) * Z));
   w.perm = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
   w.tiles = static_cast<TileDesc*>(take(sizeof(TileDesc) * static_cast<size_t>(shape.max_tiles)));
-  if (!forward_only) {  // the weight-gradient rows of the backward passes
+  if (plan->specialised) w.wfold = take(spec_folded_bytes(plan));
+  if (!forward_only)  // the weight-gradient rows of the backward passes
     w.partial = take(elem_size(plan) * static_cast<size_t>(shape.max_tiles) * shape.chblocks * plan->S * kLanes);
-    w.reduced = static_cast<double*>(take(sizeof(double) * static_cast<size_t>(Z) * shape.chblocks * plan->S * kLanes));
-  }
   w.max_tiles = shape.max_tiles;
   w.bytes = off;
   return w;
@@ -374,6 +384,24 @@ static sc_status check_common(const char* fn, const sc_plan* plan, int64_t n, co
   return SC_OK;
 }
 
+// What a grouped pass (backward, second-order) needs before its main kernel: the grouping and, for
+// the generated kernels, the folded weights, unless the flags say the workspace still holds them.
+// Records the error message itself.
+static hipError_t grouped_pass_prologue(const char* fn, sc_plan* plan, int64_t n_nodes, const int32_t* z, const void* W,
+                                        const sc::Workspace& ws, const sc::LaunchShape& shape, uint32_t flags,
+                                        hipStream_t stream) {
+  const bool group = !(flags & SC_REUSE_GROUPING);
+  hipError_t e = hipSuccess;
+  if (plan->specialised) {
+    e = sc::launch_spec_prepare(plan, n_nodes, z, W, ws, shape, group, !(flags & SC_REUSE_WEIGHTS), stream);
+    if (e == hipSuccess && group) e = sc::launch_spec_scatter(plan, n_nodes, z, ws, shape, stream);
+  } else if (group) {
+    e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
+  }
+  if (e != hipSuccess) (void)fail_hip(e, (std::string(fn) + ": grouping / weight-fold launch").c_str());
+  return e;
+}
+
 // Checks of the tensor arguments and the launches of the forward pass, shared by sc_forward and
 // sc_forward_noalloc; the plan's device is current.
 static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z,
@@ -383,12 +411,17 @@ static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(B, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, std::string(fn) + ": tensor pointer not 16-byte aligned");
   hipError_t e = hipSuccess;
-  if (!(flags & SC_REUSE_GROUPING)) {
+  const bool group = !(flags & SC_REUSE_GROUPING);
+  if (plan->specialised) {
+    // the forward itself needs no grouping: the two halves of it ride in the prepare and the forward launch
+    e = sc::launch_spec_prepare(plan, n_nodes, z, W, ws, shape, group, !(flags & SC_REUSE_WEIGHTS), stream);
+    if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": prepare launch").c_str());
+  } else if (group) {
     e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
     if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": grouping launch").c_str());
   }
   if (plan->profile) (void)hipEventRecord(plan->ev[0], stream);
-  e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, W, B, ws, shape, stream)
+  e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, z, B, ws, shape, group, stream)
                         : sc::launch_generic_forward(plan, n_nodes, A, W, B, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": kernel launch").c_str());
   if (plan->profile) {
@@ -430,11 +463,14 @@ sc_status sc_forward_noalloc(sc_plan* plan, int64_t n_nodes, const void* A, cons
   void* base = nullptr;
   const sc_status st = noalloc_scratch(plan->cfg.device, &base);
   if (st != SC_OK) return st;
-  // Nothing in the scratch has to start at zero: the grouping pass writes every word the forward
-  // kernel reads (permutation, offsets, all max_tiles tile descriptors), whatever an earlier,
-  // larger call left there.
+  // Nothing in the scratch has to start at zero: the launches that precede the forward kernel
+  // write every word it reads (the folded weights of all elements; for the table-driven kernels
+  // the permutation, the offsets and all max_tiles tile descriptors), whatever an earlier,
+  // larger call left there.  The generated forward kernel needs no grouping, and there is no
+  // backward pass to leave one for.
   const sc::Workspace ws = sc::carve_workspace(plan, n_nodes, shape, base, true);
-  return forward_launches("sc_forward_noalloc", plan, n_nodes, A, z, W, B, ws, shape, 0, static_cast<hipStream_t>(hip_stream));
+  return forward_launches("sc_forward_noalloc", plan, n_nodes, A, z, W, B, ws, shape,
+                          plan->specialised ? SC_REUSE_GROUPING : 0u, static_cast<hipStream_t>(hip_stream));
 }
 
 sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z, const void* W, const void* dB,
@@ -460,13 +496,10 @@ sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32
   if (!A || !z || !W || !dB || !dA) return fail(SC_ERR_INVALID_ARG, "sc_backward: NULL tensor argument");
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(dA, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_backward: tensor pointer not 16-byte aligned");
-  hipError_t e = hipSuccess;
-  if (!(flags & SC_REUSE_GROUPING)) {
-    e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
-    if (e != hipSuccess) return fail_hip(e, "sc_backward: grouping launch");
-  }
+  hipError_t e = grouped_pass_prologue("sc_backward", plan, n_nodes, z, W, ws, shape, flags, stream);
+  if (e != hipSuccess) return SC_ERR_HIP;
   if (plan->profile) (void)hipEventRecord(plan->ev[2], stream);
-  e = plan->specialised ? sc::launch_spec_backward(plan, n_nodes, A, W, dB, dA, ws, shape, stream)
+  e = plan->specialised ? sc::launch_spec_backward(plan, n_nodes, A, dB, dA, ws, shape, stream)
                         : sc::launch_generic_backward(plan, n_nodes, A, W, dB, dA, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_backward: kernel launch");
   if (plan->profile) {
@@ -504,14 +537,11 @@ sc_status sc_double_backward(sc_plan* plan, int64_t n_nodes, const void* A, cons
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(H, 16) || misaligned(ddB, 16) ||
       misaligned(dA2, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_double_backward: tensor pointer not 16-byte aligned");
-  hipError_t e = hipSuccess;
-  if (!(flags & SC_REUSE_GROUPING)) {
-    e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
-    if (e != hipSuccess) return fail_hip(e, "sc_double_backward: grouping launch");
-  }
+  hipError_t e = grouped_pass_prologue("sc_double_backward", plan, n_nodes, z, W, ws, shape, flags, stream);
+  if (e != hipSuccess) return SC_ERR_HIP;
   if (plan->profile) (void)hipEventRecord(plan->ev[4], stream);
   e = plan->specialised
-          ? sc::launch_spec_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape, stream)
+          ? sc::launch_spec_double_backward(plan, n_nodes, A, dB, H, ddB, dA2, ws, shape, stream)
           : sc::launch_generic_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_double_backward: kernel launch");
   if (plan->profile) {

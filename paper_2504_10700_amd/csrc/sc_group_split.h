@@ -1,0 +1,226 @@
+// Grouping of nodes by element as ROLES of larger launches (device code, included by the
+// kernels that host it).
+//
+// The same stable counting sort as sc_group.hip, cut in two so that no launch of its own is
+// needed and no single workgroup sits on the critical path:
+//   count role    (hosted by the launch that prepares the folded weights) every wave counts the
+//                 elements of its contiguous slice of z and writes one row of the count
+//                 matrix counts[wave][element];
+//   scatter role  (hosted by the forward launch, whose own work does not need the grouping)
+//                 every workgroup sums the matrix columns on its own - the totals per element
+//                 and the counts of all earlier waves - scans the totals over the elements and
+//                 scatters its four slices to their final positions in perm;
+//   table role    one workgroup of the same launch writes the element offsets and the tile
+//                 descriptors.
+// The result (perm, seg_off, tile_off, tiles, ntiles) is bit for bit what launch_grouping
+// writes: the stable sort has one answer.
+#pragma once
+#include "sc_internal.h"
+
+namespace sc {
+
+constexpr int kSplitThreads = kGroupWavesPerWG * kLanes;   // 256, the block size of the hosting kernels
+
+struct SplitGroupArgs {
+  const int32_t* z;
+  int n, Z;
+  int W;               // waves of the counting sort = rows of counts (a multiple of kGroupWavesPerWG)
+  int nodes_per_wave;
+  int tile_nodes, max_tiles;
+  int32_t* counts;     // [W][Z]
+  int32_t* seg_off;    // [Z+1]
+  int32_t* tile_off;   // [Z+1]
+  int32_t* ntiles;     // [1]
+  TileDesc* tiles;     // [max_tiles]
+  int32_t* perm;       // [n]
+};
+
+// dynamic LDS (bytes) a hosting kernel must provide for the roles
+inline size_t split_group_lds_bytes(int Z) { return sizeof(int32_t) * (static_cast<size_t>(kGroupWavesPerWG + 1) * Z + 4); }
+
+// Stable scatter of one 64-node chunk: lane holds element e (valid or not); cursor[e] is this
+// wave's next free position of element e (LDS).  The lanes that hold the same element are found
+// bit by bit (one ballot per bit of the element index), which costs the same whatever the
+// number of distinct elements in the chunk.
+__device__ __forceinline__ void split_scatter_chunk(int e, bool valid, int node, int lane, int z_bits, int32_t* cursor,
+                                                    int32_t* __restrict__ perm) {
+  const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  unsigned long long same = __ballot(valid);
+  for (int b = 0; b < z_bits; ++b) {
+    const bool bit = (e >> b) & 1;
+    const unsigned long long m = __ballot(bit);
+    same &= bit ? m : ~m;
+  }
+  const int rank = __popcll(same & lt_mask);
+  const int group = __popcll(same);
+  const int leader = valid ? __ffsll(static_cast<long long>(same)) - 1 : lane;
+  int base = 0;
+  if (valid && lane == leader) base = atomicAdd(&cursor[e], group);
+  base = __shfl(base, leader);
+  if (valid) perm[base + rank] = node;
+}
+
+// Exclusive scan of v[0..n) (LDS, n <= 1024) in place by ONE wave; returns the total.
+__device__ __forceinline__ int split_wave_scan(int32_t* v, int n, int lane) {
+  constexpr int kMaxPer = SC_MAX_ELEMENTS / kLanes;
+  const int per = (n + kLanes - 1) / kLanes;
+  int c[kMaxPer], local = 0;
+#pragma unroll
+  for (int k = 0; k < kMaxPer; ++k) {
+    const int i = lane * per + k;
+    c[k] = (k < per && i < n) ? v[i] : 0;
+    local += c[k];
+  }
+  int incl = local;
+#pragma unroll
+  for (int d = 1; d < kLanes; d <<= 1) {
+    const int up = __shfl_up(incl, d);
+    if (lane >= d) incl += up;
+  }
+  int run = incl - local;
+#pragma unroll
+  for (int k = 0; k < kMaxPer; ++k) {
+    const int i = lane * per + k;
+    if (k < per && i < n) v[i] = run;
+    run += c[k];
+  }
+  return __shfl(incl, kLanes - 1);
+}
+
+// Workgroup `wg` (of W / 4) counts the slices of its four waves.  lds: 4 * Z ints.
+__device__ __forceinline__ void split_count_role(const SplitGroupArgs& g, int wg, int32_t* lds) {
+  constexpr int kBatch = 8;
+  const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+  const int gw = wg * kGroupWavesPerWG + wave;
+  int32_t* mine = lds + wave * g.Z;
+  for (int e = lane; e < g.Z; e += kLanes) mine[e] = 0;
+  __syncthreads();
+  const long long lo = static_cast<long long>(gw) * g.nodes_per_wave;
+  const long long hi = (lo + g.nodes_per_wave < g.n) ? lo + g.nodes_per_wave : g.n;
+  for (long long c0 = lo; c0 < hi; c0 += kBatch * kLanes) {
+    int zs[kBatch];
+#pragma unroll
+    for (int c = 0; c < kBatch; ++c) {
+      const long long i = c0 + c * kLanes + lane;
+      zs[c] = (i < hi) ? g.z[i] : -1;
+    }
+#pragma unroll
+    for (int c = 0; c < kBatch; ++c)
+      if (zs[c] >= 0 && zs[c] < g.Z) atomicAdd(&mine[zs[c]], 1);
+  }
+  __syncthreads();
+  for (int e = lane; e < g.Z; e += kLanes) g.counts[static_cast<size_t>(gw) * g.Z + e] = mine[e];
+}
+
+// Column sums of the count matrix for element e: the total and, for the four waves w0..w0+3,
+// the number of nodes of e in all earlier waves.  Loads in batches of 32 independent ones.
+__device__ __forceinline__ int split_column(const SplitGroupArgs& g, int e, int w0, int (&before)[kGroupWavesPerWG]) {
+  constexpr int kLoads = 32;
+  int run = 0;
+#pragma unroll
+  for (int v = 0; v < kGroupWavesPerWG; ++v) before[v] = 0;
+  for (int w = 0; w < g.W; w += kLoads) {
+    int c[kLoads];
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) c[k] = (w + k < g.W) ? g.counts[static_cast<size_t>(w + k) * g.Z + e] : 0;
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+#pragma unroll
+      for (int v = 0; v < kGroupWavesPerWG; ++v)
+        if (w + k == w0 + v) before[v] = run;
+      run += c[k];
+    }
+  }
+  return run;
+}
+
+// Workgroup `wg` scatters the slices of its four waves.  lds: 5 * Z ints.
+__device__ __forceinline__ void split_scatter_role(const SplitGroupArgs& g, int wg, int32_t* lds) {
+  constexpr int kBatch = 8;
+  const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+  const int w0 = wg * kGroupWavesPerWG;
+  int32_t* cursor = lds;                            // [4][Z]
+  int32_t* seg = lds + kGroupWavesPerWG * g.Z;      // [Z] totals, then their exclusive scan
+  for (int e = threadIdx.x; e < g.Z; e += kSplitThreads) {
+    int before[kGroupWavesPerWG];
+    seg[e] = split_column(g, e, w0, before);
+#pragma unroll
+    for (int v = 0; v < kGroupWavesPerWG; ++v) cursor[v * g.Z + e] = before[v];
+  }
+  __syncthreads();
+  if (wave == 0) split_wave_scan(seg, g.Z, lane);
+  __syncthreads();
+  for (int e = threadIdx.x; e < g.Z; e += kSplitThreads) {
+#pragma unroll
+    for (int v = 0; v < kGroupWavesPerWG; ++v) cursor[v * g.Z + e] += seg[e];
+  }
+  __syncthreads();
+  int32_t* mine = cursor + wave * g.Z;
+  const int gw = w0 + wave;
+  const long long lo = static_cast<long long>(gw) * g.nodes_per_wave;
+  const long long hi = (lo + g.nodes_per_wave < g.n) ? lo + g.nodes_per_wave : g.n;
+  const int z_bits = 32 - __builtin_clz(g.Z);
+  for (long long c0 = lo; c0 < hi; c0 += kBatch * kLanes) {   // wave-uniform trip count
+    int zs[kBatch];
+#pragma unroll
+    for (int c = 0; c < kBatch; ++c) {
+      const long long i = c0 + c * kLanes + lane;
+      zs[c] = (i < hi) ? g.z[i] : -1;
+    }
+#pragma unroll
+    for (int c = 0; c < kBatch; ++c) {
+      if (c0 + c * kLanes >= hi) break;  // wave-uniform
+      const int e = zs[c];
+      split_scatter_chunk(e, e >= 0 && e < g.Z, static_cast<int>(c0 + c * kLanes + lane), lane, z_bits, mine, g.perm);
+    }
+  }
+}
+
+// One workgroup: element offsets, tile offsets, tile count and tile descriptors.  lds: 3 * Z + 2 ints.
+__device__ __forceinline__ void split_table_role(const SplitGroupArgs& g, int32_t* lds) {
+  int32_t* total = lds;            // [Z]
+  int32_t* seg = total + g.Z;      // [Z+1]
+  int32_t* til = seg + g.Z + 1;    // [Z+1]
+  const int t = threadIdx.x;
+  for (int e = t; e < g.Z; e += kSplitThreads) {
+    int before[kGroupWavesPerWG];
+    total[e] = split_column(g, e, -kGroupWavesPerWG, before);
+    seg[e] = total[e];
+    til[e] = (total[e] + g.tile_nodes - 1) / g.tile_nodes;
+  }
+  __syncthreads();
+  if (t < kLanes) {  // wave 0
+    const int n_valid = split_wave_scan(seg, g.Z, t);
+    const int n_tiles = split_wave_scan(til, g.Z, t);
+    if (t == 0) {
+      seg[g.Z] = n_valid;
+      til[g.Z] = n_tiles;
+      *g.ntiles = (n_tiles < g.max_tiles) ? n_tiles : g.max_tiles;
+    }
+  }
+  __syncthreads();
+  const int n_tiles = til[g.Z];
+  for (int e = t; e <= g.Z; e += kSplitThreads) {
+    g.seg_off[e] = seg[e];
+    g.tile_off[e] = til[e];
+  }
+  // element e owns tiles [til[e], til[e+1]); its nodes are split evenly (the first `rem` tiles
+  // take one node more)
+  for (int i = t; i < n_tiles && i < g.max_tiles; i += kSplitThreads) {
+    int lo = 0, hi = g.Z;  // last e with til[e] <= i (empty elements share an offset with the next one)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (til[mid] <= i) lo = mid; else hi = mid;
+    }
+    const int e = lo;
+    const int nt_e = til[e + 1] - til[e];
+    const int j = i - til[e];
+    const int base = total[e] / nt_e, rem = total[e] % nt_e;
+    const int s0 = j * base + (j < rem ? j : rem);
+    g.tiles[i] = TileDesc{e, seg[e] + s0, base + (j < rem ? 1 : 0), 0};
+  }
+  // unused descriptors say "empty": the main kernels need no separate tile count
+  for (int i = n_tiles + t; i < g.max_tiles; i += kSplitThreads) g.tiles[i] = TileDesc{0, 0, 0, 0};
+}
+
+}  // namespace sc

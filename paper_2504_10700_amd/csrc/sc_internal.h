@@ -30,8 +30,8 @@ struct Workspace {
   int32_t* counts;     // [kMaxGroupWaves][Z] scratch of the counting sort
   int32_t* perm;       // [N] node indices grouped by element (stable)
   TileDesc* tiles;     // [max_tiles]
+  void* wfold;         // generated kernels: weights folded into the internal basis, [Z][K][stride]
   void* partial;       // [max_tiles][chblocks][S][64] per-tile dW contributions
-  double* reduced;     // [Z][chblocks][S][64] per-element sums of the internal rows
   int32_t max_tiles;
   size_t bytes;
 };
@@ -50,8 +50,12 @@ struct LaunchShape {
   int tile_nodes;   // nodes per tile (per workgroup)
   int max_tiles;    // upper bound of the tile count = grid size / chblocks
   int chblocks;     // ceil(K / 64)
-  int group_waves;  // rows used of the count matrix
+  int group_waves;  // rows used of the count matrix (0: single-launch grouping)
   int nodes_per_group_wave;
+  // generated kernels: grouping as roles of the prepare / forward launches, forward tiles
+  int split_waves;           // waves of the counting sort (a multiple of kGroupWavesPerWG)
+  int split_nodes_per_wave;  // a multiple of 64
+  int fwd_tile_nodes;        // consecutive nodes per workgroup of the natural-order forward
 };
 
 }  // namespace sc

@@ -1,0 +1,143 @@
+// Streaming probes (measurement helper, see sc_probe_stream in include/sc.h): plain kernels
+// that move a known number of bytes with no arithmetic, so that a benchmark can put the
+// bandwidth this box attains next to the figures of the contraction kernels in the same run.
+//
+//   read / write / copy   16 bytes per lane and access, grid-stride, many independent accesses
+//                         in flight: the simplest traffic there is
+//   rows                  the access pattern of the fused backward kernel without its
+//                         arithmetic: one wave per gathered row, 64 B per lane of one tensor
+//                         (the A row of a node and 64 channels, 4 KB) and 16 B per lane of a
+//                         second one (its dB row, 1 KB) in, 4 KB out in whole 1 KB pieces,
+//                         the next row requested before the current one is written
+#include "sc_internal.h"
+
+namespace sc {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int kProbeThreads = 256;
+constexpr int kUnroll = 8;
+
+__global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const f4* __restrict__ src, size_t n16,
+                                                                    float* __restrict__ sink) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+  size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+  f4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (; i + (kUnroll - 1) * stride < n16; i += kUnroll * stride) {
+    f4 v[kUnroll];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) v[k] = src[i + k * stride];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) acc += v[k];
+  }
+  for (; i < n16; i += stride) acc += src[i];
+  // never true for finite data; keeps the loads alive
+  if (acc.x + acc.y + acc.z + acc.w == 1.2345e38f) sink[0] = acc.x;
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_write_kernel(f4* __restrict__ dst, size_t n16) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+  const f4 v = {1.f, 2.f, 3.f, 4.f};
+  for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n16; i += stride) dst[i] = v;
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const f4* __restrict__ src, f4* __restrict__ dst,
+                                                                    size_t n16) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+  size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+  for (; i + (kUnroll - 1) * stride < n16; i += kUnroll * stride) {
+    f4 v[kUnroll];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) v[k] = src[i + k * stride];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) dst[i + k * stride] = v[k];
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+// rows: a[n_rows][64 lanes][4 x f4], b[n_rows][64 lanes][f4] in, out[n_rows][4][64 lanes][f4].
+// Every wave takes rows wave_id, wave_id + n_waves, ... of perm (clamped into range).
+__global__ __launch_bounds__(kProbeThreads) void probe_rows_kernel(const f4* __restrict__ a, const f4* __restrict__ b,
+                                                                    f4* __restrict__ out,
+                                                                    const int32_t* __restrict__ perm, int n_rows) {
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int wave = (blockIdx.x * kProbeThreads + threadIdx.x) / kLanes;
+  const int n_waves = gridDim.x * (kProbeThreads / kLanes);
+  auto row_of = [&](int j) {
+    int r = perm[j];
+    return static_cast<size_t>(r < 0 ? 0 : (r >= n_rows ? n_rows - 1 : r));
+  };
+  if (wave >= n_rows) return;
+  f4 va[4], vb, na[4], nb;
+  size_t row = row_of(wave);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) va[k] = a[(row * kLanes + lane) * 4 + k];
+  vb = b[row * kLanes + lane];
+  for (int j = wave; j < n_rows; j += n_waves) {
+    const bool more = j + n_waves < n_rows;
+    size_t next = row;
+    if (more) {
+      next = row_of(j + n_waves);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) na[k] = a[(next * kLanes + lane) * 4 + k];
+      nb = b[next * kLanes + lane];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) out[(row * 4 + k) * kLanes + lane] = va[k] + vb;
+    if (more) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) va[k] = na[k];
+      vb = nb;
+      row = next;
+    }
+  }
+}
+
+}  // namespace
+}  // namespace sc
+
+extern "C" sc_status sc_probe_stream(int32_t kind, const void* src, const void* src2, void* dst, const int32_t* perm,
+                                     int64_t n, void* hip_stream) {
+  using namespace sc;
+  if (n < 0 || n > (int64_t(1) << 40)) return set_error(SC_ERR_INVALID_ARG, "sc_probe_stream: n out of range");
+  if (n == 0) return SC_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) != hipSuccess) return set_error(SC_ERR_HIP, "sc_probe_stream: hipGetDevice");
+  (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (cus < 1) cus = 256;
+  const int grid = cus * 8;   // eight workgroups of four waves per compute unit
+  auto bad = [](const void* p) { return !p || misaligned(p, 16); };
+  switch (kind) {
+    case SC_PROBE_READ:
+      if (bad(src) || bad(dst) || n % 16) return set_error(SC_ERR_INVALID_ARG, "sc_probe_stream: read needs src, dst (sink), n % 16 == 0");
+      hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(kProbeThreads), 0, stream, static_cast<const f4*>(src),
+                         static_cast<size_t>(n / 16), static_cast<float*>(dst));
+      break;
+    case SC_PROBE_WRITE:
+      if (bad(dst) || n % 16) return set_error(SC_ERR_INVALID_ARG, "sc_probe_stream: write needs dst, n % 16 == 0");
+      hipLaunchKernelGGL(probe_write_kernel, dim3(grid), dim3(kProbeThreads), 0, stream, static_cast<f4*>(dst),
+                         static_cast<size_t>(n / 16));
+      break;
+    case SC_PROBE_COPY:
+      if (bad(src) || bad(dst) || n % 16) return set_error(SC_ERR_INVALID_ARG, "sc_probe_stream: copy needs src, dst, n % 16 == 0");
+      hipLaunchKernelGGL(probe_copy_kernel, dim3(grid), dim3(kProbeThreads), 0, stream, static_cast<const f4*>(src),
+                         static_cast<f4*>(dst), static_cast<size_t>(n / 16));
+      break;
+    case SC_PROBE_ROWS: {
+      if (bad(src) || bad(src2) || bad(dst) || !perm || n > (int64_t(1) << 30))
+        return set_error(SC_ERR_INVALID_ARG, "sc_probe_stream: rows needs src, src2, dst, perm, n <= 2^30 rows");
+      const int64_t wgs = (n + 3) / 4;
+      hipLaunchKernelGGL(probe_rows_kernel, dim3(static_cast<unsigned>(wgs < grid ? wgs : grid)), dim3(kProbeThreads), 0,
+                         stream, static_cast<const f4*>(src), static_cast<const f4*>(src2), static_cast<f4*>(dst), perm,
+                         static_cast<int>(n));
+      break;
+    }
+    default:
+      return set_error(SC_ERR_INVALID_ARG, "sc_probe_stream: unknown kind");
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return set_error(SC_ERR_HIP, std::string("sc_probe_stream: launch: ") + hipGetErrorString(e));
+  return SC_OK;
+}

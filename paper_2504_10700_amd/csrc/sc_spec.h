@@ -13,13 +13,26 @@ void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]);
 // Waves per workgroup (= per tile) of the generated kernels.
 int spec_waves_per_tile();
 
-hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const void* W, void* B,
-                               const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
-hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,
-                                void* dA, const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
-hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t n, const void* A, const void* W,
-                                       const void* dB, const void* H, void* ddB, void* dA2, const Workspace& ws,
-                                       const LaunchShape& shape, hipStream_t stream);
+// Bytes of the folded-weight table wf[element][channel][stride] of a generated kernel.
+size_t spec_folded_bytes(const sc_plan* plan);
+
+// Launch 1: folds W into ws.wfold (fold) and / or counts the elements of z (count: first half
+// of the grouping).  Nothing is launched if both are false.
+hipError_t launch_spec_prepare(const sc_plan* plan, int64_t n, const int32_t* z, const void* W, const Workspace& ws,
+                               const LaunchShape& shape, bool count, bool fold, hipStream_t stream);
+// Second half of the grouping as a launch of its own (after launch_spec_prepare with count).
+hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
+                               const LaunchShape& shape, hipStream_t stream);
+// Forward over the nodes in natural order from ws.wfold; scatter: the second half of the
+// grouping rides in the same launch.
+hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B,
+                               const Workspace& ws, const LaunchShape& shape, bool scatter, hipStream_t stream);
+// The grouped passes read ws.wfold, ws.perm and ws.tiles.
+hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
+                                const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
+hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, const void* H,
+                                       void* ddB, void* dA2, const Workspace& ws, const LaunchShape& shape,
+                                       hipStream_t stream);
 
 // dW reduction over the tiles of every element and unfold to the external paths.
 hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,

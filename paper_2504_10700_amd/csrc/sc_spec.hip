@@ -11,6 +11,20 @@
 //               range of tiles: neighbouring tiles share the element's weights
 // Per node the next node's rows are requested before the current one is evaluated
 // (two register sets, ping-pong), so HBM latency hides behind ~300-800 VALU operations.
+//
+// One step (forward + backward of one batch) is four launches:
+//   1 prepare   the weights of every (element, channel) folded into the internal basis once,
+//               wf[element][channel block][kS][64]; other workgroups of the same launch count the
+//               elements of z (first half of the grouping)
+//   2 forward   nodes in their NATURAL order (no grouping needed: every node reads the folded
+//               weights of its element from wf, which stays in L2): consecutive workgroups
+//               stream consecutive memory.  Other workgroups of the same launch finish the
+//               grouping (scatter + tile table), which only the backward needs
+//   3 backward  nodes grouped by element (tiles), weights of the tile's element in registers,
+//               dW' summed per tile without atomics
+//   4 finalize  per (element, channel block): sum of the per-tile dW' rows in a fixed order
+//               (fp64) and the map to the external paths
+#include "sc_group_split.h"
 #include "sc_spec.h"
 
 namespace sc {
@@ -113,47 +127,118 @@ __device__ __forceinline__ int xcd_contiguous_block() {
   return (blockIdx.x % kXcds) * per + blockIdx.x / kXcds;
 }
 
+// Folded weights: wf[element][channel block][kS][64 channels]: every internal row of an
+// (element, channel block) is 256 contiguous bytes (fp32), so a wave reads it with one fully
+// coalesced instruction.  (Rows per lane - [element][channel][kS] read as 16-byte pieces - make
+// every load instruction touch 64 cache lines; with the weights read per node that bound the
+// natural-order forward by the tag rate of the vector cache: 614 us instead of 440 at 200k nodes.)
 template <typename T, typename G>
-__global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(int K, int chblocks, int n_blocks,
-                                                                    const T* __restrict__ A,
-                                                                    const T* __restrict__ W, T* __restrict__ B,
-                                                                    const TileDesc* __restrict__ tiles,
-                                                                    const int32_t* __restrict__ perm) {
+__device__ __forceinline__ void load_folded(const T* __restrict__ wf, int z, int chblocks, int cb, int lane,
+                                            T (&w)[G::kS]) {
+  const T* src = wf + (static_cast<size_t>(z) * chblocks + cb) * G::kS * kLanes + lane;
+#pragma unroll
+  for (int s = 0; s < G::kS; ++s) w[s] = src[s * kLanes];
+}
+
+// Launch 1.  Workgroups [0, count_wgs): count role of the grouping.  The others: one wave per
+// (element, 64 channels) folds W[element, :, channel] into wf.
+template <typename T, typename G>
+__global__ __launch_bounds__(kSpecThreads) void spec_prepare_kernel(SplitGroupArgs ga, int count_wgs, int K,
+                                                                    int chblocks, int n_pairs,
+                                                                    const T* __restrict__ W, T* __restrict__ wf) {
   extern __shared__ unsigned char lds_raw[];
+  if (static_cast<int>(blockIdx.x) < count_wgs) {
+    split_count_role(ga, blockIdx.x, reinterpret_cast<int32_t*>(lds_raw));
+    return;
+  }
+  const int lane = threadIdx.x & (kLanes - 1);
+  const int pair = (static_cast<int>(blockIdx.x) - count_wgs) * kSpecWaves + wave_of_thread();
+  if (pair >= n_pairs) return;
+  const int z = pair / chblocks, ch = (pair % chblocks) * kLanes + lane;
+  T w[G::kS], wz[G::kP];
+  // all kP rows are requested before the first is used (one memory latency, not one per few rows)
+  const T* src = W + static_cast<size_t>(z) * G::kP * K + ch;
+#pragma unroll
+  for (int p = 0; p < G::kP; ++p) wz[p] = src[static_cast<size_t>(p) * K];
+  asm volatile("" ::: "memory");
+  G::fold(wz, 1, w);
+  T* dst = wf + static_cast<size_t>(pair) * G::kS * kLanes + lane;   // pair = element * chblocks + channel block
+#pragma unroll
+  for (int s = 0; s < G::kS; ++s) dst[s * kLanes] = w[s];
+}
+
+// The grouping alone (a backward pass that cannot reuse a forward's grouping): scatter and table roles.
+__global__ __launch_bounds__(kSpecThreads) void spec_scatter_kernel(SplitGroupArgs ga, int scatter_wgs) {
+  extern __shared__ unsigned char lds_raw[];
+  if (static_cast<int>(blockIdx.x) < scatter_wgs) split_scatter_role(ga, blockIdx.x, reinterpret_cast<int32_t*>(lds_raw));
+  else split_table_role(ga, reinterpret_cast<int32_t*>(lds_raw));
+}
+
+// Launch 2.  Workgroups [0, scatter_wgs): scatter role; workgroup scatter_wgs (if any scatter):
+// table role; the others: forward of `tile` consecutive nodes x one 64-channel block, a
+// contiguous quarter of the nodes per wave.  A node whose element index is outside [0, Z) is
+// skipped (its row of B is left untouched), as the grouped kernels do.
+template <typename T, typename G>
+__global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupArgs ga, int scatter_wgs, int K,
+                                                                    int chblocks, int n, int Z, int tile,
+                                                                    const T* __restrict__ A,
+                                                                    const int32_t* __restrict__ z,
+                                                                    const T* __restrict__ wf, T* __restrict__ B) {
+  extern __shared__ unsigned char lds_raw[];
+  int block = blockIdx.x;
+  if (scatter_wgs > 0) {
+    if (block < scatter_wgs) {
+      split_scatter_role(ga, block, reinterpret_cast<int32_t*>(lds_raw));
+      return;
+    }
+    if (block == scatter_wgs) {
+      split_table_role(ga, reinterpret_cast<int32_t*>(lds_raw));
+      return;
+    }
+    block -= scatter_wgs + 1;
+  }
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = wave_of_thread();
   T* stage = reinterpret_cast<T*>(lds_raw) + wave * kLanes * G::kNLM;  // [64][kNLM] per wave (if used)
   constexpr bool kStageB = G::kNLM * sizeof(T) != 16;  // 16-byte rows are coalesced as they are
-  const int logical = xcd_contiguous_block();
-  if (logical >= n_blocks) return;
-  const int tile = logical / chblocks, cb = logical % chblocks;
-  const TileDesc td = tiles[tile];
-  const int j0 = td.start + td.count * wave / kSpecWaves;
-  const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
-  if (j0 >= j1) return;  // also covers the unused descriptors (count 0)
+  const int t = block / chblocks, cb = block % chblocks;
+  const int s0 = t * tile;
+  const int cnt = (n - s0 < tile) ? n - s0 : tile;
+  const int j0 = s0 + cnt * wave / kSpecWaves, j1 = s0 + cnt * (wave + 1) / kSpecWaves;
+  if (j0 >= j1) return;
   const int ch = cb * kLanes + lane;
-  T w[G::kS];
-  G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w);
-
-  T a0[G::kNlm], a1[G::kNlm], b[G::kNLM];
-  size_t node0 = perm[j0], node1 = 0;
-  Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
+  // the element indices of this wave's nodes (at most 64: one per lane), read at once so that the
+  // per-node chain is folded weights -> arithmetic, not index -> folded weights -> arithmetic
+  const int zv = (j0 + lane < j1) ? z[j0 + lane] : 0;
+  auto element = [&](int j, bool& ok) {
+    const int e = __builtin_amdgcn_readlane(zv, j - j0);
+    ok = e >= 0 && e < Z;
+    return ok ? e : 0;
+  };
+  T a0[G::kNlm], a1[G::kNlm], w0[G::kS], w1[G::kS], b[G::kNLM];
+  bool ok0 = false, ok1 = false;
+  load_folded<T, G>(wf, element(j0, ok0), chblocks, cb, lane, w0);
+  Row<T, G::kNlm>::load(A + (static_cast<size_t>(j0) * K + ch) * G::kNlm, a0);
   for (int j = j0; j < j1; j += 2) {
     if (j + 1 < j1) {
-      node1 = perm[j + 1];
-      Row<T, G::kNlm>::load(A + (node1 * K + ch) * G::kNlm, a1);
+      load_folded<T, G>(wf, element(j + 1, ok1), chblocks, cb, lane, w1);
+      Row<T, G::kNlm>::load(A + (static_cast<size_t>(j + 1) * K + ch) * G::kNlm, a1);
     }
-    G::forward(a0, w, b);
-    if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (node0 * K + cb * kLanes) * G::kNLM, stage, lane, b);
-    else Row<T, G::kNLM>::store(B + (node0 * K + ch) * G::kNLM, b);
+    if (ok0) {
+      G::forward(a0, w0, b);
+      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(j) * K + cb * kLanes) * G::kNLM, stage, lane, b);
+      else Row<T, G::kNLM>::store(B + (static_cast<size_t>(j) * K + ch) * G::kNLM, b);
+    }
     if (j + 1 < j1) {
       if (j + 2 < j1) {
-        node0 = perm[j + 2];
-        Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
+        load_folded<T, G>(wf, element(j + 2, ok0), chblocks, cb, lane, w0);
+        Row<T, G::kNlm>::load(A + (static_cast<size_t>(j + 2) * K + ch) * G::kNlm, a0);
       }
-      G::forward(a1, w, b);
-      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (node1 * K + cb * kLanes) * G::kNLM, stage, lane, b);
-      else Row<T, G::kNLM>::store(B + (node1 * K + ch) * G::kNLM, b);
+      if (ok1) {
+        G::forward(a1, w1, b);
+        if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(j + 1) * K + cb * kLanes) * G::kNLM, stage, lane, b);
+        else Row<T, G::kNLM>::store(B + (static_cast<size_t>(j + 1) * K + ch) * G::kNLM, b);
+      }
     }
   }
 }
@@ -164,11 +249,15 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(int K, int c
 // small batch a workgroup's life is a chain of latencies (fold, first rows, a handful of nodes,
 // the dW sum) and the third workgroup pays: 51.1 -> 49.3 us at 10k nodes, 138.7 -> 136.6 at
 // 30k, measured on one box; from 60k nodes on the unconstrained kernel is 1% faster.
+// That small-batch instance also streams its dA rows past the cache (non-temporal stores): the
+// kernel itself gains 2 us at 10k nodes and the launches after it another 3 us (step 99.1 -> 93.5
+// us, same box), whereas at 200k nodes the backward loses 2% with them and the next forward gains
+// as much.
 template <typename T, typename G, int kOcc = 0>
 __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(kOcc == 0 ? 1 : kOcc, 8)))
 void spec_backward_kernel(int K, int chblocks, int n_blocks,
                                                                      const T* __restrict__ A,
-                                                                     const T* __restrict__ W,
+                                                                     const T* __restrict__ wf,
                                                                      const T* __restrict__ dB, T* __restrict__ dA,
                                                                      T* __restrict__ partial,
                                                                      const TileDesc* __restrict__ tiles,
@@ -191,7 +280,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
   for (int s = 0; s < G::kS; ++s) dw[s] = T(0);
   if (j0 < j1) {
     T w[G::kS];
-    G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w);
+    load_folded<T, G>(wf, td.z, chblocks, cb, lane, w);
     T a0[G::kNlm], a1[G::kNlm], g0[G::kNLM], g1[G::kNLM], da[G::kNlm];
     size_t node0 = perm[j0], node1 = 0;
     Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
@@ -203,7 +292,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
         Row<T, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
       }
       G::backward(a0, w, g0, da, dw);
-      store_rows_coalesced<T, G::kNlm, false>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da);
+      store_rows_coalesced<T, G::kNlm, kOcc != 0>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da);
       if (j + 1 < j1) {
         if (j + 2 < j1) {
           node0 = perm[j + 2];
@@ -211,7 +300,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
           Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
         }
         G::backward(a1, w, g1, da, dw);
-        store_rows_coalesced<T, G::kNlm, false>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da);
+        store_rows_coalesced<T, G::kNlm, kOcc != 0>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da);
       }
     }
   }
@@ -244,7 +333,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
 //    (-Rpass-analysis=kernel-resource-usage) after touching it.
 template <typename T, typename G>
 __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
-    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
+    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ wf, const T* __restrict__ dB,
     const T* __restrict__ H, T* __restrict__ ddB, T* __restrict__ dA2, T* __restrict__ partial,
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ perm) {
   extern __shared__ unsigned char lds_raw[];
@@ -266,7 +355,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
   for (int s = 0; s < G::kS; ++s) dw[s] = T(0);
   if (j0 < j1) {
     T w[G::kS];
-    G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w);
+    load_folded<T, G>(wf, td.z, chblocks, cb, lane, w);
     // one register set of inputs: the next node's rows are requested right after the
     // arithmetic of the current one has consumed them, ahead of its stores
     T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
@@ -303,7 +392,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
 // See above.  LDS: w' [kSpecWaves][kS][64] | sums [kSpecWaves][kS][64] | stage [kSpecWaves][64][kNlm].
 template <typename T, typename G>
 __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void spec_double_backward_lds_kernel(
-    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
+    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ wf, const T* __restrict__ dB,
     const T* __restrict__ H, T* __restrict__ ddB, T* __restrict__ dA2, T* __restrict__ partial,
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ perm) {
   extern __shared__ unsigned char lds_raw[];
@@ -328,7 +417,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
     T* wl = red + wave * G::kS * kLanes + lane;   // this wave's slice of red holds w' until the end
     {
       T w0[G::kS];
-      G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w0);
+      load_folded<T, G>(wf, td.z, chblocks, cb, lane, w0);
 #pragma unroll
       for (int s = 0; s < G::kS; ++s) wl[s * kLanes] = w0[s];
     }
@@ -375,76 +464,74 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
 template <typename T, typename G>
 constexpr bool kUseLdsState = sizeof(T) == 4 && G::kS <= 32;
 
-// Second stage of the dW reduction, two small launches (device-scope fences, which a
-// single-launch "last wave finishes the job" scheme needs, flush the per-XCD L2s and cost
-// far more than a launch on this chip).
-// (1) One workgroup of four waves per (element, channel block, internal row): each wave sums
-//     the row over a contiguous quarter of the element's tiles in tile order (sixteen
-//     independent loads in flight), the four sums are added in wave order into
-//     reduced[e][cb][s][lane] in fp64.  Elements without nodes own no tiles and get zeros.
-// (2) One wave per (element, channel block): maps the S reduced rows to the P external
-//     paths with the generated unfold.
-// Every sum has a fixed order: results are bitwise reproducible.
-constexpr int kReduceWaves = 4;
-
-template <typename T, typename G>
-__global__ __launch_bounds__(kReduceWaves * kLanes) void spec_reduce_kernel(int chblocks, int max_tiles,
-                                                                            const T* __restrict__ partial,
-                                                                            const int32_t* __restrict__ tile_off,
-                                                                            double* __restrict__ reduced) {
-  constexpr int S = G::kS;
-  __shared__ double part[kReduceWaves][kLanes];
-  const int lane = threadIdx.x % kLanes, wave = threadIdx.x / kLanes;
-  const int s = blockIdx.x % S;
-  const int cb = (blockIdx.x / S) % chblocks;
-  const int e = blockIdx.x / (S * chblocks);
-  int t0 = tile_off[e], t1 = tile_off[e + 1];
-  if (t1 > max_tiles) t1 = max_tiles;
-  // the element's tiles are cut into kReduceWaves contiguous ranges, one per wave
-  const int nt = t1 - t0;
-  const int w0 = t0 + nt * wave / kReduceWaves, w1 = t0 + nt * (wave + 1) / kReduceWaves;
-  const size_t tstride = static_cast<size_t>(chblocks) * S * kLanes;
-  const T* src = partial + (static_cast<size_t>(cb) * S + s) * kLanes + lane;
-  constexpr int U = 16;
-  double a[U];
+// Second stage of the dW reduction and the map to the external paths, one launch.  The fold
+// matrix F (dW[p] = sum_s F[s,p] r[s]) falls into small independent blocks of one to three
+// internal rows s and the external paths p that depend on them (generated descriptors), so one
+// wave per (element, channel block, block of F) can do both steps without waiting for anyone:
+// it adds the block's rows over the element's tiles in tile order, in fp64, with the rows of up
+// to 32 tiles requested together, and writes the block's external paths.  Elements without nodes
+// own no tiles and get zeros.  Every sum has a fixed order: results are bitwise reproducible.
+// What was measured on the way here (10k / 200k nodes): a sum kernel followed by an unfold kernel
+// 11.2 / 15.6 us; one workgroup per (element, channel block) for all rows 13.5 / 31 us (the twelve
+// workgroups of the six frequent elements own 60% of the bytes); four waves per block, a quarter
+// of the tiles each, combined through LDS 13 / 14.4 us (four times the waves, most of them idle
+// for the rare elements).  A device-scope "last workgroup finishes the job" scheme inside the
+// backward kernel was far slower than a launch: its fences flush the per-XCD L2s on this chip.
+template <typename T, int R, int kMaxR>
+__device__ __forceinline__ void finalize_sum(const T* __restrict__ src, size_t tstride, int t0, int t1,
+                                             const int (&row)[kMaxR], double (&acc)[kMaxR]) {
+  constexpr int kRegs = R * static_cast<int>(sizeof(T) / 4);   // registers per tile in flight
+  constexpr int U = kRegs <= 2 ? 32 : kRegs <= 4 ? 16 : 8;
+  // batches of U tiles; past the last tile it is read again and dropped
+  for (int t = t0; t < t1; t += U) {
+    T v[U][R];
 #pragma unroll
-  for (int k = 0; k < U; ++k) a[k] = 0.0;
-  int t = w0;
-  for (; t + U <= w1; t += U) {
-    T v[U];
+    for (int u = 0; u < U; ++u) {
+      const T* at = src + (t + u < t1 ? t + u : t1 - 1) * tstride;
 #pragma unroll
-    for (int k = 0; k < U; ++k) v[k] = src[(t + k) * tstride];
+      for (int r = 0; r < R; ++r) v[u][r] = at[row[r] * kLanes];
+    }
 #pragma unroll
-    for (int k = 0; k < U; ++k) a[k] += static_cast<double>(v[k]);
-  }
-  for (; t < w1; ++t) a[0] += static_cast<double>(src[t * tstride]);
+    for (int u = 0; u < U; ++u) {
+      const bool in = t + u < t1;
 #pragma unroll
-  for (int w = U / 2; w >= 1; w /= 2)
-#pragma unroll
-    for (int k = 0; k < w; ++k) a[k] += a[k + w];
-  part[wave][lane] = a[0];
-  __syncthreads();
-  if (wave == 0) {
-    double sum = part[0][lane];
-#pragma unroll
-    for (int w = 1; w < kReduceWaves; ++w) sum += part[w][lane];
-    reduced[((static_cast<size_t>(e) * chblocks + cb) * S + s) * kLanes + lane] = sum;
+      for (int r = 0; r < R; ++r) acc[r] += in ? static_cast<double>(v[u][r]) : 0.0;
+    }
   }
 }
 
 template <typename T, typename G>
-__global__ __launch_bounds__(kLanes) void spec_unfold_kernel(int K, int chblocks,
-                                                             const double* __restrict__ reduced,
-                                                             T* __restrict__ dW) {
-  constexpr int S = G::kS;
+__global__ __launch_bounds__(kLanes) void spec_finalize_kernel(int K, int chblocks, int max_tiles,
+                                                               const T* __restrict__ partial,
+                                                               const int32_t* __restrict__ tile_off,
+                                                               T* __restrict__ dW) {
+  constexpr int S = G::kS, R = G::kMaxBlockRows;
   const int lane = threadIdx.x;
-  const int cb = blockIdx.x % chblocks;
-  const int e = blockIdx.x / chblocks;
-  const double* mine = reduced + (static_cast<size_t>(e) * chblocks + cb) * S * kLanes;
-  double r[S];
+  const int blk = blockIdx.x % G::kNumBlocks;
+  const int cb = (blockIdx.x / G::kNumBlocks) % chblocks;
+  const int e = blockIdx.x / (G::kNumBlocks * chblocks);
+  const typename G::Block d = G::kBlocks[blk];   // the whole descriptor at once: one scalar-load latency
+  int t0 = tile_off[e], t1 = tile_off[e + 1];
+  if (t1 > max_tiles) t1 = max_tiles;
+  const size_t tstride = static_cast<size_t>(chblocks) * S * kLanes;
+  const T* src = partial + static_cast<size_t>(cb) * S * kLanes + lane;
+  double sum[R];
 #pragma unroll
-  for (int q = 0; q < S; ++q) r[q] = mine[q * kLanes + lane];
-  G::unfold(r, dW + static_cast<size_t>(e) * G::kP * K + cb * kLanes + lane, K);
+  for (int r = 0; r < R; ++r) sum[r] = 0.0;
+  if (d.n_rows == 1) finalize_sum<T, 1, R>(src, tstride, t0, t1, d.row, sum);
+  else if (R >= 2 && d.n_rows == 2) finalize_sum<T, (R >= 2 ? 2 : 1), R>(src, tstride, t0, t1, d.row, sum);
+  else finalize_sum<T, R, R>(src, tstride, t0, t1, d.row, sum);
+  T* out = dW + static_cast<size_t>(e) * G::kP * K + cb * kLanes + lane;
+#pragma unroll
+  for (int i = 0; i < G::kMaxBlockPaths; ++i) {
+    if (i < d.n_paths) {   // uniform
+      double v = 0.0;
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        if (d.coef[i][r] != 0.0) v += d.coef[i][r] * sum[r];   // uniform; rows in ascending order
+      out[static_cast<size_t>(d.path[i]) * K] = static_cast<T>(v);
+    }
+  }
 }
 
 template <typename G>
@@ -456,20 +543,63 @@ bool matches(const sc_plan* plan) {
   return c.num_channels % kLanes == 0 && static_cast<int>(plan->table.paths.size()) == G::kP;
 }
 
+SplitGroupArgs group_args(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
+                          const LaunchShape& shape) {
+  SplitGroupArgs g{};
+  g.z = z;
+  g.n = static_cast<int>(n);
+  g.Z = plan->cfg.num_elements;
+  g.W = shape.split_waves;
+  g.nodes_per_wave = shape.split_nodes_per_wave;
+  g.tile_nodes = shape.tile_nodes;
+  g.max_tiles = shape.max_tiles;
+  g.counts = ws.counts;
+  g.seg_off = ws.seg_off;
+  g.tile_off = ws.tile_off;
+  g.ntiles = ws.ntiles;
+  g.tiles = ws.tiles;
+  g.perm = ws.perm;
+  return g;
+}
+
+template <typename K>
+hipError_t raise_lds_limit(K kernel, size_t lds) {
+  if (lds <= 64 * 1024) return hipSuccess;  // above the default dynamic LDS limit: raise it for this kernel
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             static_cast<int>(lds));
+}
+
 template <typename T, typename G>
-hipError_t fwd_launch(const sc_plan* plan, const void* A, const void* W, void* B, const Workspace& ws,
-                      const LaunchShape& shape, hipStream_t stream) {
-  const int n_blocks = shape.max_tiles * shape.chblocks;
-  const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
-  const size_t lds = (G::kNLM * sizeof(T) != 16) ? sizeof(T) * kSpecWaves * G::kNLM * kLanes : 0;
-  hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
-                     plan->cfg.num_channels, shape.chblocks, n_blocks, static_cast<const T*>(A),
-                     static_cast<const T*>(W), static_cast<T*>(B), ws.tiles, ws.perm);
+hipError_t prepare_launch(const sc_plan* plan, int64_t n, const int32_t* z, const void* W, const Workspace& ws,
+                          const LaunchShape& shape, bool count, bool fold, hipStream_t stream) {
+  const int count_wgs = count ? shape.split_waves / kGroupWavesPerWG : 0;
+  const int n_pairs = fold ? plan->cfg.num_elements * shape.chblocks : 0;
+  const int grid = count_wgs + (n_pairs + kSpecWaves - 1) / kSpecWaves;
+  if (grid == 0) return hipSuccess;
+  const size_t lds = count ? split_group_lds_bytes(plan->cfg.num_elements) : 0;
+  hipLaunchKernelGGL((spec_prepare_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
+                     group_args(plan, n, z, ws, shape), count_wgs, plan->cfg.num_channels, shape.chblocks, n_pairs,
+                     static_cast<const T*>(W), static_cast<T*>(ws.wfold));
   return hipGetLastError();
 }
 
 template <typename T, typename G>
-hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB, void* dA,
+hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B, const Workspace& ws,
+                      const LaunchShape& shape, bool scatter, hipStream_t stream) {
+  const int scatter_wgs = scatter ? shape.split_waves / kGroupWavesPerWG : 0;
+  const int tiles = static_cast<int>((n + shape.fwd_tile_nodes - 1) / shape.fwd_tile_nodes);
+  const int grid = (scatter ? scatter_wgs + 1 : 0) + tiles * shape.chblocks;
+  size_t lds = (G::kNLM * sizeof(T) != 16) ? sizeof(T) * kSpecWaves * G::kNLM * kLanes : 0;
+  if (scatter && split_group_lds_bytes(plan->cfg.num_elements) > lds) lds = split_group_lds_bytes(plan->cfg.num_elements);
+  hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
+                     group_args(plan, n, z, ws, shape), scatter_wgs, plan->cfg.num_channels, shape.chblocks,
+                     static_cast<int>(n), plan->cfg.num_elements, shape.fwd_tile_nodes, static_cast<const T*>(A), z,
+                     static_cast<const T*>(ws.wfold), static_cast<T*>(B));
+  return hipGetLastError();
+}
+
+template <typename T, typename G>
+hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
                       const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
@@ -478,19 +608,16 @@ hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void*
   if constexpr (sizeof(T) == 4 && G::kS <= 32) {
     if (n <= 40000) kernel = &spec_backward_kernel<T, G, 3>;   // small batches: three waves per SIMD (see the kernel)
   }
-  if (lds > 64 * 1024) {  // above the default dynamic LDS limit: raise it for this kernel
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    if (e != hipSuccess) return e;
-  }
+  const hipError_t e = raise_lds_limit(kernel, lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpecThreads), lds, stream, plan->cfg.num_channels, shape.chblocks,
-                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(W), static_cast<const T*>(dB),
+                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(ws.wfold), static_cast<const T*>(dB),
                      static_cast<T*>(dA), static_cast<T*>(ws.partial), ws.tiles, ws.perm);
   return hipGetLastError();
 }
 
 template <typename T, typename G>
-hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const void* dB, const void* H, void* ddB,
+hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* dB, const void* H, void* ddB,
                       void* dA2, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
@@ -498,13 +625,10 @@ hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const v
   const size_t lds = sizeof(T) * kSpecWaves * ((kLds ? 2 : 1) * G::kS + G::kNlm) * kLanes;
   auto kernel = &spec_double_backward_kernel<T, G>;
   if constexpr (kLds) kernel = &spec_double_backward_lds_kernel<T, G>;
-  if (lds > 64 * 1024) {  // above the default dynamic LDS limit: raise it for this kernel
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    if (e != hipSuccess) return e;
-  }
+  const hipError_t e = raise_lds_limit(kernel, lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpecThreads), lds, stream, plan->cfg.num_channels, shape.chblocks,
-                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(W), static_cast<const T*>(dB),
+                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(ws.wfold), static_cast<const T*>(dB),
                      static_cast<const T*>(H), static_cast<T*>(ddB), static_cast<T*>(dA2),
                      static_cast<T*>(ws.partial), ws.tiles, ws.perm);
   return hipGetLastError();
@@ -514,11 +638,19 @@ template <typename T, typename G>
 hipError_t finalize_launch(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
                            hipStream_t stream) {
   const int Z = plan->cfg.num_elements;
-  hipLaunchKernelGGL((spec_reduce_kernel<T, G>), dim3(Z * shape.chblocks * G::kS), dim3(kReduceWaves * kLanes), 0, stream,
-                     shape.chblocks, shape.max_tiles, static_cast<const T*>(ws.partial), ws.tile_off, ws.reduced);
-  hipLaunchKernelGGL((spec_unfold_kernel<T, G>), dim3(Z * shape.chblocks), dim3(kLanes), 0, stream,
-                     plan->cfg.num_channels, shape.chblocks, ws.reduced, static_cast<T*>(dW));
+  hipLaunchKernelGGL((spec_finalize_kernel<T, G>), dim3(Z * shape.chblocks * G::kNumBlocks), dim3(kLanes), 0, stream,
+                     plan->cfg.num_channels, shape.chblocks, shape.max_tiles, static_cast<const T*>(ws.partial),
+                     ws.tile_off, static_cast<T*>(dW));
   return hipGetLastError();
+}
+
+// Calls fn.template operator()<T, G>() for the plan's dtype and generated kernel.
+template <typename F>
+hipError_t dispatch(const sc_plan* plan, F&& fn) {
+  const bool f64 = plan->cfg.dtype == SC_F64;
+  if (plan->specialised == 1) return f64 ? fn.template operator()<double, Gen_l3n3_0e1o>() : fn.template operator()<float, Gen_l3n3_0e1o>();
+  if (plan->specialised == 2) return f64 ? fn.template operator()<double, Gen_l3n3_0e1o2e>() : fn.template operator()<float, Gen_l3n3_0e1o2e>();
+  return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -547,53 +679,68 @@ void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
 
 int spec_waves_per_tile() { return kSpecWaves; }
 
-hipError_t launch_spec_forward(const sc_plan* plan, int64_t, const void* A, const void* W, void* B,
-                               const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
-  const bool f64 = plan->cfg.dtype == SC_F64;
-  if (plan->specialised == 1)
-    return f64 ? fwd_launch<double, Gen_l3n3_0e1o>(plan, A, W, B, ws, shape, stream)
-               : fwd_launch<float, Gen_l3n3_0e1o>(plan, A, W, B, ws, shape, stream);
-  if (plan->specialised == 2)
-    return f64 ? fwd_launch<double, Gen_l3n3_0e1o2e>(plan, A, W, B, ws, shape, stream)
-               : fwd_launch<float, Gen_l3n3_0e1o2e>(plan, A, W, B, ws, shape, stream);
-  return hipErrorInvalidValue;
+size_t spec_folded_bytes(const sc_plan* plan) {
+  return static_cast<size_t>(plan->cfg.num_elements) * plan->cfg.num_channels * spec_basis_size(plan->specialised) *
+         (plan->cfg.dtype == SC_F64 ? 8 : 4);
 }
 
-hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,
-                                void* dA, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
-  const bool f64 = plan->cfg.dtype == SC_F64;
-  if (plan->specialised == 1)
-    return f64 ? bwd_launch<double, Gen_l3n3_0e1o>(plan, n, A, W, dB, dA, ws, shape, stream)
-               : bwd_launch<float, Gen_l3n3_0e1o>(plan, n, A, W, dB, dA, ws, shape, stream);
-  if (plan->specialised == 2)
-    return f64 ? bwd_launch<double, Gen_l3n3_0e1o2e>(plan, n, A, W, dB, dA, ws, shape, stream)
-               : bwd_launch<float, Gen_l3n3_0e1o2e>(plan, n, A, W, dB, dA, ws, shape, stream);
-  return hipErrorInvalidValue;
+struct PrepareFn {
+  const sc_plan* plan; int64_t n; const int32_t* z; const void* W; const Workspace& ws; const LaunchShape& shape;
+  bool count, fold; hipStream_t stream;
+  template <typename T, typename G> hipError_t operator()() const { return prepare_launch<T, G>(plan, n, z, W, ws, shape, count, fold, stream); }
+};
+struct ForwardFn {
+  const sc_plan* plan; int64_t n; const void* A; const int32_t* z; void* B; const Workspace& ws; const LaunchShape& shape;
+  bool scatter; hipStream_t stream;
+  template <typename T, typename G> hipError_t operator()() const { return fwd_launch<T, G>(plan, n, A, z, B, ws, shape, scatter, stream); }
+};
+struct BackwardFn {
+  const sc_plan* plan; int64_t n; const void* A; const void* dB; void* dA; const Workspace& ws; const LaunchShape& shape;
+  hipStream_t stream;
+  template <typename T, typename G> hipError_t operator()() const { return bwd_launch<T, G>(plan, n, A, dB, dA, ws, shape, stream); }
+};
+struct DoubleBackwardFn {
+  const sc_plan* plan; const void* A; const void* dB; const void* H; void* ddB; void* dA2; const Workspace& ws;
+  const LaunchShape& shape; hipStream_t stream;
+  template <typename T, typename G> hipError_t operator()() const { return dbl_launch<T, G>(plan, A, dB, H, ddB, dA2, ws, shape, stream); }
+};
+struct FinalizeFn {
+  const sc_plan* plan; void* dW; const Workspace& ws; const LaunchShape& shape; hipStream_t stream;
+  template <typename T, typename G> hipError_t operator()() const { return finalize_launch<T, G>(plan, dW, ws, shape, stream); }
+};
+
+hipError_t launch_spec_prepare(const sc_plan* plan, int64_t n, const int32_t* z, const void* W, const Workspace& ws,
+                               const LaunchShape& shape, bool count, bool fold, hipStream_t stream) {
+  return dispatch(plan, PrepareFn{plan, n, z, W, ws, shape, count, fold, stream});
 }
 
-hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t, const void* A, const void* W, const void* dB,
-                                       const void* H, void* ddB, void* dA2, const Workspace& ws,
-                                       const LaunchShape& shape, hipStream_t stream) {
-  const bool f64 = plan->cfg.dtype == SC_F64;
-  if (plan->specialised == 1)
-    return f64 ? dbl_launch<double, Gen_l3n3_0e1o>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream)
-               : dbl_launch<float, Gen_l3n3_0e1o>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream);
-  if (plan->specialised == 2)
-    return f64 ? dbl_launch<double, Gen_l3n3_0e1o2e>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream)
-               : dbl_launch<float, Gen_l3n3_0e1o2e>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream);
-  return hipErrorInvalidValue;
+hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
+                               const LaunchShape& shape, hipStream_t stream) {
+  const int scatter_wgs = shape.split_waves / kGroupWavesPerWG;
+  hipLaunchKernelGGL(spec_scatter_kernel, dim3(scatter_wgs + 1), dim3(kSpecThreads),
+                     split_group_lds_bytes(plan->cfg.num_elements), stream, group_args(plan, n, z, ws, shape), scatter_wgs);
+  return hipGetLastError();
+}
+
+hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B,
+                               const Workspace& ws, const LaunchShape& shape, bool scatter, hipStream_t stream) {
+  return dispatch(plan, ForwardFn{plan, n, A, z, B, ws, shape, scatter, stream});
+}
+
+hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
+                                const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
+  return dispatch(plan, BackwardFn{plan, n, A, dB, dA, ws, shape, stream});
+}
+
+hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t, const void* A, const void* dB, const void* H,
+                                       void* ddB, void* dA2, const Workspace& ws, const LaunchShape& shape,
+                                       hipStream_t stream) {
+  return dispatch(plan, DoubleBackwardFn{plan, A, dB, H, ddB, dA2, ws, shape, stream});
 }
 
 hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,
                                 hipStream_t stream) {
-  const bool f64 = plan->cfg.dtype == SC_F64;
-  if (plan->specialised == 1)
-    return f64 ? finalize_launch<double, Gen_l3n3_0e1o>(plan, dW, ws, shape, stream)
-               : finalize_launch<float, Gen_l3n3_0e1o>(plan, dW, ws, shape, stream);
-  if (plan->specialised == 2)
-    return f64 ? finalize_launch<double, Gen_l3n3_0e1o2e>(plan, dW, ws, shape, stream)
-               : finalize_launch<float, Gen_l3n3_0e1o2e>(plan, dW, ws, shape, stream);
-  return hipErrorInvalidValue;
+  return dispatch(plan, FinalizeFn{plan, dW, ws, shape, stream});
 }
 
 }  // namespace sc

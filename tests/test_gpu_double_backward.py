@@ -40,7 +40,7 @@ def wl_of(name, N, Z, K, l_max, nu_max, outs, dtype, seed, z_mode="skewed"):
     return workloads.Workload(name, N, Z, K, l_max, nu_max, outs, dtype, seed, z_mode=z_mode)
 
 
-def full_parity(sc, wl, flags=0, mutate=None):
+def full_parity(sc, wl, flags=0, mutate=None, dw_whole_tensor=True):
     say(f"case {wl.name}: N={wl.num_nodes} K={wl.num_channels} Z={wl.num_elements} {wl.dtype} flags={flags}")
     T = oracle_tables(wl)
     inp = workloads.make_inputs(wl, T.paths)
@@ -52,7 +52,8 @@ def full_parity(sc, wl, flags=0, mutate=None):
     ddB_ref, dA2_ref, dW2_ref = oracle_double_backward(osc, T, A, z, W, dB, H)
     check("ddB", ddB, ddB_ref, wl.dtype)
     check("dA2", dA2, dA2_ref, wl.dtype)
-    check_dw("dW2", dW2, dW2_ref, z, wl.dtype, case=f"{wl.name}/{wl.dtype}/flags{flags}")
+    check_dw("dW2", dW2, dW2_ref, z, wl.dtype, case=f"{wl.name}/{wl.dtype}/flags{flags}",
+             whole_tensor=dw_whole_tensor)
     # a second call that reuses the grouping gives identical bits
     again = run.double_backward(H, sc.SC_REUSE_GROUPING)
     assert all(np.array_equal(x, y) for x, y in zip((ddB, dA2, dW2), again[:3]))
@@ -87,10 +88,13 @@ def test_other_configurations(sc, l_max, nu_max, outs):
 
 
 def test_degenerate_batches(sc):
-    full_parity(sc, wl_of("one_node", 1, 89, 128, 3, 3, O01, "f32", 3301))
+    # one of 89 elements present: the 88 zero rows shrink the whole-tensor rms 9.4x, so the error of
+    # the present rows is what is held to the bar (measured on MI355X, one node: 1.34e-6 of the
+    # present rows' rms, 1.26e-5 of the whole tensor's)
+    full_parity(sc, wl_of("one_node", 1, 89, 128, 3, 3, O01, "f32", 3301), dw_whole_tensor=False)
     def all_same(inp):
         inp.z[:] = 41
-    full_parity(sc, wl_of("one_element", 130, 89, 128, 3, 3, O01, "f32", 3302), mutate=all_same)
+    full_parity(sc, wl_of("one_element", 130, 89, 128, 3, 3, O01, "f32", 3302), mutate=all_same, dw_whole_tensor=False)
 
 
 def test_empty_batch_and_argument_errors(sc):

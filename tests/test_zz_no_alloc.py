@@ -77,7 +77,7 @@ def test_limits_and_errors(sc):
     sc.sc_forward_noalloc(plan, 0, None, None, None, None)      # empty batch: nothing to do
     sc.sc_plan_destroy(plan)
     # a plan whose grouping does not fit the array at the node limit is refused, not truncated
-    big = sc.sc_plan_create(64, 3, 3, 1024, O01, sc.SC_F32, 0)
+    big = sc.sc_plan_create(256, 3, 3, 1024, O01, sc.SC_F32, 0)
     with pytest.raises(sc.ScError) as e:
         sc.sc_forward_noalloc(big, sc.SC_NOALLOC_MAX_NODES, x, x, x, x)
     assert e.value.status == sc.SC_ERR_WORKSPACE and "SC_NOALLOC_SCRATCH_BYTES" in str(e.value)
