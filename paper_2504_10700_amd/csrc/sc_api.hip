@@ -107,8 +107,7 @@ LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
     s.split_waves = static_cast<int>(gw);
     s.split_nodes_per_wave = static_cast<int>(((n + gw - 1) / gw + kLanes - 1) / kLanes * kLanes);
     if (s.split_nodes_per_wave < kLanes) s.split_nodes_per_wave = kLanes;
-    // forward: two to four nodes per wave (the folded weights come per node, so small tiles cost nothing)
-    s.fwd_tile_nodes = (n * s.chblocks <= 7168 ? 2 : 4) * (plan->specialised ? spec_waves_per_tile() : 1);
+    s.fwd_tile_nodes = 0;   // chosen at launch from the batch size and the kernel's occupancy
   }
   return s;
 }

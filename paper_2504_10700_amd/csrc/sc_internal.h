@@ -55,7 +55,7 @@ struct LaunchShape {
   // generated kernels: grouping as roles of the prepare / forward launches, forward tiles
   int split_waves;           // waves of the counting sort (a multiple of kGroupWavesPerWG)
   int split_nodes_per_wave;  // a multiple of 64
-  int fwd_tile_nodes;        // consecutive nodes per workgroup of the natural-order forward
+  int fwd_tile_nodes;        // consecutive nodes per workgroup of the natural-order forward (0: chosen at launch)
 };
 
 }  // namespace sc

@@ -481,7 +481,7 @@ template <typename T, int R, int kMaxR>
 __device__ __forceinline__ void finalize_sum(const T* __restrict__ src, size_t tstride, int t0, int t1,
                                              const int (&row)[kMaxR], double (&acc)[kMaxR]) {
   constexpr int kRegs = R * static_cast<int>(sizeof(T) / 4);   // registers per tile in flight
-  constexpr int U = kRegs <= 2 ? 32 : kRegs <= 4 ? 16 : 8;
+  constexpr int U = kRegs <= 2 ? 32 : kRegs <= 4 ? 16 : 8;   // (64 for single rows measured slower: fewer resident waves)
   // batches of U tiles; past the last tile it is read again and dropped
   for (int t = t0; t < t1; t += U) {
     T v[U][R];
@@ -583,17 +583,46 @@ hipError_t prepare_launch(const sc_plan* plan, int64_t n, const int32_t* z, cons
   return hipGetLastError();
 }
 
+// Nodes per workgroup of the natural-order forward.  All workgroups do the same work, so the
+// kernel takes (rounds of resident workgroups) x (nodes per wave): the tile is the multiple of
+// four nodes in 8..32 that minimises that product for this batch on this chip (10k nodes, 128
+// channels, three workgroups per CU: 28 nodes = one round of seven nodes per wave instead of two
+// rounds of four with 16; measured 26-28 -> 22-23 us); ties go to the size nearest 16.
+inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs) {
+  int best = 16;
+  double best_cost = 0;
+  for (int t = 8; t <= 32; t += 4) {
+    const int64_t wgs = (n + t - 1) / t * chblocks;
+    const double cost = static_cast<double>((wgs + resident_wgs - 1) / resident_wgs) * (t / kSpecWaves);
+    const bool better = t == 8 || cost < best_cost * 0.98 ||
+                        (cost <= best_cost * 1.02 && (t - 16) * (t - 16) < (best - 16) * (best - 16));
+    if (better) {
+      best = t;
+      if (t == 8 || cost < best_cost) best_cost = cost;
+    }
+  }
+  return best;
+}
+
 template <typename T, typename G>
 hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B, const Workspace& ws,
                       const LaunchShape& shape, bool scatter, hipStream_t stream) {
   const int scatter_wgs = scatter ? shape.split_waves / kGroupWavesPerWG : 0;
-  const int tiles = static_cast<int>((n + shape.fwd_tile_nodes - 1) / shape.fwd_tile_nodes);
-  const int grid = (scatter ? scatter_wgs + 1 : 0) + tiles * shape.chblocks;
   size_t lds = (G::kNLM * sizeof(T) != 16) ? sizeof(T) * kSpecWaves * G::kNLM * kLanes : 0;
   if (scatter && split_group_lds_bytes(plan->cfg.num_elements) > lds) lds = split_group_lds_bytes(plan->cfg.num_elements);
+  static const int wgs_per_cu = [] {   // resident workgroups per compute unit of this instance
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, spec_forward_kernel<T, G>, kSpecThreads, 0) != hipSuccess || nb < 1)
+      nb = 1;
+    return nb;
+  }();
+  const int tile = shape.fwd_tile_nodes > 0 ? shape.fwd_tile_nodes
+                                            : forward_tile_nodes(n, shape.chblocks, static_cast<int64_t>(wgs_per_cu) * plan->num_cus);
+  const int tiles = static_cast<int>((n + tile - 1) / tile);
+  const int grid = (scatter ? scatter_wgs + 1 : 0) + tiles * shape.chblocks;
   hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
                      group_args(plan, n, z, ws, shape), scatter_wgs, plan->cfg.num_channels, shape.chblocks,
-                     static_cast<int>(n), plan->cfg.num_elements, shape.fwd_tile_nodes, static_cast<const T*>(A), z,
+                     static_cast<int>(n), plan->cfg.num_elements, tile, static_cast<const T*>(A), z,
                      static_cast<const T*>(ws.wfold), static_cast<T*>(B));
   return hipGetLastError();
 }
