@@ -83,13 +83,16 @@ struct Row {
 // writes the k-th contiguous 1 KB of the block instead of 64 scattered 16-byte pieces
 // (four times fewer, four times larger write requests to L2; measured -10% on the whole
 // backward kernel; the same trick on the loads of A gained nothing).  stage: 64*N elements
-// of LDS owned by this wave; block: where lane 0's row goes (16-byte aligned).
+// of LDS owned by this wave; block: where lane 0's row goes (16-byte aligned); live_lanes: the
+// lanes whose rows exist (fewer than 64 in the last channel block of a channel count that is not
+// a multiple of 64).
 // kStream: non-temporal stores (the rows are not read again soon and each instruction writes
 // whole lines).  Measured on one box, library against library: forward 28.4 -> 27.0 us at 10k
 // nodes (neutral at 200k), second-order kernel 78.7 -> 77.5 us; a wash for the backward's dA
 // at 10k nodes and 1% slower at 200k, so the backward leaves it off.
 template <typename T, int N, bool kStream = true>
-__device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* stage, int lane, const T (&v)[N]) {
+__device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* stage, int lane, const T (&v)[N],
+                                                     int live_lanes = kLanes) {
   constexpr int V = 16 / sizeof(T);
   typedef T Vec __attribute__((ext_vector_type(V)));
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // earlier reads of the stage are done
@@ -108,11 +111,14 @@ __device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* s
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // other lanes' pieces are visible
   __builtin_amdgcn_wave_barrier();
-  constexpr int kPieces = kLanes * N / V;  // 16-byte pieces of the block (64*N is a multiple of V)
+  // 16-byte pieces of the block: 64*N/V of them, fewer if the last channel block is not full
+  // (live_lanes * N is a multiple of V: channel counts are multiples of four)
+  constexpr int kPieces = kLanes * N / V;
+  const int pieces = live_lanes * N / V;
 #pragma unroll
   for (int q0 = 0; q0 < kPieces; q0 += kLanes) {
     const int q = q0 + lane;
-    if (q0 + kLanes <= kPieces || q < kPieces) {
+    if (q < pieces) {
       const Vec x = *reinterpret_cast<const Vec*>(stage + q * V);
       if constexpr (kStream) __builtin_nontemporal_store(x, reinterpret_cast<Vec*>(block + q * V));
       else *reinterpret_cast<Vec*>(block + q * V) = x;
@@ -154,7 +160,9 @@ __global__ __launch_bounds__(kSpecThreads) void spec_prepare_kernel(SplitGroupAr
   const int lane = threadIdx.x & (kLanes - 1);
   const int pair = (static_cast<int>(blockIdx.x) - count_wgs) * kSpecWaves + wave_of_thread();
   if (pair >= n_pairs) return;
-  const int z = pair / chblocks, ch = (pair % chblocks) * kLanes + lane;
+  const int z = pair / chblocks, cb = pair % chblocks;
+  const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;
+  const int ch = cb * kLanes + (lane < live ? lane : live - 1);   // dead lanes repeat the last channel
   T w[G::kS], wz[G::kP];
   // all kP rows are requested before the first is used (one memory latency, not one per few rows)
   const T* src = W + static_cast<size_t>(z) * G::kP * K + ch;
@@ -206,7 +214,8 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   const int cnt = (n - s0 < tile) ? n - s0 : tile;
   const int j0 = s0 + cnt * wave / kSpecWaves, j1 = s0 + cnt * (wave + 1) / kSpecWaves;
   if (j0 >= j1) return;
-  const int ch = cb * kLanes + lane;
+  const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;   // channels of this block
+  const int ch = cb * kLanes + (lane < live ? lane : live - 1);           // dead lanes repeat the last channel
   // the element indices of this wave's nodes (at most 64: one per lane), read at once so that the
   // per-node chain is folded weights -> arithmetic, not index -> folded weights -> arithmetic
   const int zv = (j0 + lane < j1) ? z[j0 + lane] : 0;
@@ -226,8 +235,8 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
     }
     if (ok0) {
       G::forward(a0, w0, b);
-      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(j) * K + cb * kLanes) * G::kNLM, stage, lane, b);
-      else Row<T, G::kNLM>::store(B + (static_cast<size_t>(j) * K + ch) * G::kNLM, b);
+      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(j) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
+      else if (lane < live) Row<T, G::kNLM>::store(B + (static_cast<size_t>(j) * K + ch) * G::kNLM, b);
     }
     if (j + 1 < j1) {
       if (j + 2 < j1) {
@@ -236,8 +245,8 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
       }
       if (ok1) {
         G::forward(a1, w1, b);
-        if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(j + 1) * K + cb * kLanes) * G::kNLM, stage, lane, b);
-        else Row<T, G::kNLM>::store(B + (static_cast<size_t>(j + 1) * K + ch) * G::kNLM, b);
+        if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(j + 1) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
+        else if (lane < live) Row<T, G::kNLM>::store(B + (static_cast<size_t>(j + 1) * K + ch) * G::kNLM, b);
       }
     }
   }
@@ -274,7 +283,8 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
   if (td.count == 0) return;        // unused descriptor; uniform per workgroup
   const int j0 = td.start + td.count * wave / kSpecWaves;
   const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
-  const int ch = cb * kLanes + lane;
+  const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;   // channels of this block
+  const int ch = cb * kLanes + (lane < live ? lane : live - 1);           // dead lanes repeat the last channel
   T dw[G::kS];
 #pragma unroll
   for (int s = 0; s < G::kS; ++s) dw[s] = T(0);
@@ -292,7 +302,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
         Row<T, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
       }
       G::backward(a0, w, g0, da, dw);
-      store_rows_coalesced<T, G::kNlm, kOcc != 0>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da);
+      store_rows_coalesced<T, G::kNlm, kOcc != 0>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       if (j + 1 < j1) {
         if (j + 2 < j1) {
           node0 = perm[j + 2];
@@ -300,7 +310,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
           Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
         }
         G::backward(a1, w, g1, da, dw);
-        store_rows_coalesced<T, G::kNlm, kOcc != 0>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da);
+        store_rows_coalesced<T, G::kNlm, kOcc != 0>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       }
     }
   }
@@ -349,7 +359,8 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
   if (td.count == 0) return;        // unused descriptor; uniform per workgroup
   const int j0 = td.start + td.count * wave / kSpecWaves;
   const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
-  const int ch = cb * kLanes + lane;
+  const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;   // channels of this block
+  const int ch = cb * kLanes + (lane < live ? lane : live - 1);           // dead lanes repeat the last channel
   T dw[G::kS];
 #pragma unroll
   for (int s = 0; s < G::kS; ++s) dw[s] = T(0);
@@ -372,9 +383,9 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
         Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
         Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
       }
-      store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da);
-      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb);
-      else Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+      store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
+      else if (lane < live) Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
     }
   }
 #pragma unroll
@@ -409,7 +420,8 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
   if (td.count == 0) return;        // unused descriptor; uniform per workgroup
   const int j0 = td.start + td.count * wave / kSpecWaves;
   const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
-  const int ch = cb * kLanes + lane;
+  const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;   // channels of this block
+  const int ch = cb * kLanes + (lane < live ? lane : live - 1);           // dead lanes repeat the last channel
   T* dwl = acc_all + wave * G::kS * kLanes + lane;
 #pragma unroll
   for (int s = 0; s < G::kS; ++s) dwl[s * kLanes] = T(0);
@@ -446,9 +458,9 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
         Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
         Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
       }
-      store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da);
-      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb);
-      else Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+      store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
+      else if (lane < live) Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
     }
   }
   __syncthreads();
@@ -521,6 +533,7 @@ __global__ __launch_bounds__(kLanes) void spec_finalize_kernel(int K, int chbloc
   if (d.n_rows == 1) finalize_sum<T, 1, R>(src, tstride, t0, t1, d.row, sum);
   else if (R >= 2 && d.n_rows == 2) finalize_sum<T, (R >= 2 ? 2 : 1), R>(src, tstride, t0, t1, d.row, sum);
   else finalize_sum<T, R, R>(src, tstride, t0, t1, d.row, sum);
+  if (cb * kLanes + lane >= K) return;   // lanes past the last channel
   T* out = dW + static_cast<size_t>(e) * G::kP * K + cb * kLanes + lane;
 #pragma unroll
   for (int i = 0; i < G::kMaxBlockPaths; ++i) {
@@ -540,7 +553,9 @@ bool matches(const sc_plan* plan) {
   if (c.l_max != G::kLmax || c.nu_max != G::kNuMax || c.num_out != G::kNumOut) return false;
   for (int o = 0; o < G::kNumOut; ++o)
     if (c.out_l[o] != G::kOutL[o] || c.out_parity[o] != G::kOutParity[o]) return false;
-  return c.num_channels % kLanes == 0 && static_cast<int>(plan->table.paths.size()) == G::kP;
+  // channel counts that are not a multiple of 64 leave lanes of the last channel block idle; a multiple
+  // of four keeps every row block 16-byte aligned
+  return c.num_channels % 4 == 0 && static_cast<int>(plan->table.paths.size()) == G::kP;
 }
 
 SplitGroupArgs group_args(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
@@ -709,7 +724,8 @@ void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
 int spec_waves_per_tile() { return kSpecWaves; }
 
 size_t spec_folded_bytes(const sc_plan* plan) {
-  return static_cast<size_t>(plan->cfg.num_elements) * plan->cfg.num_channels * spec_basis_size(plan->specialised) *
+  const size_t chblocks = (plan->cfg.num_channels + kLanes - 1) / kLanes;   // whole 64-channel rows
+  return static_cast<size_t>(plan->cfg.num_elements) * chblocks * kLanes * spec_basis_size(plan->specialised) *
          (plan->cfg.dtype == SC_F64 ? 8 : 4);
 }
 

@@ -86,7 +86,11 @@ def test_wide_shape_small_batch(sc, flags, dtype):
 
 @pytest.mark.parametrize("K", [8, 96, 192])
 def test_channel_counts_that_do_not_fill_a_wave(sc, K):
-    full_parity(sc, wl_of(f"k{K}", 70, 3, K, 3, 3, O01, "f32", 2100 + K, z_mode="uniform"))
+    # the generated kernels serve them with idle lanes in the last 64-channel block
+    info = full_parity(sc, wl_of(f"k{K}", 70, 3, K, 3, 3, O01, "f32", 2100 + K, z_mode="uniform"))
+    assert info.specialised == 1
+    full_parity(sc, wl_of(f"k{K}w", 45, 3, K, 3, 3, O012, "f64", 2150 + K, z_mode="uniform"))
+    full_parity(sc, wl_of(f"k{K}g", 45, 3, K, 3, 3, O01, "f32", 2170 + K, z_mode="uniform"), flags=2)
 
 
 @pytest.mark.parametrize("l_max,nu_max,outs", [(0, 3, ((0, 1),)), (2, 2, O012), (3, 1, O01), (2, 3, ((2, -1), (1, 1)))])
