@@ -39,6 +39,8 @@ OUT_DIR = os.path.join(os.path.dirname(_HERE), "csrc", "generated")
 SPECS = {
     "l3n3_0e1o": (3, 3, ((0, 1), (1, -1))),
     "l3n3_0e1o2e": (3, 3, ((0, 1), (1, -1), (2, 1))),
+    "l3n3_0e1o2e3o": (3, 3, ((0, 1), (1, -1), (2, 1), (3, -1))),
+    "l1n2_0e": (1, 2, ((0, 1),)),
 }
 
 

@@ -388,11 +388,12 @@ static sc_status check_common(const char* fn, const sc_plan* plan, int64_t n, co
 // Records the error message itself.
 static hipError_t grouped_pass_prologue(const char* fn, sc_plan* plan, int64_t n_nodes, const int32_t* z, const void* W,
                                         const sc::Workspace& ws, const sc::LaunchShape& shape, uint32_t flags,
-                                        hipStream_t stream) {
+                                        bool uses_folded_table, hipStream_t stream) {
   const bool group = !(flags & SC_REUSE_GROUPING);
   hipError_t e = hipSuccess;
   if (plan->specialised) {
-    e = sc::launch_spec_prepare(plan, n_nodes, z, W, ws, shape, group, !(flags & SC_REUSE_WEIGHTS), stream);
+    e = sc::launch_spec_prepare(plan, n_nodes, z, W, ws, shape, group, uses_folded_table && !(flags & SC_REUSE_WEIGHTS),
+                                stream);
     if (e == hipSuccess && group) e = sc::launch_spec_scatter(plan, n_nodes, z, ws, shape, stream);
   } else if (group) {
     e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
@@ -495,7 +496,7 @@ sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32
   if (!A || !z || !W || !dB || !dA) return fail(SC_ERR_INVALID_ARG, "sc_backward: NULL tensor argument");
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(dA, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_backward: tensor pointer not 16-byte aligned");
-  hipError_t e = grouped_pass_prologue("sc_backward", plan, n_nodes, z, W, ws, shape, flags, stream);
+  hipError_t e = grouped_pass_prologue("sc_backward", plan, n_nodes, z, W, ws, shape, flags, true, stream);
   if (e != hipSuccess) return SC_ERR_HIP;
   if (plan->profile) (void)hipEventRecord(plan->ev[2], stream);
   e = plan->specialised ? sc::launch_spec_backward(plan, n_nodes, A, dB, dA, ws, shape, stream)
@@ -536,11 +537,11 @@ sc_status sc_double_backward(sc_plan* plan, int64_t n_nodes, const void* A, cons
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(H, 16) || misaligned(ddB, 16) ||
       misaligned(dA2, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_double_backward: tensor pointer not 16-byte aligned");
-  hipError_t e = grouped_pass_prologue("sc_double_backward", plan, n_nodes, z, W, ws, shape, flags, stream);
+  hipError_t e = grouped_pass_prologue("sc_double_backward", plan, n_nodes, z, W, ws, shape, flags, false, stream);
   if (e != hipSuccess) return SC_ERR_HIP;
   if (plan->profile) (void)hipEventRecord(plan->ev[4], stream);
   e = plan->specialised
-          ? sc::launch_spec_double_backward(plan, n_nodes, A, dB, H, ddB, dA2, ws, shape, stream)
+          ? sc::launch_spec_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape, stream)
           : sc::launch_generic_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_double_backward: kernel launch");
   if (plan->profile) {

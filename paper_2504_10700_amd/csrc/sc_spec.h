@@ -27,12 +27,12 @@ hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z,
 // grouping rides in the same launch.
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B,
                                const Workspace& ws, const LaunchShape& shape, bool scatter, hipStream_t stream);
-// The grouped passes read ws.wfold, ws.perm and ws.tiles.
+// The grouped passes read ws.perm and ws.tiles; the backward reads ws.wfold, the second-order pass folds W itself.
 hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
                                 const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
-hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, const void* H,
-                                       void* ddB, void* dA2, const Workspace& ws, const LaunchShape& shape,
-                                       hipStream_t stream);
+hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,
+                                       const void* H, void* ddB, void* dA2, const Workspace& ws,
+                                       const LaunchShape& shape, hipStream_t stream);
 
 // dW reduction over the tiles of every element and unfold to the external paths.
 hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,

@@ -35,6 +35,8 @@ __device__ __forceinline__ double sc_fma(double x, double y, double z) { return 
 
 #include "generated/sc_gen_l3n3_0e1o.inc"
 #include "generated/sc_gen_l3n3_0e1o2e.inc"
+#include "generated/sc_gen_l3n3_0e1o2e3o.inc"
+#include "generated/sc_gen_l1n2_0e.inc"
 
 constexpr int kSpecWaves = 4;
 constexpr int kSpecThreads = kSpecWaves * kLanes;
@@ -118,7 +120,7 @@ __device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* s
 #pragma unroll
   for (int q0 = 0; q0 < kPieces; q0 += kLanes) {
     const int q = q0 + lane;
-    if (q < pieces) {
+    if ((live_lanes == kLanes && q0 + kLanes <= kPieces) || q < pieces) {   // the first test is a constant for full blocks
       const Vec x = *reinterpret_cast<const Vec*>(stage + q * V);
       if constexpr (kStream) __builtin_nontemporal_store(x, reinterpret_cast<Vec*>(block + q * V));
       else *reinterpret_cast<Vec*>(block + q * V) = x;
@@ -211,44 +213,74 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   constexpr bool kStageB = G::kNLM * sizeof(T) != 16;  // 16-byte rows are coalesced as they are
   const int t = block / chblocks, cb = block % chblocks;
   const int s0 = t * tile;
-  const int cnt = (n - s0 < tile) ? n - s0 : tile;
-  const int j0 = s0 + cnt * wave / kSpecWaves, j1 = s0 + cnt * (wave + 1) / kSpecWaves;
+  const int in_tile = (n - s0 < tile) ? n - s0 : tile;
+  const int j0 = s0 + in_tile * wave / kSpecWaves, j1 = s0 + in_tile * (wave + 1) / kSpecWaves;
   if (j0 >= j1) return;
   const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;   // channels of this block
   const int ch = cb * kLanes + (lane < live ? lane : live - 1);           // dead lanes repeat the last channel
-  // the element indices of this wave's nodes (at most 64: one per lane), read at once so that the
-  // per-node chain is folded weights -> arithmetic, not index -> folded weights -> arithmetic
-  const int zv = (j0 + lane < j1) ? z[j0 + lane] : 0;
-  auto element = [&](int j, bool& ok) {
-    const int e = __builtin_amdgcn_readlane(zv, j - j0);
-    ok = e >= 0 && e < Z;
-    return ok ? e : 0;
+  // This wave's nodes (at most 64: one per lane) are visited grouped by element - a stable sort of
+  // their element indices inside the wave - so that a run of nodes of one element reads the
+  // folded weights once (they are re-read per node otherwise: 61 of 432 us at 200k nodes).  The
+  // indices are read at once, which also takes them off the per-node chain of dependent loads.
+  // Nodes with an element index outside [0, Z) sort last and are skipped.
+  const int cnt = j1 - j0;
+  int key = Z;
+  if (lane < cnt) {
+    const int e = z[j0 + lane];
+    key = (e >= 0 && e < Z) ? e : Z;
+  }
+  int rank = lane;   // lanes past the last node keep their own slot
+  if (lane < cnt) rank = 0;
+  for (int k = 0; k < cnt; ++k) {   // uniform trip count
+    const int zk = __builtin_amdgcn_readlane(key, k);
+    if (lane < cnt && (zk < key || (zk == key && k < lane))) ++rank;
+  }
+  const int order = __builtin_amdgcn_ds_permute(rank << 2, lane);   // order[p] = lane of the node visited p-th
+  auto visit = [&](int p, int& node, int& e) {
+    const int idx = __builtin_amdgcn_readlane(order, p);
+    e = __builtin_amdgcn_readlane(key, idx);
+    node = j0 + idx;
   };
   T a0[G::kNlm], a1[G::kNlm], w0[G::kS], w1[G::kS], b[G::kNLM];
-  bool ok0 = false, ok1 = false;
-  load_folded<T, G>(wf, element(j0, ok0), chblocks, cb, lane, w0);
-  Row<T, G::kNlm>::load(A + (static_cast<size_t>(j0) * K + ch) * G::kNlm, a0);
-  for (int j = j0; j < j1; j += 2) {
-    if (j + 1 < j1) {
-      load_folded<T, G>(wf, element(j + 1, ok1), chblocks, cb, lane, w1);
-      Row<T, G::kNlm>::load(A + (static_cast<size_t>(j + 1) * K + ch) * G::kNlm, a1);
-    }
-    if (ok0) {
-      G::forward(a0, w0, b);
-      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(j) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
-      else if (lane < live) Row<T, G::kNLM>::store(B + (static_cast<size_t>(j) * K + ch) * G::kNLM, b);
-    }
-    if (j + 1 < j1) {
-      if (j + 2 < j1) {
-        load_folded<T, G>(wf, element(j + 2, ok0), chblocks, cb, lane, w0);
-        Row<T, G::kNlm>::load(A + (static_cast<size_t>(j + 2) * K + ch) * G::kNlm, a0);
-      }
-      if (ok1) {
-        G::forward(a1, w1, b);
-        if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(j + 1) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
-        else if (lane < live) Row<T, G::kNLM>::store(B + (static_cast<size_t>(j + 1) * K + ch) * G::kNLM, b);
+  int n0, e0, n1 = 0, e1 = Z;
+  visit(0, n0, e0);
+  if (e0 >= Z) return;   // no valid node in this wave's share
+  load_folded<T, G>(wf, e0, chblocks, cb, lane, w0);
+  Row<T, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
+  for (int p = 0; p < cnt; p += 2) {
+    if (p + 1 < cnt) {
+      visit(p + 1, n1, e1);
+      if (e1 < Z) {
+        if (e1 == e0) {
+#pragma unroll
+          for (int s = 0; s < G::kS; ++s) w1[s] = w0[s];
+        } else {
+          load_folded<T, G>(wf, e1, chblocks, cb, lane, w1);
+        }
+        Row<T, G::kNlm>::load(A + (static_cast<size_t>(n1) * K + ch) * G::kNlm, a1);
       }
     }
+    G::forward(a0, w0, b);
+    if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(n0) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
+    else if (lane < live) Row<T, G::kNLM>::store(B + (static_cast<size_t>(n0) * K + ch) * G::kNLM, b);
+    if (p + 1 >= cnt || e1 >= Z) break;   // the valid nodes are done
+    e0 = Z;
+    if (p + 2 < cnt) {
+      visit(p + 2, n0, e0);
+      if (e0 < Z) {
+        if (e0 == e1) {
+#pragma unroll
+          for (int s = 0; s < G::kS; ++s) w0[s] = w1[s];
+        } else {
+          load_folded<T, G>(wf, e0, chblocks, cb, lane, w0);
+        }
+        Row<T, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
+      }
+    }
+    G::forward(a1, w1, b);
+    if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(n1) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
+    else if (lane < live) Row<T, G::kNLM>::store(B + (static_cast<size_t>(n1) * K + ch) * G::kNLM, b);
+    if (e0 >= Z) break;
   }
 }
 
@@ -262,7 +294,10 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
 // kernel itself gains 2 us at 10k nodes and the launches after it another 3 us (step 99.1 -> 93.5
 // us, same box), whereas at 200k nodes the backward loses 2% with them and the next forward gains
 // as much.
-template <typename T, typename G, int kOcc = 0>
+// kFull: the channel count is a multiple of 64, no lane is ever idle.  The fp32 kernel of the
+// 49-row basis sits at the limit for two waves per SIMD: 250 registers without the idle-lane
+// handling, 295 (one wave per SIMD, 736 instead of 496 us at 50k nodes / 256 channels) with it.
+template <typename T, typename G, int kOcc = 0, bool kStreamDA = false, bool kFull = false>
 __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(kOcc == 0 ? 1 : kOcc, 8)))
 void spec_backward_kernel(int K, int chblocks, int n_blocks,
                                                                      const T* __restrict__ A,
@@ -283,7 +318,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
   if (td.count == 0) return;        // unused descriptor; uniform per workgroup
   const int j0 = td.start + td.count * wave / kSpecWaves;
   const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
-  const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;   // channels of this block
+  const int live = kFull ? kLanes : (K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes);   // channels of this block
   const int ch = cb * kLanes + (lane < live ? lane : live - 1);           // dead lanes repeat the last channel
   T dw[G::kS];
 #pragma unroll
@@ -302,7 +337,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
         Row<T, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
       }
       G::backward(a0, w, g0, da, dw);
-      store_rows_coalesced<T, G::kNlm, kOcc != 0>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      store_rows_coalesced<T, G::kNlm, kStreamDA>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       if (j + 1 < j1) {
         if (j + 2 < j1) {
           node0 = perm[j + 2];
@@ -310,7 +345,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
           Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
         }
         G::backward(a1, w, g1, da, dw);
-        store_rows_coalesced<T, G::kNlm, kOcc != 0>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+        store_rows_coalesced<T, G::kNlm, kStreamDA>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       }
     }
   }
@@ -341,9 +376,9 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
 //    larger basis or fp64 it would spill.  Small changes to its text move the register
 //    allocation across the spill threshold: check the compiler's resource report
 //    (-Rpass-analysis=kernel-resource-usage) after touching it.
-template <typename T, typename G>
+template <typename T, typename G, bool kFull>
 __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
-    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ wf, const T* __restrict__ dB,
+    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
     const T* __restrict__ H, T* __restrict__ ddB, T* __restrict__ dA2, T* __restrict__ partial,
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ perm) {
   extern __shared__ unsigned char lds_raw[];
@@ -359,14 +394,14 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
   if (td.count == 0) return;        // unused descriptor; uniform per workgroup
   const int j0 = td.start + td.count * wave / kSpecWaves;
   const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
-  const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;   // channels of this block
+  const int live = kFull ? kLanes : (K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes);   // channels of this block
   const int ch = cb * kLanes + (lane < live ? lane : live - 1);           // dead lanes repeat the last channel
   T dw[G::kS];
 #pragma unroll
   for (int s = 0; s < G::kS; ++s) dw[s] = T(0);
   if (j0 < j1) {
     T w[G::kS];
-    load_folded<T, G>(wf, td.z, chblocks, cb, lane, w);
+    G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w);
     // one register set of inputs: the next node's rows are requested right after the
     // arithmetic of the current one has consumed them, ahead of its stores
     T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
@@ -385,7 +420,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
       }
       store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
-      else if (lane < live) Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+      else if (kFull || lane < live) Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
     }
   }
 #pragma unroll
@@ -401,9 +436,9 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
 }
 
 // See above.  LDS: w' [kSpecWaves][kS][64] | sums [kSpecWaves][kS][64] | stage [kSpecWaves][64][kNlm].
-template <typename T, typename G>
+template <typename T, typename G, bool kFull>
 __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void spec_double_backward_lds_kernel(
-    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ wf, const T* __restrict__ dB,
+    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
     const T* __restrict__ H, T* __restrict__ ddB, T* __restrict__ dA2, T* __restrict__ partial,
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ perm) {
   extern __shared__ unsigned char lds_raw[];
@@ -420,8 +455,8 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
   if (td.count == 0) return;        // unused descriptor; uniform per workgroup
   const int j0 = td.start + td.count * wave / kSpecWaves;
   const int j1 = td.start + td.count * (wave + 1) / kSpecWaves;
-  const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;   // channels of this block
-  const int ch = cb * kLanes + (lane < live ? lane : live - 1);           // dead lanes repeat the last channel
+  const int live = kFull ? kLanes : (K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes);   // channels of this block
+  const int ch = kFull ? cb * kLanes + lane : cb * kLanes + (lane < live ? lane : live - 1);   // dead lanes repeat the last channel
   T* dwl = acc_all + wave * G::kS * kLanes + lane;
 #pragma unroll
   for (int s = 0; s < G::kS; ++s) dwl[s * kLanes] = T(0);
@@ -429,7 +464,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
     T* wl = red + wave * G::kS * kLanes + lane;   // this wave's slice of red holds w' until the end
     {
       T w0[G::kS];
-      load_folded<T, G>(wf, td.z, chblocks, cb, lane, w0);
+      G::fold(W + static_cast<size_t>(td.z) * G::kP * K + ch, K, w0);
 #pragma unroll
       for (int s = 0; s < G::kS; ++s) wl[s * kLanes] = w0[s];
     }
@@ -460,7 +495,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
       }
       store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
-      else if (lane < live) Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+      else if (kFull || lane < live) Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
     }
   }
   __syncthreads();
@@ -553,6 +588,10 @@ bool matches(const sc_plan* plan) {
   if (c.l_max != G::kLmax || c.nu_max != G::kNuMax || c.num_out != G::kNumOut) return false;
   for (int o = 0; o < G::kNumOut; ++o)
     if (c.out_l[o] != G::kOutL[o] || c.out_parity[o] != G::kOutParity[o]) return false;
+  // the grouped kernels keep kS + kNlm columns per wave in LDS: 160 KB per compute unit at most
+  // (the four-irrep kernel in fp64 would need 171 KB: the table-driven kernels serve that plan)
+  const size_t lds = (c.dtype == SC_F64 ? 8 : 4) * static_cast<size_t>(kSpecWaves) * (G::kS + G::kNlm) * kLanes;
+  if (lds > 160 * 1024) return false;
   // channel counts that are not a multiple of 64 leave lanes of the last channel block idle; a multiple
   // of four keeps every row block 16-byte aligned
   return c.num_channels % 4 == 0 && static_cast<int>(plan->table.paths.size()) == G::kP;
@@ -600,23 +639,21 @@ hipError_t prepare_launch(const sc_plan* plan, int64_t n, const int32_t* z, cons
 
 // Nodes per workgroup of the natural-order forward.  All workgroups do the same work, so the
 // kernel takes (rounds of resident workgroups) x (nodes per wave): the tile is the multiple of
-// four nodes in 8..32 that minimises that product for this batch on this chip (10k nodes, 128
+// four nodes in 8..64 that minimises that product for this batch on this chip (10k nodes, 128
 // channels, three workgroups per CU: 28 nodes = one round of seven nodes per wave instead of two
-// rounds of four with 16; measured 26-28 -> 22-23 us); ties go to the size nearest 16.
+// rounds of four with 16); among sizes within 2% of the best the largest wins, since longer
+// shares per wave meet more runs of one element.
 inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs) {
-  int best = 16;
-  double best_cost = 0;
-  for (int t = 8; t <= 32; t += 4) {
+  auto cost = [&](int t) {
     const int64_t wgs = (n + t - 1) / t * chblocks;
-    const double cost = static_cast<double>((wgs + resident_wgs - 1) / resident_wgs) * (t / kSpecWaves);
-    const bool better = t == 8 || cost < best_cost * 0.98 ||
-                        (cost <= best_cost * 1.02 && (t - 16) * (t - 16) < (best - 16) * (best - 16));
-    if (better) {
-      best = t;
-      if (t == 8 || cost < best_cost) best_cost = cost;
-    }
-  }
-  return best;
+    return static_cast<double>((wgs + resident_wgs - 1) / resident_wgs) * (t / kSpecWaves);
+  };
+  double best = cost(8);
+  for (int t = 12; t <= 64; t += 4) best = cost(t) < best ? cost(t) : best;
+  int pick = 8;
+  for (int t = 8; t <= 64; t += 4)
+    if (cost(t) <= best * 1.02) pick = t;
+  return pick;
 }
 
 template <typename T, typename G>
@@ -648,9 +685,11 @@ hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void*
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
   const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
-  auto kernel = &spec_backward_kernel<T, G, 0>;
+  const bool full = plan->cfg.num_channels % kLanes == 0;
+  auto kernel = full ? &spec_backward_kernel<T, G, 0, false, true> : &spec_backward_kernel<T, G, 0, false, false>;
   if constexpr (sizeof(T) == 4 && G::kS <= 32) {
-    if (n <= 40000) kernel = &spec_backward_kernel<T, G, 3>;   // small batches: three waves per SIMD (see the kernel)
+    // small batches: three waves per SIMD, streamed dA (see the kernel)
+    if (n <= 40000) kernel = full ? &spec_backward_kernel<T, G, 3, true, true> : &spec_backward_kernel<T, G, 3, true, false>;
   }
   const hipError_t e = raise_lds_limit(kernel, lds);
   if (e != hipSuccess) return e;
@@ -661,18 +700,19 @@ hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void*
 }
 
 template <typename T, typename G>
-hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* dB, const void* H, void* ddB,
+hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const void* dB, const void* H, void* ddB,
                       void* dA2, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
   constexpr bool kLds = kUseLdsState<T, G>;
   const size_t lds = sizeof(T) * kSpecWaves * ((kLds ? 2 : 1) * G::kS + G::kNlm) * kLanes;
-  auto kernel = &spec_double_backward_kernel<T, G>;
-  if constexpr (kLds) kernel = &spec_double_backward_lds_kernel<T, G>;
+  const bool full = plan->cfg.num_channels % kLanes == 0;   // no idle lanes: an instance without their handling
+  auto kernel = full ? &spec_double_backward_kernel<T, G, true> : &spec_double_backward_kernel<T, G, false>;
+  if constexpr (kLds) kernel = full ? &spec_double_backward_lds_kernel<T, G, true> : &spec_double_backward_lds_kernel<T, G, false>;
   const hipError_t e = raise_lds_limit(kernel, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpecThreads), lds, stream, plan->cfg.num_channels, shape.chblocks,
-                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(ws.wfold), static_cast<const T*>(dB),
+                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(W), static_cast<const T*>(dB),
                      static_cast<const T*>(H), static_cast<T*>(ddB), static_cast<T*>(dA2),
                      static_cast<T*>(ws.partial), ws.tiles, ws.perm);
   return hipGetLastError();
@@ -694,6 +734,8 @@ hipError_t dispatch(const sc_plan* plan, F&& fn) {
   const bool f64 = plan->cfg.dtype == SC_F64;
   if (plan->specialised == 1) return f64 ? fn.template operator()<double, Gen_l3n3_0e1o>() : fn.template operator()<float, Gen_l3n3_0e1o>();
   if (plan->specialised == 2) return f64 ? fn.template operator()<double, Gen_l3n3_0e1o2e>() : fn.template operator()<float, Gen_l3n3_0e1o2e>();
+  if (plan->specialised == 3) return f64 ? fn.template operator()<double, Gen_l3n3_0e1o2e3o>() : fn.template operator()<float, Gen_l3n3_0e1o2e3o>();
+  if (plan->specialised == 4) return f64 ? fn.template operator()<double, Gen_l1n2_0e>() : fn.template operator()<float, Gen_l1n2_0e>();
   return hipErrorInvalidValue;
 }
 
@@ -702,10 +744,14 @@ hipError_t dispatch(const sc_plan* plan, F&& fn) {
 int spec_lookup(const sc_plan* plan) {
   if (matches<Gen_l3n3_0e1o>(plan)) return 1;
   if (matches<Gen_l3n3_0e1o2e>(plan)) return 2;
+  if (matches<Gen_l3n3_0e1o2e3o>(plan)) return 3;
+  if (matches<Gen_l1n2_0e>(plan)) return 4;
   return 0;
 }
 
-int spec_basis_size(int id) { return id == 1 ? Gen_l3n3_0e1o::kS : id == 2 ? Gen_l3n3_0e1o2e::kS : 0; }
+int spec_basis_size(int id) {
+  return id == 1 ? Gen_l3n3_0e1o::kS : id == 2 ? Gen_l3n3_0e1o2e::kS : id == 3 ? Gen_l3n3_0e1o2e3o::kS : id == 4 ? Gen_l1n2_0e::kS : 0;
+}
 
 template <typename G>
 void op_counts(int32_t ops[3], int32_t flops[3]) {
@@ -719,6 +765,8 @@ void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
   for (int i = 0; i < 3; ++i) ops[i] = flops[i] = 0;
   if (id == 1) op_counts<Gen_l3n3_0e1o>(ops, flops);
   if (id == 2) op_counts<Gen_l3n3_0e1o2e>(ops, flops);
+  if (id == 3) op_counts<Gen_l3n3_0e1o2e3o>(ops, flops);
+  if (id == 4) op_counts<Gen_l1n2_0e>(ops, flops);
 }
 
 int spec_waves_per_tile() { return kSpecWaves; }
@@ -745,9 +793,9 @@ struct BackwardFn {
   template <typename T, typename G> hipError_t operator()() const { return bwd_launch<T, G>(plan, n, A, dB, dA, ws, shape, stream); }
 };
 struct DoubleBackwardFn {
-  const sc_plan* plan; const void* A; const void* dB; const void* H; void* ddB; void* dA2; const Workspace& ws;
+  const sc_plan* plan; const void* A; const void* W; const void* dB; const void* H; void* ddB; void* dA2; const Workspace& ws;
   const LaunchShape& shape; hipStream_t stream;
-  template <typename T, typename G> hipError_t operator()() const { return dbl_launch<T, G>(plan, A, dB, H, ddB, dA2, ws, shape, stream); }
+  template <typename T, typename G> hipError_t operator()() const { return dbl_launch<T, G>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream); }
 };
 struct FinalizeFn {
   const sc_plan* plan; void* dW; const Workspace& ws; const LaunchShape& shape; hipStream_t stream;
@@ -777,10 +825,10 @@ hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, c
   return dispatch(plan, BackwardFn{plan, n, A, dB, dA, ws, shape, stream});
 }
 
-hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t, const void* A, const void* dB, const void* H,
-                                       void* ddB, void* dA2, const Workspace& ws, const LaunchShape& shape,
-                                       hipStream_t stream) {
-  return dispatch(plan, DoubleBackwardFn{plan, A, dB, H, ddB, dA2, ws, shape, stream});
+hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t, const void* A, const void* W, const void* dB,
+                                       const void* H, void* ddB, void* dA2, const Workspace& ws,
+                                       const LaunchShape& shape, hipStream_t stream) {
+  return dispatch(plan, DoubleBackwardFn{plan, A, W, dB, H, ddB, dA2, ws, shape, stream});
 }
 
 hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,

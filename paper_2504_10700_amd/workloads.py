@@ -47,6 +47,7 @@ class Workload:
 
 _O01 = ((0, 1), (1, -1))
 _O012 = ((0, 1), (1, -1), (2, 1))
+_O0123 = ((0, 1), (1, -1), (2, 1), (3, -1))
 
 WORKLOADS = {
     "tiny": Workload("tiny", 64, 2, 8, 1, 2, ((0, 1),), "f64", 1001, z_mode="uniform"),
@@ -55,6 +56,8 @@ WORKLOADS = {
     "large_batch": Workload("large_batch", 200_000, 89, 128, 3, 3, _O01, "f32", 1004, structures=2000),
     "wide_high_l": Workload("wide_high_l", 50_000, 89, 256, 3, 3, _O012, "f32", 1005),
     "wide_high_l_f64": Workload("wide_high_l_f64", 5_000, 89, 256, 3, 3, _O012, "f64", 1006),
+    # not one of the task's configurations: every output irrep up to L = 3 at the training-step shape
+    "outputs_l3": Workload("outputs_l3", 10_000, 89, 128, 3, 3, _O0123, "f32", 1008),
 }
 
 

@@ -87,6 +87,12 @@ def test_other_configurations(sc, l_max, nu_max, outs):
     full_parity(sc, wl_of("other", 40, 4, 64, l_max, nu_max, outs, "f64", 3200, z_mode="uniform"))
 
 
+def test_outputs_up_to_L3_generated_kernel(sc):
+    outs = ((0, 1), (1, -1), (2, 1), (3, -1))
+    full_parity(sc, wl_of("out_L3", 60, 5, 64, 3, 3, outs, "f32", 3250, z_mode="uniform"))
+    full_parity(sc, wl_of("out_L3", 60, 5, 64, 3, 3, outs, "f64", 3251, z_mode="uniform"))
+
+
 def test_degenerate_batches(sc):
     # one of 89 elements present: the 88 zero rows shrink the whole-tensor rms 9.4x, so the error of
     # the present rows is what is held to the bar (measured on MI355X, one node: 1.34e-6 of the

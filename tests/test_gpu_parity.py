@@ -68,7 +68,8 @@ def wl_of(name, N, Z, K, l_max, nu_max, outs, dtype, seed, z_mode="skewed"):
 
 @pytest.mark.parametrize("flags", [0, 2])
 def test_tiny_config_fp64(sc, flags):
-    full_parity(sc, workloads.WORKLOADS["tiny"], flags)
+    info = full_parity(sc, workloads.WORKLOADS["tiny"], flags)
+    assert info.specialised == (1 if flags == 0 else 0)    # a generated kernel serves it
 
 
 @pytest.mark.parametrize("flags", [0, 2])
@@ -100,9 +101,14 @@ def test_other_configurations(sc, l_max, nu_max, outs):
 
 @pytest.mark.parametrize("dtype", ["f32", "f64"])
 def test_outputs_up_to_L3(sc, dtype):
-    # four output irreps 0e+1o+2e+3o (16 output components) at l_max = 3, nu_max = 3: the table-driven kernels
-    full_parity(sc, wl_of("out_L3", 48, 5, 64, 3, 3, ((0, 1), (1, -1), (2, 1), (3, -1)), dtype, 2300,
-                          z_mode="uniform"))
+    # four output irreps 0e+1o+2e+3o (16 output components) at l_max = 3, nu_max = 3: a generated kernel in
+    # fp32 (in fp64 its columns would not fit the LDS: table-driven kernels), and the table-driven ones forced
+    outs = ((0, 1), (1, -1), (2, 1), (3, -1))
+    info = full_parity(sc, wl_of("out_L3", 48, 5, 64, 3, 3, outs, dtype, 2300, z_mode="uniform"))
+    assert info.specialised == (1 if dtype == "f32" else 0)
+    full_parity(sc, wl_of("out_L3g", 48, 5, 64, 3, 3, outs, dtype, 2300, z_mode="uniform"), flags=2)
+    if dtype == "f32":   # several tiles per element, a channel count that leaves lanes idle, every element of 89
+        full_parity(sc, wl_of("out_L3b", 700, 89, 96, 3, 3, outs, dtype, 2310))
 
 
 def test_degenerate_batches(sc):
