@@ -6,15 +6,17 @@ preparation of the weights done once, in the forward, and reused by the backward
 one batch of synthetic atoms that is already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W]
-                  [--workload training_step|large_batch|wide_high_l|wide_high_l_f64|medium_fwd|tiny]
+                  [--workload training_step|large_batch|wide_high_l|wide_high_l_f64|medium_fwd|outputs_l3|tiny]
 
 Default workload: `training_step` (10 000 nodes, 89 elements, 128 channels, l<=3, nu<=3,
 outputs 0e+1o, fp32, forward+backward) - the configuration the metric "atoms/sec
 symmetric-contraction fwd+bwd (128ch, l<=3, nu=3)" is quoted on.  With the default
 workload the same line also carries, under "also", a shorter measurement of
-`large_batch` (200 000 nodes, same shapes): at 10 000 nodes a step is ~0.1 ms and
+`large_batch` (200 000 nodes, same shapes): at 10 000 nodes a step is ~0.09 ms and
 launch / fixed costs weigh as much as the data movement, at 200 000 nodes they do not;
-and the second-order pass (sc_double_backward alone) on both workloads.
+of `medium_fwd`, `wide_high_l` and `outputs_l3`; of the second-order pass
+(sc_double_backward alone) on both workloads; and of the operations around the contraction.
+"attainable" holds streaming probes of the same run (what this machine reaches without arithmetic).
 
 value          nodes (atoms) per second, forward + backward, whole step (all launches)
 roofline       the dominant kernel (fused backward: dA + per-tile dW) against the HBM
@@ -747,10 +749,14 @@ def main():
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(wl, min(args.cpu_sample, wl.num_nodes))
     if args.workload == "training_step" and not args.no_also and not args.generic and args.tile_nodes == 0:
+        keys = ("value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config", "step_hbm_fraction", "roofline")
         big = measure(workloads.WORKLOADS["large_batch"], 30, 5)
-        out["also"] = {"large_batch": {k: big[k] for k in
-                                       ("value", "unit", "steps", "warmup", "ms_per_step", "config",
-                                        "step_hbm_fraction", "roofline")}}
+        out["also"] = {"large_batch": {k: big[k] for k in keys}}
+        # the other configurations of the benchmark spec: forward only at the training-step shape, and the wide one
+        # (256 channels, outputs 0e+1o+2e); then every output irrep up to L = 3 (not one of the task's)
+        for name, st, wu in (("medium_fwd", 100, 10), ("wide_high_l", 20, 3), ("outputs_l3", 40, 5)):
+            m2 = measure(workloads.WORKLOADS[name], st, wu)
+            out["also"][name] = {k: m2[k] for k in keys}
         out["also"]["double_backward_training_step"] = measure_double_backward(wl, 100, 10)
         out["also"]["double_backward_large_batch"] = measure_double_backward(workloads.WORKLOADS["large_batch"], 20, 3)
         out["also"]["channelwise_tp_training_step"] = measure_tp(workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
