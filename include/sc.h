@@ -77,6 +77,12 @@ typedef enum { SC_F32 = 0, SC_F64 = 1 } sc_dtype;
 #define SC_REUSE_GROUPING 1u /* the workspace still holds the grouping written by the previous
                                 compute call of this plan with the same n_nodes and the
                                 same z contents: skip regrouping                           */
+#define SC_Z_GROUPED 4u      /* the caller's batch is already grouped by element: z is non-decreasing.
+                                The permutation pass is skipped and the backward passes read their
+                                rows in batch order.  Pass it to every call on that batch (also to
+                                the calls that reuse the grouping).  With a z that is not
+                                non-decreasing the results are wrong (never an access outside the
+                                buffers).  The table-driven kernels ignore it.                   */
 #define SC_REUSE_WEIGHTS 2u  /* the workspace still holds the weights as the previous compute
                                 call of this plan prepared them, and W has the same contents
                                 (the backward of a step after its forward): skip that step   */

@@ -394,7 +394,7 @@ static hipError_t grouped_pass_prologue(const char* fn, sc_plan* plan, int64_t n
   if (plan->specialised) {
     e = sc::launch_spec_prepare(plan, n_nodes, z, W, ws, shape, group, uses_folded_table && !(flags & SC_REUSE_WEIGHTS),
                                 stream);
-    if (e == hipSuccess && group) e = sc::launch_spec_scatter(plan, n_nodes, z, ws, shape, stream);
+    if (e == hipSuccess && group) e = sc::launch_spec_scatter(plan, n_nodes, z, ws, shape, (flags & SC_Z_GROUPED) != 0, stream);
   } else if (group) {
     e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
   }
@@ -421,7 +421,8 @@ static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes
     if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": grouping launch").c_str());
   }
   if (plan->profile) (void)hipEventRecord(plan->ev[0], stream);
-  e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, z, B, ws, shape, group, stream)
+  e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, z, B, ws, shape,
+                                                  !group ? 0 : (flags & SC_Z_GROUPED) ? 2 : 1, stream)
                         : sc::launch_generic_forward(plan, n_nodes, A, W, B, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": kernel launch").c_str());
   if (plan->profile) {
@@ -496,6 +497,7 @@ sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32
   if (!A || !z || !W || !dB || !dA) return fail(SC_ERR_INVALID_ARG, "sc_backward: NULL tensor argument");
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(dA, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_backward: tensor pointer not 16-byte aligned");
+  if (plan->specialised && (flags & SC_Z_GROUPED)) ws.perm = nullptr;   // identity: rows are read in batch order
   hipError_t e = grouped_pass_prologue("sc_backward", plan, n_nodes, z, W, ws, shape, flags, true, stream);
   if (e != hipSuccess) return SC_ERR_HIP;
   if (plan->profile) (void)hipEventRecord(plan->ev[2], stream);
@@ -537,6 +539,7 @@ sc_status sc_double_backward(sc_plan* plan, int64_t n_nodes, const void* A, cons
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(H, 16) || misaligned(ddB, 16) ||
       misaligned(dA2, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_double_backward: tensor pointer not 16-byte aligned");
+  if (plan->specialised && (flags & SC_Z_GROUPED)) ws.perm = nullptr;   // identity: rows are read in batch order
   hipError_t e = grouped_pass_prologue("sc_double_backward", plan, n_nodes, z, W, ws, shape, flags, false, stream);
   if (e != hipSuccess) return SC_ERR_HIP;
   if (plan->profile) (void)hipEventRecord(plan->ev[4], stream);

@@ -20,14 +20,15 @@ size_t spec_folded_bytes(const sc_plan* plan);
 // of the grouping).  Nothing is launched if both are false.
 hipError_t launch_spec_prepare(const sc_plan* plan, int64_t n, const int32_t* z, const void* W, const Workspace& ws,
                                const LaunchShape& shape, bool count, bool fold, hipStream_t stream);
-// Second half of the grouping as a launch of its own (after launch_spec_prepare with count).
+// Second half of the grouping as a launch of its own (after launch_spec_prepare with count);
+// table_only: offsets and tile table without the permutation (the batch is already grouped).
 hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
-                               const LaunchShape& shape, hipStream_t stream);
-// Forward over the nodes in natural order from ws.wfold; scatter: the second half of the
-// grouping rides in the same launch.
+                               const LaunchShape& shape, bool table_only, hipStream_t stream);
+// Forward over the nodes in natural order from ws.wfold; group: the second half of the grouping
+// rides in the same launch (0 no, 1 permutation + tile table, 2 tile table only).
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B,
-                               const Workspace& ws, const LaunchShape& shape, bool scatter, hipStream_t stream);
-// The grouped passes read ws.perm and ws.tiles; the backward reads ws.wfold, the second-order pass folds W itself.
+                               const Workspace& ws, const LaunchShape& shape, int group, hipStream_t stream);
+// The grouped passes read ws.perm (null: the batch is already grouped, identity) and ws.tiles; the backward reads ws.wfold, the second-order pass folds W itself.
 hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
                                 const Workspace& ws, const LaunchShape& shape, hipStream_t stream);
 hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,

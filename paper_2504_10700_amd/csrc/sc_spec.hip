@@ -184,29 +184,27 @@ __global__ __launch_bounds__(kSpecThreads) void spec_scatter_kernel(SplitGroupAr
   else split_table_role(ga, reinterpret_cast<int32_t*>(lds_raw));
 }
 
-// Launch 2.  Workgroups [0, scatter_wgs): scatter role; workgroup scatter_wgs (if any scatter):
-// table role; the others: forward of `tile` consecutive nodes x one 64-channel block, a
+// Launch 2.  Workgroups [0, scatter_wgs): scatter role; the next `table` (0 or 1): table role;
+// the others: forward of `tile` consecutive nodes x one 64-channel block, a
 // contiguous quarter of the nodes per wave.  A node whose element index is outside [0, Z) is
 // skipped (its row of B is left untouched), as the grouped kernels do.
 template <typename T, typename G>
-__global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupArgs ga, int scatter_wgs, int K,
+__global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupArgs ga, int scatter_wgs, int table, int K,
                                                                     int chblocks, int n, int Z, int tile,
                                                                     const T* __restrict__ A,
                                                                     const int32_t* __restrict__ z,
                                                                     const T* __restrict__ wf, T* __restrict__ B) {
   extern __shared__ unsigned char lds_raw[];
   int block = blockIdx.x;
-  if (scatter_wgs > 0) {
-    if (block < scatter_wgs) {
-      split_scatter_role(ga, block, reinterpret_cast<int32_t*>(lds_raw));
-      return;
-    }
-    if (block == scatter_wgs) {
-      split_table_role(ga, reinterpret_cast<int32_t*>(lds_raw));
-      return;
-    }
-    block -= scatter_wgs + 1;
+  if (block < scatter_wgs) {
+    split_scatter_role(ga, block, reinterpret_cast<int32_t*>(lds_raw));
+    return;
   }
+  if (block < scatter_wgs + table) {
+    split_table_role(ga, reinterpret_cast<int32_t*>(lds_raw));
+    return;
+  }
+  block -= scatter_wgs + table;
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = wave_of_thread();
   T* stage = reinterpret_cast<T*>(lds_raw) + wave * kLanes * G::kNLM;  // [64][kNLM] per wave (if used)
@@ -327,12 +325,12 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
     T w[G::kS];
     load_folded<T, G>(wf, td.z, chblocks, cb, lane, w);
     T a0[G::kNlm], a1[G::kNlm], g0[G::kNLM], g1[G::kNLM], da[G::kNlm];
-    size_t node0 = perm[j0], node1 = 0;
+    size_t node0 = perm ? perm[j0] : j0, node1 = 0;   // no permutation: the batch is already grouped
     Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
     Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
     for (int j = j0; j < j1; j += 2) {
       if (j + 1 < j1) {
-        node1 = perm[j + 1];
+        node1 = perm ? perm[j + 1] : j + 1;
         Row<T, G::kNlm>::load(A + (node1 * K + ch) * G::kNlm, a1);
         Row<T, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
       }
@@ -340,7 +338,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
       store_rows_coalesced<T, G::kNlm, kStreamDA>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       if (j + 1 < j1) {
         if (j + 2 < j1) {
-          node0 = perm[j + 2];
+          node0 = perm ? perm[j + 2] : j + 2;
           Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
           Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
         }
@@ -405,7 +403,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
     // one register set of inputs: the next node's rows are requested right after the
     // arithmetic of the current one has consumed them, ahead of its stores
     T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
-    size_t node = perm[j0];
+    size_t node = perm ? perm[j0] : j0;   // no permutation: the batch is already grouped
     Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
     Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
     Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
@@ -413,7 +411,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
       G::double_backward(a, w, g, h, ddb, da, dw);
       const size_t cur = node;
       if (j + 1 < j1) {
-        node = perm[j + 1];
+        node = perm ? perm[j + 1] : j + 1;
         Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
         Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
         Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
@@ -471,7 +469,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
     // one register set of inputs: the next node's rows are requested right after the
     // arithmetic of the current one has consumed them, ahead of its stores
     T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
-    size_t node = perm[j0];
+    size_t node = perm ? perm[j0] : j0;   // no permutation: the batch is already grouped
     Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
     Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
     Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
@@ -488,7 +486,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
       for (int s = 0; s < G::kS; ++s) dwl[s * kLanes] += dw[s];
       const size_t cur = node;
       if (j + 1 < j1) {
-        node = perm[j + 1];
+        node = perm ? perm[j + 1] : j + 1;
         Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
         Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
         Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
@@ -658,10 +656,13 @@ inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs) {
 
 template <typename T, typename G>
 hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B, const Workspace& ws,
-                      const LaunchShape& shape, bool scatter, hipStream_t stream) {
+                      const LaunchShape& shape, int group, hipStream_t stream) {
+  // group: 0 no grouping roles, 1 scatter + table, 2 table only (the batch is already grouped)
+  const bool scatter = group == 1;
+  const int table = group != 0;
   const int scatter_wgs = scatter ? shape.split_waves / kGroupWavesPerWG : 0;
   size_t lds = (G::kNLM * sizeof(T) != 16) ? sizeof(T) * kSpecWaves * G::kNLM * kLanes : 0;
-  if (scatter && split_group_lds_bytes(plan->cfg.num_elements) > lds) lds = split_group_lds_bytes(plan->cfg.num_elements);
+  if (table && split_group_lds_bytes(plan->cfg.num_elements) > lds) lds = split_group_lds_bytes(plan->cfg.num_elements);
   static const int wgs_per_cu = [] {   // resident workgroups per compute unit of this instance
     int nb = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, spec_forward_kernel<T, G>, kSpecThreads, 0) != hipSuccess || nb < 1)
@@ -671,9 +672,9 @@ hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32
   const int tile = shape.fwd_tile_nodes > 0 ? shape.fwd_tile_nodes
                                             : forward_tile_nodes(n, shape.chblocks, static_cast<int64_t>(wgs_per_cu) * plan->num_cus);
   const int tiles = static_cast<int>((n + tile - 1) / tile);
-  const int grid = (scatter ? scatter_wgs + 1 : 0) + tiles * shape.chblocks;
+  const int grid = scatter_wgs + table + tiles * shape.chblocks;
   hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
-                     group_args(plan, n, z, ws, shape), scatter_wgs, plan->cfg.num_channels, shape.chblocks,
+                     group_args(plan, n, z, ws, shape), scatter_wgs, table, plan->cfg.num_channels, shape.chblocks,
                      static_cast<int>(n), plan->cfg.num_elements, tile, static_cast<const T*>(A), z,
                      static_cast<const T*>(ws.wfold), static_cast<T*>(B));
   return hipGetLastError();
@@ -681,7 +682,7 @@ hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32
 
 template <typename T, typename G>
 hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
-                      const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
+                      const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {   // ws.perm may be null
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
   const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
@@ -784,8 +785,8 @@ struct PrepareFn {
 };
 struct ForwardFn {
   const sc_plan* plan; int64_t n; const void* A; const int32_t* z; void* B; const Workspace& ws; const LaunchShape& shape;
-  bool scatter; hipStream_t stream;
-  template <typename T, typename G> hipError_t operator()() const { return fwd_launch<T, G>(plan, n, A, z, B, ws, shape, scatter, stream); }
+  int group; hipStream_t stream;
+  template <typename T, typename G> hipError_t operator()() const { return fwd_launch<T, G>(plan, n, A, z, B, ws, shape, group, stream); }
 };
 struct BackwardFn {
   const sc_plan* plan; int64_t n; const void* A; const void* dB; void* dA; const Workspace& ws; const LaunchShape& shape;
@@ -808,16 +809,16 @@ hipError_t launch_spec_prepare(const sc_plan* plan, int64_t n, const int32_t* z,
 }
 
 hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
-                               const LaunchShape& shape, hipStream_t stream) {
-  const int scatter_wgs = shape.split_waves / kGroupWavesPerWG;
+                               const LaunchShape& shape, bool table_only, hipStream_t stream) {
+  const int scatter_wgs = table_only ? 0 : shape.split_waves / kGroupWavesPerWG;
   hipLaunchKernelGGL(spec_scatter_kernel, dim3(scatter_wgs + 1), dim3(kSpecThreads),
                      split_group_lds_bytes(plan->cfg.num_elements), stream, group_args(plan, n, z, ws, shape), scatter_wgs);
   return hipGetLastError();
 }
 
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B,
-                               const Workspace& ws, const LaunchShape& shape, bool scatter, hipStream_t stream) {
-  return dispatch(plan, ForwardFn{plan, n, A, z, B, ws, shape, scatter, stream});
+                               const Workspace& ws, const LaunchShape& shape, int group, hipStream_t stream) {
+  return dispatch(plan, ForwardFn{plan, n, A, z, B, ws, shape, group, stream});
 }
 
 hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,

@@ -339,6 +339,35 @@ def test_tile_size_knob_does_not_change_results_beyond_rounding(sc):
         run.close()
 
 
+@pytest.mark.parametrize("flags", [0, 2])
+def test_batch_already_grouped_by_element(sc, flags):
+    """SC_Z_GROUPED: with a non-decreasing z the permutation pass is skipped; same bits as without
+    the flag (same tiles, same order of every sum), and parity with the oracle."""
+    wl = wl_of("sorted_z", 2500, 89, 128, 3, 3, O01, "f32", 3101)
+    T = oracle_tables(wl)
+    inp = workloads.make_inputs(wl, T.paths)
+    inp.z[:] = np.sort(inp.z)
+    run = GpuRun(sc, wl, inp, flags)
+    A, z, W, dB = run.inputs_as_computed()
+    B0 = run.forward()
+    dA0, dW0 = run.backward(sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS)
+    run.B.fill_(float("nan")), run.dA.fill_(float("nan")), run.dW.fill_(float("nan"))
+    B1 = run.forward(sc.SC_Z_GROUPED)
+    dA1, dW1 = run.backward(sc.SC_Z_GROUPED | sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS)
+    assert np.array_equal(B0, B1) and np.array_equal(dA0, dA1) and np.array_equal(dW0, dW1)
+    dA2, dW2 = run.backward(sc.SC_Z_GROUPED)      # a backward of its own: grouping without the permutation
+    assert np.array_equal(dA0, dA2) and np.array_equal(dW0, dW2)
+    check("B", B1, oracle_forward(osc, T, A, z, W), "f32")
+    dA_ref, dW_ref = oracle_backward(osc, T, A, z, W, dB)
+    check("dA", dA1, dA_ref, "f32")
+    check_dw("dW", dW1, dW_ref, z, "f32", case=f"sorted_z/flags{flags}")
+    H = workloads.make_cotangent(wl)
+    r0 = run.double_backward(H)
+    r1 = run.double_backward(H, sc.SC_Z_GROUPED)
+    assert all(np.array_equal(x, y) for x, y in zip(r0[:3], r1[:3]))
+    run.close()
+
+
 def test_out_of_range_elements_are_skipped_not_fatal(sc):
     import torch
     wl = wl_of("badz", 50, 4, 128, 3, 3, O01, "f32", 2801, z_mode="uniform")
