@@ -86,10 +86,12 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0):
     from paper_2504_10700_amd import workloads
 
     dev = torch.device("cuda:0")
-    tdt = torch.float32 if wl.dtype == "f32" else torch.float64
-    elem = 4 if wl.dtype == "f32" else 8
+    # tdt / elem: the per-node tensors; W and dW are fp32 when those are stored as bfloat16
+    tdt = {"f32": torch.float32, "f64": torch.float64, "bf16": torch.bfloat16}[wl.dtype]
+    wdt = torch.float64 if wl.dtype == "f64" else torch.float32
+    elem = {"f32": 4, "f64": 8, "bf16": 2}[wl.dtype]
     plan = sc.sc_plan_create(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps,
-                             sc.SC_F32 if wl.dtype == "f32" else sc.SC_F64, 0,
+                             {"f32": sc.SC_F32, "f64": sc.SC_F64, "bf16": sc.SC_BF16}[wl.dtype], 0,
                              sc.SC_PLAN_FORCE_GENERIC if generic else 0, tile_nodes)
     info = sc.sc_plan_info(plan)
     inp = workloads.make_inputs(wl, sc.sc_plan_paths(plan))
@@ -99,7 +101,7 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0):
     n_sets = max(2, min(8, int(np.ceil(1.0e9 / per_set))))
     A0 = torch.tensor(inp.A, dtype=tdt, device=dev)
     dB0 = torch.tensor(inp.dB, dtype=tdt, device=dev)
-    W = torch.tensor(inp.W, dtype=tdt, device=dev)
+    W = torch.tensor(inp.W, dtype=wdt, device=dev)
     z = torch.tensor(inp.z, dtype=torch.int32, device=dev)
     del inp
     sets = []
@@ -754,7 +756,9 @@ def main():
         out["also"] = {"large_batch": {k: big[k] for k in keys}}
         # the other configurations of the benchmark spec: forward only at the training-step shape, and the wide one
         # (256 channels, outputs 0e+1o+2e); then every output irrep up to L = 3 (not one of the task's)
-        for name, st, wu in (("medium_fwd", 100, 10), ("wide_high_l", 20, 3), ("outputs_l3", 40, 5)):
+        # and the training step with the per-node tensors stored as bfloat16 (half the bytes)
+        for name, st, wu in (("medium_fwd", 100, 10), ("wide_high_l", 20, 3), ("outputs_l3", 40, 5),
+                             ("training_step_bf16", 100, 10)):
             m2 = measure(workloads.WORKLOADS[name], st, wu)
             out["also"][name] = {k: m2[k] for k in keys}
         out["also"]["double_backward_training_step"] = measure_double_backward(wl, 100, 10)

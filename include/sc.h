@@ -62,7 +62,11 @@ typedef enum {
   SC_ERR_ALLOC = 5        /* host or device allocation failed                              */
 } sc_status;
 
-typedef enum { SC_F32 = 0, SC_F64 = 1 } sc_dtype;
+/* SC_BF16: the per-node tensors (A, B, dB, dA, H, ddB, dA2) are stored as bfloat16 (halving the
+ * bytes the operation must move), W and dW stay fp32 and all arithmetic is fp32; results are
+ * rounded to nearest-even on the way out.  Served by the generated kernels only (plans they do
+ * not cover fail with SC_ERR_UNSUPPORTED at creation); the channel count must be a multiple of 8. */
+typedef enum { SC_F32 = 0, SC_F64 = 1, SC_BF16 = 2 } sc_dtype;
 
 #define SC_MAX_OUT 4       /* output irreps per plan                                       */
 #define SC_MAX_L 3         /* largest l_max and largest output L                           */
@@ -96,7 +100,7 @@ typedef struct {
   int32_t num_out;                /* number of output irreps, 1..SC_MAX_OUT                          */
   int32_t out_l[SC_MAX_OUT];      /* L of each output irrep, 0..SC_MAX_L                             */
   int32_t out_parity[SC_MAX_OUT]; /* +1 = even ("e"), -1 = odd ("o")                                 */
-  int32_t dtype;                  /* sc_dtype of A, W, B, dB, dA, dW                                 */
+  int32_t dtype;                  /* sc_dtype of A, W, B, dB, dA, dW (SC_BF16: see sc_dtype)         */
   int32_t device;                 /* HIP device ordinal (ignored with SC_PLAN_HOST_ONLY)             */
   uint32_t flags;                 /* SC_PLAN_*                                                       */
   int32_t tile_nodes;             /* tuning: nodes per tile of the grouping pass; 0 = chosen by the

@@ -32,6 +32,7 @@ __global__ void fill_zero_kernel(unsigned int* p, size_t n_words) {
     p[i] = 0u;
 }
 
+// bytes of one element of W / dW / the per-tile dW rows (fp32 also when the per-node rows are bfloat16)
 size_t elem_size(const sc_plan* plan) { return plan->cfg.dtype == SC_F64 ? 8 : 4; }
 
 // Scratch of sc_forward_noalloc: the grouping of one call (what sc_forward keeps in the caller's
@@ -158,7 +159,8 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   if (cfg->num_channels < 1) return fail(SC_ERR_INVALID_ARG, "sc_plan_create: num_channels < 1");
   if (cfg->tile_nodes < 0 || cfg->tile_nodes > 65536)
     return fail(SC_ERR_INVALID_ARG, "sc_plan_create: tile_nodes outside 0..65536");
-  if (cfg->dtype != SC_F32 && cfg->dtype != SC_F64) return fail(SC_ERR_INVALID_ARG, "sc_plan_create: bad dtype");
+  if (cfg->dtype != SC_F32 && cfg->dtype != SC_F64 && cfg->dtype != SC_BF16)
+    return fail(SC_ERR_INVALID_ARG, "sc_plan_create: bad dtype");
   if (cfg->l_max < 0 || cfg->l_max > SC_MAX_L) return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: l_max outside 0..3");
   if (cfg->nu_max < 1 || cfg->nu_max > SC_MAX_NU)
     return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: nu_max outside 1..3");
@@ -191,6 +193,11 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   const int P = static_cast<int>(T.paths.size());
   plan->specialised = (cfg->flags & SC_PLAN_FORCE_GENERIC) ? 0 : sc::spec_lookup(plan);
   plan->S = plan->specialised ? sc::spec_basis_size(plan->specialised) : P;
+  if (cfg->dtype == SC_BF16 && !plan->specialised) {
+    delete plan;
+    return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: SC_BF16 is served by the generated kernels only (l_max = 3, nu_max = 3, "
+                                    "outputs 0e+1o[+2e[+3o]], or the tiny configuration; channels a multiple of 8)");
+  }
   if (plan->host_only) {
     *out_plan = plan;
     return SC_OK;

@@ -139,6 +139,7 @@ sc_status check(const char* fn, const sc_plan* plan, int32_t k_in, int64_t n) {
   if (!plan) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": plan is NULL");
   if (plan->host_only) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": the plan has no device");
   if (k_in < 1) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": k_in < 1");
+  if (plan->cfg.dtype == SC_BF16) return set_error(SC_ERR_UNSUPPORTED, std::string(fn) + ": plans with bfloat16 rows are not served");
   if (n < 0 || n > (int64_t(1) << 30)) return set_error(SC_ERR_INVALID_ARG, std::string(fn) + ": n_nodes outside 0..2^30");
   return SC_OK;
 }

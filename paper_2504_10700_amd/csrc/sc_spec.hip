@@ -24,6 +24,8 @@
 //               dW' summed per tile without atomics
 //   4 finalize  per (element, channel block): sum of the per-tile dW' rows in a fixed order
 //               (fp64) and the map to the external paths
+#include <type_traits>
+
 #include "sc_group_split.h"
 #include "sc_spec.h"
 
@@ -128,6 +130,71 @@ __device__ __forceinline__ void store_rows_coalesced(T* __restrict__ block, T* s
   }
 }
 
+// Storage type of the per-node rows (A, B, dB, dA, H, ...) when it differs from the arithmetic
+// type T: bfloat16 bits (SC_BF16: rows in bfloat16, arithmetic, weights and dW in fp32).
+typedef __bf16 bf16_bits;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_bits b) { return static_cast<float>(b); }
+// round to nearest, ties to even (the chip's own conversion instruction, two values at a time)
+__device__ __forceinline__ bf16_bits f32_to_bf16(float f) { return static_cast<bf16_bits>(f); }
+
+// Rows of N elements stored as TS, handled as T.  TS == T is Row<T, N> itself.
+template <typename T, typename TS, int N>
+struct RowIO {
+  typedef TS Vec8 __attribute__((ext_vector_type(N * sizeof(TS) == 8 ? N : 2), aligned(8)));   // an 8-byte row in one access
+  static __device__ __forceinline__ void load(const TS* __restrict__ p, T (&v)[N]) {
+    TS raw[N];
+    if constexpr (N * sizeof(TS) == 8) {
+      const Vec8 x = *reinterpret_cast<const Vec8*>(p);
+#pragma unroll
+      for (int i = 0; i < N; ++i) raw[i] = x[i];
+    } else {
+      Row<TS, N>::load(p, raw);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = bf16_to_f32(raw[i]);
+  }
+  static __device__ __forceinline__ void store(TS* __restrict__ p, const T (&v)[N]) {
+    TS raw[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) raw[i] = f32_to_bf16(v[i]);
+    if constexpr (N * sizeof(TS) == 8) {
+      Vec8 x;
+#pragma unroll
+      for (int i = 0; i < N; ++i) x[i] = raw[i];
+      *reinterpret_cast<Vec8*>(p) = x;
+    } else {
+      Row<TS, N>::store(p, raw);
+    }
+  }
+};
+template <typename T, int N>
+struct RowIO<T, T, N> : Row<T, N> {};
+
+// store_rows_coalesced for rows stored as TS; `stage` is this wave's LDS block of 64*N elements of T
+// (large enough for TS, which is never wider).
+template <typename T, typename TS, int N, bool kStream>
+struct RowsOut {
+  static __device__ __forceinline__ void store(TS* __restrict__ block, T* stage, int lane, const T (&v)[N], int live_lanes) {
+    TS raw[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) raw[i] = f32_to_bf16(v[i]);
+    store_rows_coalesced<TS, N, kStream>(block, reinterpret_cast<TS*>(stage), lane, raw, live_lanes);
+  }
+};
+template <typename T, int N, bool kStream>
+struct RowsOut<T, T, N, kStream> {
+  static __device__ __forceinline__ void store(T* __restrict__ block, T* stage, int lane, const T (&v)[N], int live_lanes) {
+    store_rows_coalesced<T, N, kStream>(block, stage, lane, v, live_lanes);
+  }
+};
+#define store_rows_as RowsOutCall
+template <typename T, typename TS, int N, bool kStream = true>
+__device__ __forceinline__ void RowsOutCall(TS* __restrict__ block, T* stage, int lane, const T (&v)[N],
+                                            int live_lanes = kLanes) {
+  RowsOut<T, TS, N, kStream>::store(block, stage, lane, v, live_lanes);
+}
+
 // blockIdx -> logical work item such that the blocks an XCD receives (round-robin by
 // blockIdx) form one contiguous range.  gridDim.x is a multiple of kXcds.
 __device__ __forceinline__ int xcd_contiguous_block() {
@@ -188,12 +255,12 @@ __global__ __launch_bounds__(kSpecThreads) void spec_scatter_kernel(SplitGroupAr
 // the others: forward of `tile` consecutive nodes x one 64-channel block, a
 // contiguous quarter of the nodes per wave.  A node whose element index is outside [0, Z) is
 // skipped (its row of B is left untouched), as the grouped kernels do.
-template <typename T, typename G>
+template <typename T, typename G, typename TS = T>
 __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupArgs ga, int scatter_wgs, int table, int K,
                                                                     int chblocks, int n, int Z, int tile,
-                                                                    const T* __restrict__ A,
+                                                                    const TS* __restrict__ A,
                                                                     const int32_t* __restrict__ z,
-                                                                    const T* __restrict__ wf, T* __restrict__ B) {
+                                                                    const T* __restrict__ wf, TS* __restrict__ B) {
   extern __shared__ unsigned char lds_raw[];
   int block = blockIdx.x;
   if (block < scatter_wgs) {
@@ -208,7 +275,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = wave_of_thread();
   T* stage = reinterpret_cast<T*>(lds_raw) + wave * kLanes * G::kNLM;  // [64][kNLM] per wave (if used)
-  constexpr bool kStageB = G::kNLM * sizeof(T) != 16;  // 16-byte rows are coalesced as they are
+  constexpr bool kStageB = G::kNLM * sizeof(TS) != 16;  // 16-byte rows are coalesced as they are
   const int t = block / chblocks, cb = block % chblocks;
   const int s0 = t * tile;
   const int in_tile = (n - s0 < tile) ? n - s0 : tile;
@@ -244,7 +311,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   visit(0, n0, e0);
   if (e0 >= Z) return;   // no valid node in this wave's share
   load_folded<T, G>(wf, e0, chblocks, cb, lane, w0);
-  Row<T, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
+  RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
   for (int p = 0; p < cnt; p += 2) {
     if (p + 1 < cnt) {
       visit(p + 1, n1, e1);
@@ -255,12 +322,12 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
         } else {
           load_folded<T, G>(wf, e1, chblocks, cb, lane, w1);
         }
-        Row<T, G::kNlm>::load(A + (static_cast<size_t>(n1) * K + ch) * G::kNlm, a1);
+        RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n1) * K + ch) * G::kNlm, a1);
       }
     }
     G::forward(a0, w0, b);
-    if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(n0) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
-    else if (lane < live) Row<T, G::kNLM>::store(B + (static_cast<size_t>(n0) * K + ch) * G::kNLM, b);
+    if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(B + (static_cast<size_t>(n0) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
+    else if (lane < live) RowIO<T, TS, G::kNLM>::store(B + (static_cast<size_t>(n0) * K + ch) * G::kNLM, b);
     if (p + 1 >= cnt || e1 >= Z) break;   // the valid nodes are done
     e0 = Z;
     if (p + 2 < cnt) {
@@ -272,12 +339,12 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
         } else {
           load_folded<T, G>(wf, e0, chblocks, cb, lane, w0);
         }
-        Row<T, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
+        RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
       }
     }
     G::forward(a1, w1, b);
-    if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(B + (static_cast<size_t>(n1) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
-    else if (lane < live) Row<T, G::kNLM>::store(B + (static_cast<size_t>(n1) * K + ch) * G::kNLM, b);
+    if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(B + (static_cast<size_t>(n1) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
+    else if (lane < live) RowIO<T, TS, G::kNLM>::store(B + (static_cast<size_t>(n1) * K + ch) * G::kNLM, b);
     if (e0 >= Z) break;
   }
 }
@@ -295,12 +362,12 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
 // kFull: the channel count is a multiple of 64, no lane is ever idle.  The fp32 kernel of the
 // 49-row basis sits at the limit for two waves per SIMD: 250 registers without the idle-lane
 // handling, 295 (one wave per SIMD, 736 instead of 496 us at 50k nodes / 256 channels) with it.
-template <typename T, typename G, int kOcc = 0, bool kStreamDA = false, bool kFull = false>
+template <typename T, typename G, int kOcc = 0, bool kStreamDA = false, bool kFull = false, typename TS = T>
 __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(kOcc == 0 ? 1 : kOcc, 8)))
 void spec_backward_kernel(int K, int chblocks, int n_blocks,
-                                                                     const T* __restrict__ A,
+                                                                     const TS* __restrict__ A,
                                                                      const T* __restrict__ wf,
-                                                                     const T* __restrict__ dB, T* __restrict__ dA,
+                                                                     const TS* __restrict__ dB, TS* __restrict__ dA,
                                                                      T* __restrict__ partial,
                                                                      const TileDesc* __restrict__ tiles,
                                                                      const int32_t* __restrict__ perm) {
@@ -326,24 +393,24 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
     load_folded<T, G>(wf, td.z, chblocks, cb, lane, w);
     T a0[G::kNlm], a1[G::kNlm], g0[G::kNLM], g1[G::kNLM], da[G::kNlm];
     size_t node0 = perm ? perm[j0] : j0, node1 = 0;   // no permutation: the batch is already grouped
-    Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
-    Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
+    RowIO<T, TS, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
+    RowIO<T, TS, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
     for (int j = j0; j < j1; j += 2) {
       if (j + 1 < j1) {
         node1 = perm ? perm[j + 1] : j + 1;
-        Row<T, G::kNlm>::load(A + (node1 * K + ch) * G::kNlm, a1);
-        Row<T, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
+        RowIO<T, TS, G::kNlm>::load(A + (node1 * K + ch) * G::kNlm, a1);
+        RowIO<T, TS, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
       }
       G::backward(a0, w, g0, da, dw);
-      store_rows_coalesced<T, G::kNlm, kStreamDA>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      store_rows_as<T, TS, G::kNlm, kStreamDA>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       if (j + 1 < j1) {
         if (j + 2 < j1) {
           node0 = perm ? perm[j + 2] : j + 2;
-          Row<T, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
-          Row<T, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
+          RowIO<T, TS, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
+          RowIO<T, TS, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
         }
         G::backward(a1, w, g1, da, dw);
-        store_rows_coalesced<T, G::kNlm, kStreamDA>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+        store_rows_as<T, TS, G::kNlm, kStreamDA>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
       }
     }
   }
@@ -374,15 +441,15 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
 //    larger basis or fp64 it would spill.  Small changes to its text move the register
 //    allocation across the spill threshold: check the compiler's resource report
 //    (-Rpass-analysis=kernel-resource-usage) after touching it.
-template <typename T, typename G, bool kFull>
+template <typename T, typename G, bool kFull, typename TS = T>
 __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
-    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
-    const T* __restrict__ H, T* __restrict__ ddB, T* __restrict__ dA2, T* __restrict__ partial,
+    int K, int chblocks, int n_blocks, const TS* __restrict__ A, const T* __restrict__ W, const TS* __restrict__ dB,
+    const TS* __restrict__ H, TS* __restrict__ ddB, TS* __restrict__ dA2, T* __restrict__ partial,
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ perm) {
   extern __shared__ unsigned char lds_raw[];
   T* red = reinterpret_cast<T*>(lds_raw);  // [kSpecWaves][kS][64]
   T* stage = red + kSpecWaves * G::kS * kLanes + wave_of_thread() * kLanes * G::kNlm;  // [64][kNlm] per wave
-  constexpr bool kStageB = G::kNLM * sizeof(T) != 16;
+  constexpr bool kStageB = G::kNLM * sizeof(TS) != 16;
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
   const int logical = xcd_contiguous_block();
@@ -404,21 +471,21 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
     // arithmetic of the current one has consumed them, ahead of its stores
     T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
     size_t node = perm ? perm[j0] : j0;   // no permutation: the batch is already grouped
-    Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
-    Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
-    Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+    RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+    RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+    RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
     for (int j = j0; j < j1; ++j) {
       G::double_backward(a, w, g, h, ddb, da, dw);
       const size_t cur = node;
       if (j + 1 < j1) {
         node = perm ? perm[j + 1] : j + 1;
-        Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
-        Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
-        Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+        RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+        RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+        RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
       }
-      store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
-      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
-      else if (kFull || lane < live) Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+      store_rows_as<T, TS, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
+      else if (kFull || lane < live) RowIO<T, TS, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
     }
   }
 #pragma unroll
@@ -434,16 +501,16 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
 }
 
 // See above.  LDS: w' [kSpecWaves][kS][64] | sums [kSpecWaves][kS][64] | stage [kSpecWaves][64][kNlm].
-template <typename T, typename G, bool kFull>
+template <typename T, typename G, bool kFull, typename TS = T>
 __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void spec_double_backward_lds_kernel(
-    int K, int chblocks, int n_blocks, const T* __restrict__ A, const T* __restrict__ W, const T* __restrict__ dB,
-    const T* __restrict__ H, T* __restrict__ ddB, T* __restrict__ dA2, T* __restrict__ partial,
+    int K, int chblocks, int n_blocks, const TS* __restrict__ A, const T* __restrict__ W, const TS* __restrict__ dB,
+    const TS* __restrict__ H, TS* __restrict__ ddB, TS* __restrict__ dA2, T* __restrict__ partial,
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ perm) {
   extern __shared__ unsigned char lds_raw[];
   T* red = reinterpret_cast<T*>(lds_raw);  // [kSpecWaves][kS][64]: every wave's w' columns
   T* acc_all = red + kSpecWaves * G::kS * kLanes;                         // [kSpecWaves][kS][64] dW2' sums
   T* stage = acc_all + kSpecWaves * G::kS * kLanes + wave_of_thread() * kLanes * G::kNlm;  // [64][kNlm] per wave
-  constexpr bool kStageB = G::kNLM * sizeof(T) != 16;
+  constexpr bool kStageB = G::kNLM * sizeof(TS) != 16;
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
   const int logical = xcd_contiguous_block();
@@ -470,9 +537,9 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
     // arithmetic of the current one has consumed them, ahead of its stores
     T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
     size_t node = perm ? perm[j0] : j0;   // no permutation: the batch is already grouped
-    Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
-    Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
-    Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+    RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+    RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+    RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
     for (int j = j0; j < j1; ++j) {
       T w[G::kS];
       asm volatile("" ::: "memory");  // keep the reads of w' inside the loop (registers are short)
@@ -487,13 +554,13 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
       const size_t cur = node;
       if (j + 1 < j1) {
         node = perm ? perm[j + 1] : j + 1;
-        Row<T, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
-        Row<T, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
-        Row<T, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+        RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+        RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+        RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
       }
-      store_rows_coalesced<T, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
-      if constexpr (kStageB) store_rows_coalesced<T, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
-      else if (kFull || lane < live) Row<T, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+      store_rows_as<T, TS, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
+      else if (kFull || lane < live) RowIO<T, TS, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
     }
   }
   __syncthreads();
@@ -591,8 +658,8 @@ bool matches(const sc_plan* plan) {
   const size_t lds = (c.dtype == SC_F64 ? 8 : 4) * static_cast<size_t>(kSpecWaves) * (G::kS + G::kNlm) * kLanes;
   if (lds > 160 * 1024) return false;
   // channel counts that are not a multiple of 64 leave lanes of the last channel block idle; a multiple
-  // of four keeps every row block 16-byte aligned
-  return c.num_channels % 4 == 0 && static_cast<int>(plan->table.paths.size()) == G::kP;
+  // of four (eight for bfloat16 rows) keeps every row block 16-byte aligned
+  return c.num_channels % (c.dtype == SC_BF16 ? 8 : 4) == 0 && static_cast<int>(plan->table.paths.size()) == G::kP;
 }
 
 SplitGroupArgs group_args(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
@@ -654,18 +721,18 @@ inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs) {
   return pick;
 }
 
-template <typename T, typename G>
+template <typename T, typename G, typename TS>
 hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B, const Workspace& ws,
                       const LaunchShape& shape, int group, hipStream_t stream) {
   // group: 0 no grouping roles, 1 scatter + table, 2 table only (the batch is already grouped)
   const bool scatter = group == 1;
   const int table = group != 0;
   const int scatter_wgs = scatter ? shape.split_waves / kGroupWavesPerWG : 0;
-  size_t lds = (G::kNLM * sizeof(T) != 16) ? sizeof(T) * kSpecWaves * G::kNLM * kLanes : 0;
+  size_t lds = (G::kNLM * sizeof(TS) != 16) ? sizeof(T) * kSpecWaves * G::kNLM * kLanes : 0;
   if (table && split_group_lds_bytes(plan->cfg.num_elements) > lds) lds = split_group_lds_bytes(plan->cfg.num_elements);
   static const int wgs_per_cu = [] {   // resident workgroups per compute unit of this instance
     int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, spec_forward_kernel<T, G>, kSpecThreads, 0) != hipSuccess || nb < 1)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, spec_forward_kernel<T, G, TS>, kSpecThreads, 0) != hipSuccess || nb < 1)
       nb = 1;
     return nb;
   }();
@@ -673,34 +740,35 @@ hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32
                                             : forward_tile_nodes(n, shape.chblocks, static_cast<int64_t>(wgs_per_cu) * plan->num_cus);
   const int tiles = static_cast<int>((n + tile - 1) / tile);
   const int grid = scatter_wgs + table + tiles * shape.chblocks;
-  hipLaunchKernelGGL((spec_forward_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
+  hipLaunchKernelGGL((spec_forward_kernel<T, G, TS>), dim3(grid), dim3(kSpecThreads), lds, stream,
                      group_args(plan, n, z, ws, shape), scatter_wgs, table, plan->cfg.num_channels, shape.chblocks,
-                     static_cast<int>(n), plan->cfg.num_elements, tile, static_cast<const T*>(A), z,
-                     static_cast<const T*>(ws.wfold), static_cast<T*>(B));
+                     static_cast<int>(n), plan->cfg.num_elements, tile, static_cast<const TS*>(A), z,
+                     static_cast<const T*>(ws.wfold), static_cast<TS*>(B));
   return hipGetLastError();
 }
 
-template <typename T, typename G>
+template <typename T, typename G, typename TS>
 hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
                       const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {   // ws.perm may be null
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
   const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
   const bool full = plan->cfg.num_channels % kLanes == 0;
-  auto kernel = full ? &spec_backward_kernel<T, G, 0, false, true> : &spec_backward_kernel<T, G, 0, false, false>;
-  if constexpr (sizeof(T) == 4 && G::kS <= 32) {
-    // small batches: three waves per SIMD, streamed dA (see the kernel)
-    if (n <= 40000) kernel = full ? &spec_backward_kernel<T, G, 3, true, true> : &spec_backward_kernel<T, G, 3, true, false>;
+  auto kernel = full ? &spec_backward_kernel<T, G, 0, false, true, TS> : &spec_backward_kernel<T, G, 0, false, false, TS>;
+  if constexpr (sizeof(T) == 4 && G::kS <= 32 && std::is_same<T, TS>::value) {
+    // small batches: three waves per SIMD, streamed dA (see the kernel; with bfloat16 rows that instance
+    // would need 52 bytes of scratch per lane)
+    if (n <= 40000) kernel = full ? &spec_backward_kernel<T, G, 3, true, true, TS> : &spec_backward_kernel<T, G, 3, true, false, TS>;
   }
   const hipError_t e = raise_lds_limit(kernel, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpecThreads), lds, stream, plan->cfg.num_channels, shape.chblocks,
-                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(ws.wfold), static_cast<const T*>(dB),
-                     static_cast<T*>(dA), static_cast<T*>(ws.partial), ws.tiles, ws.perm);
+                     n_blocks, static_cast<const TS*>(A), static_cast<const T*>(ws.wfold), static_cast<const TS*>(dB),
+                     static_cast<TS*>(dA), static_cast<T*>(ws.partial), ws.tiles, ws.perm);
   return hipGetLastError();
 }
 
-template <typename T, typename G>
+template <typename T, typename G, typename TS>
 hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const void* dB, const void* H, void* ddB,
                       void* dA2, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
@@ -708,13 +776,13 @@ hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const v
   constexpr bool kLds = kUseLdsState<T, G>;
   const size_t lds = sizeof(T) * kSpecWaves * ((kLds ? 2 : 1) * G::kS + G::kNlm) * kLanes;
   const bool full = plan->cfg.num_channels % kLanes == 0;   // no idle lanes: an instance without their handling
-  auto kernel = full ? &spec_double_backward_kernel<T, G, true> : &spec_double_backward_kernel<T, G, false>;
-  if constexpr (kLds) kernel = full ? &spec_double_backward_lds_kernel<T, G, true> : &spec_double_backward_lds_kernel<T, G, false>;
+  auto kernel = full ? &spec_double_backward_kernel<T, G, true, TS> : &spec_double_backward_kernel<T, G, false, TS>;
+  if constexpr (kLds) kernel = full ? &spec_double_backward_lds_kernel<T, G, true, TS> : &spec_double_backward_lds_kernel<T, G, false, TS>;
   const hipError_t e = raise_lds_limit(kernel, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpecThreads), lds, stream, plan->cfg.num_channels, shape.chblocks,
-                     n_blocks, static_cast<const T*>(A), static_cast<const T*>(W), static_cast<const T*>(dB),
-                     static_cast<const T*>(H), static_cast<T*>(ddB), static_cast<T*>(dA2),
+                     n_blocks, static_cast<const TS*>(A), static_cast<const T*>(W), static_cast<const TS*>(dB),
+                     static_cast<const TS*>(H), static_cast<TS*>(ddB), static_cast<TS*>(dA2),
                      static_cast<T*>(ws.partial), ws.tiles, ws.perm);
   return hipGetLastError();
 }
@@ -729,15 +797,26 @@ hipError_t finalize_launch(const sc_plan* plan, void* dW, const Workspace& ws, c
   return hipGetLastError();
 }
 
-// Calls fn.template operator()<T, G>() for the plan's dtype and generated kernel.
+// Calls fn.template operator()<T, G, TS>() for the plan's dtype (T arithmetic and weights, TS
+// storage of the per-node rows) and generated kernel.
+template <typename G, typename F>
+hipError_t dispatch_dtype(const sc_plan* plan, F&& fn) {
+  switch (plan->cfg.dtype) {
+    case SC_F64: return fn.template operator()<double, G, double>();
+    case SC_BF16: return fn.template operator()<float, G, bf16_bits>();
+    default: return fn.template operator()<float, G, float>();
+  }
+}
+
 template <typename F>
 hipError_t dispatch(const sc_plan* plan, F&& fn) {
-  const bool f64 = plan->cfg.dtype == SC_F64;
-  if (plan->specialised == 1) return f64 ? fn.template operator()<double, Gen_l3n3_0e1o>() : fn.template operator()<float, Gen_l3n3_0e1o>();
-  if (plan->specialised == 2) return f64 ? fn.template operator()<double, Gen_l3n3_0e1o2e>() : fn.template operator()<float, Gen_l3n3_0e1o2e>();
-  if (plan->specialised == 3) return f64 ? fn.template operator()<double, Gen_l3n3_0e1o2e3o>() : fn.template operator()<float, Gen_l3n3_0e1o2e3o>();
-  if (plan->specialised == 4) return f64 ? fn.template operator()<double, Gen_l1n2_0e>() : fn.template operator()<float, Gen_l1n2_0e>();
-  return hipErrorInvalidValue;
+  switch (plan->specialised) {
+    case 1: return dispatch_dtype<Gen_l3n3_0e1o>(plan, fn);
+    case 2: return dispatch_dtype<Gen_l3n3_0e1o2e>(plan, fn);
+    case 3: return dispatch_dtype<Gen_l3n3_0e1o2e3o>(plan, fn);
+    case 4: return dispatch_dtype<Gen_l1n2_0e>(plan, fn);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
@@ -775,32 +854,32 @@ int spec_waves_per_tile() { return kSpecWaves; }
 size_t spec_folded_bytes(const sc_plan* plan) {
   const size_t chblocks = (plan->cfg.num_channels + kLanes - 1) / kLanes;   // whole 64-channel rows
   return static_cast<size_t>(plan->cfg.num_elements) * chblocks * kLanes * spec_basis_size(plan->specialised) *
-         (plan->cfg.dtype == SC_F64 ? 8 : 4);
+         (plan->cfg.dtype == SC_F64 ? 8 : 4);   // weights: fp32 also for bfloat16 rows
 }
 
 struct PrepareFn {
   const sc_plan* plan; int64_t n; const int32_t* z; const void* W; const Workspace& ws; const LaunchShape& shape;
   bool count, fold; hipStream_t stream;
-  template <typename T, typename G> hipError_t operator()() const { return prepare_launch<T, G>(plan, n, z, W, ws, shape, count, fold, stream); }
+  template <typename T, typename G, typename TS> hipError_t operator()() const { return prepare_launch<T, G>(plan, n, z, W, ws, shape, count, fold, stream); }
 };
 struct ForwardFn {
   const sc_plan* plan; int64_t n; const void* A; const int32_t* z; void* B; const Workspace& ws; const LaunchShape& shape;
   int group; hipStream_t stream;
-  template <typename T, typename G> hipError_t operator()() const { return fwd_launch<T, G>(plan, n, A, z, B, ws, shape, group, stream); }
+  template <typename T, typename G, typename TS> hipError_t operator()() const { return fwd_launch<T, G, TS>(plan, n, A, z, B, ws, shape, group, stream); }
 };
 struct BackwardFn {
   const sc_plan* plan; int64_t n; const void* A; const void* dB; void* dA; const Workspace& ws; const LaunchShape& shape;
   hipStream_t stream;
-  template <typename T, typename G> hipError_t operator()() const { return bwd_launch<T, G>(plan, n, A, dB, dA, ws, shape, stream); }
+  template <typename T, typename G, typename TS> hipError_t operator()() const { return bwd_launch<T, G, TS>(plan, n, A, dB, dA, ws, shape, stream); }
 };
 struct DoubleBackwardFn {
   const sc_plan* plan; const void* A; const void* W; const void* dB; const void* H; void* ddB; void* dA2; const Workspace& ws;
   const LaunchShape& shape; hipStream_t stream;
-  template <typename T, typename G> hipError_t operator()() const { return dbl_launch<T, G>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream); }
+  template <typename T, typename G, typename TS> hipError_t operator()() const { return dbl_launch<T, G, TS>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream); }
 };
 struct FinalizeFn {
   const sc_plan* plan; void* dW; const Workspace& ws; const LaunchShape& shape; hipStream_t stream;
-  template <typename T, typename G> hipError_t operator()() const { return finalize_launch<T, G>(plan, dW, ws, shape, stream); }
+  template <typename T, typename G, typename TS> hipError_t operator()() const { return finalize_launch<T, G>(plan, dW, ws, shape, stream); }
 };
 
 hipError_t launch_spec_prepare(const sc_plan* plan, int64_t n, const int32_t* z, const void* W, const Workspace& ws,

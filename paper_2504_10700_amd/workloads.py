@@ -30,7 +30,7 @@ class Workload:
     l_max: int
     nu_max: int
     out_irreps: Tuple[Tuple[int, int], ...]   # (L, parity)
-    dtype: str                                # "f32" | "f64"
+    dtype: str                                # "f32" | "f64" | "bf16" (rows in bfloat16, weights and arithmetic fp32)
     seed: int
     z_mode: str = "skewed"                    # "uniform" | "skewed"
     structures: Optional[int] = None          # concatenated structures (sizes 10..190)
@@ -58,6 +58,8 @@ WORKLOADS = {
     "wide_high_l_f64": Workload("wide_high_l_f64", 5_000, 89, 256, 3, 3, _O012, "f64", 1006),
     # not one of the task's configurations: every output irrep up to L = 3 at the training-step shape
     "outputs_l3": Workload("outputs_l3", 10_000, 89, 128, 3, 3, _O0123, "f32", 1008),
+    # the training step with A, B, dB, dA stored as bfloat16
+    "training_step_bf16": Workload("training_step_bf16", 10_000, 89, 128, 3, 3, _O01, "bf16", 1003),
 }
 
 

@@ -23,7 +23,25 @@ def rel_err_f64(got, ref):
     return float((np.abs(np.asarray(got, dtype=np.float64) - ref) / den).max())
 
 
+BF16_REL = 2.0 ** -8   # bfloat16 keeps 8 significant bits: rounding to nearest is within 2^-9 of the value
+
+
+def check_bf16_rows(name, got, ref):
+    """Per-node results of a plan with bfloat16 rows: the fp32 result rounded to bfloat16, against
+    the oracle evaluated on the bfloat16-rounded inputs.  Element by element
+    |got - ref| <= 2^-8 |ref| + 1e-5 rms(ref): one bfloat16 rounding (2^-9 relative, doubled for
+    values the fp32 error moves across a rounding boundary) on top of the fp32 bar."""
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    rms = np.sqrt((ref ** 2).mean()) if ref.size else 1.0
+    excess = np.abs(got - ref) - (BF16_REL * np.abs(ref) + F32_TOL * rms)
+    worst = float(excess.max()) if ref.size else 0.0
+    assert worst <= 0.0, f"{name}: exceeds the bfloat16 bound by {worst:.3e} (rms {rms:.3e})"
+
+
 def check(name, got, ref, dtype):
+    if dtype == "bf16":
+        return check_bf16_rows(name, got, ref)
     if dtype == "f32":
         err, tol = rel_err_f32(got, ref), F32_TOL
     else:
@@ -48,7 +66,7 @@ def check_dw(name, dW, dW_ref, z, dtype, case="", whole_tensor=True):
     present = np.unique(z[(z >= 0) & (z < num_elements)])
     absent = np.setdiff1d(np.arange(num_elements), present)
     assert not np.asarray(dW)[absent].any(), f"{name}: rows of absent elements must be exactly zero"
-    fn, tol = (rel_err_f32, F32_TOL) if dtype == "f32" else (rel_err_f64, F64_TOL)
+    fn, tol = (rel_err_f32, F32_TOL) if dtype in ("f32", "bf16") else (rel_err_f64, F64_TOL)   # dW is fp32 with bf16 rows
     whole = fn(dW, dW_ref)
     rows = fn(np.asarray(dW)[present], np.asarray(dW_ref)[present]) if present.size else 0.0
     print(f"{case} {name}: whole-tensor error {whole:.3e}, present-rows error {rows:.3e} "
@@ -116,12 +134,14 @@ class GpuRun:
         import torch
         self.sc, self.wl, self.torch = sc, wl, torch
         self.dev = torch.device("cuda:0")
-        self.tdt = torch.float32 if wl.dtype == "f32" else torch.float64
+        # tdt: the per-node tensors; wdt: W and dW (fp32 when the rows are bfloat16)
+        self.tdt = {"f32": torch.float32, "f64": torch.float64, "bf16": torch.bfloat16}[wl.dtype]
+        self.wdt = torch.float64 if wl.dtype == "f64" else torch.float32
         self.plan = sc.sc_plan_create(wl.num_channels, wl.l_max, wl.nu_max, wl.num_elements, wl.out_irreps,
-                                      sc.SC_F32 if wl.dtype == "f32" else sc.SC_F64, 0, flags)
+                                      {"f32": sc.SC_F32, "f64": sc.SC_F64, "bf16": sc.SC_BF16}[wl.dtype], 0, flags)
         self.N = inp.A.shape[0] if n_nodes is None else n_nodes
         self.A = torch.tensor(inp.A, dtype=self.tdt, device=self.dev)
-        self.W = torch.tensor(inp.W, dtype=self.tdt, device=self.dev)
+        self.W = torch.tensor(inp.W, dtype=self.wdt, device=self.dev)
         self.dB = torch.tensor(inp.dB, dtype=self.tdt, device=self.dev)
         self.z = torch.tensor(inp.z, dtype=torch.int32, device=self.dev)
         self.B = torch.full((self.N, wl.num_channels, wl.n_LM), float("nan"), dtype=self.tdt, device=self.dev)
@@ -133,13 +153,13 @@ class GpuRun:
     def forward(self, flags=0):
         self.sc.sc_forward(self.plan, self.N, self.A, self.z, self.W, self.B, self.ws, self.ws_bytes, flags)
         self.torch.cuda.synchronize()
-        return self.B.cpu().numpy()
+        return self.B.float().cpu().numpy() if self.wl.dtype == "bf16" else self.B.cpu().numpy()
 
     def backward(self, flags=0):
         self.sc.sc_backward(self.plan, self.N, self.A, self.z, self.W, self.dB, self.dA, self.dW, self.ws,
                             self.ws_bytes, flags)
         self.torch.cuda.synchronize()
-        return self.dA.cpu().numpy(), self.dW.cpu().numpy()
+        return (self.dA.float().cpu().numpy() if self.wl.dtype == "bf16" else self.dA.cpu().numpy()), self.dW.cpu().numpy()
 
     def double_backward(self, H, flags=0):
         """H: numpy array of the shape of A.  Returns (ddB, dA2, dW2, H as computed in fp64)."""
@@ -151,6 +171,8 @@ class GpuRun:
         self.sc.sc_double_backward(self.plan, self.N, self.A, self.z, self.W, self.dB, Hd, ddB, dA2, dW2, self.ws,
                                    self.ws_bytes, flags)
         torch.cuda.synchronize()
+        if self.wl.dtype == "bf16":
+            ddB, dA2 = ddB.float(), dA2.float()
         return ddB.cpu().numpy(), dA2.cpu().numpy(), dW2.cpu().numpy(), Hd.double().cpu().numpy()
 
     def inputs_as_computed(self):

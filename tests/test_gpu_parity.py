@@ -339,6 +339,23 @@ def test_tile_size_knob_does_not_change_results_beyond_rounding(sc):
         run.close()
 
 
+@pytest.mark.parametrize("outs", [O01, O012])
+def test_bfloat16_rows(sc, outs):
+    """SC_BF16: A, B, dB, dA stored as bfloat16, W and dW in fp32, arithmetic in fp32.  The oracle
+    sees the bfloat16-rounded inputs; the per-node results are held to one bfloat16 rounding on
+    top of the fp32 bar, dW (fp32, summed from fp32 contributions) to the fp32 bar itself."""
+    info = full_parity(sc, wl_of("bf16_rows", 900, 89, 128, 3, 3, outs, "bf16", 3201))
+    assert info.specialised == 1
+    full_parity(sc, wl_of("bf16_rows_k72", 130, 7, 72, 3, 3, outs, "bf16", 3202, z_mode="uniform"))   # idle lanes
+    # not served: table-driven kernels, channel counts that are not a multiple of eight
+    with pytest.raises(sc.ScError) as e:
+        sc.sc_plan_create(128, 3, 3, 89, outs, sc.SC_BF16, 0, sc.SC_PLAN_FORCE_GENERIC)
+    assert e.value.status == sc.SC_ERR_UNSUPPORTED
+    with pytest.raises(sc.ScError) as e:
+        sc.sc_plan_create(100, 3, 3, 89, outs, sc.SC_BF16, 0)
+    assert e.value.status == sc.SC_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("flags", [0, 2])
 def test_batch_already_grouped_by_element(sc, flags):
     """SC_Z_GROUPED: with a non-decreasing z the permutation pass is skipped; same bits as without
