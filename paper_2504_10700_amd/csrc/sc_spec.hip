@@ -287,7 +287,9 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   // their element indices inside the wave - so that a run of nodes of one element reads the
   // folded weights once (they are re-read per node otherwise: 61 of 432 us at 200k nodes).  The
   // indices are read at once, which also takes them off the per-node chain of dependent loads.
-  // Nodes with an element index outside [0, Z) sort last and are skipped.
+  // Nodes with an element index outside [0, Z) sort last and are skipped.  (A third row buffer, i.e.
+  // the rows of node p+2 requested while node p is evaluated, measured the same at 10k nodes and 3%
+  // slower at 200k.)
   const int cnt = j1 - j0;
   int key = Z;
   if (lane < cnt) {

@@ -125,6 +125,14 @@ def test_degenerate_batches(sc):
     full_parity(sc, wl_of("two_elements", 97, 89, 128, 3, 3, O01, "f32", 2303), mutate=two_elems, dw_whole_tensor=False)
 
 
+@pytest.mark.parametrize("N", [2, 63, 64, 65, 255, 256, 257, 1025])
+def test_batch_sizes_around_the_chunk_boundaries(sc, N):
+    # the grouping deals 64-node chunks to waves and 256-node slices to workgroups; the forward deals
+    # 8..64-node tiles: sizes just below, at and above those boundaries, with few elements so that every
+    # element has several tiles
+    full_parity(sc, wl_of(f"ragged{N}", N, 5, 64, 3, 3, O01, "f32", 2900 + N, z_mode="uniform"))
+
+
 def test_empty_batch(sc):
     import torch
     wl = wl_of("empty", 0, 5, 128, 3, 3, O01, "f32", 2400)
