@@ -26,7 +26,7 @@ Readings of what the paper leaves open:
   which contradicts both the listing and the stated goal of balance;
 * the come-back test compares the least room among the bins still accepting after the pass
   with the most room among the bins given up in that pass;
-* bins keep the number they were opened with: round one opens 0..M-1, later rounds continue;
+* bins keep the number they were opened with: the first round opens 0..M-1, later rounds continue;
   bins that stay empty (M is rounded up to a multiple of G) are kept, so every round
   contributes a multiple of G bins;
 * a graph larger than C can never be placed: an error.
