@@ -583,7 +583,7 @@ constexpr bool kUseLdsState = sizeof(T) == 4 && G::kS <= 32;
 // internal rows s and the external paths p that depend on them (generated descriptors), so one
 // wave per (element, channel block, block of F) can do both steps without waiting for anyone:
 // it adds the block's rows over the element's tiles in tile order, in fp64, with the rows of up
-// to 32 tiles requested together, and writes the block's external paths.  Elements without nodes
+// to 32 tiles requested together (16 for two-row blocks), and writes the block's external paths.  Elements without nodes
 // own no tiles and get zeros.  Every sum has a fixed order: results are bitwise reproducible.
 // What was measured on the way here (10k / 200k nodes): a sum kernel followed by an unfold kernel
 // 11.2 / 15.6 us; one workgroup per (element, channel block) for all rows 13.5 / 31 us (the twelve
@@ -595,7 +595,7 @@ template <typename T, int R, int kMaxR>
 __device__ __forceinline__ void finalize_sum(const T* __restrict__ src, size_t tstride, int t0, int t1,
                                              const int (&row)[kMaxR], double (&acc)[kMaxR]) {
   constexpr int kRegs = R * static_cast<int>(sizeof(T) / 4);   // registers per tile in flight
-  constexpr int U = kRegs <= 2 ? 32 : kRegs <= 4 ? 16 : 8;   // (64 for single rows measured slower: fewer resident waves)
+  constexpr int U = kRegs <= 1 ? 32 : kRegs <= 2 ? 16 : 8;   // (more in flight measured slower: fewer resident waves)
   // batches of U tiles; past the last tile it is read again and dropped
   for (int t = t0; t < t1; t += U) {
     T v[U][R];
