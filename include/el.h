@@ -74,6 +74,23 @@ sc_status el_sc_forward(sc_plan* plan, int32_t k_in, int64_t n_nodes, const void
                         const int32_t* z, const void* W, void* B, void* workspace, size_t workspace_bytes,
                         void* hip_stream);
 
+/* Backward of el_sc_forward for an upstream gradient dB [n_nodes][K][n_LM] (training, Section 2.2):
+ *   dX     [n_nodes][k_in][(l_max+1)^2]   gradient with respect to X        (overwritten)
+ *   dW_lin [l_max+1][k_in][K]             gradient with respect to W_lin    (overwritten)
+ *   dW     [Z][num_paths][K]              gradient with respect to W        (overwritten)
+ * Three steps through the workspace, not one kernel: A is computed again (the fused forward never
+ * wrote it), sc_backward gives dA and dW, el_backward gives dX and dW_lin.  dW needs the atoms
+ * grouped by element and dW_lin a sum over all atoms, so A and dA pass through memory in any
+ * arrangement of this backward; what one kernel could save is one read of A.
+ * workspace: device memory, 256-byte aligned, at least el_sc_backward_workspace_bytes() (A and dA
+ * plus the larger of the two inner workspaces).  Same conventions and reproducibility as
+ * sc_backward and el_backward.  n_nodes == 0 zeroes dW and dW_lin.  Plans with bfloat16 rows are
+ * not served. */
+sc_status el_sc_backward_workspace_bytes(const sc_plan* plan, int32_t k_in, int64_t n_nodes, size_t* bytes);
+sc_status el_sc_backward(sc_plan* plan, int32_t k_in, int64_t n_nodes, const void* X, const void* W_lin,
+                         const int32_t* z, const void* W, const void* dB, void* dX, void* dW_lin, void* dW,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

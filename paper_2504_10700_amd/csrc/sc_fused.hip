@@ -225,4 +225,59 @@ sc_status el_sc_forward(sc_plan* plan, int32_t k_in, int64_t n_nodes, const void
   return SC_OK;
 }
 
+// Workspace of el_sc_backward: A | dA | the larger of the two inner workspaces.
+static size_t backward_inner_bytes(const sc_plan* plan, int32_t k_in, int64_t n, sc_status* st) {
+  using namespace sc;
+  size_t a = 0, b = 0;
+  *st = sc_workspace_bytes(plan, n, &a);
+  if (*st != SC_OK) return 0;
+  const el_config lc = linear_config(plan, k_in);
+  *st = el_workspace_bytes(&lc, n, &b);
+  return round256(a > b ? a : b);
+}
+
+sc_status el_sc_backward_workspace_bytes(const sc_plan* plan, int32_t k_in, int64_t n_nodes, size_t* bytes) {
+  using namespace sc;
+  sc_status st = check("el_sc_backward_workspace_bytes", plan, k_in, n_nodes);
+  if (st != SC_OK) return st;
+  if (!bytes) return set_error(SC_ERR_INVALID_ARG, "el_sc_backward_workspace_bytes: bytes is NULL");
+  const size_t inner = backward_inner_bytes(plan, k_in, n_nodes, &st);
+  if (st != SC_OK) return st;
+  *bytes = 2 * a_bytes(plan, n_nodes) + inner + 256;
+  return SC_OK;
+}
+
+sc_status el_sc_backward(sc_plan* plan, int32_t k_in, int64_t n_nodes, const void* X, const void* W_lin,
+                         const int32_t* z, const void* W, const void* dB, void* dX, void* dW_lin, void* dW,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  using namespace sc;
+  sc_status st = check("el_sc_backward", plan, k_in, n_nodes);
+  if (st != SC_OK) return st;
+  if (!dW_lin || !dW) return set_error(SC_ERR_INVALID_ARG, "el_sc_backward: dW_lin or dW is NULL");
+  const el_config lc = linear_config(plan, k_in);
+  if (n_nodes == 0) {   // both weight gradients are zero
+    st = sc_backward(plan, 0, nullptr, nullptr, nullptr, nullptr, nullptr, dW, nullptr, 0, 0, hip_stream);
+    if (st != SC_OK) return st;
+    return el_backward(&lc, 0, nullptr, W_lin, nullptr, nullptr, dW_lin, nullptr, 0, hip_stream);
+  }
+  if (!X || !W_lin || !z || !W || !dB || !dX)
+    return set_error(SC_ERR_INVALID_ARG, "el_sc_backward: NULL tensor argument");
+  size_t need = 0;
+  st = el_sc_backward_workspace_bytes(plan, k_in, n_nodes, &need);
+  if (st != SC_OK) return st;
+  if (!workspace || workspace_bytes < need)
+    return set_error(SC_ERR_WORKSPACE, "el_sc_backward: workspace missing or smaller than el_sc_backward_workspace_bytes()");
+  if (misaligned(workspace, 256)) return set_error(SC_ERR_WORKSPACE, "el_sc_backward: workspace not 256-byte aligned");
+  char* base = static_cast<char*>(workspace);
+  void* A = base;
+  void* dA = base + a_bytes(plan, n_nodes);
+  void* inner = base + 2 * a_bytes(plan, n_nodes);
+  const size_t inner_bytes = workspace_bytes - 2 * a_bytes(plan, n_nodes);
+  st = el_forward(&lc, n_nodes, X, W_lin, A, hip_stream);                                  // A again: the forward never wrote it
+  if (st != SC_OK) return st;
+  st = sc_backward(plan, n_nodes, A, z, W, dB, dA, dW, inner, inner_bytes, 0, hip_stream);  // dA and dW
+  if (st != SC_OK) return st;
+  return el_backward(&lc, n_nodes, X, W_lin, dA, dX, dW_lin, inner, inner_bytes, hip_stream);  // dX and dW_lin
+}
+
 }  // extern "C"

@@ -7,6 +7,7 @@ import ctypes as C
 from .binding import SC_F32, SC_F64, ScError, _check, _ptr, _stream, lib  # noqa: F401
 
 EXPORTS = ("el_forward", "el_workspace_bytes", "el_backward", "el_sc_is_fused", "el_sc_workspace_bytes",
+           "el_sc_backward_workspace_bytes", "el_sc_backward",
            "el_sc_forward")
 
 
@@ -29,6 +30,8 @@ lib.el_backward.argtypes = [C.POINTER(el_config), _i64, _vp, _vp, _vp, _vp, _vp,
 lib.el_sc_is_fused.argtypes = [_vp, C.c_int32]
 lib.el_sc_workspace_bytes.argtypes = [_vp, C.c_int32, _i64, C.POINTER(C.c_size_t)]
 lib.el_sc_forward.argtypes = [_vp, C.c_int32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+lib.el_sc_backward_workspace_bytes.argtypes = [_vp, C.c_int32, _i64, C.POINTER(C.c_size_t)]
+lib.el_sc_backward.argtypes = [_vp, C.c_int32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
 for _name in EXPORTS:
     getattr(lib, _name).restype = C.c_int
 
@@ -62,3 +65,15 @@ def el_sc_forward(plan, k_in: int, n_nodes: int, X, W_lin, z, W, B, workspace, w
                   stream=None) -> None:
     _check(lib.el_sc_forward(plan.handle, k_in, n_nodes, _ptr(X), _ptr(W_lin), _ptr(z), _ptr(W), _ptr(B), _ptr(workspace),
                              workspace_bytes, _stream(stream)))
+
+
+def el_sc_backward_workspace_bytes(plan, k_in: int, n_nodes: int) -> int:
+    n = C.c_size_t()
+    _check(lib.el_sc_backward_workspace_bytes(plan.handle, k_in, n_nodes, C.byref(n)))
+    return n.value
+
+
+def el_sc_backward(plan, k_in: int, n_nodes: int, X, W_lin, z, W, dB, dX, dW_lin, dW, workspace, workspace_bytes: int,
+                   stream=None) -> None:
+    _check(lib.el_sc_backward(plan.handle, k_in, n_nodes, _ptr(X), _ptr(W_lin), _ptr(z), _ptr(W), _ptr(dB), _ptr(dX),
+                              _ptr(dW_lin), _ptr(dW), _ptr(workspace), workspace_bytes, _stream(stream)))
