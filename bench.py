@@ -690,7 +690,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="training_step")
-    ap.add_argument("--cpu-sample", type=int, default=1024, help="nodes the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=3072, help="nodes the oracle is timed on (0 = skip); 3072 take about 12 s")
     ap.add_argument("--generic", action="store_true", help="force the table-driven kernels")
     ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
     ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
