@@ -706,19 +706,20 @@ hipError_t prepare_launch(const sc_plan* plan, int64_t n, const int32_t* z, cons
 
 // Nodes per workgroup of the natural-order forward.  All workgroups do the same work, so the
 // kernel takes (rounds of resident workgroups) x (nodes per wave): the tile is the multiple of
-// four nodes in 8..64 that minimises that product for this batch on this chip (10k nodes, 128
+// four nodes in 8..32 (8..64 for the larger bases) that minimises that product for this batch on this chip (10k nodes, 128
 // channels, three workgroups per CU: 28 nodes = one round of seven nodes per wave instead of two
-// rounds of four with 16); among sizes within 2% of the best the largest wins, since longer
-// shares per wave meet more runs of one element.
-inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs) {
+// rounds of four with 16); among sizes within 2% of the best the largest up to `most` wins, since
+// longer shares per wave meet more runs of one element (measured best at 200k nodes: 24..32 nodes
+// with the 29-row basis, 48 with the 49-row basis, whose weights cost more to re-read).
+inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs, int most) {
   auto cost = [&](int t) {
     const int64_t wgs = (n + t - 1) / t * chblocks;
     return static_cast<double>((wgs + resident_wgs - 1) / resident_wgs) * (t / kSpecWaves);
   };
   double best = cost(8);
-  for (int t = 12; t <= 64; t += 4) best = cost(t) < best ? cost(t) : best;
+  for (int t = 12; t <= most; t += 4) best = cost(t) < best ? cost(t) : best;
   int pick = 8;
-  for (int t = 8; t <= 64; t += 4)
+  for (int t = 8; t <= most; t += 4)
     if (cost(t) <= best * 1.02) pick = t;
   return pick;
 }
@@ -739,7 +740,8 @@ hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32
     return nb;
   }();
   const int tile = shape.fwd_tile_nodes > 0 ? shape.fwd_tile_nodes
-                                            : forward_tile_nodes(n, shape.chblocks, static_cast<int64_t>(wgs_per_cu) * plan->num_cus);
+                                            : forward_tile_nodes(n, shape.chblocks, static_cast<int64_t>(wgs_per_cu) * plan->num_cus,
+                                                                 G::kS > 32 ? 64 : 32);
   const int tiles = static_cast<int>((n + tile - 1) / tile);
   const int grid = scatter_wgs + table + tiles * shape.chblocks;
   hipLaunchKernelGGL((spec_forward_kernel<T, G, TS>), dim3(grid), dim3(kSpecThreads), lds, stream,
