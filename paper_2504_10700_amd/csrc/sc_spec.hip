@@ -4,11 +4,14 @@
 // Mapping (Algorithm 2 of arXiv 2504.10700 is independent per atom and channel):
 //   lane      = channel (64 consecutive channels per wave: the A row of a node is read as
 //               64 B per lane, a wave covers 4 KB of contiguous HBM; B/dB rows are 16 B per lane)
-//   wave      = a run of nodes of ONE element (weights folded once into registers)
-//   workgroup = 4 waves = one tile of the grouping pass x one 64-channel block; its waves
-//               add their dW' rows through LDS, so one partial row set leaves per tile
-//   grid      = tiles x channel blocks, remapped so that each XCD (own L2) gets a contiguous
-//               range of tiles: neighbouring tiles share the element's weights
+//   forward   workgroup = 4 waves = a tile of consecutive nodes of the batch x one 64-channel
+//               block; a wave visits its share of the nodes grouped by element and reads the
+//               folded weights of a run once
+//   backward, second-order pass
+//             workgroup = 4 waves = one tile of the grouping (nodes of ONE element) x one
+//               64-channel block, the element's folded weights in registers; its waves add their
+//               dW' rows through LDS, so one partial row set leaves per tile; the grid is
+//               remapped so that each XCD (own L2) gets a contiguous range of tiles
 // Per node the next node's rows are requested before the current one is evaluated
 // (two register sets, ping-pong), so HBM latency hides behind ~300-800 VALU operations.
 //
