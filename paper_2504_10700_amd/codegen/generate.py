@@ -41,6 +41,7 @@ SPECS = {
     "l3n3_0e1o2e": (3, 3, ((0, 1), (1, -1), (2, 1))),
     "l3n3_0e1o2e3o": (3, 3, ((0, 1), (1, -1), (2, 1), (3, -1))),
     "l1n2_0e": (1, 2, ((0, 1),)),
+    "l3n3_0e": (3, 3, ((0, 1),)),      # scalar outputs only: the product of a model's last layer
 }
 
 

@@ -196,7 +196,7 @@ sc_status sc_plan_create(const sc_config* cfg, sc_plan** out_plan) {
   if (cfg->dtype == SC_BF16 && !plan->specialised) {
     delete plan;
     return fail(SC_ERR_UNSUPPORTED, "sc_plan_create: SC_BF16 is served by the generated kernels only (l_max = 3, nu_max = 3, "
-                                    "outputs 0e+1o[+2e[+3o]], or the tiny configuration; channels a multiple of 8)");
+                                    "outputs 0e, 0e+1o, 0e+1o+2e or 0e+1o+2e+3o, or the tiny configuration; channels a multiple of 8)");
   }
   if (plan->host_only) {
     *out_plan = plan;

@@ -42,6 +42,7 @@ __device__ __forceinline__ double sc_fma(double x, double y, double z) { return 
 #include "generated/sc_gen_l3n3_0e1o2e.inc"
 #include "generated/sc_gen_l3n3_0e1o2e3o.inc"
 #include "generated/sc_gen_l1n2_0e.inc"
+#include "generated/sc_gen_l3n3_0e.inc"
 
 constexpr int kSpecWaves = 4;
 constexpr int kSpecThreads = kSpecWaves * kLanes;
@@ -822,6 +823,7 @@ hipError_t dispatch(const sc_plan* plan, F&& fn) {
     case 2: return dispatch_dtype<Gen_l3n3_0e1o2e>(plan, fn);
     case 3: return dispatch_dtype<Gen_l3n3_0e1o2e3o>(plan, fn);
     case 4: return dispatch_dtype<Gen_l1n2_0e>(plan, fn);
+    case 5: return dispatch_dtype<Gen_l3n3_0e>(plan, fn);
     default: return hipErrorInvalidValue;
   }
 }
@@ -833,11 +835,12 @@ int spec_lookup(const sc_plan* plan) {
   if (matches<Gen_l3n3_0e1o2e>(plan)) return 2;
   if (matches<Gen_l3n3_0e1o2e3o>(plan)) return 3;
   if (matches<Gen_l1n2_0e>(plan)) return 4;
+  if (matches<Gen_l3n3_0e>(plan)) return 5;
   return 0;
 }
 
 int spec_basis_size(int id) {
-  return id == 1 ? Gen_l3n3_0e1o::kS : id == 2 ? Gen_l3n3_0e1o2e::kS : id == 3 ? Gen_l3n3_0e1o2e3o::kS : id == 4 ? Gen_l1n2_0e::kS : 0;
+  return id == 1 ? Gen_l3n3_0e1o::kS : id == 2 ? Gen_l3n3_0e1o2e::kS : id == 3 ? Gen_l3n3_0e1o2e3o::kS : id == 4 ? Gen_l1n2_0e::kS : id == 5 ? Gen_l3n3_0e::kS : 0;
 }
 
 template <typename G>
@@ -854,6 +857,7 @@ void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
   if (id == 2) op_counts<Gen_l3n3_0e1o2e>(ops, flops);
   if (id == 3) op_counts<Gen_l3n3_0e1o2e3o>(ops, flops);
   if (id == 4) op_counts<Gen_l1n2_0e>(ops, flops);
+  if (id == 5) op_counts<Gen_l3n3_0e>(ops, flops);
 }
 
 int spec_waves_per_tile() { return kSpecWaves; }

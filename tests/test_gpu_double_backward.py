@@ -93,6 +93,11 @@ def test_outputs_up_to_L3_generated_kernel(sc):
     full_parity(sc, wl_of("out_L3", 60, 5, 64, 3, 3, outs, "f64", 3251, z_mode="uniform"))
 
 
+def test_scalar_outputs_only(sc):
+    full_parity(sc, wl_of("out_0e", 300, 89, 128, 3, 3, ((0, 1),), "f32", 3270))
+    full_parity(sc, wl_of("out_0e", 100, 5, 64, 3, 3, ((0, 1),), "f64", 3271, z_mode="uniform"))
+
+
 def test_bfloat16_rows(sc):
     full_parity(sc, wl_of("bf16_rows", 500, 89, 128, 3, 3, O01, "bf16", 3260))
     full_parity(sc, wl_of("bf16_rows", 200, 9, 128, 3, 3, O012, "bf16", 3261, z_mode="uniform"))

@@ -99,6 +99,16 @@ def test_other_configurations(sc, l_max, nu_max, outs):
     full_parity(sc, wl_of("other", 40, 4, 64, l_max, nu_max, outs, "f64", 2200, z_mode="uniform"))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f64", "bf16"])
+def test_scalar_outputs_only(sc, dtype):
+    # outputs 0e alone (the product of a model's last layer) at l_max = 3, nu_max = 3: a generated kernel
+    info = full_parity(sc, wl_of("out_0e", 400, 89, 128, 3, 3, ((0, 1),), dtype, 2350))
+    assert info.specialised == 1
+    if dtype == "f32":
+        full_parity(sc, wl_of("out_0e_k40", 90, 6, 40, 3, 3, ((0, 1),), dtype, 2351, z_mode="uniform"))
+        full_parity(sc, wl_of("out_0e_g", 90, 6, 64, 3, 3, ((0, 1),), dtype, 2352, z_mode="uniform"), flags=2)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "f64"])
 def test_outputs_up_to_L3(sc, dtype):
     # four output irreps 0e+1o+2e+3o (16 output components) at l_max = 3, nu_max = 3: a generated kernel in
