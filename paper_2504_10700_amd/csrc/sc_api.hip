@@ -79,9 +79,12 @@ LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
   const int64_t target_wgs = static_cast<int64_t>(plan->num_cus) * (plan->specialised ? 6 : 8);
   // expected tiles ~ n / t + (half a tile of rounding per element that occurs)
   int64_t t = (n * s.chblocks + target_wgs - 1) / target_wgs;
-  // At least four nodes per wave, two on very small batches (measured on the generated kernels, 128
-  // channels: 36 -> 31.5 us per step at 1k nodes, 50 -> 45 us at 3k, no difference at 4k, slower from 6k on).
-  const int64_t lo = (n * s.chblocks <= 7168 ? 2 : 4) * waves_per_tile, hi = 32 * waves_per_tile;
+  // At least four nodes per wave, three on small and two on very small batches (measured on the generated
+  // kernels, 128 channels, nodes per tile -> us per step: 1024 nodes 8 -> 25.5, 12 -> 27.0, 16 -> 28.4;
+  // 3072 nodes 8 -> 39.9, 12 -> 37.6, 16 -> 42.1; 5000 nodes 8 -> 49.3, 12 -> 48.8, 16 -> 50.3; 10000 nodes
+  // 12 -> 85.7, 16 -> 85.8, 24 -> 88.0).
+  const int64_t work = n * s.chblocks;
+  const int64_t lo = (work <= 2560 ? 2 : work <= 12288 ? 3 : 4) * waves_per_tile, hi = 32 * waves_per_tile;
   if (t < lo) t = lo;
   if (t > hi) t = hi;
   if (plan->cfg.tile_nodes > 0) t = plan->cfg.tile_nodes;
