@@ -105,6 +105,83 @@ class Program:
         c["total"] = sum(c.values())
         return c
 
+    # ---- rewriting
+    def prescale_single_products(self) -> "Program":
+        """Returns an equivalent program with fewer operations: a product x*y that is used once, by
+        `x*y*c + z` with a literal c, costs two operations for one term.  Where several such terms
+        share a factor and |c|, that factor is scaled once (s = y*|c|) and every term becomes one
+        fused multiply-add x*s + z (z - x*s for negative c).  Factor-constant pairs are chosen
+        greedily, most shared first; pairs used once are left as they are."""
+        live = self.live_ops()
+        uses = [0] * len(self.ops)
+        for i, op in enumerate(self.ops):
+            if live[i]:
+                for a in op[1:]:
+                    if isinstance(a, int) and not isinstance(a, bool) and op[0] != INP:
+                        uses[a] += 1
+        for _, x in self.outputs:
+            if x is not None:
+                uses[x] += 1
+        cand = {}   # cfma id -> (x, y, c, z, product id)
+        for k, op in enumerate(self.ops):
+            if live[k] and op[0] == CFMA:
+                prod = self.ops[op[1]]
+                if prod[0] == MUL and uses[op[1]] == 1:
+                    cand[k] = (prod[1], prod[2], op[2], op[3], op[1])
+        assign = {}   # cfma id -> (factor to scale, other factor)
+        remaining = dict(cand)
+        while remaining:
+            votes: Dict[Tuple[int, float], int] = {}
+            for x, y, c, _, _ in remaining.values():
+                for f in {x, y}:
+                    votes[(f, abs(c))] = votes.get((f, abs(c)), 0) + 1
+            (f, c), n = max(votes.items(), key=lambda kv: (kv[1], -kv[0][0], -kv[0][1]))
+            if n < 2:
+                break
+            for k in [k for k, (x, y, cc, _, _) in remaining.items() if abs(cc) == c and f in (x, y)]:
+                x, y = remaining[k][0], remaining[k][1]
+                assign[k] = (f, y if f == x else x)
+                del remaining[k]
+        q = Program()
+        new: Dict[int, int] = {}
+        scaled: Dict[Tuple[int, float], int] = {}
+        skip = {cand[k][4] for k in assign}
+        for i, op in enumerate(self.ops):
+            if op[0] == INP:
+                new[i] = q.inp(op[1])
+                continue
+            if not live[i] or i in skip:
+                continue
+            if i in assign:
+                f, other = assign[i]
+                _, _, c, z, _ = cand[i]
+                if (f, abs(c)) not in scaled:
+                    scaled[(f, abs(c))] = q.cmul(new[f], abs(c))
+                s_ = scaled[(f, abs(c))]
+                new[i] = q.fma(new[other], s_, new[z]) if c > 0 else q.fnma(new[other], s_, new[z])
+                continue
+            k = op[0]
+            a = [new[v] if isinstance(v, int) and not isinstance(v, bool) else v for v in op[1:]]
+            if k == MUL:
+                new[i] = q.mul(a[0], a[1])
+            elif k == ADD:
+                new[i] = q.add(a[0], a[1])
+            elif k == SUB:
+                new[i] = q.sub(a[0], a[1])
+            elif k == FMA:
+                new[i] = q.fma(a[0], a[1], a[2])
+            elif k == FNMA:
+                new[i] = q.fnma(a[0], a[1], a[2])
+            elif k == CMUL:
+                new[i] = q.cmul(a[0], a[1])
+            elif k == CFMA:
+                new[i] = q.cfma(a[0], a[1], a[2])
+            else:
+                raise ValueError(k)
+        for lv, x in self.outputs:
+            q.out(lv, new[x] if x is not None else None)
+        return q
+
     # ---- evaluation
     def evaluate(self, inputs: Dict[str, np.ndarray], dtype=np.float64) -> Dict[str, np.ndarray]:
         live = self.live_ops()
