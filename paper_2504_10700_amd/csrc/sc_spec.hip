@@ -312,43 +312,38 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
     e = __builtin_amdgcn_readlane(key, idx);
     node = j0 + idx;
   };
-  T a0[G::kNlm], a1[G::kNlm], w0[G::kS], w1[G::kS], b[G::kNLM];
-  int n0, e0, n1 = 0, e1 = Z;
+  // Rows: two register sets in turn (the next node's row is requested before the current node is
+  // evaluated).  Weights: ONE register set, reloaded from the folded table (L2) right before a node of
+  // another element is evaluated - a second set for prefetching them costs 29-68 registers and with
+  // them a wave per SIMD, which hides that latency better than the prefetch does.
+  T a0[G::kNlm], a1[G::kNlm], w[G::kS], b[G::kNLM];
+  int n0, e0, n1 = 0, e1 = Z, e_w = -1;
   visit(0, n0, e0);
   if (e0 >= Z) return;   // no valid node in this wave's share
-  load_folded<T, G>(wf, e0, chblocks, cb, lane, w0);
   RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
   for (int p = 0; p < cnt; p += 2) {
     if (p + 1 < cnt) {
       visit(p + 1, n1, e1);
-      if (e1 < Z) {
-        if (e1 == e0) {
-#pragma unroll
-          for (int s = 0; s < G::kS; ++s) w1[s] = w0[s];
-        } else {
-          load_folded<T, G>(wf, e1, chblocks, cb, lane, w1);
-        }
-        RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n1) * K + ch) * G::kNlm, a1);
-      }
+      if (e1 < Z) RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n1) * K + ch) * G::kNlm, a1);
     }
-    G::forward(a0, w0, b);
+    if (e0 != e_w) {
+      load_folded<T, G>(wf, e0, chblocks, cb, lane, w);
+      e_w = e0;
+    }
+    G::forward(a0, w, b);
     if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(B + (static_cast<size_t>(n0) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
     else if (lane < live) RowIO<T, TS, G::kNLM>::store(B + (static_cast<size_t>(n0) * K + ch) * G::kNLM, b);
     if (p + 1 >= cnt || e1 >= Z) break;   // the valid nodes are done
     e0 = Z;
     if (p + 2 < cnt) {
       visit(p + 2, n0, e0);
-      if (e0 < Z) {
-        if (e0 == e1) {
-#pragma unroll
-          for (int s = 0; s < G::kS; ++s) w0[s] = w1[s];
-        } else {
-          load_folded<T, G>(wf, e0, chblocks, cb, lane, w0);
-        }
-        RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
-      }
+      if (e0 < Z) RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
     }
-    G::forward(a1, w1, b);
+    if (e1 != e_w) {
+      load_folded<T, G>(wf, e1, chblocks, cb, lane, w);
+      e_w = e1;
+    }
+    G::forward(a1, w, b);
     if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(B + (static_cast<size_t>(n1) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
     else if (lane < live) RowIO<T, TS, G::kNLM>::store(B + (static_cast<size_t>(n1) * K + ch) * G::kNLM, b);
     if (e0 >= Z) break;
@@ -711,7 +706,7 @@ hipError_t prepare_launch(const sc_plan* plan, int64_t n, const int32_t* z, cons
 // Nodes per workgroup of the natural-order forward.  All workgroups do the same work, so the
 // kernel takes (rounds of resident workgroups) x (nodes per wave): the tile is the multiple of
 // four nodes in 8..32 (8..64 for the larger bases) that minimises that product for this batch on this chip (10k nodes, 128
-// channels, three workgroups per CU: 28 nodes = one round of seven nodes per wave instead of two
+// channels, four workgroups per CU: 20 nodes = one round of five nodes per wave instead of two
 // rounds of four with 16); among sizes within 2% of the best the largest up to `most` wins, since
 // longer shares per wave meet more runs of one element (measured best at 200k nodes: 24..32 nodes
 // with the 29-row basis, 48 with the 49-row basis, whose weights cost more to re-read).
