@@ -412,6 +412,17 @@ static hipError_t grouped_pass_prologue(const char* fn, sc_plan* plan, int64_t n
   return e;
 }
 
+// SC_COMPONENT_MAJOR is served by the generated forward and backward kernels of plans whose rows
+// are stored in the arithmetic type.
+static sc_status check_layout_flag(const char* fn, const sc_plan* plan, uint32_t flags) {
+  if (!(flags & SC_COMPONENT_MAJOR)) return SC_OK;
+  if (!plan->specialised)
+    return fail(SC_ERR_UNSUPPORTED, std::string(fn) + ": SC_COMPONENT_MAJOR needs a plan served by a generated kernel (sc_info.specialised)");
+  if (plan->cfg.dtype == SC_BF16)
+    return fail(SC_ERR_UNSUPPORTED, std::string(fn) + ": SC_COMPONENT_MAJOR is not served for bfloat16 rows");
+  return SC_OK;
+}
+
 // Checks of the tensor arguments and the launches of the forward pass, shared by sc_forward and
 // sc_forward_noalloc; the plan's device is current.
 static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes, const void* A, const int32_t* z,
@@ -420,6 +431,8 @@ static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes
   if (!A || !z || !W || !B) return fail(SC_ERR_INVALID_ARG, std::string(fn) + ": NULL tensor argument");
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(B, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, std::string(fn) + ": tensor pointer not 16-byte aligned");
+  const sc_status layout = check_layout_flag(fn, plan, flags);
+  if (layout != SC_OK) return layout;
   hipError_t e = hipSuccess;
   const bool group = !(flags & SC_REUSE_GROUPING);
   if (plan->specialised) {
@@ -432,7 +445,8 @@ static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes
   }
   if (plan->profile) (void)hipEventRecord(plan->ev[0], stream);
   e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, z, B, ws, shape,
-                                                  !group ? 0 : (flags & SC_Z_GROUPED) ? 2 : 1, stream)
+                                                  !group ? 0 : (flags & SC_Z_GROUPED) ? 2 : 1,
+                                                  (flags & SC_COMPONENT_MAJOR) != 0, stream)
                         : sc::launch_generic_forward(plan, n_nodes, A, W, B, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": kernel launch").c_str());
   if (plan->profile) {
@@ -507,11 +521,13 @@ sc_status sc_backward(sc_plan* plan, int64_t n_nodes, const void* A, const int32
   if (!A || !z || !W || !dB || !dA) return fail(SC_ERR_INVALID_ARG, "sc_backward: NULL tensor argument");
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(dA, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_backward: tensor pointer not 16-byte aligned");
+  st = check_layout_flag("sc_backward", plan, flags);
+  if (st != SC_OK) return st;
   if (plan->specialised && (flags & SC_Z_GROUPED)) ws.perm = nullptr;   // identity: rows are read in batch order
   hipError_t e = grouped_pass_prologue("sc_backward", plan, n_nodes, z, W, ws, shape, flags, true, stream);
   if (e != hipSuccess) return SC_ERR_HIP;
   if (plan->profile) (void)hipEventRecord(plan->ev[2], stream);
-  e = plan->specialised ? sc::launch_spec_backward(plan, n_nodes, A, dB, dA, ws, shape, stream)
+  e = plan->specialised ? sc::launch_spec_backward(plan, n_nodes, A, dB, dA, ws, shape, (flags & SC_COMPONENT_MAJOR) != 0, stream)
                         : sc::launch_generic_backward(plan, n_nodes, A, W, dB, dA, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_backward: kernel launch");
   if (plan->profile) {
@@ -549,6 +565,8 @@ sc_status sc_double_backward(sc_plan* plan, int64_t n_nodes, const void* A, cons
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(H, 16) || misaligned(ddB, 16) ||
       misaligned(dA2, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_double_backward: tensor pointer not 16-byte aligned");
+  if (flags & SC_COMPONENT_MAJOR)
+    return fail(SC_ERR_UNSUPPORTED, "sc_double_backward: SC_COMPONENT_MAJOR is served by sc_forward and sc_backward only");
   if (plan->specialised && (flags & SC_Z_GROUPED)) ws.perm = nullptr;   // identity: rows are read in batch order
   hipError_t e = grouped_pass_prologue("sc_double_backward", plan, n_nodes, z, W, ws, shape, flags, false, stream);
   if (e != hipSuccess) return SC_ERR_HIP;

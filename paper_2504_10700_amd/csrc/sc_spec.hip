@@ -14,6 +14,9 @@
 //               remapped so that each XCD (own L2) gets a contiguous range of tiles
 // Per node the next node's rows are requested before the current one is evaluated
 // (two register sets, ping-pong), so HBM latency hides behind ~300-800 VALU operations.
+// kCM instances of the forward and backward kernels serve the component-major layout
+// ([node][component][channel], SC_COMPONENT_MAJOR): same mapping and arithmetic, rows accessed
+// through Cols instead of Row.
 //
 // One step (forward + backward of one batch) is four launches:
 //   1 prepare   the weights of every (element, channel) folded into the internal basis once,
@@ -175,6 +178,26 @@ struct RowIO {
 template <typename T, int N>
 struct RowIO<T, T, N> : Row<T, N> {};
 
+// Component-major rows (SC_COMPONENT_MAJOR: tensors laid out [node][component][channel]): the N
+// components of one (node, channel) lie K elements apart, and a wave's access to one component
+// covers 64 consecutive channels - coalesced as it is, loads and stores alike, so nothing passes
+// through LDS.  p points at component 0 of the lane's channel.
+template <typename T, int N>
+struct Cols {
+  static __device__ __forceinline__ void load(const T* __restrict__ p, int K, T (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = p[static_cast<size_t>(i) * K];
+  }
+  template <bool kStream>
+  static __device__ __forceinline__ void store(T* __restrict__ p, int K, const T (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      if constexpr (kStream) __builtin_nontemporal_store(v[i], p + static_cast<size_t>(i) * K);
+      else p[static_cast<size_t>(i) * K] = v[i];
+    }
+  }
+};
+
 // store_rows_coalesced for rows stored as TS; `stage` is this wave's LDS block of 64*N elements of T
 // (large enough for TS, which is never wider).
 template <typename T, typename TS, int N, bool kStream>
@@ -259,7 +282,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_scatter_kernel(SplitGroupAr
 // the others: forward of `tile` consecutive nodes x one 64-channel block, a
 // contiguous quarter of the nodes per wave.  A node whose element index is outside [0, Z) is
 // skipped (its row of B is left untouched), as the grouped kernels do.
-template <typename T, typename G, typename TS = T>
+template <typename T, typename G, typename TS = T, bool kCM = false>
 __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupArgs ga, int scatter_wgs, int table, int K,
                                                                     int chblocks, int n, int Z, int tile,
                                                                     const TS* __restrict__ A,
@@ -317,35 +340,47 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   // another element is evaluated - a second set for prefetching them costs 29-68 registers and with
   // them a wave per SIMD, which hides that latency better than the prefetch does.
   T a0[G::kNlm], a1[G::kNlm], w[G::kS], b[G::kNLM];
+  static_assert(!kCM || std::is_same<T, TS>::value, "component-major rows are stored in the arithmetic type");
+  auto load_a = [&](int node, T (&a)[G::kNlm]) {
+    if constexpr (kCM) Cols<TS, G::kNlm>::load(A + static_cast<size_t>(node) * G::kNlm * K + ch, K, a);
+    else RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(node) * K + ch) * G::kNlm, a);
+  };
+  auto store_b = [&](int node) {
+    if constexpr (kCM) {
+      if (lane < live) Cols<TS, G::kNLM>::template store<true>(B + static_cast<size_t>(node) * G::kNLM * K + ch, K, b);
+    } else if constexpr (kStageB) {
+      store_rows_as<T, TS, G::kNLM>(B + (static_cast<size_t>(node) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
+    } else if (lane < live) {
+      RowIO<T, TS, G::kNLM>::store(B + (static_cast<size_t>(node) * K + ch) * G::kNLM, b);
+    }
+  };
   int n0, e0, n1 = 0, e1 = Z, e_w = -1;
   visit(0, n0, e0);
   if (e0 >= Z) return;   // no valid node in this wave's share
-  RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
+  load_a(n0, a0);
   for (int p = 0; p < cnt; p += 2) {
     if (p + 1 < cnt) {
       visit(p + 1, n1, e1);
-      if (e1 < Z) RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n1) * K + ch) * G::kNlm, a1);
+      if (e1 < Z) load_a(n1, a1);
     }
     if (e0 != e_w) {
       load_folded<T, G>(wf, e0, chblocks, cb, lane, w);
       e_w = e0;
     }
     G::forward(a0, w, b);
-    if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(B + (static_cast<size_t>(n0) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
-    else if (lane < live) RowIO<T, TS, G::kNLM>::store(B + (static_cast<size_t>(n0) * K + ch) * G::kNLM, b);
+    store_b(n0);
     if (p + 1 >= cnt || e1 >= Z) break;   // the valid nodes are done
     e0 = Z;
     if (p + 2 < cnt) {
       visit(p + 2, n0, e0);
-      if (e0 < Z) RowIO<T, TS, G::kNlm>::load(A + (static_cast<size_t>(n0) * K + ch) * G::kNlm, a0);
+      if (e0 < Z) load_a(n0, a0);
     }
     if (e1 != e_w) {
       load_folded<T, G>(wf, e1, chblocks, cb, lane, w);
       e_w = e1;
     }
     G::forward(a1, w, b);
-    if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(B + (static_cast<size_t>(n1) * K + cb * kLanes) * G::kNLM, stage, lane, b, live);
-    else if (lane < live) RowIO<T, TS, G::kNLM>::store(B + (static_cast<size_t>(n1) * K + ch) * G::kNLM, b);
+    store_b(n1);
     if (e0 >= Z) break;
   }
 }
@@ -363,7 +398,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
 // kFull: the channel count is a multiple of 64, no lane is ever idle.  The fp32 kernel of the
 // 49-row basis sits at the limit for two waves per SIMD: 250 registers without the idle-lane
 // handling, 295 (one wave per SIMD, 736 instead of 496 us at 50k nodes / 256 channels) with it.
-template <typename T, typename G, int kOcc = 0, bool kStreamDA = false, bool kFull = false, typename TS = T>
+template <typename T, typename G, int kOcc = 0, bool kStreamDA = false, bool kFull = false, typename TS = T, bool kCM = false>
 __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(kOcc == 0 ? 1 : kOcc, 8)))
 void spec_backward_kernel(int K, int chblocks, int n_blocks,
                                                                      const TS* __restrict__ A,
@@ -393,25 +428,39 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
     T w[G::kS];
     load_folded<T, G>(wf, td.z, chblocks, cb, lane, w);
     T a0[G::kNlm], a1[G::kNlm], g0[G::kNLM], g1[G::kNLM], da[G::kNlm];
+    static_assert(!kCM || std::is_same<T, TS>::value, "component-major rows are stored in the arithmetic type");
+    auto load_rows = [&](size_t node, T (&a)[G::kNlm], T (&g)[G::kNLM]) {
+      if constexpr (kCM) {
+        Cols<TS, G::kNlm>::load(A + node * G::kNlm * K + ch, K, a);
+        Cols<TS, G::kNLM>::load(dB + node * G::kNLM * K + ch, K, g);
+      } else {
+        RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+        RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+      }
+    };
+    auto store_da = [&](size_t node) {
+      if constexpr (kCM) {
+        if (kFull || lane < live) Cols<TS, G::kNlm>::template store<kStreamDA>(dA + node * G::kNlm * K + ch, K, da);
+      } else {
+        store_rows_as<T, TS, G::kNlm, kStreamDA>(dA + (node * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      }
+    };
     size_t node0 = perm ? perm[j0] : j0, node1 = 0;   // no permutation: the batch is already grouped
-    RowIO<T, TS, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
-    RowIO<T, TS, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
+    load_rows(node0, a0, g0);
     for (int j = j0; j < j1; j += 2) {
       if (j + 1 < j1) {
         node1 = perm ? perm[j + 1] : j + 1;
-        RowIO<T, TS, G::kNlm>::load(A + (node1 * K + ch) * G::kNlm, a1);
-        RowIO<T, TS, G::kNLM>::load(dB + (node1 * K + ch) * G::kNLM, g1);
+        load_rows(node1, a1, g1);
       }
       G::backward(a0, w, g0, da, dw);
-      store_rows_as<T, TS, G::kNlm, kStreamDA>(dA + (node0 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      store_da(node0);
       if (j + 1 < j1) {
         if (j + 2 < j1) {
           node0 = perm ? perm[j + 2] : j + 2;
-          RowIO<T, TS, G::kNlm>::load(A + (node0 * K + ch) * G::kNlm, a0);
-          RowIO<T, TS, G::kNLM>::load(dB + (node0 * K + ch) * G::kNLM, g0);
+          load_rows(node0, a0, g0);
         }
         G::backward(a1, w, g1, da, dw);
-        store_rows_as<T, TS, G::kNlm, kStreamDA>(dA + (node1 * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+        store_da(node1);
       }
     }
   }
@@ -723,7 +772,7 @@ inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs, int
   return pick;
 }
 
-template <typename T, typename G, typename TS>
+template <typename T, typename G, typename TS, bool kCM = false>
 hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B, const Workspace& ws,
                       const LaunchShape& shape, int group, hipStream_t stream) {
   // group: 0 no grouping roles, 1 scatter + table, 2 table only (the batch is already grouped)
@@ -734,7 +783,7 @@ hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32
   if (table && split_group_lds_bytes(plan->cfg.num_elements) > lds) lds = split_group_lds_bytes(plan->cfg.num_elements);
   static const int wgs_per_cu = [] {   // resident workgroups per compute unit of this instance
     int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, spec_forward_kernel<T, G, TS>, kSpecThreads, 0) != hipSuccess || nb < 1)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, spec_forward_kernel<T, G, TS, kCM>, kSpecThreads, 0) != hipSuccess || nb < 1)
       nb = 1;
     return nb;
   }();
@@ -743,25 +792,27 @@ hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32
                                                                  G::kS > 32 ? 64 : 32);
   const int tiles = static_cast<int>((n + tile - 1) / tile);
   const int grid = scatter_wgs + table + tiles * shape.chblocks;
-  hipLaunchKernelGGL((spec_forward_kernel<T, G, TS>), dim3(grid), dim3(kSpecThreads), lds, stream,
+  hipLaunchKernelGGL((spec_forward_kernel<T, G, TS, kCM>), dim3(grid), dim3(kSpecThreads), lds, stream,
                      group_args(plan, n, z, ws, shape), scatter_wgs, table, plan->cfg.num_channels, shape.chblocks,
                      static_cast<int>(n), plan->cfg.num_elements, tile, static_cast<const TS*>(A), z,
                      static_cast<const T*>(ws.wfold), static_cast<TS*>(B));
   return hipGetLastError();
 }
 
-template <typename T, typename G, typename TS>
+template <typename T, typename G, typename TS, bool kCM = false>
 hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
                       const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {   // ws.perm may be null
   const int n_blocks = shape.max_tiles * shape.chblocks;
   const int grid = (n_blocks + kXcds - 1) / kXcds * kXcds;
   const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
   const bool full = plan->cfg.num_channels % kLanes == 0;
-  auto kernel = full ? &spec_backward_kernel<T, G, 0, false, true, TS> : &spec_backward_kernel<T, G, 0, false, false, TS>;
+  auto kernel = full ? &spec_backward_kernel<T, G, 0, false, true, TS, kCM> : &spec_backward_kernel<T, G, 0, false, false, TS, kCM>;
   if constexpr (sizeof(T) == 4 && G::kS <= 32 && std::is_same<T, TS>::value) {
     // small batches: three waves per SIMD, streamed dA (see the kernel; with bfloat16 rows that instance
     // would need 52 bytes of scratch per lane)
-    if (n <= 40000) kernel = full ? &spec_backward_kernel<T, G, 3, true, true, TS> : &spec_backward_kernel<T, G, 3, true, false, TS>;
+    // (channel counts that leave lanes idle keep the unconstrained kernel: held to 168 registers the
+    // idle-lane handling would push 188 bytes per lane to scratch)
+    if (n <= 40000 && full) kernel = &spec_backward_kernel<T, G, 3, true, true, TS, kCM>;
   }
   const hipError_t e = raise_lds_limit(kernel, lds);
   if (e != hipSuccess) return e;
@@ -870,13 +921,27 @@ struct PrepareFn {
 };
 struct ForwardFn {
   const sc_plan* plan; int64_t n; const void* A; const int32_t* z; void* B; const Workspace& ws; const LaunchShape& shape;
-  int group; hipStream_t stream;
-  template <typename T, typename G, typename TS> hipError_t operator()() const { return fwd_launch<T, G, TS>(plan, n, A, z, B, ws, shape, group, stream); }
+  int group; bool component_major; hipStream_t stream;
+  template <typename T, typename G, typename TS> hipError_t operator()() const {
+    if constexpr (std::is_same<T, TS>::value) {
+      if (component_major) return fwd_launch<T, G, TS, true>(plan, n, A, z, B, ws, shape, group, stream);
+    } else if (component_major) {
+      return hipErrorInvalidValue;   // refused by the caller: rows stored in another type have no such kernel
+    }
+    return fwd_launch<T, G, TS>(plan, n, A, z, B, ws, shape, group, stream);
+  }
 };
 struct BackwardFn {
   const sc_plan* plan; int64_t n; const void* A; const void* dB; void* dA; const Workspace& ws; const LaunchShape& shape;
-  hipStream_t stream;
-  template <typename T, typename G, typename TS> hipError_t operator()() const { return bwd_launch<T, G, TS>(plan, n, A, dB, dA, ws, shape, stream); }
+  bool component_major; hipStream_t stream;
+  template <typename T, typename G, typename TS> hipError_t operator()() const {
+    if constexpr (std::is_same<T, TS>::value) {
+      if (component_major) return bwd_launch<T, G, TS, true>(plan, n, A, dB, dA, ws, shape, stream);
+    } else if (component_major) {
+      return hipErrorInvalidValue;
+    }
+    return bwd_launch<T, G, TS>(plan, n, A, dB, dA, ws, shape, stream);
+  }
 };
 struct DoubleBackwardFn {
   const sc_plan* plan; const void* A; const void* W; const void* dB; const void* H; void* ddB; void* dA2; const Workspace& ws;
@@ -902,13 +967,15 @@ hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z,
 }
 
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B,
-                               const Workspace& ws, const LaunchShape& shape, int group, hipStream_t stream) {
-  return dispatch(plan, ForwardFn{plan, n, A, z, B, ws, shape, group, stream});
+                               const Workspace& ws, const LaunchShape& shape, int group, bool component_major,
+                               hipStream_t stream) {
+  return dispatch(plan, ForwardFn{plan, n, A, z, B, ws, shape, group, component_major, stream});
 }
 
 hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,
-                                const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
-  return dispatch(plan, BackwardFn{plan, n, A, dB, dA, ws, shape, stream});
+                                const Workspace& ws, const LaunchShape& shape, bool component_major,
+                                hipStream_t stream) {
+  return dispatch(plan, BackwardFn{plan, n, A, dB, dA, ws, shape, component_major, stream});
 }
 
 hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t, const void* A, const void* W, const void* dB,

@@ -403,6 +403,69 @@ def test_batch_already_grouped_by_element(sc, flags):
     run.close()
 
 
+@pytest.mark.parametrize("case", [
+    ("cm_0e1o", 900, 89, 128, O01, "f32"),
+    ("cm_0e1o_k72", 130, 7, 72, O01, "f32"),           # idle lanes in the second channel block
+    ("cm_0e1o2e", 400, 89, 256, O012, "f32"),
+    ("cm_0e1o_f64", 150, 5, 64, O01, "f64"),
+    ("cm_L3", 150, 5, 64, O01 + ((2, 1), (3, -1)), "f32"),
+])
+def test_component_major_layout(sc, case):
+    """SC_COMPONENT_MAJOR: A, B, dB, dA as [node][component][channel].  Same arithmetic per (node,
+    channel) as the default layout, so the per-node results are the default layout's bits
+    transposed; dW goes through the same sums and is compared with the oracle and bitwise too."""
+    import torch
+    name, N, Z, K, outs, dtype = case
+    wl = wl_of(name, N, Z, K, 3, 3, outs, dtype, 3301, z_mode="skewed" if Z == 89 else "uniform")
+    say(f"case {name}: N={N} K={K} Z={Z} {dtype}")
+    T = oracle_tables(wl)
+    inp = workloads.make_inputs(wl, T.paths)
+    run = GpuRun(sc, wl, inp)
+    assert sc.sc_plan_info(run.plan).specialised == 1
+    A, z, W, dB = run.inputs_as_computed()
+    B0 = run.forward()
+    dA0, dW0 = run.backward(sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS)
+    # the same buffers' contents, component-major
+    run.A = run.A.transpose(1, 2).contiguous()
+    run.dB = run.dB.transpose(1, 2).contiguous()
+    run.B = torch.full((N, wl.n_LM, K), float("nan"), dtype=run.tdt, device=run.dev)
+    run.dA = torch.full_like(run.A, float("nan"))
+    run.dW.fill_(float("nan"))
+    cm = sc.SC_COMPONENT_MAJOR
+    B1 = run.forward(cm).transpose(0, 2, 1)
+    dA1, dW1 = run.backward(cm | sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS)
+    dA1 = dA1.transpose(0, 2, 1)
+    check("B", B1, oracle_forward(osc, T, A, z, W), dtype)
+    dA_ref, dW_ref = oracle_backward(osc, T, A, z, W, dB)
+    check("dA", dA1, dA_ref, dtype)
+    check_dw("dW", dW1, dW_ref, z, dtype, case=f"{name}/{dtype}/component_major")
+    assert np.array_equal(B0, B1) and np.array_equal(dA0, dA1) and np.array_equal(dW0, dW1)
+    dA2, dW2 = run.backward(cm)    # a backward of its own (grouping and weights prepared again)
+    assert np.array_equal(dA1, dA2.transpose(0, 2, 1)) and np.array_equal(dW1, dW2)
+    # not served: the second-order pass, table-driven plans, bfloat16 rows
+    with pytest.raises(sc.ScError) as e:
+        run.double_backward(workloads.make_cotangent(wl).transpose(0, 2, 1).copy(), cm)
+    assert e.value.status == sc.SC_ERR_UNSUPPORTED
+    run.close()
+    if name == "cm_0e1o":
+        for plan_dtype, plan_flags in ((sc.SC_F32, sc.SC_PLAN_FORCE_GENERIC), (sc.SC_BF16, 0)):
+            plan = sc.sc_plan_create(K, 3, 3, Z, outs, plan_dtype, 0, plan_flags)
+            tdt = torch.bfloat16 if plan_dtype == sc.SC_BF16 else torch.float32
+            a = torch.zeros((4, 16, K), dtype=tdt, device="cuda")
+            b = torch.zeros((4, wl.n_LM, K), dtype=tdt, device="cuda")
+            w = torch.zeros((Z, len(T.paths), K), dtype=torch.float32, device="cuda")
+            zz = torch.zeros(4, dtype=torch.int32, device="cuda")
+            nbytes = sc.sc_workspace_bytes(plan, 4)
+            ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+            with pytest.raises(sc.ScError) as e:
+                sc.sc_forward(plan, 4, a, zz, w, b, ws, nbytes, cm)
+            assert e.value.status == sc.SC_ERR_UNSUPPORTED
+            with pytest.raises(sc.ScError) as e:
+                sc.sc_backward(plan, 4, a, zz, w, b, torch.empty_like(a), torch.empty_like(w), ws, nbytes, cm)
+            assert e.value.status == sc.SC_ERR_UNSUPPORTED
+            sc.sc_plan_destroy(plan)
+
+
 def test_out_of_range_elements_are_skipped_not_fatal(sc):
     import torch
     wl = wl_of("badz", 50, 4, 128, 3, 3, O01, "f32", 2801, z_mode="uniform")
