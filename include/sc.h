@@ -91,13 +91,13 @@ typedef enum { SC_F32 = 0, SC_F64 = 1, SC_BF16 = 2 } sc_dtype;
                                 call of this plan prepared them, and W has the same contents
                                 (the backward of a step after its forward): skip that step   */
 
-#define SC_COMPONENT_MAJOR 8u /* sc_forward and sc_backward: the per-node tensors A, B, dB and dA are laid
-                                 out [n_nodes][component][K] (channel fastest) instead of
-                                 [n_nodes][K][component]; W and dW keep their layout.  Served for plans
-                                 with a generated kernel (sc_info.specialised) and fp32 or fp64 rows;
-                                 otherwise, and in sc_double_backward, the call fails with
-                                 SC_ERR_UNSUPPORTED and launches nothing.  Results are those of the
-                                 default layout, bit for bit, transposed.                          */
+#define SC_COMPONENT_MAJOR 8u /* the per-node tensors (A, B, dB, dA, and H, ddB, dA2 of the second-order
+                                 pass) are laid out [n_nodes][component][K] (channel fastest) instead
+                                 of [n_nodes][K][component]; W and dW keep their layout.  Served for
+                                 plans with a generated kernel (sc_info.specialised) and fp32 or fp64
+                                 rows; otherwise the call fails with SC_ERR_UNSUPPORTED and launches
+                                 nothing.  The per-node results are those of the default layout,
+                                 bit for bit, transposed.                                         */
 
 typedef struct {
   int32_t struct_size;            /* = sizeof(sc_config), ABI guard                                  */

@@ -412,7 +412,7 @@ static hipError_t grouped_pass_prologue(const char* fn, sc_plan* plan, int64_t n
   return e;
 }
 
-// SC_COMPONENT_MAJOR is served by the generated forward and backward kernels of plans whose rows
+// SC_COMPONENT_MAJOR is served by the generated kernels of plans whose rows
 // are stored in the arithmetic type.
 static sc_status check_layout_flag(const char* fn, const sc_plan* plan, uint32_t flags) {
   if (!(flags & SC_COMPONENT_MAJOR)) return SC_OK;
@@ -565,14 +565,15 @@ sc_status sc_double_backward(sc_plan* plan, int64_t n_nodes, const void* A, cons
   if (misaligned(A, 16) || misaligned(W, 16) || misaligned(dB, 16) || misaligned(H, 16) || misaligned(ddB, 16) ||
       misaligned(dA2, 16) || misaligned(z, 4))
     return fail(SC_ERR_INVALID_ARG, "sc_double_backward: tensor pointer not 16-byte aligned");
-  if (flags & SC_COMPONENT_MAJOR)
-    return fail(SC_ERR_UNSUPPORTED, "sc_double_backward: SC_COMPONENT_MAJOR is served by sc_forward and sc_backward only");
+  st = check_layout_flag("sc_double_backward", plan, flags);
+  if (st != SC_OK) return st;
   if (plan->specialised && (flags & SC_Z_GROUPED)) ws.perm = nullptr;   // identity: rows are read in batch order
   hipError_t e = grouped_pass_prologue("sc_double_backward", plan, n_nodes, z, W, ws, shape, flags, false, stream);
   if (e != hipSuccess) return SC_ERR_HIP;
   if (plan->profile) (void)hipEventRecord(plan->ev[4], stream);
   e = plan->specialised
-          ? sc::launch_spec_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape, stream)
+          ? sc::launch_spec_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape,
+                                            (flags & SC_COMPONENT_MAJOR) != 0, stream)
           : sc::launch_generic_double_backward(plan, n_nodes, A, W, dB, H, ddB, dA2, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, "sc_double_backward: kernel launch");
   if (plan->profile) {

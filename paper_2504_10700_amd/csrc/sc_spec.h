@@ -26,7 +26,7 @@ hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z,
                                const LaunchShape& shape, bool table_only, hipStream_t stream);
 // Forward over the nodes in natural order from ws.wfold; group: the second half of the grouping
 // rides in the same launch (0 no, 1 permutation + tile table, 2 tile table only).
-// component_major (forward and backward): the per-node tensors are laid out [node][component][channel]
+// component_major: the per-node tensors are laid out [node][component][channel]
 // (SC_COMPONENT_MAJOR; plans whose rows are stored in the arithmetic type only).
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B,
                                const Workspace& ws, const LaunchShape& shape, int group, bool component_major,
@@ -37,7 +37,7 @@ hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, c
                                 hipStream_t stream);
 hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t n, const void* A, const void* W, const void* dB,
                                        const void* H, void* ddB, void* dA2, const Workspace& ws,
-                                       const LaunchShape& shape, hipStream_t stream);
+                                       const LaunchShape& shape, bool component_major, hipStream_t stream);
 
 // dW reduction over the tiles of every element and unfold to the external paths.
 hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,

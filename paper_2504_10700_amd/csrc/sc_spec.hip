@@ -491,7 +491,39 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
 //    larger basis or fp64 it would spill.  Small changes to its text move the register
 //    allocation across the spill threshold: check the compiler's resource report
 //    (-Rpass-analysis=kernel-resource-usage) after touching it.
-template <typename T, typename G, bool kFull, typename TS = T>
+// Rows of one node in the second-order kernels, in either layout (see Cols).
+template <typename T, typename TS, typename G, bool kCM>
+struct NodeRows2 {
+  static __device__ __forceinline__ void load(const TS* __restrict__ A, const TS* __restrict__ H, const TS* __restrict__ dB,
+                                              size_t node, int K, int ch, T (&a)[G::kNlm], T (&h)[G::kNlm], T (&g)[G::kNLM]) {
+    if constexpr (kCM) {
+      Cols<TS, G::kNlm>::load(A + node * G::kNlm * K + ch, K, a);
+      Cols<TS, G::kNlm>::load(H + node * G::kNlm * K + ch, K, h);
+      Cols<TS, G::kNLM>::load(dB + node * G::kNLM * K + ch, K, g);
+    } else {
+      RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
+      RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
+      RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+    }
+  }
+  template <bool kFull>
+  static __device__ __forceinline__ void store(TS* __restrict__ dA2, TS* __restrict__ ddB, size_t node, int K, int cb, int ch,
+                                               T* stage, int lane, int live, const T (&da)[G::kNlm], const T (&ddb)[G::kNLM]) {
+    if constexpr (kCM) {
+      if (kFull || lane < live) {
+        Cols<TS, G::kNlm>::template store<true>(dA2 + node * G::kNlm * K + ch, K, da);
+        Cols<TS, G::kNLM>::template store<true>(ddB + node * G::kNLM * K + ch, K, ddb);
+      }
+    } else {
+      constexpr bool kStageB = G::kNLM * sizeof(TS) != 16;
+      store_rows_as<T, TS, G::kNlm>(dA2 + (node * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
+      if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(ddB + (node * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
+      else if (kFull || lane < live) RowIO<T, TS, G::kNLM>::store(ddB + (node * K + ch) * G::kNLM, ddb);
+    }
+  }
+};
+
+template <typename T, typename G, bool kFull, typename TS = T, bool kCM = false>
 __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
     int K, int chblocks, int n_blocks, const TS* __restrict__ A, const T* __restrict__ W, const TS* __restrict__ dB,
     const TS* __restrict__ H, TS* __restrict__ ddB, TS* __restrict__ dA2, T* __restrict__ partial,
@@ -499,7 +531,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
   extern __shared__ unsigned char lds_raw[];
   T* red = reinterpret_cast<T*>(lds_raw);  // [kSpecWaves][kS][64]
   T* stage = red + kSpecWaves * G::kS * kLanes + wave_of_thread() * kLanes * G::kNlm;  // [64][kNlm] per wave
-  constexpr bool kStageB = G::kNLM * sizeof(TS) != 16;
+  static_assert(!kCM || std::is_same<T, TS>::value, "component-major rows are stored in the arithmetic type");
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
   const int logical = xcd_contiguous_block();
@@ -521,21 +553,15 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
     // arithmetic of the current one has consumed them, ahead of its stores
     T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
     size_t node = perm ? perm[j0] : j0;   // no permutation: the batch is already grouped
-    RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
-    RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
-    RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+    NodeRows2<T, TS, G, kCM>::load(A, H, dB, node, K, ch, a, h, g);
     for (int j = j0; j < j1; ++j) {
       G::double_backward(a, w, g, h, ddb, da, dw);
       const size_t cur = node;
       if (j + 1 < j1) {
         node = perm ? perm[j + 1] : j + 1;
-        RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
-        RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
-        RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+        NodeRows2<T, TS, G, kCM>::load(A, H, dB, node, K, ch, a, h, g);
       }
-      store_rows_as<T, TS, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
-      if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
-      else if (kFull || lane < live) RowIO<T, TS, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+      NodeRows2<T, TS, G, kCM>::template store<kFull>(dA2, ddB, cur, K, cb, ch, stage, lane, live, da, ddb);
     }
   }
 #pragma unroll
@@ -551,7 +577,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
 }
 
 // See above.  LDS: w' [kSpecWaves][kS][64] | sums [kSpecWaves][kS][64] | stage [kSpecWaves][64][kNlm].
-template <typename T, typename G, bool kFull, typename TS = T>
+template <typename T, typename G, bool kFull, typename TS = T, bool kCM = false>
 __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void spec_double_backward_lds_kernel(
     int K, int chblocks, int n_blocks, const TS* __restrict__ A, const T* __restrict__ W, const TS* __restrict__ dB,
     const TS* __restrict__ H, TS* __restrict__ ddB, TS* __restrict__ dA2, T* __restrict__ partial,
@@ -560,7 +586,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
   T* red = reinterpret_cast<T*>(lds_raw);  // [kSpecWaves][kS][64]: every wave's w' columns
   T* acc_all = red + kSpecWaves * G::kS * kLanes;                         // [kSpecWaves][kS][64] dW2' sums
   T* stage = acc_all + kSpecWaves * G::kS * kLanes + wave_of_thread() * kLanes * G::kNlm;  // [64][kNlm] per wave
-  constexpr bool kStageB = G::kNLM * sizeof(TS) != 16;
+  static_assert(!kCM || std::is_same<T, TS>::value, "component-major rows are stored in the arithmetic type");
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
   const int logical = xcd_contiguous_block();
@@ -587,9 +613,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
     // arithmetic of the current one has consumed them, ahead of its stores
     T a[G::kNlm], h[G::kNlm], g[G::kNLM], da[G::kNlm], ddb[G::kNLM];
     size_t node = perm ? perm[j0] : j0;   // no permutation: the batch is already grouped
-    RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
-    RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
-    RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+    NodeRows2<T, TS, G, kCM>::load(A, H, dB, node, K, ch, a, h, g);
     for (int j = j0; j < j1; ++j) {
       T w[G::kS];
       asm volatile("" ::: "memory");  // keep the reads of w' inside the loop (registers are short)
@@ -604,13 +628,9 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
       const size_t cur = node;
       if (j + 1 < j1) {
         node = perm ? perm[j + 1] : j + 1;
-        RowIO<T, TS, G::kNlm>::load(A + (node * K + ch) * G::kNlm, a);
-        RowIO<T, TS, G::kNlm>::load(H + (node * K + ch) * G::kNlm, h);
-        RowIO<T, TS, G::kNLM>::load(dB + (node * K + ch) * G::kNLM, g);
+        NodeRows2<T, TS, G, kCM>::load(A, H, dB, node, K, ch, a, h, g);
       }
-      store_rows_as<T, TS, G::kNlm>(dA2 + (cur * K + cb * kLanes) * G::kNlm, stage, lane, da, live);
-      if constexpr (kStageB) store_rows_as<T, TS, G::kNLM>(ddB + (cur * K + cb * kLanes) * G::kNLM, stage, lane, ddb, live);
-      else if (kFull || lane < live) RowIO<T, TS, G::kNLM>::store(ddB + (cur * K + ch) * G::kNLM, ddb);
+      NodeRows2<T, TS, G, kCM>::template store<kFull>(dA2, ddB, cur, K, cb, ch, stage, lane, live, da, ddb);
     }
   }
   __syncthreads();
@@ -822,7 +842,7 @@ hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void*
   return hipGetLastError();
 }
 
-template <typename T, typename G, typename TS>
+template <typename T, typename G, typename TS, bool kCM = false>
 hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const void* dB, const void* H, void* ddB,
                       void* dA2, const Workspace& ws, const LaunchShape& shape, hipStream_t stream) {
   const int n_blocks = shape.max_tiles * shape.chblocks;
@@ -830,8 +850,8 @@ hipError_t dbl_launch(const sc_plan* plan, const void* A, const void* W, const v
   constexpr bool kLds = kUseLdsState<T, G>;
   const size_t lds = sizeof(T) * kSpecWaves * ((kLds ? 2 : 1) * G::kS + G::kNlm) * kLanes;
   const bool full = plan->cfg.num_channels % kLanes == 0;   // no idle lanes: an instance without their handling
-  auto kernel = full ? &spec_double_backward_kernel<T, G, true, TS> : &spec_double_backward_kernel<T, G, false, TS>;
-  if constexpr (kLds) kernel = full ? &spec_double_backward_lds_kernel<T, G, true, TS> : &spec_double_backward_lds_kernel<T, G, false, TS>;
+  auto kernel = full ? &spec_double_backward_kernel<T, G, true, TS, kCM> : &spec_double_backward_kernel<T, G, false, TS, kCM>;
+  if constexpr (kLds) kernel = full ? &spec_double_backward_lds_kernel<T, G, true, TS, kCM> : &spec_double_backward_lds_kernel<T, G, false, TS, kCM>;
   const hipError_t e = raise_lds_limit(kernel, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpecThreads), lds, stream, plan->cfg.num_channels, shape.chblocks,
@@ -945,8 +965,15 @@ struct BackwardFn {
 };
 struct DoubleBackwardFn {
   const sc_plan* plan; const void* A; const void* W; const void* dB; const void* H; void* ddB; void* dA2; const Workspace& ws;
-  const LaunchShape& shape; hipStream_t stream;
-  template <typename T, typename G, typename TS> hipError_t operator()() const { return dbl_launch<T, G, TS>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream); }
+  const LaunchShape& shape; bool component_major; hipStream_t stream;
+  template <typename T, typename G, typename TS> hipError_t operator()() const {
+    if constexpr (std::is_same<T, TS>::value) {
+      if (component_major) return dbl_launch<T, G, TS, true>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream);
+    } else if (component_major) {
+      return hipErrorInvalidValue;
+    }
+    return dbl_launch<T, G, TS>(plan, A, W, dB, H, ddB, dA2, ws, shape, stream);
+  }
 };
 struct FinalizeFn {
   const sc_plan* plan; void* dW; const Workspace& ws; const LaunchShape& shape; hipStream_t stream;
@@ -980,8 +1007,8 @@ hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, c
 
 hipError_t launch_spec_double_backward(const sc_plan* plan, int64_t, const void* A, const void* W, const void* dB,
                                        const void* H, void* ddB, void* dA2, const Workspace& ws,
-                                       const LaunchShape& shape, hipStream_t stream) {
-  return dispatch(plan, DoubleBackwardFn{plan, A, W, dB, H, ddB, dA2, ws, shape, stream});
+                                       const LaunchShape& shape, bool component_major, hipStream_t stream) {
+  return dispatch(plan, DoubleBackwardFn{plan, A, W, dB, H, ddB, dA2, ws, shape, component_major, stream});
 }
 
 hipError_t launch_spec_finalize(const sc_plan* plan, void* dW, const Workspace& ws, const LaunchShape& shape,

@@ -10,7 +10,7 @@ import pytest
 
 from oracle import symmetric_contraction as osc
 from paper_2504_10700_amd import workloads
-from gpu_util import GpuRun, check, check_dw, rel_err_f32, oracle_forward, oracle_backward
+from gpu_util import GpuRun, check, check_dw, rel_err_f32, oracle_forward, oracle_backward, oracle_double_backward
 
 pytestmark = pytest.mark.gpu
 
@@ -411,9 +411,10 @@ def test_batch_already_grouped_by_element(sc, flags):
     ("cm_L3", 150, 5, 64, O01 + ((2, 1), (3, -1)), "f32"),
 ])
 def test_component_major_layout(sc, case):
-    """SC_COMPONENT_MAJOR: A, B, dB, dA as [node][component][channel].  Same arithmetic per (node,
-    channel) as the default layout, so the per-node results are the default layout's bits
-    transposed; dW goes through the same sums and is compared with the oracle and bitwise too."""
+    """SC_COMPONENT_MAJOR: A, B, dB, dA (and H, ddB, dA2 of the second-order pass) as
+    [node][component][channel].  Same arithmetic per (node, channel) as the default layout, so the
+    per-node results are the default layout's bits transposed; dW and dW2 (sums over nodes inside
+    another instance of the kernel) are held to the oracle like any other result."""
     import torch
     name, N, Z, K, outs, dtype = case
     wl = wl_of(name, N, Z, K, 3, 3, outs, dtype, 3301, z_mode="skewed" if Z == 89 else "uniform")
@@ -425,6 +426,8 @@ def test_component_major_layout(sc, case):
     A, z, W, dB = run.inputs_as_computed()
     B0 = run.forward()
     dA0, dW0 = run.backward(sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS)
+    H = workloads.make_cotangent(wl)
+    second0 = run.double_backward(H, sc.SC_REUSE_GROUPING)
     # the same buffers' contents, component-major
     run.A = run.A.transpose(1, 2).contiguous()
     run.dB = run.dB.transpose(1, 2).contiguous()
@@ -439,14 +442,18 @@ def test_component_major_layout(sc, case):
     dA_ref, dW_ref = oracle_backward(osc, T, A, z, W, dB)
     check("dA", dA1, dA_ref, dtype)
     check_dw("dW", dW1, dW_ref, z, dtype, case=f"{name}/{dtype}/component_major")
-    assert np.array_equal(B0, B1) and np.array_equal(dA0, dA1) and np.array_equal(dW0, dW1)
+    assert np.array_equal(B0, B1) and np.array_equal(dA0, dA1)
     dA2, dW2 = run.backward(cm)    # a backward of its own (grouping and weights prepared again)
     assert np.array_equal(dA1, dA2.transpose(0, 2, 1)) and np.array_equal(dW1, dW2)
-    # not served: the second-order pass, table-driven plans, bfloat16 rows
-    with pytest.raises(sc.ScError) as e:
-        run.double_backward(workloads.make_cotangent(wl).transpose(0, 2, 1).copy(), cm)
-    assert e.value.status == sc.SC_ERR_UNSUPPORTED
+    ddB1, dA21, dW21, _ = run.double_backward(H.transpose(0, 2, 1).copy(), cm | sc.SC_REUSE_GROUPING)
+    ddB1, dA21 = ddB1.transpose(0, 2, 1), dA21.transpose(0, 2, 1)
+    ddB_ref, dA2_ref, dW2_ref = oracle_double_backward(osc, T, A, z, W, dB, second0[3])
+    check("ddB", ddB1, ddB_ref, dtype)
+    check("dA2", dA21, dA2_ref, dtype)
+    check_dw("dW2", dW21, dW2_ref, z, dtype, case=f"{name}/{dtype}/component_major/second-order")
+    assert np.array_equal(second0[0], ddB1) and np.array_equal(second0[1], dA21)
     run.close()
+    # not served: table-driven plans, bfloat16 rows
     if name == "cm_0e1o":
         for plan_dtype, plan_flags in ((sc.SC_F32, sc.SC_PLAN_FORCE_GENERIC), (sc.SC_BF16, 0)):
             plan = sc.sc_plan_create(K, 3, 3, Z, outs, plan_dtype, 0, plan_flags)
