@@ -201,10 +201,9 @@ def graph_indices(sender: np.ndarray, receiver: np.ndarray, num_nodes: int):
     return row_ptr, send_ptr, send_edge
 
 
-def make_tp_inputs(wl: TPWorkload, paths: Sequence[Sequence[int]]) -> TPInputs:
-    """Draws the graph, then Y, h, R, dA (in that order) in fp64 from default_rng(seed).
-    `paths`: the caller's path table, rows (l1, l2, l3), used only to count the paths per l3."""
-    rng = np.random.default_rng(wl.seed)
+def make_tp_graph(wl: TPWorkload, rng: np.random.Generator):
+    """The graph of a tensor-product workload drawn from `rng` (the first draws of make_tp_inputs):
+    (sender, receiver) per edge, edges grouped by receiver."""
     N = wl.num_nodes
     deg = np.minimum(rng.poisson(wl.mean_degree, size=N), 4 * wl.mean_degree)
     deg[rng.random(N) < 0.01] = 0
@@ -223,6 +222,16 @@ def make_tp_inputs(wl: TPWorkload, paths: Sequence[Sequence[int]]) -> TPInputs:
     lo, span = first[receiver], size_of[receiver]
     sender = (lo + rng.integers(0, 1 << 30, size=E) % np.maximum(span - 1, 1)).astype(np.int32)
     sender += (sender >= receiver).astype(np.int32)      # never the receiver itself
+    return sender, receiver
+
+
+def make_tp_inputs(wl: TPWorkload, paths: Sequence[Sequence[int]]) -> TPInputs:
+    """Draws the graph, then Y, h, R, dA (in that order) in fp64 from default_rng(seed).
+    `paths`: the caller's path table, rows (l1, l2, l3), used only to count the paths per l3."""
+    rng = np.random.default_rng(wl.seed)
+    N = wl.num_nodes
+    sender, receiver = make_tp_graph(wl, rng)
+    E = int(receiver.size)
     paths = np.asarray(paths, dtype=np.int64).reshape(-1, 3)
     per_l3 = np.bincount(paths[:, 2], minlength=wl.L_max + 1)
     scale = 1.0 / np.sqrt(max(wl.mean_degree, 1) * per_l3[paths[:, 2]])

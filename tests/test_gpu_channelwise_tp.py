@@ -279,6 +279,73 @@ def test_full_size_every_atom_and_edge(tp, name):
     run.close()
 
 
+def test_edge_tensors_that_pass_two_to_the_31_elements(tp):
+    """Maximum sizes: 90 000 atoms, ~1.78 M edges, so R and dR hold 2.3e9 elements (9 GB each):
+    element offsets pass 2^31 and byte offsets 2^33 in the kernels.  The graph comes from the
+    workload generator, the tensors are drawn on the device (seeded).  The oracle sees three
+    ranges of receiving atoms - the first, the ones whose edges straddle element offset 2^31 of R,
+    the last - for A, dY and dR, and three sets of sending atoms with every edge they send for dh."""
+    import torch
+    wl = wl_of("tp_two_to_the_31", 90_000, 20, 128, 3, 1, 3, "f32", 5401)
+    cfg = oracle_cfg(wl)
+    paths = otp.enumerate_paths(cfg)
+    sender, receiver = workloads.make_tp_graph(wl, np.random.default_rng(wl.seed))
+    N, E, P = wl.num_nodes, int(receiver.size), len(paths)
+    row_ptr, send_ptr, send_edge = workloads.graph_indices(sender, receiver, N)
+    say(f"case {wl.name}: N={N} E={E} K={wl.num_channels}")
+    assert E * P * wl.num_channels > (1 << 31)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32)
+    per_l3 = np.bincount(np.asarray(paths)[:, 2], minlength=wl.L_max + 1)
+    scale = torch.tensor(1.0 / np.sqrt(wl.mean_degree * per_l3[np.asarray(paths)[:, 2]]), dtype=torch.float32, device=dev)
+    Y, h = rnd(E, wl.n_Y), rnd(N, wl.num_channels, wl.n_h)
+    R = rnd(E, P, wl.num_channels)
+    R *= scale[None, :, None]
+    dA = rnd(N, wl.num_channels, wl.n_out)
+    i32 = lambda x: torch.tensor(x, dtype=torch.int32, device=dev)
+    d_sender, d_row_ptr, d_send_ptr, d_send_edge = i32(sender), i32(row_ptr), i32(send_ptr), i32(send_edge)
+    A = torch.full((N, wl.num_channels, wl.n_out), float("nan"), dtype=torch.float32, device=dev)
+    dY, dh, dR = (torch.full_like(x, float("nan")) for x in (Y, h, R))
+    plan = tp.tp_plan_create(wl.num_channels, wl.l_Y, wl.l_h, wl.L_max, tp.SC_F32, 0, 0)
+    assert tp.tp_plan_info(plan).specialised == 1
+    nbytes = tp.tp_workspace_bytes(plan, E)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    tp.tp_forward(plan, N, N, E, Y, h, R, d_sender, d_row_ptr, A)
+    tp.tp_backward(plan, N, N, E, Y, h, R, d_sender, d_row_ptr, d_send_ptr, d_send_edge, dA, dY, dh, dR, ws, nbytes)
+    torch.cuda.synchronize()
+    assert all(bool(torch.isfinite(x).all()) for x in (A, dY, dh, dR))
+    no_edges, silent = np.diff(row_ptr) == 0, np.diff(send_ptr) == 0
+    assert not bool(A[i32(np.flatnonzero(no_edges)).long()].any()) and not bool(dh[i32(np.flatnonzero(silent)).long()].any())
+    f64 = lambda x: x.double().cpu().numpy()
+    h_host = f64(h)
+    e_mid = (1 << 31) // (P * wl.num_channels)        # the edge whose rows of R start at element offset 2^31
+    a_mid = int(receiver[e_mid])
+    for name, a0, a1 in (("first atoms", 0, 40), ("atoms around 2^31", a_mid - 20, a_mid + 20), ("last atoms", N - 40, N)):
+        e0, e1 = int(row_ptr[a0]), int(row_ptr[a1])
+        if name == "atoms around 2^31":
+            assert e0 < e_mid < e1
+        es = slice(e0, e1)
+        recv = receiver[es] - a0
+        A_ref = otp.forward(cfg, f64(Y[es]), h_host, f64(R[es]), sender[es], recv, a1 - a0)
+        dY_ref, _, dR_ref = otp.backward(cfg, f64(Y[es]), h_host, f64(R[es]), sender[es], recv, f64(dA[a0:a1]))
+        check(f"A({name})", A[a0:a1].cpu().numpy(), A_ref, "f32")
+        check(f"dY({name})", dY[es].cpu().numpy(), dY_ref, "f32")
+        check(f"dR({name})", dR[es].cpu().numpy(), dR_ref, "f32")
+    # dh of some senders: the oracle on the sub-graph of every edge they send
+    for name, j0, j1 in (("first senders", 0, 30), ("senders around 2^31", a_mid - 15, a_mid + 15), ("last senders", N - 30, N)):
+        edges = send_edge[send_ptr[j0]:send_ptr[j1]].astype(np.int64)
+        recv_atoms, recv = np.unique(receiver[edges], return_inverse=True)
+        sel = torch.tensor(edges, device=dev)
+        _, dh_ref, _ = otp.backward(cfg, f64(Y[sel]), h_host, f64(R[sel]), sender[edges], recv.astype(np.int32),
+                                    f64(dA[torch.tensor(recv_atoms, device=dev).long()]))
+        check(f"dh({name})", dh[j0:j1].cpu().numpy(), dh_ref[j0:j1], "f32")
+    tp.tp_plan_destroy(plan)
+    del Y, h, R, dA, A, dY, dh, dR, ws
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("flags", [0, 2])
 def test_wrong_index_arrays_stay_inside_the_buffers(tp, flags):
     """The index arrays are not validated, but every index is clamped where it is read: a list with

@@ -315,6 +315,77 @@ def test_wide_high_l_prefix_tail_and_consistency(sc):
     prefix_parity(sc, workloads.WORKLOADS["wide_high_l"], 4096, 256)
 
 
+def test_batch_whose_tensors_pass_two_to_the_31_elements(sc):
+    """Maximum sizes: 1.1 M nodes, so A and dA hold 2.25e9 elements (9 GB each): element offsets
+    pass 2^31 and byte offsets 2^33 inside every kernel.  Inputs are drawn on the device (seeded);
+    the oracle sees the nodes at the start, around element offset 2^31 and at the end; a run on
+    the 20 000 nodes around that offset alone must give the same bits per node; dW of the whole
+    batch must be the sum of the dW of eight consecutive pieces (separate runs, added in fp64)."""
+    import torch
+    N, K, Z = 1_100_000, 128, 89
+    wl = wl_of("two_to_the_31", N, Z, K, 3, 3, O01, "f32", 3401)
+    say(f"case {wl.name}: N={N} K={K}")
+    T = oracle_tables(wl)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    A = torch.randn((N, K, wl.n_lm), generator=gen, device=dev, dtype=torch.float32)
+    dB = torch.randn((N, K, wl.n_LM), generator=gen, device=dev, dtype=torch.float32)
+    z_host = np.random.default_rng(wl.seed).choice(Z, size=N, p=workloads.element_probabilities(Z, "skewed")).astype(np.int32)
+    z = torch.tensor(z_host, device=dev)
+    W_host = workloads.make_inputs(wl, T.paths, num_nodes=8).W
+    W = torch.tensor(W_host, dtype=torch.float32, device=dev)
+    B = torch.full((N, K, wl.n_LM), float("nan"), dtype=torch.float32, device=dev)
+    dA = torch.full_like(A, float("nan"))
+    dW = torch.full_like(W, float("nan"))
+    plan = sc.sc_plan_create(K, 3, 3, Z, O01, sc.SC_F32, 0, 0)
+    assert sc.sc_plan_info(plan).specialised == 1
+    nbytes = sc.sc_workspace_bytes(plan, N)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    def run(lo, hi, B_out, dA_out, dW_out):
+        n = hi - lo
+        sc.sc_forward(plan, n, A[lo:hi], z[lo:hi], W, B_out, ws, nbytes, 0)
+        sc.sc_backward(plan, n, A[lo:hi], z[lo:hi], W, dB[lo:hi], dA_out, dW_out, ws, nbytes,
+                       sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS)
+        torch.cuda.synchronize()
+
+    run(0, N, B, dA, dW)
+    assert bool(torch.isfinite(B).all()) and bool(torch.isfinite(dA).all()) and bool(torch.isfinite(dW).all())
+    mid = (1 << 31) // (K * wl.n_lm)          # the node whose row of A starts at element offset 2^31
+    assert 0 < mid - 10_000 and mid + 10_000 < N
+    Wd = W.double().cpu().numpy()
+    for name, lo, hi in (("start", 0, 48), ("around 2^31", mid - 24, mid + 24), ("end", N - 48, N)):
+        a, g, zz = A[lo:hi].double().cpu().numpy(), dB[lo:hi].double().cpu().numpy(), z_host[lo:hi]
+        check(f"B({name})", B[lo:hi].cpu().numpy(), osc.forward(T, a, zz, Wd), "f32")
+        dA_ref, _ = osc.backward(T, a, zz, Wd, g)
+        check(f"dA({name})", dA[lo:hi].cpu().numpy(), dA_ref, "f32")
+    # the same nodes as a batch of their own: same bits per node
+    lo, hi = mid - 10_000, mid + 10_000
+    Bs = torch.empty((hi - lo, K, wl.n_LM), dtype=torch.float32, device=dev)
+    dAs = torch.empty((hi - lo, K, wl.n_lm), dtype=torch.float32, device=dev)
+    dWs = torch.empty_like(W)
+    run(lo, hi, Bs, dAs, dWs)
+    assert torch.equal(Bs, B[lo:hi]) and torch.equal(dAs, dA[lo:hi])
+    # dW: eight consecutive pieces
+    total = torch.zeros(W.shape, dtype=torch.float64, device=dev)
+    bounds = [N * q // 8 for q in range(9)]
+    for q in range(8):
+        lo, hi = bounds[q], bounds[q + 1]
+        Bq = torch.empty((hi - lo, K, wl.n_LM), dtype=torch.float32, device=dev)
+        dAq = torch.empty((hi - lo, K, wl.n_lm), dtype=torch.float32, device=dev)
+        run(lo, hi, Bq, dAq, dWs)
+        assert torch.equal(Bq, B[lo:hi]) and torch.equal(dAq, dA[lo:hi])
+        total += dWs.double()
+        del Bq, dAq
+    err = rel_err_f32(dW.cpu().numpy(), total.cpu().numpy())
+    say(f"  dW(whole) against the sum of eight pieces: {err:.3e}")
+    assert err <= 1e-5
+    sc.sc_plan_destroy(plan)
+    del A, dA, B, dB, ws
+    torch.cuda.empty_cache()
+
+
 def test_three_launch_grouping_and_many_elements(sc):
     # more than 16384 nodes: the grouping runs as three launches
     full_parity(sc, wl_of("n20000", 20_000, 89, 128, 3, 3, O01, "f32", 2601))
