@@ -207,7 +207,8 @@ def measure_attainable(n_nodes=10_000, chblocks=2, reps=20):
         return ev[0].elapsed_time(ev[1]) / reps * 1e-3
 
     out = {"unit": "GB/s", "note": "library streaming probes, same run; rows = the backward kernel's access "
-                                   "pattern (9216 B per row of 64 channels) without arithmetic"}
+                                   "pattern (9216 B per row of 64 channels) without arithmetic; forward_rows = the "
+                                   "forward kernel's (5120 B per row, batch order)"}
     nbytes = 1 << 30
     bufs = [torch.empty(nbytes // 4, dtype=torch.float32, device=dev).normal_() for _ in range(3)]
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
@@ -230,10 +231,16 @@ def measure_attainable(n_nodes=10_000, chblocks=2, reps=20):
         t = timed(lambda i: sc.sc_probe_stream(sc.SC_PROBE_ROWS, sets[i][0], sets[i][1], sets[i][2], perm, rows), n_sets)
         out[label] = rows * 9216 / t / 1e9
         out[label + "_us"] = t * 1e6
+        # the forward's traffic (4 KB in, 1 KB out per row) in the order of the batch
+        ident = torch.arange(rows, dtype=torch.int32, device=dev)
+        t = timed(lambda i: sc.sc_probe_stream(sc.SC_PROBE_ROWS_FORWARD, sets[i][0], None, sets[i][1], ident, rows), n_sets)
+        out["forward_" + label] = rows * 5120 / t / 1e9
+        out["forward_" + label + "_us"] = t * 1e6
         del sets
         torch.cuda.empty_cache()
     out["frac_of_peak"] = {k: out[k] / HBM_PEAK_GBS for k in ("read", "write", "copy", "rows_at_batch_size",
-                                                              "rows_at_20x_batch_size")}
+                                                              "rows_at_20x_batch_size", "forward_rows_at_batch_size",
+                                                              "forward_rows_at_20x_batch_size")}
     return out
 
 

@@ -240,11 +240,14 @@ sc_status sc_profile_read_double_backward(sc_plan* plan, float* ms);
  *                   in the order perm[0..n) (int32, values in [0, n); clamped), reads 4096 bytes
  *                   of src (64 B per lane) and 1024 bytes of src2 (16 B per lane) and writes
  *                   4096 bytes of dst; moves n * 9216 bytes
- * n bytes must be a multiple of 16.  src2 and perm are used by SC_PROBE_ROWS only. */
+ *   SC_PROBE_ROWS_FORWARD  the same walk with the forward kernel's traffic: per row 4096 bytes of
+ *                   src in and 1024 bytes of dst out (src2 unused); moves n * 5120 bytes
+ * n bytes must be a multiple of 16.  src2 and perm are used by the row patterns only. */
 #define SC_PROBE_READ 0
 #define SC_PROBE_WRITE 1
 #define SC_PROBE_COPY 2
 #define SC_PROBE_ROWS 3
+#define SC_PROBE_ROWS_FORWARD 4
 sc_status sc_probe_stream(int32_t kind, const void* src, const void* src2, void* dst, const int32_t* perm,
                           int64_t n, void* hip_stream);
 

@@ -208,7 +208,7 @@ def sc_double_backward(plan: Plan, n_nodes: int, A, z, W, dB, H, ddB, dA2, dW2, 
                                   _ptr(dA2), _ptr(dW2), _ptr(workspace), workspace_bytes, flags, _stream(stream)))
 
 
-SC_PROBE_READ, SC_PROBE_WRITE, SC_PROBE_COPY, SC_PROBE_ROWS = 0, 1, 2, 3
+SC_PROBE_READ, SC_PROBE_WRITE, SC_PROBE_COPY, SC_PROBE_ROWS, SC_PROBE_ROWS_FORWARD = 0, 1, 2, 3, 4
 
 
 def sc_probe_stream(kind: int, src, src2, dst, perm, n: int, stream=None) -> None:

@@ -9,6 +9,7 @@
 //                         (the A row of a node and 64 channels, 4 KB) and 16 B per lane of a
 //                         second one (its dB row, 1 KB) in, 4 KB out in whole 1 KB pieces,
 //                         the next row requested before the current one is written
+//   forward rows          the same walk with the forward kernel's traffic: 4 KB in, 1 KB out per row
 #include "sc_internal.h"
 
 namespace sc {
@@ -72,6 +73,8 @@ __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const f4* __r
 
 // rows: a[n_rows][64 lanes][4 x f4], b[n_rows][64 lanes][f4] in, out[n_rows][4][64 lanes][f4].
 // Every wave takes rows wave_id, wave_id + n_waves, ... of perm (clamped into range).
+// kForward: only a is read, and out is [n_rows][64 lanes][f4].
+template <bool kForward>
 __global__ __launch_bounds__(kProbeThreads) void probe_rows_kernel(const f4* __restrict__ a, const f4* __restrict__ b,
                                                                     f4* __restrict__ out,
                                                                     const int32_t* __restrict__ perm, int n_rows) {
@@ -83,11 +86,11 @@ __global__ __launch_bounds__(kProbeThreads) void probe_rows_kernel(const f4* __r
     return static_cast<size_t>(r < 0 ? 0 : (r >= n_rows ? n_rows - 1 : r));
   };
   if (wave >= n_rows) return;
-  f4 va[4], vb, na[4], nb;
+  f4 va[4], vb = {0.f, 0.f, 0.f, 0.f}, na[4], nb = vb;
   size_t row = row_of(wave);
 #pragma unroll
   for (int k = 0; k < 4; ++k) va[k] = a[(row * kLanes + lane) * 4 + k];
-  vb = b[row * kLanes + lane];
+  if constexpr (!kForward) vb = b[row * kLanes + lane];
   for (int j = wave; j < n_rows; j += n_waves) {
     const bool more = j + n_waves < n_rows;
     size_t next = row;
@@ -95,10 +98,14 @@ __global__ __launch_bounds__(kProbeThreads) void probe_rows_kernel(const f4* __r
       next = row_of(j + n_waves);
 #pragma unroll
       for (int k = 0; k < 4; ++k) na[k] = a[(next * kLanes + lane) * 4 + k];
-      nb = b[next * kLanes + lane];
+      if constexpr (!kForward) nb = b[next * kLanes + lane];
     }
+    if constexpr (kForward) {
+      __builtin_nontemporal_store(va[0] + va[1] + va[2] + va[3], out + row * kLanes + lane);
+    } else {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) out[(row * 4 + k) * kLanes + lane] = va[k] + vb;
+      for (int k = 0; k < 4; ++k) out[(row * 4 + k) * kLanes + lane] = va[k] + vb;
+    }
     if (more) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) va[k] = na[k];
@@ -139,13 +146,20 @@ extern "C" sc_status sc_probe_stream(int32_t kind, const void* src, const void* 
       hipLaunchKernelGGL(probe_copy_kernel, dim3(grid), dim3(kProbeThreads), 0, stream, static_cast<const f4*>(src),
                          static_cast<f4*>(dst), static_cast<size_t>(n / 16));
       break;
-    case SC_PROBE_ROWS: {
-      if (bad(src) || bad(src2) || bad(dst) || !perm || n > (int64_t(1) << 30))
-        return set_error(SC_ERR_INVALID_ARG, "sc_probe_stream: rows needs src, src2, dst, perm, n <= 2^30 rows");
-      const int64_t wgs = (n + 3) / 4, most = cus * 8;   // at most eight workgroups per compute unit, each walking rows
-      hipLaunchKernelGGL(probe_rows_kernel, dim3(static_cast<unsigned>(wgs < most ? wgs : most)), dim3(kProbeThreads), 0,
-                         stream, static_cast<const f4*>(src), static_cast<const f4*>(src2), static_cast<f4*>(dst), perm,
-                         static_cast<int>(n));
+    case SC_PROBE_ROWS:
+    case SC_PROBE_ROWS_FORWARD: {
+      const bool fwd = kind == SC_PROBE_ROWS_FORWARD;
+      if (bad(src) || (!fwd && bad(src2)) || bad(dst) || !perm || n > (int64_t(1) << 30))
+        return set_error(SC_ERR_INVALID_ARG, "sc_probe_stream: rows needs src, src2 (backward pattern), dst, perm, n <= 2^30 rows");
+      // eight workgroups per compute unit at most (sixteen for the lighter forward pattern), each walking rows
+      const int64_t wgs = (n + 3) / 4, most = cus * (fwd ? 16 : 8);
+      const dim3 grid_rows(static_cast<unsigned>(wgs < most ? wgs : most));
+      if (fwd)
+        hipLaunchKernelGGL(probe_rows_kernel<true>, grid_rows, dim3(kProbeThreads), 0, stream, static_cast<const f4*>(src),
+                           static_cast<const f4*>(src2), static_cast<f4*>(dst), perm, static_cast<int>(n));
+      else
+        hipLaunchKernelGGL(probe_rows_kernel<false>, grid_rows, dim3(kProbeThreads), 0, stream, static_cast<const f4*>(src),
+                           static_cast<const f4*>(src2), static_cast<f4*>(dst), perm, static_cast<int>(n));
       break;
     }
     default:
