@@ -79,7 +79,7 @@ def describe(wl):
             + (", forward+backward" if wl.backward else ", forward only"))
 
 
-def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=False):
+def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=False, z_grouped=False):
     import numpy as np
     import torch
     from paper_2504_10700_amd import binding as sc
@@ -104,7 +104,10 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=Fals
     W = torch.tensor(inp.W, dtype=wdt, device=dev)
     z = torch.tensor(inp.z, dtype=torch.int32, device=dev)
     del inp
-    layout = sc.SC_COMPONENT_MAJOR if component_major else 0
+    call_flags = sc.SC_COMPONENT_MAJOR if component_major else 0
+    if z_grouped:   # a batch whose nodes the caller has ordered by element (A, dB are iid: only z changes)
+        z = torch.sort(z).values.contiguous()
+        call_flags |= sc.SC_Z_GROUPED
     if component_major:   # the same rows as [node][component][channel]
         A0, dB0 = A0.transpose(1, 2).contiguous(), dB0.transpose(1, 2).contiguous()
     sets = []
@@ -121,11 +124,11 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=Fals
 
     def step(i):
         f = sets[i % n_sets]
-        sc.sc_forward(plan, N, f["A"], z, W, f["B"], ws, ws_bytes, layout)
+        sc.sc_forward(plan, N, f["A"], z, W, f["B"], ws, ws_bytes, call_flags)
         if wl.backward:
             b = sets[(i + n_sets // 2) % n_sets]   # another copy of A: no cache reuse across fwd -> bwd
             sc.sc_backward(plan, N, b["A"], z, W, b["dB"], b["dA"], dW, ws, ws_bytes,
-                           sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS | layout)
+                           sc.SC_REUSE_GROUPING | sc.SC_REUSE_WEIGHTS | call_flags)
 
     for i in range(warmup):
         step(i)
@@ -161,7 +164,7 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=Fals
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath) and wl.backward and info.specialised and tile_nodes == 0 and not component_major:
+    if os.path.exists(tpath) and wl.backward and info.specialised and tile_nodes == 0 and not component_major and not z_grouped:
         ent = json.load(open(tpath)).get(wl.name)
         if ent:
             traffic = 1024.0 * (ent["fetch_kib"] * ent["fetch_scale"] + ent["write_kib"] * ent["write_scale"])
@@ -173,7 +176,8 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=Fals
         "config": {"workload": describe(wl), "num_paths": int(info.num_paths),
                    "kernel": "generated" if info.specialised else "table-driven",
                    "buffer_sets_rotated": n_sets, "tile_nodes": tile_nodes,
-                   "layout": "[node][component][channel]" if component_major else "[node][channel][component]"},
+                   "layout": "[node][component][channel]" if component_major else "[node][channel][component]",
+                   "z_order": "grouped by element (SC_Z_GROUPED)" if z_grouped else "as drawn"},
         "step_hbm_fraction": value * (step_bytes / N) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel_ms": k_ms,
@@ -706,6 +710,8 @@ def main():
     ap.add_argument("--tile-nodes", type=int, default=0, help="tuning: nodes per tile (0 = library default)")
     ap.add_argument("--component-major", action="store_true",
                     help="per-node tensors laid out [node][component][channel] (SC_COMPONENT_MAJOR)")
+    ap.add_argument("--z-grouped", action="store_true",
+                    help="the batch arrives ordered by element and the calls say so (SC_Z_GROUPED)")
     ap.add_argument("--no-also", action="store_true", help="skip the extra measurements under \"also\"")
     ap.add_argument("--no-probe", action="store_true", help="skip the streaming probes (\"attainable\")")
     ap.add_argument("--linear", action="store_true",
@@ -754,7 +760,7 @@ def main():
     if args.double_backward:
         print(json.dumps(measure_double_backward(wl, args.steps, args.warmup, args.tile_nodes)))
         return
-    m = measure(wl, args.steps, args.warmup, args.generic, args.tile_nodes, args.component_major)
+    m = measure(wl, args.steps, args.warmup, args.generic, args.tile_nodes, args.component_major, args.z_grouped)
     out = {"metric": METRIC, "value": m["value"], "unit": m["unit"], "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": m["dtype"], "data": "synthetic", "config": m["config"],
@@ -764,7 +770,7 @@ def main():
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(wl, min(args.cpu_sample, wl.num_nodes))
     if (args.workload == "training_step" and not args.no_also and not args.generic and args.tile_nodes == 0
-            and not args.component_major):
+            and not args.component_major and not args.z_grouped):
         keys = ("value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config", "step_hbm_fraction", "roofline")
         big = measure(workloads.WORKLOADS["large_batch"], 30, 5)
         out["also"] = {"large_batch": {k: big[k] for k in keys}}
@@ -777,6 +783,10 @@ def main():
             out["also"][name] = {k: m2[k] for k in keys}
         m2 = measure(wl, 100, 10, component_major=True)     # the other layout of the per-node tensors
         out["also"]["training_step_component_major"] = {k: m2[k] for k in keys}
+        m2 = measure(wl, 100, 10, z_grouped=True)           # nodes ordered by element by the caller
+        out["also"]["training_step_z_grouped"] = {k: m2[k] for k in keys}
+        m2 = measure(workloads.WORKLOADS["large_batch"], 30, 5, z_grouped=True)
+        out["also"]["large_batch_z_grouped"] = {k: m2[k] for k in keys}
         out["also"]["double_backward_training_step"] = measure_double_backward(wl, 100, 10)
         out["also"]["double_backward_large_batch"] = measure_double_backward(workloads.WORKLOADS["large_batch"], 20, 3)
         out["also"]["channelwise_tp_training_step"] = measure_tp(workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
