@@ -76,6 +76,11 @@ typedef enum { SC_F32 = 0, SC_F64 = 1, SC_BF16 = 2 } sc_dtype;
 /* sc_config.flags */
 #define SC_PLAN_HOST_ONLY 1u     /* build tables only; no device is touched, compute calls fail   */
 #define SC_PLAN_FORCE_GENERIC 2u /* use the table-driven kernels even if a specialised one exists */
+#define SC_PLAN_WINDOW_ORDER 4u  /* tuning: let sc_forward order its visits by element inside windows of
+                                    the batch for every batch size (default: from SC_WINDOW_ORDER_MIN_NODES
+                                    nodes on, below which the ordering costs more than it saves).  Results
+                                    do not depend on it.                                              */
+#define SC_WINDOW_ORDER_MIN_NODES 8192
 
 /* flags of sc_forward / sc_backward / sc_double_backward */
 #define SC_REUSE_GROUPING 1u /* the workspace still holds the grouping written by the previous

@@ -24,7 +24,7 @@ SC_OK = 0
 SC_ERR_INVALID_ARG, SC_ERR_UNSUPPORTED, SC_ERR_WORKSPACE, SC_ERR_HIP, SC_ERR_ALLOC = 1, 2, 3, 4, 5
 SC_F32, SC_F64, SC_BF16 = 0, 1, 2
 SC_MAX_OUT = 4
-SC_PLAN_HOST_ONLY, SC_PLAN_FORCE_GENERIC = 1, 2
+SC_PLAN_HOST_ONLY, SC_PLAN_FORCE_GENERIC, SC_PLAN_WINDOW_ORDER = 1, 2, 4
 SC_REUSE_GROUPING, SC_REUSE_WEIGHTS, SC_Z_GROUPED, SC_COMPONENT_MAJOR = 1, 2, 4, 8
 SC_NOALLOC_MAX_NODES, SC_NOALLOC_SCRATCH_BYTES = 65536, 8 << 20
 

@@ -132,6 +132,10 @@ Workspace carve_workspace(const sc_plan* plan, int64_t n, const LaunchShape& sha
   w.perm = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
   w.tiles = static_cast<TileDesc*>(take(sizeof(TileDesc) * static_cast<size_t>(shape.max_tiles)));
   if (plan->specialised) w.wfold = take(spec_folded_bytes(plan));
+  if (plan->specialised && !forward_only) {   // forward-only workspaces never run the grouping that writes these
+    w.wnode = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
+    w.wkey = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
+  }
   if (!forward_only)  // the weight-gradient rows of the backward passes
     w.partial = take(elem_size(plan) * static_cast<size_t>(shape.max_tiles) * shape.chblocks * plan->S * kLanes);
   w.max_tiles = shape.max_tiles;
@@ -403,7 +407,7 @@ static hipError_t grouped_pass_prologue(const char* fn, sc_plan* plan, int64_t n
   hipError_t e = hipSuccess;
   if (plan->specialised) {
     e = sc::launch_spec_prepare(plan, n_nodes, z, W, ws, shape, group, uses_folded_table && !(flags & SC_REUSE_WEIGHTS),
-                                stream);
+                                false, stream);
     if (e == hipSuccess && group) e = sc::launch_spec_scatter(plan, n_nodes, z, ws, shape, (flags & SC_Z_GROUPED) != 0, stream);
   } else if (group) {
     e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
@@ -435,9 +439,13 @@ static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes
   if (layout != SC_OK) return layout;
   hipError_t e = hipSuccess;
   const bool group = !(flags & SC_REUSE_GROUPING);
+  // the prepare launch also orders windows of the batch by element for the forward kernel (not for a
+  // batch that is ordered already, nor for small ones, where that costs more than it saves)
+  const bool window_order = plan->specialised && !(flags & SC_Z_GROUPED) && ws.wnode != nullptr &&
+                            (n_nodes >= SC_WINDOW_ORDER_MIN_NODES || (plan->cfg.flags & SC_PLAN_WINDOW_ORDER));
   if (plan->specialised) {
     // the forward itself needs no grouping: the two halves of it ride in the prepare and the forward launch
-    e = sc::launch_spec_prepare(plan, n_nodes, z, W, ws, shape, group, !(flags & SC_REUSE_WEIGHTS), stream);
+    e = sc::launch_spec_prepare(plan, n_nodes, z, W, ws, shape, group, !(flags & SC_REUSE_WEIGHTS), window_order, stream);
     if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": prepare launch").c_str());
   } else if (group) {
     e = sc::launch_grouping(plan, n_nodes, z, ws, shape, stream);
@@ -445,7 +453,7 @@ static sc_status forward_launches(const char* fn, sc_plan* plan, int64_t n_nodes
   }
   if (plan->profile) (void)hipEventRecord(plan->ev[0], stream);
   e = plan->specialised ? sc::launch_spec_forward(plan, n_nodes, A, z, B, ws, shape,
-                                                  !group ? 0 : (flags & SC_Z_GROUPED) ? 2 : 1,
+                                                  !group ? 0 : (flags & SC_Z_GROUPED) ? 2 : 1, window_order,
                                                   (flags & SC_COMPONENT_MAJOR) != 0, stream)
                         : sc::launch_generic_forward(plan, n_nodes, A, W, B, ws, shape, stream);
   if (e != hipSuccess) return fail_hip(e, (std::string(fn) + ": kernel launch").c_str());

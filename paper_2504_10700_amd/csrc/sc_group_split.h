@@ -6,6 +6,10 @@
 //   count role    (hosted by the launch that prepares the folded weights) every wave counts the
 //                 elements of its contiguous slice of z and writes one row of the count
 //                 matrix counts[wave][element];
+//   window role   (same launch, only for a forward pass) one workgroup per window of 1024 nodes
+//                 orders the window's nodes by element: the order in which the forward kernel,
+//                 which needs no grouping for its results, visits them so that it meets long
+//                 runs of one element;
 //   scatter role  (hosted by the forward launch, whose own work does not need the grouping)
 //                 every workgroup sums the matrix columns on its own - the totals per element
 //                 and the counts of all earlier waves - scans the totals over the elements and
@@ -33,9 +37,14 @@ struct SplitGroupArgs {
   int32_t* ntiles;     // [1]
   TileDesc* tiles;     // [max_tiles]
   int32_t* perm;       // [n]
+  // window order for the forward kernel (both null: not wanted): position j holds a node and its
+  // element index (Z for an index outside [0, Z)); every window of kWindowNodes positions holds
+  // the nodes of the same range of the batch, stably ordered by element, invalid ones last
+  int32_t* wnode;      // [n]
+  int32_t* wkey;       // [n]
 };
 
-// dynamic LDS (bytes) a hosting kernel must provide for the roles
+// dynamic LDS (bytes) a hosting kernel must provide for the count, scatter and table roles
 inline size_t split_group_lds_bytes(int Z) { return sizeof(int32_t) * (static_cast<size_t>(kGroupWavesPerWG + 1) * Z + 4); }
 
 // Stable scatter of one 64-node chunk: lane holds element e (valid or not); cursor[e] is this
@@ -58,6 +67,37 @@ __device__ __forceinline__ void split_scatter_chunk(int e, bool valid, int node,
   if (valid && lane == leader) base = atomicAdd(&cursor[e], group);
   base = __shfl(base, leader);
   if (valid) perm[base + rank] = node;
+}
+
+// The same ranking for the window order: returns the position of the lane's node (valid lanes: the
+// next free position of its element in cursor; lanes with an index outside [0, Z): the next free
+// position in *cursor_invalid; lanes past the end: -1).
+__device__ __forceinline__ int split_place_chunk(int e, bool in_range, bool valid, int lane, int z_bits, int32_t* cursor,
+                                                 int32_t* cursor_invalid) {
+  const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  unsigned long long same = __ballot(valid);
+  for (int b = 0; b < z_bits; ++b) {
+    const bool bit = (e >> b) & 1;
+    const unsigned long long m = __ballot(bit);
+    same &= bit ? m : ~m;
+  }
+  const int rank = __popcll(same & lt_mask);
+  const int group = __popcll(same);
+  const int leader = valid ? __ffsll(static_cast<long long>(same)) - 1 : lane;
+  int base = 0;
+  if (valid && lane == leader) base = atomicAdd(&cursor[e], group);
+  base = __shfl(base, leader);
+  // nodes whose index is outside the range
+  const unsigned long long bad = __ballot(in_range && !valid);
+  int bad_base = 0;
+  if (bad != 0ull) {   // wave-uniform
+    const int first = __ffsll(static_cast<long long>(bad)) - 1;
+    if (lane == first) bad_base = atomicAdd(cursor_invalid, __popcll(bad));
+    bad_base = __shfl(bad_base, first);
+  }
+  if (valid) return base + rank;
+  if (in_range) return bad_base + __popcll(bad & lt_mask);
+  return -1;
 }
 
 // Exclusive scan of v[0..n) (LDS, n <= 1024) in place by ONE wave; returns the total.
@@ -110,6 +150,79 @@ __device__ __forceinline__ void split_count_role(const SplitGroupArgs& g, int wg
   }
   __syncthreads();
   for (int e = lane; e < g.Z; e += kLanes) g.counts[static_cast<size_t>(gw) * g.Z + e] = mine[e];
+}
+
+// Window order for the forward kernel: workgroup `win` orders the nodes [win * kWindowNodes, ...) of
+// the batch by element (stable; nodes with an index outside [0, Z) last) and writes, for every
+// position of the window, the node and its element index.  A counting sort inside the workgroup:
+// every wave counts its 256 nodes (kept in registers), the counts are summed over the waves and
+// scanned over the elements, every wave places its nodes.  lds: split_window_lds_bytes(Z).
+constexpr int kWindowChunks = 4;                                              // 64-node chunks per wave
+constexpr int kWindowNodes = kGroupWavesPerWG * kWindowChunks * kLanes;       // 1024
+inline size_t split_window_lds_bytes(int Z) { return sizeof(int32_t) * (static_cast<size_t>(2 * kGroupWavesPerWG + 1) * Z + 2 * kGroupWavesPerWG); }
+
+__device__ __forceinline__ void split_window_role(const SplitGroupArgs& g, int win, int32_t* lds) {
+  const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+  int32_t* mine = lds + wave * g.Z;                                   // [4][Z] counts per wave
+  int32_t* invalid = lds + kGroupWavesPerWG * g.Z;                    // [4] nodes with an index outside [0, Z), per wave
+  int32_t* cursor_invalid = invalid + kGroupWavesPerWG;               // [4]
+  int32_t* seg = cursor_invalid + kGroupWavesPerWG;                   // [Z] totals of the window, then their scan
+  int32_t* cursor = seg + g.Z;                                        // [4][Z]
+  const long long base = static_cast<long long>(win) * kWindowNodes;
+  const long long lo = base + static_cast<long long>(wave) * kWindowChunks * kLanes;
+  const long long hi = (lo + kWindowChunks * kLanes < g.n) ? lo + kWindowChunks * kLanes : g.n;
+  int zs[kWindowChunks];
+#pragma unroll
+  for (int c = 0; c < kWindowChunks; ++c) {
+    const long long i = lo + c * kLanes + lane;
+    zs[c] = (i < hi) ? g.z[i] : -1;
+  }
+  for (int e = lane; e < g.Z; e += kLanes) mine[e] = 0;
+  if (threadIdx.x < kGroupWavesPerWG) invalid[threadIdx.x] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int c = 0; c < kWindowChunks; ++c) {
+    if (zs[c] >= 0 && zs[c] < g.Z) atomicAdd(&mine[zs[c]], 1);
+    else if (lo + c * kLanes + lane < hi) atomicAdd(&invalid[wave], 1);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < g.Z; e += kSplitThreads) {
+    int run = 0;
+#pragma unroll
+    for (int v = 0; v < kGroupWavesPerWG; ++v) {
+      cursor[v * g.Z + e] = run;      // nodes of e in the earlier waves
+      run += lds[v * g.Z + e];
+    }
+    seg[e] = run;
+  }
+  __syncthreads();
+  int n_valid = 0;
+  if (wave == 0) n_valid = split_wave_scan(seg, g.Z, lane);
+  if (threadIdx.x == 0) {
+    int run = n_valid;                 // the invalid nodes follow the valid ones
+#pragma unroll
+    for (int v = 0; v < kGroupWavesPerWG; ++v) {
+      cursor_invalid[v] = run;
+      run += invalid[v];
+    }
+  }
+  __syncthreads();
+  int32_t* my_cursor = cursor + wave * g.Z;
+  for (int e = lane; e < g.Z; e += kLanes) my_cursor[e] += seg[e];
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const int z_bits = 32 - __builtin_clz(g.Z);
+#pragma unroll
+  for (int c = 0; c < kWindowChunks; ++c) {
+    if (lo + c * kLanes >= hi) break;  // wave-uniform
+    const long long i = lo + c * kLanes + lane;
+    const bool in_range = i < hi, valid = in_range && zs[c] >= 0 && zs[c] < g.Z;
+    const int pos = split_place_chunk(zs[c], in_range, valid, lane, z_bits, my_cursor, &cursor_invalid[wave]);
+    if (pos >= 0) {
+      g.wnode[base + pos] = static_cast<int32_t>(i);
+      g.wkey[base + pos] = valid ? zs[c] : g.Z;
+    }
+  }
 }
 
 // Column sums of the count matrix for element e: the total and, for the four waves w0..w0+3,

@@ -242,19 +242,24 @@ __device__ __forceinline__ void load_folded(const T* __restrict__ wf, int z, int
   for (int s = 0; s < G::kS; ++s) w[s] = src[s * kLanes];
 }
 
-// Launch 1.  Workgroups [0, count_wgs): count role of the grouping.  The others: one wave per
-// (element, 64 channels) folds W[element, :, channel] into wf.
+// Launch 1.  Workgroups [0, window_wgs): window role (order of the forward pass); the next
+// count_wgs: count role of the grouping.  The others: one wave per (element, 64 channels) folds
+// W[element, :, channel] into wf.
 template <typename T, typename G>
-__global__ __launch_bounds__(kSpecThreads) void spec_prepare_kernel(SplitGroupArgs ga, int count_wgs, int K,
+__global__ __launch_bounds__(kSpecThreads) void spec_prepare_kernel(SplitGroupArgs ga, int count_wgs, int window_wgs, int K,
                                                                     int chblocks, int n_pairs,
                                                                     const T* __restrict__ W, T* __restrict__ wf) {
   extern __shared__ unsigned char lds_raw[];
-  if (static_cast<int>(blockIdx.x) < count_wgs) {
-    split_count_role(ga, blockIdx.x, reinterpret_cast<int32_t*>(lds_raw));
+  if (static_cast<int>(blockIdx.x) < window_wgs) {   // the longest role first
+    split_window_role(ga, blockIdx.x, reinterpret_cast<int32_t*>(lds_raw));
+    return;
+  }
+  if (static_cast<int>(blockIdx.x) < window_wgs + count_wgs) {
+    split_count_role(ga, blockIdx.x - window_wgs, reinterpret_cast<int32_t*>(lds_raw));
     return;
   }
   const int lane = threadIdx.x & (kLanes - 1);
-  const int pair = (static_cast<int>(blockIdx.x) - count_wgs) * kSpecWaves + wave_of_thread();
+  const int pair = (static_cast<int>(blockIdx.x) - window_wgs - count_wgs) * kSpecWaves + wave_of_thread();
   if (pair >= n_pairs) return;
   const int z = pair / chblocks, cb = pair % chblocks;
   const int live = K - cb * kLanes < kLanes ? K - cb * kLanes : kLanes;
@@ -317,10 +322,23 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   // Nodes with an element index outside [0, Z) sort last and are skipped.  (A third row buffer, i.e.
   // the rows of node p+2 requested while node p is evaluated, measured the same at 10k nodes and 3%
   // slower at 200k.)
+  // With the window order of the prepare launch (ga.wnode) the wave's positions hold nodes of a
+  // 1024-node window that are ordered by element already, so the runs are long: 0.2 instead of 0.8
+  // reads of the weights per node with 89 elements of skewed frequency, which is what the forward
+  // gains from a batch ordered by element (427 -> 385 us at 200k nodes; the weights are L2 hits, but
+  // 2.4 GB of them per launch next to 1.6 GB of A).  The sort inside the wave stays: it moves nodes
+  // with an invalid index to the end and joins runs across a window boundary.
   const int cnt = j1 - j0;
-  int key = Z;
+  int key = Z, mine = j0 + lane;   // the lane's node and its element index
   if (lane < cnt) {
-    const int e = z[j0 + lane];
+    int e;
+    if (ga.wnode) {   // positions follow the window order written by the count role (uniform)
+      mine = ga.wnode[j0 + lane];
+      mine = mine < 0 ? 0 : (mine >= n ? n - 1 : mine);
+      e = ga.wkey[j0 + lane];
+    } else {
+      e = z[j0 + lane];
+    }
     key = (e >= 0 && e < Z) ? e : Z;
   }
   int rank = lane;   // lanes past the last node keep their own slot
@@ -333,7 +351,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   auto visit = [&](int p, int& node, int& e) {
     const int idx = __builtin_amdgcn_readlane(order, p);
     e = __builtin_amdgcn_readlane(key, idx);
-    node = j0 + idx;
+    node = __builtin_amdgcn_readlane(mine, idx);
   };
   // Rows: two register sets in turn (the next node's row is requested before the current node is
   // evaluated).  Weights: ONE register set, reloaded from the folded table (L2) right before a node of
@@ -733,7 +751,7 @@ bool matches(const sc_plan* plan) {
 }
 
 SplitGroupArgs group_args(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
-                          const LaunchShape& shape) {
+                          const LaunchShape& shape, bool window_order = false) {
   SplitGroupArgs g{};
   g.z = z;
   g.n = static_cast<int>(n);
@@ -748,6 +766,8 @@ SplitGroupArgs group_args(const sc_plan* plan, int64_t n, const int32_t* z, cons
   g.ntiles = ws.ntiles;
   g.tiles = ws.tiles;
   g.perm = ws.perm;
+  g.wnode = window_order ? ws.wnode : nullptr;
+  g.wkey = window_order ? ws.wkey : nullptr;
   return g;
 }
 
@@ -760,14 +780,17 @@ hipError_t raise_lds_limit(K kernel, size_t lds) {
 
 template <typename T, typename G>
 hipError_t prepare_launch(const sc_plan* plan, int64_t n, const int32_t* z, const void* W, const Workspace& ws,
-                          const LaunchShape& shape, bool count, bool fold, hipStream_t stream) {
+                          const LaunchShape& shape, bool count, bool fold, bool window_order, hipStream_t stream) {
   const int count_wgs = count ? shape.split_waves / kGroupWavesPerWG : 0;
+  const bool window = window_order && ws.wnode && ws.wkey;
+  const int window_wgs = window ? static_cast<int>((n + kWindowNodes - 1) / kWindowNodes) : 0;
   const int n_pairs = fold ? plan->cfg.num_elements * shape.chblocks : 0;
-  const int grid = count_wgs + (n_pairs + kSpecWaves - 1) / kSpecWaves;
+  const int grid = window_wgs + count_wgs + (n_pairs + kSpecWaves - 1) / kSpecWaves;
   if (grid == 0) return hipSuccess;
-  const size_t lds = count ? split_group_lds_bytes(plan->cfg.num_elements) : 0;
+  const size_t lds = window ? split_window_lds_bytes(plan->cfg.num_elements)
+                            : count ? split_group_lds_bytes(plan->cfg.num_elements) : 0;
   hipLaunchKernelGGL((spec_prepare_kernel<T, G>), dim3(grid), dim3(kSpecThreads), lds, stream,
-                     group_args(plan, n, z, ws, shape), count_wgs, plan->cfg.num_channels, shape.chblocks, n_pairs,
+                     group_args(plan, n, z, ws, shape, window), count_wgs, window_wgs, plan->cfg.num_channels, shape.chblocks, n_pairs,
                      static_cast<const T*>(W), static_cast<T*>(ws.wfold));
   return hipGetLastError();
 }
@@ -794,7 +817,7 @@ inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs, int
 
 template <typename T, typename G, typename TS, bool kCM = false>
 hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B, const Workspace& ws,
-                      const LaunchShape& shape, int group, hipStream_t stream) {
+                      const LaunchShape& shape, int group, bool window_order, hipStream_t stream) {
   // group: 0 no grouping roles, 1 scatter + table, 2 table only (the batch is already grouped)
   const bool scatter = group == 1;
   const int table = group != 0;
@@ -813,7 +836,7 @@ hipError_t fwd_launch(const sc_plan* plan, int64_t n, const void* A, const int32
   const int tiles = static_cast<int>((n + tile - 1) / tile);
   const int grid = scatter_wgs + table + tiles * shape.chblocks;
   hipLaunchKernelGGL((spec_forward_kernel<T, G, TS, kCM>), dim3(grid), dim3(kSpecThreads), lds, stream,
-                     group_args(plan, n, z, ws, shape), scatter_wgs, table, plan->cfg.num_channels, shape.chblocks,
+                     group_args(plan, n, z, ws, shape, window_order), scatter_wgs, table, plan->cfg.num_channels, shape.chblocks,
                      static_cast<int>(n), plan->cfg.num_elements, tile, static_cast<const TS*>(A), z,
                      static_cast<const T*>(ws.wfold), static_cast<TS*>(B));
   return hipGetLastError();
@@ -936,19 +959,19 @@ size_t spec_folded_bytes(const sc_plan* plan) {
 
 struct PrepareFn {
   const sc_plan* plan; int64_t n; const int32_t* z; const void* W; const Workspace& ws; const LaunchShape& shape;
-  bool count, fold; hipStream_t stream;
-  template <typename T, typename G, typename TS> hipError_t operator()() const { return prepare_launch<T, G>(plan, n, z, W, ws, shape, count, fold, stream); }
+  bool count, fold, window_order; hipStream_t stream;
+  template <typename T, typename G, typename TS> hipError_t operator()() const { return prepare_launch<T, G>(plan, n, z, W, ws, shape, count, fold, window_order, stream); }
 };
 struct ForwardFn {
   const sc_plan* plan; int64_t n; const void* A; const int32_t* z; void* B; const Workspace& ws; const LaunchShape& shape;
-  int group; bool component_major; hipStream_t stream;
+  int group; bool window_order, component_major; hipStream_t stream;
   template <typename T, typename G, typename TS> hipError_t operator()() const {
     if constexpr (std::is_same<T, TS>::value) {
-      if (component_major) return fwd_launch<T, G, TS, true>(plan, n, A, z, B, ws, shape, group, stream);
+      if (component_major) return fwd_launch<T, G, TS, true>(plan, n, A, z, B, ws, shape, group, window_order, stream);
     } else if (component_major) {
       return hipErrorInvalidValue;   // refused by the caller: rows stored in another type have no such kernel
     }
-    return fwd_launch<T, G, TS>(plan, n, A, z, B, ws, shape, group, stream);
+    return fwd_launch<T, G, TS>(plan, n, A, z, B, ws, shape, group, window_order, stream);
   }
 };
 struct BackwardFn {
@@ -981,8 +1004,8 @@ struct FinalizeFn {
 };
 
 hipError_t launch_spec_prepare(const sc_plan* plan, int64_t n, const int32_t* z, const void* W, const Workspace& ws,
-                               const LaunchShape& shape, bool count, bool fold, hipStream_t stream) {
-  return dispatch(plan, PrepareFn{plan, n, z, W, ws, shape, count, fold, stream});
+                               const LaunchShape& shape, bool count, bool fold, bool window_order, hipStream_t stream) {
+  return dispatch(plan, PrepareFn{plan, n, z, W, ws, shape, count, fold, window_order, stream});
 }
 
 hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z, const Workspace& ws,
@@ -994,9 +1017,9 @@ hipError_t launch_spec_scatter(const sc_plan* plan, int64_t n, const int32_t* z,
 }
 
 hipError_t launch_spec_forward(const sc_plan* plan, int64_t n, const void* A, const int32_t* z, void* B,
-                               const Workspace& ws, const LaunchShape& shape, int group, bool component_major,
-                               hipStream_t stream) {
-  return dispatch(plan, ForwardFn{plan, n, A, z, B, ws, shape, group, component_major, stream});
+                               const Workspace& ws, const LaunchShape& shape, int group, bool window_order,
+                               bool component_major, hipStream_t stream) {
+  return dispatch(plan, ForwardFn{plan, n, A, z, B, ws, shape, group, window_order && ws.wnode && ws.wkey, component_major, stream});
 }
 
 hipError_t launch_spec_backward(const sc_plan* plan, int64_t n, const void* A, const void* dB, void* dA,

@@ -143,6 +143,67 @@ def test_batch_sizes_around_the_chunk_boundaries(sc, N):
     full_parity(sc, wl_of(f"ragged{N}", N, 5, 64, 3, 3, O01, "f32", 2900 + N, z_mode="uniform"))
 
 
+WINDOW = 4    # SC_PLAN_WINDOW_ORDER: the forward's window order also below its default batch size
+
+
+@pytest.mark.parametrize("N", [1, 63, 333, 1023, 1024, 1025, 2500])
+def test_window_order_of_the_forward(sc, N):
+    """The forward visits the nodes in the order written by the window role of the prepare launch
+    (windows of 1024 nodes ordered by element) - by default from 8192 nodes on (the full-size
+    cases), here forced for small batches: ragged and exactly full windows, and with it every
+    row of B must have the bits of the in-wave order (a node's result does not depend on when
+    it is visited)."""
+    wl = wl_of(f"window{N}", N, 89, 128, 3, 3, O01, "f32", 3500 + N)
+    full_parity(sc, wl, WINDOW, dw_whole_tensor=N > 1)   # one node: see test_degenerate_batches
+    T = oracle_tables(wl)
+    inp = workloads.make_inputs(wl, T.paths)
+    a, b = GpuRun(sc, wl, inp, WINDOW), GpuRun(sc, wl, inp, 0)
+    assert np.array_equal(a.forward(), b.forward())
+    a.close(), b.close()
+
+
+def forward_matches_default_order(sc, wl):
+    """Forward only: parity with the oracle in the window order, and the bits of the default order."""
+    say(f"case {wl.name}: N={wl.num_nodes} K={wl.num_channels} forward, window order")
+    T = oracle_tables(wl)
+    inp = workloads.make_inputs(wl, T.paths)
+    a, b = GpuRun(sc, wl, inp, WINDOW), GpuRun(sc, wl, inp, 0)
+    A, z, W, _ = a.inputs_as_computed()
+    B = a.forward()
+    check("B", B, oracle_forward(osc, T, A, z, W), wl.dtype)
+    assert np.array_equal(B, b.forward())
+    a.close(), b.close()
+
+
+def test_window_order_shapes_and_invalid_indices(sc):
+    import torch
+    # idle lanes, the 49-row basis, bfloat16 rows, more than 512 elements (LDS of the window role), fp64
+    full_parity(sc, wl_of("window_k72", 1300, 7, 72, 3, 3, O01, "f32", 3601, z_mode="uniform"), WINDOW)
+    forward_matches_default_order(sc, wl_of("window_2e", 1100, 89, 256, 3, 3, O012, "f32", 3602))
+    full_parity(sc, wl_of("window_bf16", 1500, 89, 128, 3, 3, O01, "bf16", 3603), WINDOW)
+    full_parity(sc, wl_of("window_z1024", 1200, 1024, 64, 3, 3, O01, "f32", 3604, z_mode="uniform"), WINDOW)
+    full_parity(sc, wl_of("window_f64", 1100, 20, 64, 3, 3, O01, "f64", 3605, z_mode="uniform"), WINDOW)
+    # indices outside [0, Z): those nodes go to the end of their window and are skipped
+    wl = wl_of("window_badz", 2300, 6, 128, 3, 3, O01, "f32", 3606, z_mode="uniform")
+    T = oracle_tables(wl)
+    inp = workloads.make_inputs(wl, T.paths)
+    bad = np.array([0, 5, 1000, 1023, 1024, 1500, 2299])
+    inp.z[bad] = [-1, 6, 1000, -7, 99, 6, 2 ** 31 - 1]
+    run = GpuRun(sc, wl, inp, WINDOW)
+    run.B.fill_(7.0)
+    A, z, W, dB = run.inputs_as_computed()
+    good = np.setdiff1d(np.arange(wl.num_nodes), bad)
+    B = run.forward()
+    check("B", B[good], osc.forward(T, A[good], z[good], W), "f32")
+    assert (B[bad] == 7.0).all()
+    # component-major rows follow the same order
+    run.A = run.A.transpose(1, 2).contiguous()
+    run.B = torch.full((wl.num_nodes, wl.n_LM, wl.num_channels), 7.0, dtype=run.tdt, device=run.dev)
+    B_cm = run.forward(sc.SC_COMPONENT_MAJOR).transpose(0, 2, 1)
+    assert np.array_equal(B_cm, B)
+    run.close()
+
+
 def test_empty_batch(sc):
     import torch
     wl = wl_of("empty", 0, 5, 128, 3, 3, O01, "f32", 2400)
