@@ -79,7 +79,7 @@ def describe(wl):
             + (", forward+backward" if wl.backward else ", forward only"))
 
 
-def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=False, z_grouped=False):
+def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=False, z_grouped=False, rotate=True):
     import numpy as np
     import torch
     from paper_2504_10700_amd import binding as sc
@@ -99,6 +99,8 @@ def measure(wl, steps, warmup, generic=False, tile_nodes=0, component_major=Fals
 
     per_set = N * K * (2 * wl.n_lm + 2 * wl.n_LM) * elem
     n_sets = max(2, min(8, int(np.ceil(1.0e9 / per_set))))
+    if not rotate:     # every step on the same buffers: what fits stays in the 256 MB last-level cache
+        n_sets = 1
     A0 = torch.tensor(inp.A, dtype=tdt, device=dev)
     dB0 = torch.tensor(inp.dB, dtype=tdt, device=dev)
     W = torch.tensor(inp.W, dtype=wdt, device=dev)
@@ -265,6 +267,8 @@ def measure_double_backward(wl, steps, warmup, tile_nodes=0):
     N, K = wl.num_nodes, wl.num_channels
     per_set = N * K * (3 * wl.n_lm + 2 * wl.n_LM) * elem
     n_sets = max(2, min(8, int(np.ceil(1.0e9 / per_set))))
+    if not rotate:     # every step on the same buffers: what fits stays in the 256 MB last-level cache
+        n_sets = 1
     A0 = torch.tensor(inp.A, dtype=tdt, device=dev)
     dB0 = torch.tensor(inp.dB, dtype=tdt, device=dev)
     H0 = torch.tensor(workloads.make_cotangent(wl), dtype=tdt, device=dev)
@@ -783,6 +787,8 @@ def main():
             out["also"][name] = {k: m2[k] for k in keys}
         m2 = measure(wl, 100, 10, component_major=True)     # the other layout of the per-node tensors
         out["also"]["training_step_component_major"] = {k: m2[k] for k in keys}
+        m2 = measure(wl, 100, 10, rotate=False)             # same buffers every step (cache-resident: not the headline)
+        out["also"]["training_step_cache_resident"] = {k: m2[k] for k in keys}
         m2 = measure(wl, 100, 10, z_grouped=True)           # nodes ordered by element by the caller
         out["also"]["training_step_z_grouped"] = {k: m2[k] for k in keys}
         m2 = measure(workloads.WORKLOADS["large_batch"], 30, 5, z_grouped=True)

@@ -69,48 +69,14 @@ __device__ __forceinline__ void split_scatter_chunk(int e, bool valid, int node,
   if (valid) perm[base + rank] = node;
 }
 
-// The same ranking for the window order: returns the position of the lane's node (valid lanes: the
-// next free position of its element in cursor; lanes with an index outside [0, Z): the next free
-// position in *cursor_invalid; lanes past the end: -1).
-__device__ __forceinline__ int split_place_chunk(int e, bool in_range, bool valid, int lane, int z_bits, int32_t* cursor,
-                                                 int32_t* cursor_invalid) {
-  const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  unsigned long long same = __ballot(valid);
-  for (int b = 0; b < z_bits; ++b) {
-    const bool bit = (e >> b) & 1;
-    const unsigned long long m = __ballot(bit);
-    same &= bit ? m : ~m;
-  }
-  const int rank = __popcll(same & lt_mask);
-  const int group = __popcll(same);
-  const int leader = valid ? __ffsll(static_cast<long long>(same)) - 1 : lane;
-  int base = 0;
-  if (valid && lane == leader) base = atomicAdd(&cursor[e], group);
-  base = __shfl(base, leader);
-  // nodes whose index is outside the range
-  const unsigned long long bad = __ballot(in_range && !valid);
-  int bad_base = 0;
-  if (bad != 0ull) {   // wave-uniform
-    const int first = __ffsll(static_cast<long long>(bad)) - 1;
-    if (lane == first) bad_base = atomicAdd(cursor_invalid, __popcll(bad));
-    bad_base = __shfl(bad_base, first);
-  }
-  if (valid) return base + rank;
-  if (in_range) return bad_base + __popcll(bad & lt_mask);
-  return -1;
-}
-
-// Exclusive scan of v[0..n) (LDS, n <= 1024) in place by ONE wave; returns the total.
+// Exclusive scan of v[0..n) (LDS, n <= 1024) in place by ONE wave; returns the total.  Lane l owns
+// the `per` consecutive entries from l * per; they are read twice (sum, then running sums) so that
+// the loops run `per` times (two for 89 elements), not the sixteen of the largest n.
 __device__ __forceinline__ int split_wave_scan(int32_t* v, int n, int lane) {
-  constexpr int kMaxPer = SC_MAX_ELEMENTS / kLanes;
-  const int per = (n + kLanes - 1) / kLanes;
-  int c[kMaxPer], local = 0;
-#pragma unroll
-  for (int k = 0; k < kMaxPer; ++k) {
-    const int i = lane * per + k;
-    c[k] = (k < per && i < n) ? v[i] : 0;
-    local += c[k];
-  }
+  const int per = (n + kLanes - 1) / kLanes;   // uniform
+  const int first = lane * per;
+  int local = 0;
+  for (int k = 0; k < per; ++k) local += (first + k < n) ? v[first + k] : 0;
   int incl = local;
 #pragma unroll
   for (int d = 1; d < kLanes; d <<= 1) {
@@ -118,11 +84,12 @@ __device__ __forceinline__ int split_wave_scan(int32_t* v, int n, int lane) {
     if (lane >= d) incl += up;
   }
   int run = incl - local;
-#pragma unroll
-  for (int k = 0; k < kMaxPer; ++k) {
-    const int i = lane * per + k;
-    if (k < per && i < n) v[i] = run;
-    run += c[k];
+  for (int k = 0; k < per; ++k) {
+    if (first + k < n) {
+      const int c = v[first + k];
+      v[first + k] = run;
+      run += c;
+    }
   }
   return __shfl(incl, kLanes - 1);
 }
@@ -211,17 +178,45 @@ __device__ __forceinline__ void split_window_role(const SplitGroupArgs& g, int w
   for (int e = lane; e < g.Z; e += kLanes) my_cursor[e] += seg[e];
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
+  // the four chunks step by step side by side (ballots, then the four cursor updates, then the four
+  // broadcasts), so that the LDS latencies overlap; the updates of one cursor stay in chunk order
   const int z_bits = 32 - __builtin_clz(g.Z);
+  const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  bool in_range[kWindowChunks], valid[kWindowChunks];
+  unsigned long long same[kWindowChunks], bad[kWindowChunks];
+  int leader[kWindowChunks], base_pos[kWindowChunks], bad_pos[kWindowChunks];
 #pragma unroll
   for (int c = 0; c < kWindowChunks; ++c) {
-    if (lo + c * kLanes >= hi) break;  // wave-uniform
-    const long long i = lo + c * kLanes + lane;
-    const bool in_range = i < hi, valid = in_range && zs[c] >= 0 && zs[c] < g.Z;
-    const int pos = split_place_chunk(zs[c], in_range, valid, lane, z_bits, my_cursor, &cursor_invalid[wave]);
-    if (pos >= 0) {
-      g.wnode[base + pos] = static_cast<int32_t>(i);
-      g.wkey[base + pos] = valid ? zs[c] : g.Z;
+    in_range[c] = lo + c * kLanes + lane < hi;
+    valid[c] = in_range[c] && zs[c] >= 0 && zs[c] < g.Z;
+    same[c] = __ballot(valid[c]);
+    for (int b = 0; b < z_bits; ++b) {
+      const bool bit = (zs[c] >> b) & 1;
+      const unsigned long long m = __ballot(bit);
+      same[c] &= bit ? m : ~m;
     }
+    bad[c] = __ballot(in_range[c] && !valid[c]);
+    leader[c] = valid[c] ? __ffsll(static_cast<long long>(same[c])) - 1 : lane;
+  }
+#pragma unroll
+  for (int c = 0; c < kWindowChunks; ++c) {
+    base_pos[c] = 0;
+    if (valid[c] && lane == leader[c]) base_pos[c] = atomicAdd(&my_cursor[zs[c]], __popcll(same[c]));
+    bad_pos[c] = 0;
+    if (bad[c] != 0ull && lane == __ffsll(static_cast<long long>(bad[c])) - 1)
+      bad_pos[c] = atomicAdd(&cursor_invalid[wave], __popcll(bad[c]));
+  }
+#pragma unroll
+  for (int c = 0; c < kWindowChunks; ++c) {
+    base_pos[c] = __shfl(base_pos[c], leader[c]);
+    if (bad[c] != 0ull) bad_pos[c] = __shfl(bad_pos[c], __ffsll(static_cast<long long>(bad[c])) - 1);   // uniform
+  }
+#pragma unroll
+  for (int c = 0; c < kWindowChunks; ++c) {
+    if (!in_range[c]) continue;
+    const int pos = valid[c] ? base_pos[c] + __popcll(same[c] & lt_mask) : bad_pos[c] + __popcll(bad[c] & lt_mask);
+    g.wnode[base + pos] = static_cast<int32_t>(lo + c * kLanes + lane);
+    g.wkey[base + pos] = valid[c] ? zs[c] : g.Z;
   }
 }
 
