@@ -267,8 +267,6 @@ def measure_double_backward(wl, steps, warmup, tile_nodes=0):
     N, K = wl.num_nodes, wl.num_channels
     per_set = N * K * (3 * wl.n_lm + 2 * wl.n_LM) * elem
     n_sets = max(2, min(8, int(np.ceil(1.0e9 / per_set))))
-    if not rotate:     # every step on the same buffers: what fits stays in the 256 MB last-level cache
-        n_sets = 1
     A0 = torch.tensor(inp.A, dtype=tdt, device=dev)
     dB0 = torch.tensor(inp.dB, dtype=tdt, device=dev)
     H0 = torch.tensor(workloads.make_cotangent(wl), dtype=tdt, device=dev)
