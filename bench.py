@@ -14,9 +14,12 @@ symmetric-contraction fwd+bwd (128ch, l<=3, nu=3)" is quoted on.  With the defau
 workload the same line also carries, under "also", a shorter measurement of
 `large_batch` (200 000 nodes, same shapes): at 10 000 nodes a step is ~0.09 ms and
 launch / fixed costs weigh as much as the data movement, at 200 000 nodes they do not;
-of `medium_fwd`, `wide_high_l` and `outputs_l3`; of the second-order pass
+of `medium_fwd`, `wide_high_l`, `outputs_l3` and the bfloat16-row variant; of the training
+step in the other layout (--component-major), on the same buffers every step (cache-resident,
+labelled so) and with batches ordered by element (--z-grouped); of the second-order pass
 (sc_double_backward alone) on both workloads; and of the operations around the contraction.
-"attainable" holds streaming probes of the same run (what this machine reaches without arithmetic).
+"attainable" holds streaming probes of the same run (what this machine reaches without arithmetic,
+for plain reads / writes / copies and for the access patterns of the two main kernels).
 
 value          nodes (atoms) per second, forward + backward, whole step (all launches)
 roofline       the dominant kernel (fused backward: dA + per-tile dW) against the HBM
