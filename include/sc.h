@@ -185,8 +185,8 @@ sc_status sc_forward(sc_plan* plan, int64_t n_nodes, const void* A, const int32_
  * allocating routine.
  * Limits: n_nodes <= SC_NOALLOC_MAX_NODES, and the plan's forward scratch for n_nodes must fit
  * SC_NOALLOC_SCRATCH_BYTES (about 1.9 MB for 89 elements x 128 channels in fp32, 5.1 MB for
- * 256 channels with 0e+1o+2e outputs); beyond them the call fails with SC_ERR_WORKSPACE and
- * launches nothing.
+ * 256 channels with 0e+1o+2e outputs, plus 8 bytes per node); beyond them the call fails with
+ * SC_ERR_WORKSPACE and launches nothing.
  * Every GPU holds ONE such array (SC_NOALLOC_SCRATCH_BYTES of device memory per GPU the
  * library is loaded on, until the process ends), shared by all plans and streams: calls of
  * sc_forward_noalloc that can overlap in time on one GPU race on it and must be ordered by

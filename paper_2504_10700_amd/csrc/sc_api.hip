@@ -132,7 +132,7 @@ Workspace carve_workspace(const sc_plan* plan, int64_t n, const LaunchShape& sha
   w.perm = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
   w.tiles = static_cast<TileDesc*>(take(sizeof(TileDesc) * static_cast<size_t>(shape.max_tiles)));
   if (plan->specialised) w.wfold = take(spec_folded_bytes(plan));
-  if (plan->specialised && !forward_only) {   // forward-only workspaces never run the grouping that writes these
+  if (plan->specialised) {
     w.wnode = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
     w.wkey = static_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n)));
   }
@@ -497,10 +497,11 @@ sc_status sc_forward_noalloc(sc_plan* plan, int64_t n_nodes, const void* A, cons
   const sc_status st = noalloc_scratch(plan->cfg.device, &base);
   if (st != SC_OK) return st;
   // Nothing in the scratch has to start at zero: the launches that precede the forward kernel
-  // write every word it reads (the folded weights of all elements; for the table-driven kernels
-  // the permutation, the offsets and all max_tiles tile descriptors), whatever an earlier,
-  // larger call left there.  The generated forward kernel needs no grouping, and there is no
-  // backward pass to leave one for.
+  // write every word it reads (the folded weights of all elements and, from
+  // SC_WINDOW_ORDER_MIN_NODES nodes on, the window order of all n_nodes positions; for the
+  // table-driven kernels the permutation, the offsets and all max_tiles tile descriptors),
+  // whatever an earlier, larger call left there.  The generated forward kernel needs no grouping,
+  // and there is no backward pass to leave one for.
   const sc::Workspace ws = sc::carve_workspace(plan, n_nodes, shape, base, true);
   return forward_launches("sc_forward_noalloc", plan, n_nodes, A, z, W, B, ws, shape,
                           plan->specialised ? SC_REUSE_GROUPING : 0u, static_cast<hipStream_t>(hip_stream));

@@ -32,7 +32,7 @@ struct Workspace {
   TileDesc* tiles;     // [max_tiles]
   void* wfold;         // generated kernels: weights folded into the internal basis, [Z][K][stride]
   int32_t* wnode;      // generated kernels: [N] window order of the forward pass (node per position) ...
-  int32_t* wkey;       // ... and [N] its element index (Z: outside the range); null in a forward-only workspace
+  int32_t* wkey;       // ... and [N] its element index (Z: outside the range)
   void* partial;       // [max_tiles][chblocks][S][64] per-tile dW contributions
   int32_t max_tiles;
   size_t bytes;
