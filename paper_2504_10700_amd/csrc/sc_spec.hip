@@ -21,11 +21,13 @@
 // One step (forward + backward of one batch) is four launches:
 //   1 prepare   the weights of every (element, channel) folded into the internal basis once,
 //               wf[element][channel block][kS][64]; other workgroups of the same launch count the
-//               elements of z (first half of the grouping)
-//   2 forward   nodes in their NATURAL order (no grouping needed: every node reads the folded
-//               weights of its element from wf, which stays in L2): consecutive workgroups
-//               stream consecutive memory.  Other workgroups of the same launch finish the
-//               grouping (scatter + tile table), which only the backward needs
+//               elements of z (first half of the grouping) and, for larger batches, order every
+//               window of 1024 nodes by element (the order of the forward's visits)
+//   2 forward   nodes in batch order, inside a window by element (no grouping needed: every node
+//               reads the folded weights of its element from wf, which stays in L2, once per run
+//               of an element): consecutive workgroups stream the same stretch of memory.  Other
+//               workgroups of the same launch finish the grouping (scatter + tile table), which
+//               only the backward needs
 //   3 backward  nodes grouped by element (tiles), weights of the tile's element in registers,
 //               dW' summed per tile without atomics
 //   4 finalize  per (element, channel block): sum of the per-tile dW' rows in a fixed order
