@@ -27,6 +27,22 @@ def test_library_exports_every_declared_symbol():
         assert getattr(sc.lib, name) is not None
 
 
+def test_binding_constants_are_the_header_s():
+    """Every #define and enumerator of include/sc.h that the binding repeats has the header's value."""
+    header = open(os.path.join(ROOT, "include", "sc.h")).read()
+    defines = {}
+    for m in re.finditer(r"^#define\s+(SC_[A-Z0-9_]+)\s+\(?([0-9]+)u?\s*(?:<<\s*([0-9]+))?\)?", header, flags=re.M):
+        defines[m.group(1)] = int(m.group(2)) << int(m.group(3) or 0)      # "4u", "65536", "(8u << 20)"
+    for name, value in re.findall(r"\b(SC_[A-Z0-9_]+)\s*=\s*([0-9]+)\b", header):   # enumerators
+        defines.setdefault(name, int(value))
+    repeated = [n for n in defines if hasattr(sc, n)]
+    assert {"SC_REUSE_GROUPING", "SC_REUSE_WEIGHTS", "SC_Z_GROUPED", "SC_COMPONENT_MAJOR", "SC_PLAN_HOST_ONLY",
+            "SC_PLAN_FORCE_GENERIC", "SC_PLAN_WINDOW_ORDER", "SC_NOALLOC_MAX_NODES", "SC_NOALLOC_SCRATCH_BYTES",
+            "SC_PROBE_ROWS_FORWARD", "SC_BF16", "SC_ERR_WORKSPACE"} <= set(repeated)
+    for n in repeated:
+        assert getattr(sc, n) == defines[n], n
+
+
 def host_plan(K, l_max, nu_max, Z, outs, dtype=sc.SC_F64):
     return sc.sc_plan_create(K, l_max, nu_max, Z, outs, dtype, 0, sc.SC_PLAN_HOST_ONLY)
 
