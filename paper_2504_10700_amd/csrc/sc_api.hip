@@ -72,24 +72,39 @@ sc_status set_error(sc_status code, const std::string& msg) { return fail(code, 
 LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
   LaunchShape s{};
   s.chblocks = (plan->cfg.num_channels + kLanes - 1) / kLanes;
-  // Tiles are sized for about six (tile x channel block) workgroups per compute unit on
-  // small batches - measured best on MI355X between 3 and 12 - and stay bounded for large
-  // ones (the per-tile dW rows cost memory traffic inversely proportional to the tile size).
   const int waves_per_tile = plan->specialised ? spec_waves_per_tile() : 1;
-  const int64_t target_wgs = static_cast<int64_t>(plan->num_cus) * (plan->specialised ? 6 : 8);
-  // expected tiles ~ n / t + (half a tile of rounding per element that occurs)
-  int64_t t = (n * s.chblocks + target_wgs - 1) / target_wgs;
-  // At least four nodes per wave, three on small and two on very small batches (measured on the generated
-  // kernels, 128 channels, nodes per tile -> us per step: 1024 nodes 8 -> 25.5, 12 -> 27.0, 16 -> 28.4;
-  // 3072 nodes 8 -> 39.9, 12 -> 37.6, 16 -> 42.1; 5000 nodes 8 -> 49.3, 12 -> 48.8, 16 -> 50.3; 10000 nodes
-  // 12 -> 85.7, 16 -> 85.8, 24 -> 88.0).
   const int64_t work = n * s.chblocks;
-  const int64_t lo = (work <= 2560 ? 2 : work <= 12288 ? 3 : 4) * waves_per_tile, hi = 32 * waves_per_tile;
-  if (t < lo) t = lo;
-  if (t > hi) t = hi;
-  if (plan->cfg.tile_nodes > 0) t = plan->cfg.tile_nodes;
-  s.tile_nodes = static_cast<int>(t);
-  s.max_tiles = static_cast<int>(n / s.tile_nodes) + plan->cfg.num_elements;
+  int64_t t;
+  if (plan->specialised) {
+    // Generated kernels: the grouped sequence is cut every t positions and at element boundaries, and the
+    // pieces are processed largest first (see split_table_role).  t: a whole number of nodes per wave such
+    // that the whole pieces make about one and a half workgroups per compute unit (the shorter pieces next
+    // to element boundaries fill the rest), at least two and at most 32 nodes per wave.  Measured on
+    // MI355X, 128 channels, 89 elements of skewed frequency, us per step against t: 3072 nodes 8 -> 37.0,
+    // 16 -> 34.8, 24 -> 36.8; 5000 nodes 12 -> 55.5, 20 -> 49.8, 32 -> 51.4; 10000 nodes 28 -> 88.7, 40 -> 85.9,
+    // 56 -> 84.4, 80 -> 90.0; 15000 nodes 24 -> 111.0, 56 -> 109.7, 128 -> 124.0; flat within 2% from 20000 on.
+    const int64_t target = static_cast<int64_t>(plan->num_cus) * 3 / 2;
+    t = (work + target - 1) / target;
+    t = (t + waves_per_tile - 1) / waves_per_tile * waves_per_tile;
+    const int64_t lo = 2 * waves_per_tile, hi = 32 * waves_per_tile;
+    if (t < lo) t = lo;
+    if (t > hi) t = hi;
+    if (plan->cfg.tile_nodes > 0) t = plan->cfg.tile_nodes;
+    s.tile_nodes = static_cast<int>(t);
+    s.max_tiles = static_cast<int>(n / s.tile_nodes) + 1 + plan->cfg.num_elements;
+  } else {
+    // Table-driven kernels: every element's nodes split evenly into tiles of at most t nodes, about eight
+    // (tile x channel block) workgroups per compute unit on small batches, bounded for large ones (the
+    // per-tile dW rows cost memory traffic inversely proportional to the tile size).
+    const int64_t target_wgs = static_cast<int64_t>(plan->num_cus) * 8;
+    t = (work + target_wgs - 1) / target_wgs;
+    const int64_t lo = work <= 2560 ? 2 : work <= 12288 ? 3 : 4, hi = 32;
+    if (t < lo) t = lo;
+    if (t > hi) t = hi;
+    if (plan->cfg.tile_nodes > 0) t = plan->cfg.tile_nodes;
+    s.tile_nodes = static_cast<int>(t);
+    s.max_tiles = static_cast<int>(n / s.tile_nodes) + plan->cfg.num_elements;
+  }
   // Grouping: one single-workgroup launch for small batches (group_waves = 0), else three
   // launches with about four 64-node chunks per wave, at most kMaxGroupWaves waves.
   if (n <= 16384 && plan->cfg.num_elements <= 512) {  // 16 waves x 16 chunks x 64 nodes

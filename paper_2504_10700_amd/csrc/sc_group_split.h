@@ -45,7 +45,7 @@ struct SplitGroupArgs {
 };
 
 // dynamic LDS (bytes) a hosting kernel must provide for the count, scatter and table roles
-inline size_t split_group_lds_bytes(int Z) { return sizeof(int32_t) * (static_cast<size_t>(kGroupWavesPerWG + 1) * Z + 4); }
+inline size_t split_group_lds_bytes(int Z) { return sizeof(int32_t) * (static_cast<size_t>(kGroupWavesPerWG + 1) * Z + 4 + 256); }
 
 // Stable scatter of one 64-node chunk: lane holds element e (valid or not); cursor[e] is this
 // wave's next free position of element e (LDS).  The lanes that hold the same element are found
@@ -284,48 +284,78 @@ __device__ __forceinline__ void split_scatter_role(const SplitGroupArgs& g, int 
   }
 }
 
-// One workgroup: element offsets, tile offsets, tile count and tile descriptors.  lds: 3 * Z + 2 ints.
+// One workgroup: element offsets, tile offsets, tile count and tile descriptors.
+//
+// Tiles: the grouped sequence (positions 0..n_valid of perm) is cut every g.tile_nodes positions
+// and at every change of element; a tile is one piece.  Whole pieces take one workgroup of a main
+// kernel for the same time, and the pieces next to element boundaries are shorter, so the
+// descriptors are stored LARGEST FIRST: workgroups are dispatched in index order, the short
+// pieces come last and fill the slots the first finishers leave (largest-first list scheduling;
+// with equal tiles - every element split evenly - the last round of workgroups ran with most of
+// the chip idle: 2.2 rounds cost three).  The per-tile dW rows stay in (element, position) order
+// through TileDesc::id, which is what the second stage of the dW reduction walks.
+// lds: split_group_lds_bytes(Z).
+constexpr int kTileSizeBins = 256;   // tiles of 255 nodes and more share a bin
+
+__device__ __forceinline__ TileDesc split_tile(const SplitGroupArgs& g, const int32_t* total, const int32_t* seg,
+                                               const int32_t* til, int i) {
+  int lo = 0, hi = g.Z;  // last e with til[e] <= i (empty elements share an offset with the next one)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (til[mid] <= i) lo = mid; else hi = mid;
+  }
+  const int e = lo;
+  const int r = seg[e] / g.tile_nodes + (i - til[e]);             // the cut this piece lies in
+  const long long cut0 = static_cast<long long>(r) * g.tile_nodes, cut1 = cut0 + g.tile_nodes;
+  const int end_e = seg[e] + total[e];
+  const int start = cut0 > seg[e] ? static_cast<int>(cut0) : seg[e];
+  const int end = cut1 < end_e ? static_cast<int>(cut1) : end_e;
+  return TileDesc{e, start, end - start, i};
+}
+
 __device__ __forceinline__ void split_table_role(const SplitGroupArgs& g, int32_t* lds) {
   int32_t* total = lds;            // [Z]
   int32_t* seg = total + g.Z;      // [Z+1]
   int32_t* til = seg + g.Z + 1;    // [Z+1]
+  int32_t* bins = til + g.Z + 1;   // [kTileSizeBins] tiles per size, largest size first; then their offsets
   const int t = threadIdx.x;
   for (int e = t; e < g.Z; e += kSplitThreads) {
     int before[kGroupWavesPerWG];
     total[e] = split_column(g, e, -kGroupWavesPerWG, before);
     seg[e] = total[e];
-    til[e] = (total[e] + g.tile_nodes - 1) / g.tile_nodes;
   }
+  for (int b = t; b < kTileSizeBins; b += kSplitThreads) bins[b] = 0;
   __syncthreads();
   if (t < kLanes) {  // wave 0
     const int n_valid = split_wave_scan(seg, g.Z, t);
+    if (t == 0) seg[g.Z] = n_valid;
+  }
+  __syncthreads();
+  for (int e = t; e < g.Z; e += kSplitThreads)   // cuts that element e's positions touch
+    til[e] = total[e] > 0 ? (seg[e] + total[e] - 1) / g.tile_nodes - seg[e] / g.tile_nodes + 1 : 0;
+  __syncthreads();
+  if (t < kLanes) {
     const int n_tiles = split_wave_scan(til, g.Z, t);
     if (t == 0) {
-      seg[g.Z] = n_valid;
       til[g.Z] = n_tiles;
       *g.ntiles = (n_tiles < g.max_tiles) ? n_tiles : g.max_tiles;
     }
   }
   __syncthreads();
-  const int n_tiles = til[g.Z];
+  const int n_tiles = til[g.Z] < g.max_tiles ? til[g.Z] : g.max_tiles;
   for (int e = t; e <= g.Z; e += kSplitThreads) {
     g.seg_off[e] = seg[e];
     g.tile_off[e] = til[e];
   }
-  // element e owns tiles [til[e], til[e+1]); its nodes are split evenly (the first `rem` tiles
-  // take one node more)
-  for (int i = t; i < n_tiles && i < g.max_tiles; i += kSplitThreads) {
-    int lo = 0, hi = g.Z;  // last e with til[e] <= i (empty elements share an offset with the next one)
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (til[mid] <= i) lo = mid; else hi = mid;
-    }
-    const int e = lo;
-    const int nt_e = til[e + 1] - til[e];
-    const int j = i - til[e];
-    const int base = total[e] / nt_e, rem = total[e] % nt_e;
-    const int s0 = j * base + (j < rem ? j : rem);
-    g.tiles[i] = TileDesc{e, seg[e] + s0, base + (j < rem ? 1 : 0), 0};
+  // largest first: count the tiles per size, scan, place
+  auto bin_of = [](int count) { return kTileSizeBins - 1 - (count < kTileSizeBins - 1 ? count : kTileSizeBins - 1); };
+  for (int i = t; i < n_tiles; i += kSplitThreads) atomicAdd(&bins[bin_of(split_tile(g, total, seg, til, i).count)], 1);
+  __syncthreads();
+  if (t < kLanes) split_wave_scan(bins, kTileSizeBins, t);
+  __syncthreads();
+  for (int i = t; i < n_tiles; i += kSplitThreads) {
+    const TileDesc d = split_tile(g, total, seg, til, i);
+    g.tiles[atomicAdd(&bins[bin_of(d.count)], 1)] = d;
   }
   // unused descriptors say "empty": the main kernels need no separate tile count
   for (int i = n_tiles + t; i < g.max_tiles; i += kSplitThreads) g.tiles[i] = TileDesc{0, 0, 0, 0};

@@ -17,9 +17,12 @@ constexpr int kGroupWavesPerWG = 4; // grouping kernels: waves per workgroup
 constexpr int kMaxGroupWaves = 256; // grouping kernels: total waves (rows of the count matrix)
 
 // One tile = the nodes one workgroup of a main kernel processes: a run of
-// consecutive positions of `perm` that all belong to one element.
+// consecutive positions of `perm` that all belong to one element.  id: the tile's rank in
+// (element, position) order - the index of its row set among the per-tile dW rows; the grouping
+// of the generated kernels stores the descriptors largest tile first, so id differs from the
+// descriptor's own index there (the table-driven kernels keep both equal and ignore it).
 struct TileDesc {
-  int32_t z, start, count, pad;
+  int32_t z, start, count, id;
 };
 
 // Device-side view of the workspace (all pointers into the caller's buffer).

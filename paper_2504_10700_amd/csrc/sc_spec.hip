@@ -432,7 +432,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
   T* stage = red + kSpecWaves * G::kS * kLanes + wave_of_thread() * kLanes * G::kNlm;  // [64][kNlm] per wave
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
-  const int logical = xcd_contiguous_block();
+  const int logical = blockIdx.x;   // descriptors are stored largest tile first: dispatch order is the schedule
   if (logical >= n_blocks) return;  // uniform per workgroup
   const int tile = logical / chblocks, cb = logical % chblocks;
   const TileDesc td = tiles[tile];
@@ -488,7 +488,7 @@ void spec_backward_kernel(int K, int chblocks, int n_blocks,
 #pragma unroll
   for (int s = 0; s < G::kS; ++s) red[(wave * G::kS + s) * kLanes + lane] = dw[s];
   __syncthreads();
-  T* out = partial + (static_cast<size_t>(tile) * chblocks + cb) * G::kS * kLanes;
+  T* out = partial + (static_cast<size_t>(td.id) * chblocks + cb) * G::kS * kLanes;   // rows in (element, position) order
   for (int i = threadIdx.x; i < G::kS * kLanes; i += kSpecThreads) {
     T acc = red[i];
 #pragma unroll
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
   static_assert(!kCM || std::is_same<T, TS>::value, "component-major rows are stored in the arithmetic type");
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
-  const int logical = xcd_contiguous_block();
+  const int logical = blockIdx.x;   // descriptors are stored largest tile first: dispatch order is the schedule
   if (logical >= n_blocks) return;  // uniform per workgroup
   const int tile = logical / chblocks, cb = logical % chblocks;
   const TileDesc td = tiles[tile];
@@ -587,7 +587,7 @@ __global__ __launch_bounds__(kSpecThreads) void spec_double_backward_kernel(
 #pragma unroll
   for (int s = 0; s < G::kS; ++s) red[(wave * G::kS + s) * kLanes + lane] = dw[s];
   __syncthreads();
-  T* out = partial + (static_cast<size_t>(tile) * chblocks + cb) * G::kS * kLanes;
+  T* out = partial + (static_cast<size_t>(td.id) * chblocks + cb) * G::kS * kLanes;   // rows in (element, position) order
   for (int i = threadIdx.x; i < G::kS * kLanes; i += kSpecThreads) {
     T acc = red[i];
 #pragma unroll
@@ -609,7 +609,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
   static_assert(!kCM || std::is_same<T, TS>::value, "component-major rows are stored in the arithmetic type");
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
-  const int logical = xcd_contiguous_block();
+  const int logical = blockIdx.x;   // descriptors are stored largest tile first: dispatch order is the schedule
   if (logical >= n_blocks) return;  // uniform per workgroup
   const int tile = logical / chblocks, cb = logical % chblocks;
   const TileDesc td = tiles[tile];
@@ -654,7 +654,7 @@ __global__ __launch_bounds__(kSpecThreads) __attribute__((amdgpu_waves_per_eu(2,
     }
   }
   __syncthreads();
-  T* out = partial + (static_cast<size_t>(tile) * chblocks + cb) * G::kS * kLanes;
+  T* out = partial + (static_cast<size_t>(td.id) * chblocks + cb) * G::kS * kLanes;   // rows in (element, position) order
   for (int i = threadIdx.x; i < G::kS * kLanes; i += kSpecThreads) {
     T acc = acc_all[i];
 #pragma unroll

@@ -119,8 +119,12 @@ def test_argument_errors_are_reported_not_crashed():
     sc.sc_plan_destroy(None)
 
 
-def test_workspace_grows_with_the_batch():
+def test_workspace_size_follows_the_batch():
+    # per-node parts grow with the batch; the per-tile dW rows follow the tile count, which the tile size
+    # chosen for the batch moves both ways (sc.h: size one buffer for several batch sizes by their maximum)
     plan = host_plan(128, 3, 3, 89, O01, sc.SC_F32)
     sizes = [sc.sc_workspace_bytes(plan, n) for n in (1, 100, 3072, 10_000, 200_000)]
-    assert sizes == sorted(sizes)
+    assert all(b > 0 and b % 256 == 0 for b in sizes) and sizes[-1] == max(sizes) and sizes[0] == min(sizes)
+    # never less than the per-node arrays (permutation, window order) and the folded weights
+    assert all(b >= 12 * n + 89 * 2 * 29 * 256 for b, n in zip(sizes, (1, 100, 3072, 10_000, 200_000)))
     sc.sc_plan_destroy(plan)
