@@ -79,14 +79,15 @@ LaunchShape launch_shape(const sc_plan* plan, int64_t n) {
     // Generated kernels: the grouped sequence is cut every t positions and at element boundaries, and the
     // pieces are processed largest first (see split_table_role).  t: a whole number of nodes per wave such
     // that the whole pieces make about one and a half workgroups per compute unit (the shorter pieces next
-    // to element boundaries fill the rest), at least two and at most 32 nodes per wave.  Measured on
-    // MI355X, 128 channels, 89 elements of skewed frequency, us per step against t: 3072 nodes 8 -> 37.0,
-    // 16 -> 34.8, 24 -> 36.8; 5000 nodes 12 -> 55.5, 20 -> 49.8, 32 -> 51.4; 10000 nodes 28 -> 88.7, 40 -> 85.9,
-    // 56 -> 84.4, 80 -> 90.0; 15000 nodes 24 -> 111.0, 56 -> 109.7, 128 -> 124.0; flat within 2% from 20000 on.
+    // to element boundaries fill the rest), at least two and at most 24 nodes per wave.  Measured on
+    // MI355X, 128 channels, 89 elements of skewed frequency, us per step against t: 3072 nodes 8 -> 37.8,
+    // 16 -> 34.2, 24 -> 35.8; 5000 nodes 12 -> 53.1, 24 -> 50.1, 40 -> 52.4; 10000 nodes 24 -> 83.0, 40 -> 81.9,
+    // 56 -> 80.8, 80 -> 86.2; 15000 nodes 24 -> 107.5, 80 -> 106.1, 128 -> 117.4; 40000 nodes 32 -> 250.6,
+    // 96 -> 246.0, 128 -> 258.1; 200000 nodes 64 -> 1160, 96 -> 1151, 128 -> 1155.
     const int64_t target = static_cast<int64_t>(plan->num_cus) * 3 / 2;
     t = (work + target - 1) / target;
     t = (t + waves_per_tile - 1) / waves_per_tile * waves_per_tile;
-    const int64_t lo = 2 * waves_per_tile, hi = 32 * waves_per_tile;
+    const int64_t lo = 2 * waves_per_tile, hi = 24 * waves_per_tile;
     if (t < lo) t = lo;
     if (t > hi) t = hi;
     if (plan->cfg.tile_nodes > 0) t = plan->cfg.tile_nodes;

@@ -405,16 +405,16 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
   }
 }
 
-// kOcc = waves per SIMD the kernel is held to (0: the compiler's choice).  The fp32 kernel of the
-// small basis needs 171 registers if left alone, three over the limit for three waves per SIMD;
-// held to 168 (two values go to scratch) it runs three workgroups per CU instead of two.  On a
-// small batch a workgroup's life is a chain of latencies (fold, first rows, a handful of nodes,
-// the dW sum) and the third workgroup pays: 51.1 -> 49.3 us at 10k nodes, 138.7 -> 136.6 at
-// 30k, measured on one box; from 60k nodes on the unconstrained kernel is 1% faster.
-// That small-batch instance also streams its dA rows past the cache (non-temporal stores): the
-// kernel itself gains 2 us at 10k nodes and the launches after it another 3 us (step 99.1 -> 93.5
-// us, same box), whereas at 200k nodes the backward loses 2% with them and the next forward gains
-// as much.
+// kOcc = waves per SIMD the kernel is held to (0: the compiler's choice, which every launch uses now).
+// The fp32 kernel of the small basis needs 171 registers if left alone, three over the limit for
+// three waves per SIMD; held to 168 (two values go to scratch) it ran three workgroups per CU
+// instead of two, which paid while small batches were cut into many equal tiles (51.1 -> 49.3 us
+// at 10k nodes).  With tiles processed largest first and about one and a half whole tiles per CU
+// the third workgroup is rarely resident, and the unconstrained kernel is faster (step 82.8 -> 80.8
+// us at 10k nodes, same box).
+// kStreamDA: the dA rows are streamed past the cache (non-temporal stores), for batches up to
+// 40 000 nodes: the kernel itself gains 2 us at 10k nodes and the launches after it another 3 us,
+// whereas at 200k nodes the backward loses 2% with them and the next forward gains as much.
 // kFull: the channel count is a multiple of 64, no lane is ever idle.  The fp32 kernel of the
 // 49-row basis sits at the limit for two waves per SIMD: 250 registers without the idle-lane
 // handling, 295 (one wave per SIMD, 736 instead of 496 us at 50k nodes / 256 channels) with it.
@@ -852,12 +852,9 @@ hipError_t bwd_launch(const sc_plan* plan, int64_t n, const void* A, const void*
   const size_t lds = sizeof(T) * kSpecWaves * (G::kS + G::kNlm) * kLanes;
   const bool full = plan->cfg.num_channels % kLanes == 0;
   auto kernel = full ? &spec_backward_kernel<T, G, 0, false, true, TS, kCM> : &spec_backward_kernel<T, G, 0, false, false, TS, kCM>;
-  if constexpr (sizeof(T) == 4 && G::kS <= 32 && std::is_same<T, TS>::value) {
-    // small batches: three waves per SIMD, streamed dA (see the kernel; with bfloat16 rows that instance
-    // would need 52 bytes of scratch per lane)
-    // (channel counts that leave lanes idle keep the unconstrained kernel: held to 168 registers the
-    // idle-lane handling would push 188 bytes per lane to scratch)
-    if (n <= 40000 && full) kernel = &spec_backward_kernel<T, G, 3, true, true, TS, kCM>;
+  if constexpr (sizeof(T) == 4) {
+    // small batches: dA streamed past the cache (see the kernel)
+    if (n <= 40000 && full) kernel = &spec_backward_kernel<T, G, 0, true, true, TS, kCM>;
   }
   const hipError_t e = raise_lds_limit(kernel, lds);
   if (e != hipSuccess) return e;
