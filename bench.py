@@ -392,18 +392,19 @@ def measure_tp(wl, steps, warmup):
     tp.tp_profile_enable(plan, False)
     tp.tp_plan_destroy(plan)
     fwd_ms, bwd_ms, dhs_ms = (float(x) for x in np.mean(np.array(ms), axis=0))
-    # algorithmic bytes per launch: the per-edge tensors once each (R, Y, sender index; dR out) plus
+    # algorithmic bytes per launch: the per-edge tensors once each (R, Y, one index; dR out) plus
     # the per-node tensors once (h, dA in; A out); gathered rows are counted once per node.  The
-    # edge-walking backward kernel also writes per-edge shares of dh and dY partials into the
-    # workspace, which the two small sum kernels read back: that is overhead of this implementation,
-    # reported separately and not counted as algorithmic bytes (it shows up in `traffic`).
+    # backward kernel also writes dY partials per channel block into the workspace (and, table-driven
+    # kernels only, per-edge shares of dh), which small sum kernels read back: that is overhead of this
+    # implementation, reported separately and not counted as algorithmic bytes (it shows up in `traffic`).
+    # The generated backward writes dh itself (one more per-node tensor out).
     node_h, node_A = N * K * wl.n_h * elem, N * K * wl.n_out * elem
     chblocks = (K + 63) // 64
     fwd_bytes = E * (P * K * elem + wl.n_Y * elem + 4) + node_h + node_A
-    bwd_bytes = E * (2 * P * K * elem + wl.n_Y * elem + 4) + node_h + node_A
-    bwd_ws_bytes = E * (K * wl.n_h + chblocks * wl.n_Y) * elem    # workspace spill: not algorithmic bytes
+    bwd_bytes = E * (2 * P * K * elem + wl.n_Y * elem + 4) + node_h + node_A + (node_h if info.specialised else 0)
+    bwd_ws_bytes = E * ((0 if info.specialised else K * wl.n_h) + chblocks * wl.n_Y) * elem   # not algorithmic bytes
     bwd_rate = bwd_bytes / (bwd_ms * 1e-3) / 1e9
-    step_bytes = fwd_bytes + bwd_bytes + E * wl.n_Y * elem + node_h   # + dY and dh out
+    step_bytes = fwd_bytes + bwd_bytes + E * wl.n_Y * elem + (0 if info.specialised else node_h)   # + dY (and dh) out
     k_ops = info.ops[1]
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -420,14 +421,18 @@ def measure_tp(wl, steps, warmup):
                                f"l_Y={wl.l_Y}, l_h={wl.l_h}, L_max={wl.L_max}, {P} paths, forward+backward",
                    "kernel": "generated" if info.specialised else "table-driven"},
         "step_hbm_fraction": step_bytes / (dt / steps) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": "backward over the edges (dR, dY partials, per-edge dh shares)",
+        "roofline": {"bound": "hbm",
+                     "kernel": "backward over the edges grouped by sender (dR, dY partials, dh)" if info.specialised
+                               else "backward over the edges (dR, dY partials, per-edge dh shares)",
                      "achieved": bwd_rate, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_rate / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel_ms": bwd_ms, "algorithmic_bytes_per_launch": bwd_bytes,
                      "workspace_bytes_written_per_launch": bwd_ws_bytes,
                      "valu_issue_frac": E * K * k_ops / (bwd_ms * 1e-3) / VALU_ISSUE_PEAK if k_ops else None,
                      "forward": {"kernel_ms": fwd_ms, "algorithmic_bytes_per_launch": fwd_bytes,
                                  "achieved": fwd_bytes / (fwd_ms * 1e-3) / 1e9},
-                     "dh_sum": {"kernel_ms": dhs_ms, "bytes_per_launch": E * K * wl.n_h * elem + node_h,
+                     # only the table-driven kernels sum per-edge shares of dh in a launch of its own
+                     "dh_sum": None if info.specialised else
+                               {"kernel_ms": dhs_ms, "bytes_per_launch": E * K * wl.n_h * elem + node_h,
                                 "achieved": (E * K * wl.n_h * elem + node_h) / (dhs_ms * 1e-3) / 1e9}},
     }
 

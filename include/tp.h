@@ -101,7 +101,8 @@ sc_status tp_forward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, int
                      void* hip_stream);
 
 /* Bytes of device workspace tp_backward and tp_double_backward need (partial sums of dY per 64-channel block and
- * the per-edge shares of dh: about n_edges * (K * n_h + ceil(K/64) * n_Y) elements). */
+ * the per-edge shares of dh or d2h: about n_edges * (K * n_h + ceil(K/64) * n_Y) elements; the backward of the
+ * generated kernels keeps only the edges' receiver indices where the shares would be). */
 sc_status tp_workspace_bytes(const tp_plan* plan, int64_t n_edges, size_t* bytes);
 
 /* Backward of tp_forward for an upstream gradient dA [n_nodes_out][K][n_out] (training by
@@ -110,9 +111,12 @@ sc_status tp_workspace_bytes(const tp_plan* plan, int64_t n_edges, size_t* bytes
  * send_ptr dev int32 [n_nodes_in + 1] and send_edge dev int32 [n_edges] group the edges by
  * sender (see the header comment).  workspace: device memory, 256-byte aligned, at least
  * tp_workspace_bytes(plan, n_edges).  All sums have a fixed order: results are bitwise
- * reproducible for identical inputs.  One launch walks the edges grouped by receiver (dR,
- * partial dY and every edge's share of dh into the workspace), one sums the dY partials and
- * one sums, per sender, the shares of the edges it sends. */
+ * reproducible for identical inputs.  Generated kernels: one launch walks the edges grouped by
+ * sender, in the order of send_edge (dR and the partial dY of every edge; dh of an atom is summed
+ * in registers and written once, zero for an atom that sends nothing), one sums the dY partials.
+ * dR and dY of an edge are written by the walk of the sender under which send_edge lists it: an
+ * edge that send_edge omits keeps whatever dR and dY held.  Table-driven kernels walk by receiver,
+ * write every edge's share of dh into the workspace and sum the shares per sender in a third launch. */
 sc_status tp_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, int64_t n_edges, const void* Y,
                       const void* h, const void* R, const int32_t* sender, const int32_t* row_ptr,
                       const int32_t* send_ptr, const int32_t* send_edge, const void* dA, void* dY, void* dh,

@@ -274,9 +274,29 @@ sc_status tp_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_out, in
   const tp::BwdArgs a{n_nodes_in, n_nodes_out, n_edges, Y,  h,  R,         sender,
                       row_ptr,    send_ptr,    send_edge, dA, dY, dh, dR, workspace, dh_edge};
   hipError_t e = hipSuccess;
+  if (plan->specialised) {
+    // generated kernels: one pass over the edges grouped by sender writes dR, the dY partials and dh itself
+    if (n_nodes_in > 0) {
+      if (plan->profile) (void)hipEventRecord(plan->ev[2], stream);
+      e = tp::launch_spec_backward(plan, a, stream);
+      if (e != hipSuccess) return fail_hip(e, "tp_backward: edge kernel launch");
+      if (plan->profile) {
+        (void)hipEventRecord(plan->ev[3], stream);
+        plan->ev_used[1] = true;
+        (void)hipEventRecord(plan->ev[4], stream);   // no separate dh sum on this path
+        (void)hipEventRecord(plan->ev[5], stream);
+        plan->ev_used[2] = true;
+      }
+    }
+    if (n_nodes_out > 0 && n_edges > 0) {
+      e = tp::launch_dY_sum(plan, a, stream);
+      if (e != hipSuccess) return fail_hip(e, "tp_backward: dY sum launch");
+    }
+    return SC_OK;
+  }
   if (n_nodes_out > 0 && n_edges > 0) {
     if (plan->profile) (void)hipEventRecord(plan->ev[2], stream);
-    e = plan->specialised ? tp::launch_spec_backward(plan, a, stream) : tp::launch_generic_backward(plan, a, stream);
+    e = tp::launch_generic_backward(plan, a, stream);
     if (e != hipSuccess) return fail_hip(e, "tp_backward: edge kernel launch");
     if (plan->profile) {
       (void)hipEventRecord(plan->ev[3], stream);

@@ -79,7 +79,7 @@ struct BwdArgs {
   const void* dA;
   void *dY, *dh, *dR;
   void* dY_partial;  // [chblocks][n_edges][n_Y] of the plan's dtype
-  void* dh_edge;     // [n_edges][K][n_h]: every edge's share of its sender's dh
+  void* dh_edge;     // [n_edges][K][n_h]: every edge's share of its sender's dh (table-driven and second-order kernels)
 };
 
 // Second-order pass: the backward's arguments (dY, dh, dR of BwdArgs receive d2Y, d2h, d2R)
@@ -101,6 +101,8 @@ hipError_t launch_dh_sum(const tp_plan* plan, const BwdArgs& a, hipStream_t stre
 int spec_lookup(const tp_plan* plan);
 void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]);
 hipError_t launch_spec_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream);
+// edges walked by sender: writes dR, the dY partials and dh itself (every atom's row, zero for atoms that send
+// nothing); a.dh_edge receives the edges' receivers (int32), not shares.  Valid for n_in > 0, also without edges.
 hipError_t launch_spec_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream);
 
 }  // namespace tp

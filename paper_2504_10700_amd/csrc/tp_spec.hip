@@ -6,11 +6,13 @@
 // sums the edges of a receiver):
 //   lane      = channel (64 consecutive channels per wave): a path's weights R[e][p][:] are one
 //               contiguous 256 B row per wave, the sender's features h[j][k][:] 16 B per lane
-//   wave      = one (receiving atom, 64-channel block): it walks the edges the atom receives and
-//               keeps the atom's sum (forward) or its dA row (backward) in registers: no
-//               atomics, a fixed summation order, one store per atom.  The backward writes per
-//               edge: dR, the channel block's partial of dY, and the edge's share of its
-//               sender's dh, which a small second kernel sums per sender.
+//   wave      = forward: one (receiving atom, 64-channel block); it walks the edges the atom
+//               receives and keeps the atom's sum in registers.  Backward: one (sending atom,
+//               64-channel block); it walks the edges the atom sends, keeps the atom's h row and
+//               its dh sum in registers and gathers the receivers' dA rows; per edge it writes dR
+//               and the channel block's partial of dY.  Either way: no atomics, a fixed summation
+//               order, one store per atom.  The second-order pass walks by receiver (ddA in
+//               registers) and writes every edge's share of d2h, which a small kernel sums per sender.
 //   Y[e][:]   is the same for all lanes: it is read with scalar loads and enters the
 //               arithmetic as scalar operands
 // The next edge's rows are requested before the current edge is evaluated (two register sets
@@ -198,13 +200,28 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(int K, int chblocks, 
   store_rows_coalesced<T, G::kNout>(A + (node * K + cb * kLanes) * G::kNout, out_stage[wave], lane, acc);
 }
 
-// dR of every edge, this channel block's partial of dY and the edge's share of dh; walks the
-// edges grouped by receiver.
+// receiver[e] for every edge, from the receivers' offsets: one thread per receiving atom.
+__global__ __launch_bounds__(256) void edge_receiver_kernel(int64_t n_out_nodes, const EdgeList el,
+                                                            int32_t* __restrict__ receiver) {
+  const int64_t node = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
+  if (node >= n_out_nodes) return;
+  const int e0 = el.first(node), e1 = el.first(node + 1);
+  for (int e = e0; e < e1; ++e) receiver[e] = static_cast<int32_t>(node);
+}
+
+// The backward walks the edges grouped by SENDER: one wave = one (sending atom, 64-channel block).
+// It keeps the atom's h row and its dh sum in registers, walks the edges the atom sends
+// (send_edge order: the order of the sum) and gathers per edge the dA row of the receiver (rows of
+// one structure, met in the XCD's L2) next to the edge's own R rows; dR and the channel block's
+// partial of dY leave per edge, dh leaves once per atom: no per-edge shares
+// of dh go to memory and come back.  Atoms that send nothing get a zero row.  Every index is
+// clamped where it is used.
 template <typename T, typename G>
-__global__ __launch_bounds__(kThreads) void backward_kernel(
-    int K, int chblocks, int64_t n_units, int64_t n_edges, const T* __restrict__ Y, const T* __restrict__ h,
-    const T* __restrict__ R, const EdgeList el,
-    const T* __restrict__ dA, T* __restrict__ dR, T* __restrict__ dY_partial, T* __restrict__ dh_edge) {
+__global__ __launch_bounds__(kThreads) void backward_by_sender_kernel(
+    int K, int chblocks, int64_t n_units, int64_t n_out_nodes, int n_edges, const T* __restrict__ Y,
+    const T* __restrict__ h, const T* __restrict__ R, const int32_t* __restrict__ send_ptr,
+    const int32_t* __restrict__ send_edge, const int32_t* __restrict__ receiver, const T* __restrict__ dA,
+    T* __restrict__ dR, T* __restrict__ dY_partial, T* __restrict__ dh) {
   __shared__ T stage_all[kWaves][G::kNY * kStageStride];
   const int lane = threadIdx.x & (kLanes - 1);
   const int wave = uniform(threadIdx.x / kLanes);
@@ -214,44 +231,66 @@ __global__ __launch_bounds__(kThreads) void backward_kernel(
   const size_t node = unit / chblocks;
   const int cb = static_cast<int>(unit % chblocks);
   const int ch = cb * kLanes + lane;
-  const int e0 = uniform(el.first(node)), e1 = uniform(el.first(node + 1));
-  if (e0 >= e1) return;
-  T g[G::kNout];
-  load_row<T, G::kNout>(dA + (node * K + ch) * G::kNout, g);
-  T r0[G::kP], r1[G::kP], h0[G::kNh], h1[G::kNh];
-  load_weights<T, G::kP>(R, e0, K, ch, r0);
-  load_row<T, G::kNh>(h + (el.snd(e0) * K + ch) * G::kNh, h0);
-  int jn = (e0 + 1 < e1) ? el.raw(e0 + 1) : 0;
-
-  // One edge: arithmetic, dR row stores, dY summed over the 64 lanes in a fixed order.
-  auto finish_edge = [&](int e, const T (&r)[G::kP], const T (&hh)[G::kNh]) {
-    T y[G::kNY], dr[G::kP], dy[G::kNY], dhe[G::kNh];
-    load_uniform<T, G::kNY>(Y, e, y);
-    G::backward(y, hh, r, g, dr, dy, dhe);
-    T* out = dR + static_cast<size_t>(e) * G::kP * K + ch;
-#pragma unroll
-    for (int p = 0; p < G::kP; ++p) __builtin_nontemporal_store(dr[p], out + static_cast<size_t>(p) * K);
-    store_row<T, G::kNh>(dh_edge + (static_cast<size_t>(e) * K + ch) * G::kNh, dhe);
-    lane_sum_store<T, G::kNY>(stage, lane, dy, dY_partial + (static_cast<size_t>(cb) * n_edges + e) * G::kNY);
+  auto pos = [&](int v) { return v < 0 ? 0 : (v > n_edges ? n_edges : v); };
+  auto edge = [&](int q) {
+    const int e = send_edge[q];
+    return e < 0 ? 0 : (e >= n_edges ? n_edges - 1 : e);
   };
+  auto atom = [&](int r) { return static_cast<size_t>(r < 0 ? 0 : (r >= n_out_nodes ? n_out_nodes - 1 : r)); };
+  const int q0 = uniform(pos(send_ptr[node])), q1 = uniform(pos(send_ptr[node + 1]));
+  T acc[G::kNh];
+#pragma unroll
+  for (int c = 0; c < G::kNh; ++c) acc[c] = T(0);
+  if (q0 < q1) {
+    T hh[G::kNh];
+    load_row<T, G::kNh>(h + (node * K + ch) * G::kNh, hh);
+    T r0[G::kP], r1[G::kP], g0[G::kNout], g1[G::kNout];
+    int ea = uniform(edge(q0)), eb = 0;
+    load_weights<T, G::kP>(R, ea, K, ch, r0);
+    load_row<T, G::kNout>(dA + (atom(uniform(receiver[ea])) * K + ch) * G::kNout, g0);
+    // edge id and receiver of the edge after the current one, read one step ahead of its rows
+    int en = (q0 + 1 < q1) ? uniform(edge(q0 + 1)) : 0;
+    int rn = uniform(receiver[en]);
 
-  for (int e = e0; e < e1; e += 2) {
-    int jn2 = 0;
-    if (e + 1 < e1) {
-      load_weights<T, G::kP>(R, e + 1, K, ch, r1);
-      load_row<T, G::kNh>(h + (el.node(jn) * K + ch) * G::kNh, h1);
-      if (e + 2 < e1) jn2 = el.raw(e + 2);
-    }
-    finish_edge(e, r0, h0);
-    if (e + 1 < e1) {
-      if (e + 2 < e1) {
-        load_weights<T, G::kP>(R, e + 2, K, ch, r0);
-        load_row<T, G::kNh>(h + (el.node(jn2) * K + ch) * G::kNh, h0);
-        if (e + 3 < e1) jn = el.raw(e + 3);
+    // One edge: arithmetic, dR row stores, dY summed over the 64 lanes in a fixed order, dh added up.
+    auto finish_edge = [&](int e, const T (&r)[G::kP], const T (&g)[G::kNout]) {
+      T y[G::kNY], dr[G::kP], dy[G::kNY], dhe[G::kNh];
+      load_uniform<T, G::kNY>(Y, e, y);
+      G::backward(y, hh, r, g, dr, dy, dhe);
+      T* out = dR + static_cast<size_t>(e) * G::kP * K + ch;
+#pragma unroll
+      for (int p = 0; p < G::kP; ++p) __builtin_nontemporal_store(dr[p], out + static_cast<size_t>(p) * K);
+#pragma unroll
+      for (int c = 0; c < G::kNh; ++c) acc[c] += dhe[c];
+      lane_sum_store<T, G::kNY>(stage, lane, dy, dY_partial + (static_cast<size_t>(cb) * n_edges + e) * G::kNY);
+    };
+
+    for (int q = q0; q < q1; q += 2) {
+      if (q + 1 < q1) {
+        eb = en;
+        load_weights<T, G::kP>(R, eb, K, ch, r1);
+        load_row<T, G::kNout>(dA + (atom(rn) * K + ch) * G::kNout, g1);
+        if (q + 2 < q1) {
+          en = uniform(edge(q + 2));
+          rn = uniform(receiver[en]);
+        }
       }
-      finish_edge(e + 1, r1, h1);
+      finish_edge(ea, r0, g0);
+      if (q + 1 < q1) {
+        if (q + 2 < q1) {
+          ea = en;
+          load_weights<T, G::kP>(R, ea, K, ch, r0);
+          load_row<T, G::kNout>(dA + (atom(rn) * K + ch) * G::kNout, g0);
+          if (q + 3 < q1) {
+            en = uniform(edge(q + 3));
+            rn = uniform(receiver[en]);
+          }
+        }
+        finish_edge(eb, r1, g1);
+      }
     }
   }
+  store_row<T, G::kNh>(dh + (node * K + ch) * G::kNh, acc);
 }
 
 // Second-order pass: the backward's walk with the cotangents HR (per edge and path), Hh (at the
@@ -351,11 +390,21 @@ hipError_t fwd_launch(const tp_plan* plan, const FwdArgs& a, hipStream_t stream)
 template <typename T, typename G>
 hipError_t bwd_launch(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
   const int K = plan->cfg.num_channels, chblocks = K / kLanes;
-  const int64_t n_units = a.n_out_nodes * chblocks;
-  hipLaunchKernelGGL((backward_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
-                     n_units, a.n_edges, static_cast<const T*>(a.Y), static_cast<const T*>(a.h),
-                     static_cast<const T*>(a.R), EdgeList{a.sender, a.row_ptr, static_cast<int>(a.n_in), static_cast<int>(a.n_edges)}, static_cast<const T*>(a.dA),
-                     static_cast<T*>(a.dR), static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh_edge));
+  const EdgeList el{a.sender, a.row_ptr, static_cast<int>(a.n_in), static_cast<int>(a.n_edges)};
+  int32_t* receiver = static_cast<int32_t*>(a.dh_edge);   // the shares' part of the workspace is free on this path
+  if (a.n_edges > 0 && a.n_out_nodes > 0) {
+    hipLaunchKernelGGL(edge_receiver_kernel, dim3(static_cast<unsigned>((a.n_out_nodes + 255) / 256)), dim3(256), 0,
+                       stream, a.n_out_nodes, el, receiver);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int64_t n_units = a.n_in * chblocks;
+  // without receivers or edges no list is walked: every atom gets its zero row
+  hipLaunchKernelGGL((backward_by_sender_kernel<T, G>), dim3(grid_for(n_units)), dim3(kThreads), 0, stream, K, chblocks,
+                     n_units, a.n_out_nodes, a.n_out_nodes > 0 ? static_cast<int>(a.n_edges) : 0,
+                     static_cast<const T*>(a.Y), static_cast<const T*>(a.h), static_cast<const T*>(a.R), a.send_ptr,
+                     a.send_edge, receiver, static_cast<const T*>(a.dA), static_cast<T*>(a.dR),
+                     static_cast<T*>(a.dY_partial), static_cast<T*>(a.dh));
   return hipGetLastError();
 }
 
@@ -404,11 +453,11 @@ void spec_op_counts(int id, int32_t ops[3], int32_t flops[3]) {
 hipError_t launch_spec_forward(const tp_plan* plan, const FwdArgs& a, hipStream_t stream) {
   TP_DISPATCH(fwd_launch, (plan, a, stream))
 }
-hipError_t launch_spec_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
-  TP_DISPATCH(bwd_launch, (plan, a, stream))
-}
 hipError_t launch_spec_double_backward(const tp_plan* plan, const DblArgs& a, hipStream_t stream) {
   TP_DISPATCH(dbl_launch, (plan, a, stream))
+}
+hipError_t launch_spec_backward(const tp_plan* plan, const BwdArgs& a, hipStream_t stream) {
+  TP_DISPATCH(bwd_launch, (plan, a, stream))
 }
 
 }  // namespace tp
