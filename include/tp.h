@@ -140,8 +140,10 @@ sc_status tp_double_backward(tp_plan* plan, int64_t n_nodes_in, int64_t n_nodes_
 
 /* Measurement helper as in sc.h: while enabled, tp_forward / tp_backward bracket their
  * main kernels with HIP events; tp_profile_read returns the durations in milliseconds of
- * the forward kernel, the edge-walking backward kernel and the per-sender sum of dh of the
- * most recent calls (negative if none). */
+ * the forward kernel, the edge-walking backward kernel (with the generated kernels: the
+ * receiver indices and the walk by sender) and the per-sender sum of dh (table-driven kernels;
+ * the generated backward has no such launch and reports the time between two events with
+ * nothing in between) of the most recent calls (negative if none). */
 sc_status tp_profile_enable(tp_plan* plan, int32_t on);
 sc_status tp_profile_read(tp_plan* plan, float* forward_ms, float* backward_ms, float* dh_sum_ms);
 /* Same for the edge-walking kernel of the most recent tp_double_backward call. */
