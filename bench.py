@@ -733,7 +733,7 @@ def main():
     ap.add_argument("--balanced-batches", action="store_true",
                     help="measure only the host load balancer (1M graphs) and print its object")
     ap.add_argument("--tp", action="store_true",
-                    help="measure only the channelwise tensor product (--workload tp_training_step|tp_first_layer|tp_tiny)")
+                    help="measure only the channelwise tensor product (--workload tp_training_step|tp_large_batch|tp_first_layer|tp_tiny)")
     ap.add_argument("--attainable", action="store_true",
                     help="measure only the streaming probes (read, write, copy, backward-like rows) and print their object")
     ap.add_argument("--double-backward", action="store_true",
@@ -802,6 +802,7 @@ def main():
         out["also"]["double_backward_training_step"] = measure_double_backward(wl, 100, 10)
         out["also"]["double_backward_large_batch"] = measure_double_backward(workloads.WORKLOADS["large_batch"], 20, 3)
         out["also"]["channelwise_tp_training_step"] = measure_tp(workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
+        out["also"]["channelwise_tp_large_batch"] = measure_tp(workloads.TP_WORKLOADS["tp_large_batch"], 10, 2)
         out["also"]["channelwise_tp_double_backward_training_step"] = measure_tp_double_backward(
             workloads.TP_WORKLOADS["tp_training_step"], 20, 3)
         out["also"]["channel_mixing_linear"] = measure_linear()
