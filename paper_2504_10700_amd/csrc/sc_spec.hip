@@ -374,34 +374,43 @@ __global__ __launch_bounds__(kSpecThreads) void spec_forward_kernel(SplitGroupAr
       RowIO<T, TS, G::kNLM>::store(B + (static_cast<size_t>(node) * K + ch) * G::kNLM, b);
     }
   };
-  int n0, e0, n1 = 0, e1 = Z, e_w = -1;
+  // The loop takes two nodes per trip and every load in it is issued without a condition of its
+  // own, in a fixed order: the weights of a new element first, then the rows of the next node, then
+  // the arithmetic of the current node, which waits for its own operands only.  (A request under
+  // a condition makes the compiler wait for ALL outstanding loads at the join, the request just
+  // issued included, before the arithmetic it is meant to overlap; the scheduling barrier keeps the
+  // compiler from moving the request down into that arithmetic to save registers.)  The last trip
+  // of an even share requests its last node's rows once more; an odd share ends with a single node.
+  const int valid = __builtin_popcountll(__ballot(key < Z));   // they come first in the visiting order
+  if (valid == 0) return;   // no valid node in this wave's share
+  int n0, e0, n1, e1, e_w = -1;
   visit(0, n0, e0);
-  if (e0 >= Z) return;   // no valid node in this wave's share
   load_a(n0, a0);
-  for (int p = 0; p < cnt; p += 2) {
-    if (p + 1 < cnt) {
-      visit(p + 1, n1, e1);
-      if (e1 < Z) load_a(n1, a1);
-    }
+  int p = 0;
+  for (; p + 1 < valid; p += 2) {
     if (e0 != e_w) {
       load_folded<T, G>(wf, e0, chblocks, cb, lane, w);
       e_w = e0;
     }
+    visit(p + 1, n1, e1);
+    load_a(n1, a1);
+    __builtin_amdgcn_sched_barrier(0);
     G::forward(a0, w, b);
     store_b(n0);
-    if (p + 1 >= cnt || e1 >= Z) break;   // the valid nodes are done
-    e0 = Z;
-    if (p + 2 < cnt) {
-      visit(p + 2, n0, e0);
-      if (e0 < Z) load_a(n0, a0);
-    }
     if (e1 != e_w) {
       load_folded<T, G>(wf, e1, chblocks, cb, lane, w);
       e_w = e1;
     }
+    visit(p + 2 < valid ? p + 2 : valid - 1, n0, e0);
+    load_a(n0, a0);
+    __builtin_amdgcn_sched_barrier(0);
     G::forward(a1, w, b);
     store_b(n1);
-    if (e0 >= Z) break;
+  }
+  if (p < valid) {
+    if (e0 != e_w) load_folded<T, G>(wf, e0, chblocks, cb, lane, w);
+    G::forward(a0, w, b);
+    store_b(n0);
   }
 }
 
