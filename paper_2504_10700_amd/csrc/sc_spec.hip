@@ -811,13 +811,19 @@ hipError_t prepare_launch(const sc_plan* plan, int64_t n, const int32_t* z, cons
 // four nodes in 8..32 (8..64 for the larger bases) that minimises that product for this batch on this chip (10k nodes, 128
 // channels, four workgroups per CU: 20 nodes = one round of five nodes per wave instead of two
 // rounds of four with 16); among sizes within 2% of the best the largest up to `most` wins, since
-// longer shares per wave meet more runs of one element (measured best at 200k nodes: 24..32 nodes
-// with the 29-row basis, 48 with the 49-row basis, whose weights cost more to re-read).
+// longer shares per wave meet more runs of one element (measured best at 200k nodes before the
+// window order: 24..32 nodes with the 29-row basis, 48 with the 49-row basis, whose weights cost
+// more to re-read).  From eight rounds on the rounds no longer tell (workgroups are replaced as
+// they end) and, with the window order making the runs long whatever the share, the small bases
+// do best with five nodes per wave: 200k nodes, 29-row basis, forward 373 us with 20 nodes per
+// workgroup against 376 (16), 381 (24), 387 (28), 391 (32); the 49-row basis shows no preference
+// between 20 and 48 (268 us at 50k nodes, 256 channels) and keeps the rule above.
 inline int forward_tile_nodes(int64_t n, int chblocks, int64_t resident_wgs, int most) {
   auto cost = [&](int t) {
     const int64_t wgs = (n + t - 1) / t * chblocks;
     return static_cast<double>((wgs + resident_wgs - 1) / resident_wgs) * (t / kSpecWaves);
   };
+  if (most <= 32 && (n + 19) / 20 * chblocks >= 8 * resident_wgs) return 20;
   double best = cost(8);
   for (int t = 12; t <= most; t += 4) best = cost(t) < best ? cost(t) : best;
   int pick = 8;
